@@ -1,0 +1,229 @@
+"""CPU oracle of the COVAP hot path -- TEST INFRASTRUCTURE, not product code.
+
+Thin ctypes wrapper over ``covap_oracle.c`` (plain C, built with gcc).  Only
+``tests/``, ``__graft_entry__.smoke()`` and ``bench.py``'s ``cpu_baseline`` leg
+may import this package; the HIP library never does, and this package never
+imports the HIP binding.  All arrays are numpy, host memory.
+
+The arithmetic lives in the C file; this module only marshals arguments.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "covap_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+CFLAGS = ["-O2", "-std=c99", "-ffp-contract=off", "-fPIC", "-shared", "-Wall", "-Wextra"]
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc.  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", *CFLAGS, "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+_i64p = C.POINTER(C.c_int64)
+_i32p = C.POINTER(C.c_int32)
+_f32p = C.POINTER(C.c_float)
+_u16p = C.POINTER(C.c_uint16)
+_u32p = C.POINTER(C.c_uint32)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = C.CDLL(_LIB)
+        L.orc_plan_offsets.restype = C.c_int64
+        L.orc_plan_offsets.argtypes = [_i64p, C.c_int32, _i64p]
+        L.orc_plan_fixed_shards.restype = C.c_int64
+        L.orc_plan_fixed_shards.argtypes = [C.c_int64, C.c_int64, _i64p, _i64p]
+        L.orc_plan_buckets.restype = C.c_int32
+        L.orc_plan_buckets.argtypes = [_i64p, C.c_int64, C.c_int64, _i32p]
+        L.orc_plan_median_parts.restype = C.c_int64
+        L.orc_plan_median_parts.argtypes = [_i64p, C.c_int32, C.c_int64, C.c_int32, _i32p]
+        L.orc_plan_even_slices.restype = C.c_int32
+        L.orc_plan_even_slices.argtypes = [C.c_int64, C.c_int32, C.c_int64, _i64p]
+        L.orc_selected.restype = C.c_int32
+        L.orc_selected.argtypes = [C.c_int64, C.c_uint64, C.c_int32]
+        L.orc_packed_elems.restype = C.c_int64
+        L.orc_packed_elems.argtypes = [_i64p, C.c_int64, C.c_int64, C.c_int32, C.c_uint64]
+        L.orc_f32_to_bf16.restype = C.c_uint16
+        L.orc_f32_to_bf16.argtypes = [C.c_float]
+        L.orc_bf16_to_f32.restype = C.c_float
+        L.orc_bf16_to_f32.argtypes = [C.c_uint16]
+        for name, ptr in (("f32", _f32p), ("bf16", _u16p)):
+            f = getattr(L, "orc_compress_" + name)
+            f.restype = C.c_int64
+            f.argtypes = [ptr, ptr, ptr, _i64p, _i64p, C.c_int64, C.c_int64, C.c_int32,
+                          C.c_uint64, C.c_float]
+            g = getattr(L, "orc_decompress_" + name)
+            g.restype = None
+            g.argtypes = [ptr, C.c_int32, C.c_int64, ptr, _i64p, _i64p, C.c_int64, C.c_int64,
+                          C.c_int32, C.c_uint64]
+        L.orc_topk_f32.restype = C.c_int32
+        L.orc_topk_f32.argtypes = [_f32p, _f32p, C.c_int64, C.c_int64, C.c_float, _f32p, _u32p]
+        L.orc_ratio_from_ccr.restype = C.c_int32
+        L.orc_ratio_from_ccr.argtypes = [C.c_double, _i32p]
+        L.orc_ef_coeff.restype = C.c_float
+        L.orc_ef_coeff.argtypes = [C.c_float, C.c_uint64, C.c_uint64, C.c_float]
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray, ptr):
+    return a.ctypes.data_as(ptr)
+
+
+def _chk(a: np.ndarray, dtype) -> np.ndarray:
+    if a.dtype != dtype or not a.flags.c_contiguous:
+        raise TypeError(f"expected C-contiguous {dtype}, got {a.dtype}")
+    return a
+
+
+# ------------------------------------------------------------------ planner
+
+class ShardTable:
+    """Shard list of one arena: off[s], len[s], bucket[s]; D elements in all."""
+
+    def __init__(self, off, length, bucket, D, tensor_offsets=None):
+        self.off = np.ascontiguousarray(off, dtype=np.int64)
+        self.len = np.ascontiguousarray(length, dtype=np.int64)
+        self.bucket = np.ascontiguousarray(bucket, dtype=np.int32)
+        self.D = int(D)
+        self.tensor_offsets = tensor_offsets
+
+    @property
+    def n_shards(self) -> int:
+        return int(self.off.shape[0])
+
+    @property
+    def n_buckets(self) -> int:
+        return int(self.bucket[-1]) + 1 if self.n_shards else 0
+
+    def bucket_range(self, b: int):
+        """Shard range [lo, hi) of bucket b; b = -1 means every shard."""
+        if b < 0:
+            return 0, self.n_shards
+        idx = np.nonzero(self.bucket == b)[0]
+        return int(idx[0]), int(idx[-1]) + 1
+
+
+def plan_fixed(tensor_numel, shard_elems: int, bucket_cap_elems: int) -> ShardTable:
+    numel = np.ascontiguousarray(tensor_numel, dtype=np.int64)
+    offs = np.zeros(max(len(numel), 1), dtype=np.int64)
+    D = lib().orc_plan_offsets(_p(numel, _i64p), len(numel), _p(offs, _i64p))
+    n = lib().orc_plan_fixed_shards(D, shard_elems, None, None)
+    off = np.zeros(max(n, 1), dtype=np.int64)
+    ln = np.zeros(max(n, 1), dtype=np.int64)
+    lib().orc_plan_fixed_shards(D, shard_elems, _p(off, _i64p), _p(ln, _i64p))
+    bucket = np.zeros(max(n, 1), dtype=np.int32)
+    lib().orc_plan_buckets(_p(ln, _i64p), n, bucket_cap_elems, _p(bucket, _i32p))
+    return ShardTable(off[:n], ln[:n], bucket[:n], D, offs[:len(numel)])
+
+
+def median_parts(numel, ref: int, interval: int):
+    numel = np.ascontiguousarray(numel, dtype=np.int64)
+    parts = np.zeros(len(numel), dtype=np.int32)
+    total = lib().orc_plan_median_parts(_p(numel, _i64p), len(numel), ref, interval,
+                                        _p(parts, _i32p))
+    return parts, int(total)
+
+
+def even_slices(numel: int, parts: int, align: int):
+    out = np.zeros(parts, dtype=np.int64)
+    n = lib().orc_plan_even_slices(numel, parts, align, _p(out, _i64p))
+    return out[:n]
+
+
+def selected(s: int, t: int, interval: int) -> bool:
+    return bool(lib().orc_selected(s, t, interval))
+
+
+def packed_elems(tab: ShardTable, interval: int, t: int, bucket: int = -1) -> int:
+    lo, hi = tab.bucket_range(bucket)
+    return int(lib().orc_packed_elems(_p(tab.len, _i64p), lo, hi, interval, t))
+
+
+def packed_base(tab: ShardTable, interval: int, t: int, bucket: int) -> int:
+    lo, _ = tab.bucket_range(bucket)
+    return int(lib().orc_packed_elems(_p(tab.len, _i64p), 0, lo, interval, t))
+
+
+# ------------------------------------------------------------------ hot path
+
+def _kind(a: np.ndarray):
+    if a.dtype == np.float32:
+        return "f32", _f32p
+    if a.dtype == np.uint16:
+        return "bf16", _u16p
+    raise TypeError("oracle arrays are float32, or uint16 holding bf16 bit patterns")
+
+
+def compress(tab: ShardTable, interval: int, t: int, G, R, send, c: float = 1.0,
+             bucket: int = -1) -> int:
+    """In place: R becomes the new residual, send receives the packed shards."""
+    name, ptr = _kind(G)
+    for a in (G, R, send):
+        _chk(a, G.dtype)
+    lo, hi = tab.bucket_range(bucket)
+    f = getattr(lib(), "orc_compress_" + name)
+    return int(f(_p(G, ptr), _p(R, ptr), _p(send, ptr), _p(tab.off, _i64p), _p(tab.len, _i64p),
+                 lo, hi, interval, t, c))
+
+
+def decompress(tab: ShardTable, interval: int, t: int, recv, out, bucket: int = -1) -> None:
+    """recv: [N, stride] packed payload rows; out: dense arena, fully written."""
+    name, ptr = _kind(recv)
+    _chk(recv, recv.dtype)
+    _chk(out, recv.dtype)
+    assert recv.ndim == 2
+    lo, hi = tab.bucket_range(bucket)
+    f = getattr(lib(), "orc_decompress_" + name)
+    f(_p(recv, ptr), recv.shape[0], recv.shape[1], _p(out, ptr), _p(tab.off, _i64p),
+      _p(tab.len, _i64p), lo, hi, interval, t)
+
+
+def topk(G, R, k: int, c: float = 1.0):
+    """In place on R.  Returns (vals[k] float32, idx[k] uint32) in ascending index."""
+    _chk(G, np.float32)
+    _chk(R, np.float32)
+    vals = np.zeros(max(k, 1), dtype=np.float32)
+    idx = np.zeros(max(k, 1), dtype=np.uint32)
+    rc = lib().orc_topk_f32(_p(G, _f32p), _p(R, _f32p), G.shape[0], k, c, _p(vals, _f32p),
+                            _p(idx, _u32p))
+    if rc != 0:
+        raise ValueError("orc_topk_f32: bad n or k")
+    return vals[:k], idx[:k]
+
+
+def f32_to_bf16(x: float) -> int:
+    return int(lib().orc_f32_to_bf16(x))
+
+
+def bf16_to_f32(h: int) -> float:
+    return float(lib().orc_bf16_to_f32(h))
+
+
+# ------------------------------------------------------------------ policy
+
+def ratio_from_ccr(ccr: float) -> int:
+    k = C.c_int32(0)
+    if lib().orc_ratio_from_ccr(ccr, C.byref(k)) != 0:
+        raise ValueError("CCR must be a positive finite number")
+    return int(k.value)
+
+
+def ef_coeff(init_value: float, num_steps: int, ascend_steps: int, ascend_range: float) -> float:
+    if ascend_steps <= 0:
+        raise ValueError("ascend_steps must be positive")
+    return float(lib().orc_ef_coeff(init_value, num_steps, ascend_steps, ascend_range))

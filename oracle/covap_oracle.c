@@ -1,0 +1,382 @@
+/*
+ * covap_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, single-threaded CPU statement of what the COVAP per-iteration
+ * gradient-compression path computes, written from the paper
+ * (arXiv 2311.04499).  Only tests, the smoke check and the benchmark's
+ * cpu_baseline leg may call it.  It shares no code with the HIP library: it
+ * has its own planner, its own filter, its own bf16 conversion.
+ *
+ * Every function walks the data in the order the paper states the operation:
+ * shard by shard, element by element, worker by worker.  No blocking, fusion
+ * or reordering.  Compile with -ffp-contract=off so that the only fused
+ * multiply-add is the one written as fmaf().
+ *
+ * Index conventions (the paper leaves the base open): shards ("tensors" after
+ * sharding, Sec. III-C) and iterations (num_steps, Sec. III-A) are 0-based.
+ *
+ * Pins: tests/test_oracle_*.py check every function below against brute force,
+ * closed forms and the figures the paper prints.  No function here is
+ * "parity unpinned" except orc_plan_buckets (the paper gives no bucket rule;
+ * buckets only partition launches and never change a result).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------ */
+/* Planner                                                             */
+/* ------------------------------------------------------------------ */
+
+/* Flat arena: gradients of consecutive layers are laid end to end in one
+ * communication buffer (Sec. II-B, Sec. III-A).  offsets[i] = sum of numel
+ * before tensor i.  Returns the total D. */
+int64_t orc_plan_offsets(const int64_t *numel, int32_t n, int64_t *offsets)
+{
+    int64_t d = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        if (offsets) offsets[i] = d;
+        d += numel[i];
+    }
+    return d;
+}
+
+/* Fixed-size sharding of the arena: shard s covers [s*S, min((s+1)*S, D)).
+ * After sharding every shard counts as one "tensor" for the filter
+ * (Sec. III-C, last paragraph).  Returns the number of shards; fills off/len
+ * when they are not NULL. */
+int64_t orc_plan_fixed_shards(int64_t D, int64_t S, int64_t *off, int64_t *len)
+{
+    int64_t n = 0;
+    for (int64_t b = 0; b < D; b += S) {
+        int64_t l = D - b;
+        if (l > S) l = S;
+        if (off) off[n] = b;
+        if (len) len[n] = l;
+        ++n;
+    }
+    return n;
+}
+
+/* Buckets: consecutive shards are grouped greedily; a bucket is closed when
+ * the next shard would push it over cap_elems (a shard larger than the cap is
+ * a bucket by itself).  The paper only says communication tensors are about
+ * 25 MB (Sec. III-A); this rule is this build's reading.  Returns the number
+ * of buckets and writes the bucket id of each shard. */
+int32_t orc_plan_buckets(const int64_t *len, int64_t n_sh, int64_t cap_elems,
+                         int32_t *bucket_of)
+{
+    int32_t b = 0;
+    int64_t fill = 0;
+    for (int64_t s = 0; s < n_sh; ++s) {
+        if (fill > 0 && fill + len[s] > cap_elems) {
+            ++b;
+            fill = 0;
+        }
+        bucket_of[s] = b;
+        fill += len[s];
+    }
+    return n_sh > 0 ? b + 1 : 0;
+}
+
+/* Median-based tensor sharding (Sec. III-C): given the element counts of the
+ * communication tensors, a tensor holding at least twice the reference count
+ * is cut evenly into floor(numel/ref) parts, but never more than I parts.
+ * ref <= 0 asks for the statistical median of numel[] (mean of the two middle
+ * values for an even count).  parts[i] receives the number of pieces of
+ * tensor i; the return value is the total number of units the filter then
+ * sees. */
+static int cmp_i64(const void *a, const void *b)
+{
+    int64_t x = *(const int64_t *)a, y = *(const int64_t *)b;
+    return (x > y) - (x < y);
+}
+
+int64_t orc_plan_median_parts(const int64_t *numel, int32_t n, int64_t ref,
+                              int32_t I, int32_t *parts)
+{
+    if (n <= 0) return 0;
+    if (ref <= 0) {
+        int64_t *tmp = (int64_t *)malloc(sizeof(int64_t) * (size_t)n);
+        memcpy(tmp, numel, sizeof(int64_t) * (size_t)n);
+        qsort(tmp, (size_t)n, sizeof(int64_t), cmp_i64);
+        ref = (n % 2) ? tmp[n / 2] : (tmp[n / 2 - 1] + tmp[n / 2]) / 2;
+        free(tmp);
+        if (ref <= 0) ref = 1;
+    }
+    int64_t total = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        int64_t p = numel[i] / ref;
+        if (p > I) p = I;
+        if (p < 2) p = 1;
+        parts[i] = (int32_t)p;
+        total += p;
+    }
+    return total;
+}
+
+/* Even slicing of one tensor of `numel` elements into `parts` pieces: every
+ * piece but the last has ceil(numel/parts) rounded up to a multiple of
+ * `align` elements; the last takes the rest.  Writes piece lengths to len[]
+ * and returns how many pieces are non-empty (always `parts` unless the
+ * rounding used the tensor up early). */
+int32_t orc_plan_even_slices(int64_t numel, int32_t parts, int64_t align,
+                             int64_t *len)
+{
+    int64_t piece = (numel + parts - 1) / parts;
+    piece = (piece + align - 1) / align * align;
+    int32_t n = 0;
+    int64_t left = numel;
+    while (left > 0 && n < parts) {
+        int64_t l = (n == parts - 1 || left < piece) ? left : piece;
+        len[n++] = l;
+        left -= l;
+    }
+    return n;
+}
+
+/* ------------------------------------------------------------------ */
+/* Coarse-grained filter (Sec. III-A; Definition 1)                    */
+/* ------------------------------------------------------------------ */
+
+/* Shard s is communicated in iteration t when (s + t) mod I == 0. */
+int32_t orc_selected(int64_t s, uint64_t t, int32_t I)
+{
+    uint64_t a = (uint64_t)(s % I);
+    uint64_t b = t % (uint64_t)I;
+    return ((a + b) % (uint64_t)I) == 0 ? 1 : 0;
+}
+
+/* Number of elements the selected shards in [sh_lo, sh_hi) hold at step t. */
+int64_t orc_packed_elems(const int64_t *len, int64_t sh_lo, int64_t sh_hi,
+                         int32_t I, uint64_t t)
+{
+    int64_t p = 0;
+    for (int64_t s = sh_lo; s < sh_hi; ++s)
+        if (orc_selected(s, t, I)) p += len[s];
+    return p;
+}
+
+/* ------------------------------------------------------------------ */
+/* bf16 <-> fp32 (own implementation; round to nearest, ties to even)  */
+/* ------------------------------------------------------------------ */
+
+static float bf16_to_f32(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+static uint16_t f32_to_bf16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) /* NaN: keep it a NaN */
+        return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t keep = u >> 16;
+    uint32_t drop = u & 0xffffu;
+    if (drop > 0x8000u || (drop == 0x8000u && (keep & 1u))) keep += 1u;
+    return (uint16_t)keep;
+}
+
+uint16_t orc_f32_to_bf16(float f) { return f32_to_bf16(f); }
+float orc_bf16_to_f32(uint16_t h) { return bf16_to_f32(h); }
+
+/* ------------------------------------------------------------------ */
+/* Compress: error feedback + filter + pack + residual (Algorithm 1)   */
+/* ------------------------------------------------------------------ */
+
+/*
+ * For every element i of shards [sh_lo, sh_hi):
+ *     a = G[i] + c * R[i]              Alg. 1 line 2, with the scheduler's
+ *                                      coefficient c (one rounding: fmaf)
+ *     selected shard:   send[p++] = a; R[i] = +0   (G' = a, so G - G' = 0)
+ *     unselected shard: R[i] = a                   (G' = 0, Definition 1)
+ * send is indexed from the start of the step's packed layout over ALL shards:
+ * p starts at the packed size of shards [0, sh_lo).  Returns the number of
+ * elements written to send.
+ */
+int64_t orc_compress_f32(const float *G, float *R, float *send,
+                         const int64_t *off, const int64_t *len,
+                         int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t,
+                         float c)
+{
+    int64_t p = orc_packed_elems(len, 0, sh_lo, I, t);
+    int64_t p0 = p;
+    for (int64_t s = sh_lo; s < sh_hi; ++s) {
+        int sel = orc_selected(s, t, I);
+        for (int64_t i = off[s]; i < off[s] + len[s]; ++i) {
+            float a = fmaf(c, R[i], G[i]);
+            if (sel) {
+                send[p++] = a;
+                R[i] = 0.0f;
+            } else {
+                R[i] = a;
+            }
+        }
+    }
+    return p - p0;
+}
+
+/* Same with bf16 storage: operands widen to fp32, one fmaf, one RNE back. */
+int64_t orc_compress_bf16(const uint16_t *G, uint16_t *R, uint16_t *send,
+                          const int64_t *off, const int64_t *len,
+                          int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t,
+                          float c)
+{
+    int64_t p = orc_packed_elems(len, 0, sh_lo, I, t);
+    int64_t p0 = p;
+    for (int64_t s = sh_lo; s < sh_hi; ++s) {
+        int sel = orc_selected(s, t, I);
+        for (int64_t i = off[s]; i < off[s] + len[s]; ++i) {
+            float a = fmaf(c, bf16_to_f32(R[i]), bf16_to_f32(G[i]));
+            uint16_t h = f32_to_bf16(a);
+            if (sel) {
+                send[p++] = h;
+                R[i] = 0;
+            } else {
+                R[i] = h;
+            }
+        }
+    }
+    return p - p0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Decompress: N-way average + unpack (Sec. II-A AllReduce + DP mean)  */
+/* ------------------------------------------------------------------ */
+
+/*
+ * recv holds N workers' packed payloads, row w at recv + w*stride, each in
+ * the layout orc_compress_* writes.  For shards [sh_lo, sh_hi):
+ *     selected:   out[i] = (((recv[0][q] + recv[1][q]) + ...) + recv[N-1][q]) / N
+ *     unselected: out[i] = +0                     (Definition 1, "otherwise")
+ * The sum is a left fold over w = 0..N-1 in fp32; the division is IEEE.
+ */
+void orc_decompress_f32(const float *recv, int32_t N, int64_t stride,
+                        float *out, const int64_t *off, const int64_t *len,
+                        int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t)
+{
+    int64_t q = orc_packed_elems(len, 0, sh_lo, I, t);
+    for (int64_t s = sh_lo; s < sh_hi; ++s) {
+        int sel = orc_selected(s, t, I);
+        for (int64_t i = off[s]; i < off[s] + len[s]; ++i) {
+            if (sel) {
+                float acc = recv[q];
+                for (int32_t w = 1; w < N; ++w) acc += recv[(int64_t)w * stride + q];
+                out[i] = acc / (float)N;
+                ++q;
+            } else {
+                out[i] = 0.0f;
+            }
+        }
+    }
+}
+
+/* bf16 payloads: fp32 accumulator, one RNE at the end. */
+void orc_decompress_bf16(const uint16_t *recv, int32_t N, int64_t stride,
+                         uint16_t *out, const int64_t *off, const int64_t *len,
+                         int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t)
+{
+    int64_t q = orc_packed_elems(len, 0, sh_lo, I, t);
+    for (int64_t s = sh_lo; s < sh_hi; ++s) {
+        int sel = orc_selected(s, t, I);
+        for (int64_t i = off[s]; i < off[s] + len[s]; ++i) {
+            if (sel) {
+                float acc = bf16_to_f32(recv[q]);
+                for (int32_t w = 1; w < N; ++w)
+                    acc += bf16_to_f32(recv[(int64_t)w * stride + q]);
+                out[i] = f32_to_bf16(acc / (float)N);
+                ++q;
+            } else {
+                out[i] = 0;
+            }
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Top-k sparsifier with error feedback (contrast; Sec. I, Table II)   */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    uint32_t key;
+    uint32_t idx;
+} keyidx_t;
+
+static int cmp_key_desc_idx_asc(const void *a, const void *b)
+{
+    const keyidx_t *x = (const keyidx_t *)a, *y = (const keyidx_t *)b;
+    if (x->key != y->key) return x->key > y->key ? -1 : 1;
+    return (x->idx > y->idx) - (x->idx < y->idx);
+}
+
+static int cmp_u32(const void *a, const void *b)
+{
+    uint32_t x = *(const uint32_t *)a, y = *(const uint32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * a[i] = G[i] + c*R[i] (Alg. 1 line 2); keep the k entries of largest
+ * magnitude.  Magnitudes are ordered by the bit pattern of |a| read as an
+ * unsigned integer (a total order; NaN sorts above Inf); among equal
+ * magnitudes the lower index wins.  Output: (vals, idx) in ascending index;
+ * residual R = a with the kept entries set to +0 (Alg. 1 line 4).
+ * The selection is a full sort: slow, and plainly the definition.
+ * Returns 0, or -1 when k or n is out of range or memory runs out.
+ */
+int32_t orc_topk_f32(const float *G, float *R, int64_t n, int64_t k, float c,
+                     float *vals, uint32_t *idx)
+{
+    if (n < 0 || k < 0 || k > n || n > (int64_t)0xffffffffLL) return -1;
+    keyidx_t *ki = (keyidx_t *)malloc(sizeof(keyidx_t) * (size_t)(n ? n : 1));
+    if (!ki) return -1;
+    for (int64_t i = 0; i < n; ++i) {
+        float a = fmaf(c, R[i], G[i]);
+        R[i] = a;
+        uint32_t u;
+        memcpy(&u, &a, 4);
+        ki[i].key = u & 0x7fffffffu;
+        ki[i].idx = (uint32_t)i;
+    }
+    qsort(ki, (size_t)n, sizeof(keyidx_t), cmp_key_desc_idx_asc);
+    for (int64_t j = 0; j < k; ++j) idx[j] = ki[j].idx;
+    free(ki);
+    qsort(idx, (size_t)k, sizeof(uint32_t), cmp_u32);
+    for (int64_t j = 0; j < k; ++j) {
+        vals[j] = R[idx[j]];
+        R[idx[j]] = 0.0f;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Host policy                                                         */
+/* ------------------------------------------------------------------ */
+
+/* Interval from the communication-to-computation ratio: I = ceil(CCR), and
+ * never below 1 (ratio 1 = no compression) (Sec. III-B).  Returns 0, or -1
+ * for a CCR that is not a positive finite number. */
+int32_t orc_ratio_from_ccr(double ccr, int32_t *I)
+{
+    if (!(ccr > 0.0) || isinf(ccr) || ccr > 2147483647.0) return -1;
+    double c = ceil(ccr);
+    *I = c < 1.0 ? 1 : (int32_t)c;
+    return 0;
+}
+
+/* Error-feedback scheduler (Sec. III-D):
+ *   coefficient = min(init_value + floor(num_steps/ascend_steps)*ascend_range, 1)
+ * evaluated in double from the fp32 parameters, then rounded to fp32. */
+float orc_ef_coeff(float init_value, uint64_t num_steps, uint64_t ascend_steps,
+                   float ascend_range)
+{
+    double rises = (double)(num_steps / ascend_steps);
+    double v = (double)init_value + rises * (double)ascend_range;
+    if (v > 1.0) v = 1.0;
+    return (float)v;
+}

@@ -1,0 +1,189 @@
+"""Pins for the oracle's planner, filter and host policy (CPU only).
+
+Each check ties the oracle to something other than itself: the congruence of
+Definition 1 worked out by hand (golden table), the coverage guarantees
+Sec. III-A states, the figures of Table I / Table V / Sec. III-C, and plain
+integer arithmetic redone here.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2311_04499_amd import workloads
+
+
+# ------------------------------------------------------------------ filter
+
+def test_filter_matches_hand_table(golden):
+    for row in golden("filter_I4.txt"):
+        step, want = int(row[0]), {int(x) for x in row[1:]}
+        got = {s for s in range(12) if oracle.selected(s, step, 4)}
+        assert got == want, (step, got, want)
+
+
+def test_filter_coverage_brute_force():
+    """Sec. III-A: every tensor is communicated exactly once in every I
+    iterations, and exactly one tensor out of every I consecutive tensors is
+    communicated in each iteration."""
+    for n_sh, I in itertools.product(range(1, 13), range(1, 7)):
+        for t0 in range(0, 3 * I):
+            # once per I consecutive iterations, for every shard
+            for s in range(n_sh):
+                hits = sum(oracle.selected(s, t, I) for t in range(t0, t0 + I))
+                assert hits == 1, (n_sh, I, t0, s)
+            # one of every I consecutive shards, in every iteration
+            for s0 in range(0, max(n_sh - I + 1, 0)):
+                hits = sum(oracle.selected(s, t0, I) for s in range(s0, s0 + I))
+                assert hits == 1, (n_sh, I, t0, s0)
+
+
+def test_filter_anchor_and_direction():
+    # (0 + 0) mod I = 0: shard 0 goes out in iteration 0, for every I
+    for I in range(1, 9):
+        assert oracle.selected(0, 0, I)
+        assert oracle.selected(0, I, I)
+        # in iteration 1 the congruence picks shard I-1 (not shard 1, unless I == 2)
+        assert oracle.selected(I - 1, 1, I)
+        if I > 2:
+            assert not oracle.selected(1, 1, I)
+
+
+def test_filter_interval_one_selects_everything():
+    # ratio 1 is the baseline without compression (Sec. IV-B)
+    assert all(oracle.selected(s, t, 1) for s in range(20) for t in range(5))
+
+
+def test_filter_huge_step_no_overflow():
+    big = 2 ** 64 - 1
+    for I in (3, 4, 7, 16):
+        sel = [s for s in range(2 * I) if oracle.selected(s, big, I)]
+        want = [s for s in range(2 * I) if (s + big) % I == 0]   # python ints: exact
+        assert sel == want
+
+
+def test_packed_elems_sum_over_a_period_is_D():
+    tab = oracle.plan_fixed([1000, 37, 5000, 1], 256, 1 << 30)
+    for I in (1, 2, 3, 5, 8):
+        for t0 in (0, 1, 7):
+            total = sum(oracle.packed_elems(tab, I, t) for t in range(t0, t0 + I))
+            assert total == tab.D
+
+
+# ------------------------------------------------------------------ planner
+
+def test_model_sizes_and_fixed_shards(golden):
+    for row in golden("model_sizes.txt"):
+        cfg, n_tensors, D, S, n_sh, last = map(int, row)
+        wl = workloads.config(cfg)
+        assert len(wl.shapes) == n_tensors
+        assert wl.D == D
+        assert wl.shard_elems == S
+        tab = oracle.plan_fixed(wl.numel, S, 1 << 40)
+        assert tab.D == D
+        assert tab.n_shards == n_sh == -(-D // S)
+        assert int(tab.len[-1]) == last
+        assert int(tab.len.sum()) == D
+        assert np.all(tab.off % 4 == 0)
+        assert np.all(tab.off[1:] == tab.off[:-1] + tab.len[:-1])
+        assert np.all(tab.len[:-1] == S)
+        # tensor offsets: exclusive prefix sum
+        assert list(tab.tensor_offsets) == [sum(wl.numel[:i]) for i in range(n_tensors)]
+
+
+def test_packed_range_per_config():
+    """min/max packed elements over a period, from integer arithmetic alone."""
+    want = {1: (163840, 167178), 2: (6356992, 6422528), 3: (17825792, 18874368),
+            4: (18087936, 18350080), 5: (22020096, 23068672)}
+    for cfg, (lo, hi) in want.items():
+        wl = workloads.config(cfg)
+        tab = oracle.plan_fixed(wl.numel, wl.shard_elems, 1 << 40)
+        p = [oracle.packed_elems(tab, wl.K, t) for t in range(wl.K)]
+        # independent count: shards s with (s+t)%K==0 are s = r, r+K, ...
+        for t in range(wl.K):
+            r = (-t) % wl.K
+            manual = sum(int(tab.len[s]) for s in range(r, tab.n_shards, wl.K))
+            assert manual == p[t]
+        assert (min(p), max(p)) == (lo, hi), (cfg, min(p), max(p))
+
+
+def test_buckets_partition_shards_in_order():
+    tab = oracle.plan_fixed([10_000], 1000, 2500)
+    # greedy: 2 shards of 1000 fit under 2500, the third would exceed it
+    assert list(tab.bucket) == [0, 0, 1, 1, 2, 2, 3, 3, 4, 4]
+    tab = oracle.plan_fixed([10_000], 4000, 2500)   # shard larger than the cap
+    assert list(tab.bucket) == [0, 1, 2]
+    for b in range(tab.n_buckets):
+        lo, hi = tab.bucket_range(b)
+        assert hi > lo
+    # per-bucket packed sizes add up to the whole step's
+    tab = oracle.plan_fixed([123_457], 1024, 5000)
+    for t in range(6):
+        parts = sum(oracle.packed_elems(tab, 3, t, b) for b in range(tab.n_buckets))
+        assert parts == oracle.packed_elems(tab, 3, t)
+
+
+def test_median_sharding_worked_example(golden):
+    rows = golden("vgg19_tensors.txt")
+    numel = [int(r[1]) for r in rows]
+    want = [int(r[2]) for r in rows]
+    assert sum(numel) == 143667240                      # Table V total
+    parts, total = oracle.median_parts(numel, 5590260, 1000)
+    assert list(parts) == want and total == 26          # Sec. III-C
+    # never more than I pieces
+    parts, total = oracle.median_parts(numel, 5590260, 4)
+    assert list(parts) == [1, 3, 4, 1, 1, 1] and total == 11
+    parts, _ = oracle.median_parts(numel, 5590260, 2)
+    assert list(parts) == [1, 2, 2, 1, 1, 1]
+    # the statistical median of the six counts is (7079424+7669760)/2
+    parts, total = oracle.median_parts(numel, 0, 1000)
+    med = (7079424 + 7669760) // 2
+    assert list(parts) == [max(1, n // med) for n in numel] and total == 20
+
+
+def test_even_slices():
+    for numel, parts, align in [(107480576, 19, 4), (16781312, 3, 4), (1000, 3, 4), (10, 4, 4),
+                                (7, 2, 8), (4096, 4, 8)]:
+        ln = oracle.even_slices(numel, parts, align)
+        assert int(ln.sum()) == numel
+        assert len(ln) <= parts
+        assert np.all(ln[:-1] % align == 0)
+        assert np.all(ln[:-1] == ln[0])
+        assert ln[-1] <= ln[0]
+        assert ln[0] - numel / parts < align + 1        # even up to the alignment
+
+
+# ------------------------------------------------------------------ policy
+
+def test_ratio_policy_paper_values(golden):
+    for row in golden("ratio_policy.txt"):
+        assert oracle.ratio_from_ccr(float(row[0])) == int(row[1])
+
+
+def test_ratio_policy_edges():
+    assert oracle.ratio_from_ccr(6.0) == 6
+    assert oracle.ratio_from_ccr(0.5) == 1          # never below "no compression"
+    assert oracle.ratio_from_ccr(1.0) == 1
+    assert oracle.ratio_from_ccr(1.0000001) == 2
+    for bad in (0.0, -1.0, float("nan"), float("inf")):
+        with pytest.raises(ValueError):
+            oracle.ratio_from_ccr(bad)
+
+
+def test_ef_coefficient_closed_form():
+    # init 0.1, +0.1 every 100 steps: 0.1 for steps 0..99, 0.2 for 100..199, ... capped at 1
+    for n in (0, 1, 99, 100, 199, 200, 555, 899, 900, 901, 10 ** 6, 2 ** 63):
+        got = oracle.ef_coeff(0.1, n, 100, 0.1)
+        want = min(np.float32(0.1).astype(np.float64) + (n // 100) * np.float32(0.1).astype(np.float64), 1.0)
+        assert got == np.float32(want)
+        assert got <= 1.0
+    assert oracle.ef_coeff(0.1, 899, 100, 0.1) < 1.0
+    assert oracle.ef_coeff(0.1, 900, 100, 0.1) == 1.0
+    # init 1 means plain Algorithm 1 from the first step
+    assert all(oracle.ef_coeff(1.0, n, 7, 0.25) == 1.0 for n in range(50))
+    # nondecreasing in the step
+    vals = [oracle.ef_coeff(0.3, n, 10, 0.05) for n in range(300)]
+    assert all(b >= a for a, b in zip(vals, vals[1:]))
+    assert math.isclose(vals[25], 0.3 + 2 * 0.05, rel_tol=1e-6)

@@ -1,0 +1,373 @@
+"""Pins for the oracle's compress / decompress / top-k (CPU only).
+
+The oracle is checked against what the paper and arithmetic fix, never against
+itself: the K=1 identity (Sec. IV-B), the error-feedback identities of
+Algorithm 1, exact conservation laws on integer-valued data, the contraction
+equality that follows from Definition 1, closed forms for the average, and
+library routines (numpy / torch sort, topk, bf16 cast) on cases that reduce to
+them.  Scatter/gather helpers below are written here independently from the
+shard table, so a wrong index in the oracle shows up.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_04499_amd import workloads
+
+
+def scatter_packed(tab, I, t, send, D):
+    """Independent unpack: place the packed buffer back at the arena positions
+    of the shards that Definition 1 keeps at step t; zeros elsewhere."""
+    dense = np.zeros(D, dtype=send.dtype)
+    p = 0
+    for s in range(tab.n_shards):
+        if (s + t) % I == 0:
+            o, l = int(tab.off[s]), int(tab.len[s])
+            dense[o:o + l] = send[p:p + l]
+            p += l
+    return dense, p
+
+
+def keep_mask(tab, I, t, D):
+    m = np.zeros(D, dtype=bool)
+    for s in range(tab.n_shards):
+        if (s + t) % I == 0:
+            m[int(tab.off[s]):int(tab.off[s] + tab.len[s])] = True
+    return m
+
+
+def bits(x):
+    return np.ascontiguousarray(x).view(np.uint32)
+
+
+CASES = [([1000, 37, 5000, 1], 256, 3), ([4096 * 3], 4096, 4), ([10], 4, 2), ([5], 8, 3),
+         ([777, 778, 779], 100, 16), ([2048], 64, 5)]
+
+
+# ------------------------------------------------------------------ compress
+
+@pytest.mark.parametrize("numel,S,I", CASES)
+def test_k1_is_identity(numel, S, I):
+    """Ratio 1 = no compression: everything is sent, nothing is kept back."""
+    tab = oracle.plan_fixed(numel, S, 1 << 30)
+    rng = np.random.default_rng(1)
+    G = rng.standard_normal(tab.D).astype(np.float32)
+    G[G == 0] = 1.0
+    R = np.zeros(tab.D, np.float32)
+    send = np.full(tab.D, np.nan, np.float32)
+    for t in range(3):
+        n = oracle.compress(tab, 1, t, G, R, send)
+        assert n == tab.D
+        assert np.array_equal(bits(send), bits(G))
+        assert not R.any() and not np.signbit(R).any()
+
+
+@pytest.mark.parametrize("numel,S,I", CASES)
+@pytest.mark.parametrize("c", [1.0, 0.5, 0.3])
+def test_error_feedback_identity(numel, S, I, c):
+    """Algorithm 1: every element of G + c*R_old ends up either in the payload
+    or in the new residual, and the other of the two is exactly +0."""
+    tab = oracle.plan_fixed(numel, S, 1 << 30)
+    rng = np.random.default_rng(2)
+    R = rng.standard_normal(tab.D).astype(np.float32)
+    for t in range(2 * I + 1):
+        G = rng.standard_normal(tab.D).astype(np.float32)
+        R_old = R.copy()
+        send = np.full(tab.D, np.nan, np.float32)
+        n = oracle.compress(tab, I, t, G, R, send, c)
+        dense, p = scatter_packed(tab, I, t, send, tab.D)
+        assert n == p == oracle.packed_elems(tab, I, t)
+        assert np.all(np.isnan(send[n:]))                       # nothing written past the end
+        # A = G + c*R_old with ONE rounding: evaluate exactly in float64
+        # (a 24x24-bit product plus a 24-bit addend is exact there when the
+        # exponents are close, as they are for these inputs), then round once.
+        A = (G.astype(np.float64) + np.float64(np.float32(c)) * R_old.astype(np.float64)).astype(np.float32)
+        m = keep_mask(tab, I, t, tab.D)
+        assert np.array_equal(bits(dense[m]), bits(A[m]))
+        assert np.array_equal(bits(R[~m]), bits(A[~m]))
+        assert not bits(R[m]).any()                             # +0, not -0
+        assert np.array_equal(dense + R, A)                     # sent + residual == G + c*R_old
+
+
+def test_conservation_over_many_steps_integer_data():
+    """With c = 1 nothing is ever lost: the sum of everything sent plus what is
+    still held back equals the sum of all gradients, exactly (integer-valued
+    fp32 data make every addition exact)."""
+    tab = oracle.plan_fixed([3000, 500, 77], 128, 1 << 30)
+    I, T = 4, 11
+    R = np.zeros(tab.D, np.float32)
+    total_sent = np.zeros(tab.D, np.float64)
+    total_grad = np.zeros(tab.D, np.float64)
+    for t in range(T):
+        G = workloads.integer_valued(tab.D, seed=100 + t).numpy()
+        total_grad += G
+        send = np.zeros(tab.D, np.float32)
+        oracle.compress(tab, I, t, G, R, send)
+        dense, _ = scatter_packed(tab, I, t, send, tab.D)
+        total_sent += dense
+    assert np.array_equal(total_sent + R, total_grad)
+
+
+def test_sent_value_is_left_fold_of_intervening_gradients():
+    """A shard sent at step t carries ((g_{t-I+1} + g_{t-I+2}) + ...) + g_t,
+    accumulated in that order in fp32."""
+    tab = oracle.plan_fixed([1024], 64, 1 << 30)
+    I = 4
+    rng = np.random.default_rng(5)
+    Gs = [rng.standard_normal(tab.D).astype(np.float32) for _ in range(3 * I)]
+    R = np.zeros(tab.D, np.float32)
+    last_sent = {}
+    for t, G in enumerate(Gs):
+        send = np.zeros(tab.D, np.float32)
+        oracle.compress(tab, I, t, G, R, send)
+        dense, _ = scatter_packed(tab, I, t, send, tab.D)
+        for s in range(tab.n_shards):
+            if (s + t) % I == 0:
+                o, l = int(tab.off[s]), int(tab.len[s])
+                first = last_sent.get(s, -1) + 1
+                acc = np.zeros(l, np.float32)                   # residual starts at +0
+                for u in range(first, t + 1):
+                    acc = Gs[u][o:o + l] + acc                  # a = G + 1*R
+                assert np.array_equal(dense[o:o + l], acc), (t, s)
+                last_sent[s] = t
+
+
+@pytest.mark.parametrize("numel,S,I", CASES)
+def test_contraction_equality(numel, S, I):
+    """Definition 1 keeps each coordinate in exactly one of I consecutive
+    steps, hence sum_t ||x - COVAP_t(x)||^2 = (I-1) ||x||^2 (which gives the
+    k-contraction bound of Sec. III-D with equality on average)."""
+    tab = oracle.plan_fixed(numel, S, 1 << 30)
+    x = workloads.integer_valued(tab.D, seed=9, lo=-30, hi=30).numpy()
+    norm2 = int((x.astype(np.int64) ** 2).sum())
+    for t0 in (0, 3):
+        acc = 0
+        for t in range(t0, t0 + I):
+            R = np.zeros(tab.D, np.float32)
+            send = np.zeros(tab.D, np.float32)
+            oracle.compress(tab, I, t, x, R, send)              # R = x - COVAP_t(x)
+            acc += int((R.astype(np.int64) ** 2).sum())
+        assert acc == (I - 1) * norm2
+
+
+def test_per_bucket_calls_equal_one_whole_call():
+    tab = oracle.plan_fixed([50_000, 123], 1000, 4500)
+    assert tab.n_buckets > 3
+    I = 3
+    rng = np.random.default_rng(3)
+    G = rng.standard_normal(tab.D).astype(np.float32)
+    R0 = rng.standard_normal(tab.D).astype(np.float32)
+    for t in range(I):
+        Ra, Rb = R0.copy(), R0.copy()
+        sa = np.zeros(tab.D, np.float32)
+        sb = np.zeros(tab.D, np.float32)
+        na = oracle.compress(tab, I, t, G, Ra, sa, 0.5)
+        nb = sum(oracle.compress(tab, I, t, G, Rb, sb, 0.5, bucket=b) for b in range(tab.n_buckets))
+        assert na == nb
+        assert np.array_equal(bits(sa), bits(sb)) and np.array_equal(bits(Ra), bits(Rb))
+
+
+def test_signed_zero_and_nonfinite():
+    tab = oracle.plan_fixed([8], 4, 1 << 30)
+    G = np.array([-0.0, 0.0, np.inf, -np.inf, np.nan, 1.0, -0.0, 2.0], np.float32)
+    R = np.zeros(8, np.float32)
+    send = np.zeros(8, np.float32)
+    oracle.compress(tab, 2, 0, G, R, send)                      # shard 0 sent, shard 1 kept
+    # -0 + (+0) = +0 under round-to-nearest: value-equal, not bit-equal, to the input
+    assert bits(send[:4]).tolist() == [0, 0, 0x7f800000, 0xff800000]
+    # a sent element leaves residual +0 even when it was infinite
+    assert not bits(R[:4]).any()
+    assert np.isnan(R[4]) and R[5] == 1.0 and bits(R[6:7])[0] == 0 and R[7] == 2.0
+
+
+# ------------------------------------------------------------------ decompress
+
+def test_average_closed_form_and_zero_fill():
+    tab = oracle.plan_fixed([1000, 24], 64, 1 << 30)
+    I = 4
+    for N in (1, 2, 3, 5, 8, 64):
+        for t in range(I):
+            P = oracle.packed_elems(tab, I, t)
+            stride = P + 12
+            q = np.arange(stride, dtype=np.float32)
+            recv = np.stack([(w + 1) * 7 + q * N for w in range(N)]).astype(np.float32)
+            out = np.full(tab.D, np.nan, np.float32)
+            oracle.decompress(tab, I, t, recv, out)
+            # sum_w ((w+1)*7 + q*N) = 7*N(N+1)/2 + q*N*N, exact in fp32 here
+            want_packed = ((7 * N * (N + 1) // 2 + np.arange(P, dtype=np.int64) * N * N) / N)
+            dense, used = scatter_packed(tab, I, t, want_packed.astype(np.float32), tab.D)
+            assert used == P
+            m = keep_mask(tab, I, t, tab.D)
+            np.testing.assert_allclose(out[m], dense[m], rtol=6e-8, atol=0)
+            if N & (N - 1) == 0 or N in (1,):
+                assert np.array_equal(out[m], dense[m])
+            assert not bits(out[~m]).any()                       # +0 where nothing was sent
+
+
+def test_average_is_left_fold_in_worker_order():
+    tab = oracle.plan_fixed([4096], 256, 1 << 30)
+    I, N, t = 2, 7, 1
+    P = oracle.packed_elems(tab, I, t)
+    rng = np.random.default_rng(7)
+    recv = (rng.standard_normal((N, P)) * np.logspace(-3, 3, N)[:, None]).astype(np.float32)
+    out = np.zeros(tab.D, np.float32)
+    oracle.decompress(tab, I, t, recv, out)
+    acc = recv[0].copy()
+    for w in range(1, N):
+        acc = acc + recv[w]
+    want, _ = scatter_packed(tab, I, t, acc / np.float32(N), tab.D)
+    assert np.array_equal(bits(out), bits(want))
+    # the order matters in the last place: a right fold differs somewhere
+    acc_r = recv[N - 1].copy()
+    for w in range(N - 2, -1, -1):
+        acc_r = acc_r + recv[w]
+    assert not np.array_equal(acc_r, acc)
+    # N = 1 returns the payload itself
+    out1 = np.zeros(tab.D, np.float32)
+    oracle.decompress(tab, I, t, recv[:1].copy(), out1)
+    want1, _ = scatter_packed(tab, I, t, recv[0], tab.D)
+    assert np.array_equal(bits(out1), bits(want1))
+
+
+def test_average_division_is_correctly_rounded():
+    """acc / N for N that is not a power of two: compare with the exact quotient
+    rounded once (float64 holds fp32/N to far more than 2x24 bits, so rounding
+    the float64 quotient to fp32 equals the correctly rounded quotient)."""
+    tab = oracle.plan_fixed([3000], 3000 // 4 * 4, 1 << 30)
+    rng = np.random.default_rng(11)
+    for N in (3, 5, 6, 7, 11, 24):
+        recv = np.zeros((N, tab.D), np.float32)
+        recv[0] = rng.standard_normal(tab.D).astype(np.float32)
+        recv[0, :8] = [1e-45, 3e-45, 1.1754942e-38, 1e-40, 3.4e38, -3.4e38, 7e-46, -1e-45]
+        out = np.zeros(tab.D, np.float32)
+        oracle.decompress(tab, 1, 0, recv, out)
+        want = (recv[0].astype(np.float64) / N).astype(np.float32)
+        assert np.array_equal(bits(out), bits(want))
+
+
+def test_round_trip_compress_then_average_of_identical_workers():
+    """N identical workers: the average of their payloads, unpacked, equals the
+    dense filtered gradient COVAP_t(G + c*R)."""
+    tab = oracle.plan_fixed([5000, 300], 512, 1 << 30)
+    I, N = 3, 4
+    rng = np.random.default_rng(4)
+    G = rng.standard_normal(tab.D).astype(np.float32)
+    for t in range(I):
+        R = np.zeros(tab.D, np.float32)
+        P = oracle.packed_elems(tab, I, t)
+        send = np.zeros(P, np.float32)
+        oracle.compress(tab, I, t, G, R, send)
+        recv = np.tile(send, (N, 1))
+        out = np.zeros(tab.D, np.float32)
+        oracle.decompress(tab, I, t, recv, out)
+        m = keep_mask(tab, I, t, tab.D)
+        assert np.array_equal(out[m], G[m]) and not out[~m].any()
+        assert np.array_equal(out + R, G)
+
+
+# ------------------------------------------------------------------ top-k
+
+def lexsort_topk(A, k):
+    key = bits(np.abs(A)).astype(np.int64)
+    order = np.lexsort((np.arange(len(A)), -key))               # key descending, index ascending
+    return np.sort(order[:k]).astype(np.uint32)
+
+
+@pytest.mark.parametrize("n,k", [(1, 0), (1, 1), (7, 3), (64, 0), (64, 1), (64, 64), (50, 17), (1000, 10)])
+def test_topk_against_sort(n, k):
+    rng = np.random.default_rng(n * 131 + k)
+    for trial, gen in enumerate([lambda: rng.standard_normal(n),
+                                 lambda: rng.integers(-3, 4, n),          # many ties, zeros
+                                 lambda: np.zeros(n), lambda: np.full(n, -2.5)]):
+        G = gen().astype(np.float32)
+        R0 = (rng.standard_normal(n) * (trial == 0)).astype(np.float32)
+        R = R0.copy()
+        vals, idx = oracle.topk(G, R, k, 0.5)
+        A = (G.astype(np.float64) + 0.5 * R0.astype(np.float64)).astype(np.float32)
+        want = lexsort_topk(A, k)
+        assert np.array_equal(idx, want)
+        assert np.array_equal(bits(vals), bits(A[want]))
+        dense = np.zeros(n, np.float32)
+        dense[idx] = vals
+        assert np.array_equal(dense + R, A)                     # kept + residual == A
+        assert not bits(R[idx]).any()
+
+
+def test_topk_reduces_to_library_topk_when_magnitudes_are_distinct():
+    n, k = 5000, 50
+    rng = np.random.default_rng(0)
+    G = rng.permutation(n).astype(np.float32) + 1.0             # distinct magnitudes
+    G *= rng.choice([-1.0, 1.0], n).astype(np.float32)
+    R = np.zeros(n, np.float32)
+    vals, idx = oracle.topk(G, R, k)
+    want = torch.topk(torch.from_numpy(np.abs(G)), k).indices.numpy()
+    assert set(idx.tolist()) == set(want.tolist())
+    assert np.all(np.diff(idx.astype(np.int64)) > 0)
+
+
+def test_topk_ties_take_lowest_index_and_nan_sorts_on_top():
+    G = np.array([1, -1, 1, 5, -1, 1], np.float32)
+    R = np.zeros(6, np.float32)
+    vals, idx = oracle.topk(G, R, 3)
+    assert idx.tolist() == [0, 1, 3] and vals.tolist() == [1, -1, 5]
+    G = np.array([1, np.inf, np.nan, 2], np.float32)
+    R = np.zeros(4, np.float32)
+    _, idx = oracle.topk(G, R, 1)
+    assert idx.tolist() == [2]
+    with pytest.raises(ValueError):
+        oracle.topk(G, R, 5)
+
+
+# ------------------------------------------------------------------ bf16
+
+def test_bf16_conversion_against_torch_cast():
+    # every bf16 pattern widens exactly
+    h = np.arange(65536, dtype=np.uint32)
+    wide = (h << 16).astype(np.uint32).view(np.float32)
+    for v in (0, 1, 0x3f80, 0x7f7f, 0x7f80, 0x8000, 0xff80, 0x0001, 0x807f):
+        assert np.float32(oracle.bf16_to_f32(v)).view(np.uint32) == np.uint32(v << 16)
+    # rounding: below half, exactly half (both parities), above half, for many exponents
+    pats = []
+    for hi in list(range(0, 0x7f80, 97)) + [0x7f7f, 0x7f7e, 0x0000, 0x0001, 0x007f, 0x0080]:
+        for lo in (0x0000, 0x0001, 0x7fff, 0x8000, 0x8001, 0xffff):
+            for sign in (0, 0x80000000):
+                pats.append(sign | (hi << 16) | lo)
+    f = np.array(pats, dtype=np.uint32).view(np.float32)
+    want = torch.from_numpy(f.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = np.array([oracle.f32_to_bf16(x) for x in f], dtype=np.uint16)
+    assert np.array_equal(got, want)
+    assert wide[0x7f80] == np.inf
+    # NaN stays NaN
+    assert (oracle.f32_to_bf16(float("nan")) & 0x7fff) > 0x7f80
+
+
+def test_bf16_compress_and_average_against_torch():
+    tab = oracle.plan_fixed([4096 + 40], 256, 1 << 30)
+    I = 3
+    g = torch.Generator().manual_seed(3)
+    G = (torch.randn(tab.D, generator=g) * 1e-3).to(torch.bfloat16)
+    R = (torch.randn(tab.D, generator=g) * 1e-3).to(torch.bfloat16)
+    for t in range(I):
+        Gn = G.view(torch.int16).numpy().view(np.uint16).copy()
+        Rn = R.view(torch.int16).numpy().view(np.uint16).copy()
+        send = np.zeros(tab.D, np.uint16)
+        n = oracle.compress(tab, I, t, Gn, Rn, send, 0.5)
+        A = torch.addcmul(G.double(), torch.tensor(0.5, dtype=torch.float64), R.double()).float().to(torch.bfloat16)
+        An = A.view(torch.int16).numpy().view(np.uint16)
+        dense, p = scatter_packed(tab, I, t, send, tab.D)
+        assert p == n
+        m = keep_mask(tab, I, t, tab.D)
+        assert np.array_equal(dense[m], An[m]) and np.array_equal(Rn[~m], An[~m]) and not Rn[m].any()
+        # average of N rows: fp32 left fold, one rounding to bf16 at the end
+        N = 5
+        recv_t = (torch.randn(N, n + 8, generator=g) * 1e-3).to(torch.bfloat16)
+        recv = recv_t.view(torch.int16).numpy().view(np.uint16).copy()
+        out = np.full(tab.D, 0xffff, np.uint16)
+        oracle.decompress(tab, I, t, recv, out)
+        acc = recv_t[0].float()
+        for w in range(1, N):
+            acc = acc + recv_t[w].float()
+        avg = (acc / N).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)[:n]
+        want, _ = scatter_packed(tab, I, t, avg, tab.D)
+        assert np.array_equal(out, want)
