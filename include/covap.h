@@ -1,0 +1,208 @@
+/*
+ * covap.h -- C ABI of libcovap: the per-iteration gradient-compression hot
+ * path of COVAP (arXiv 2311.04499) as hand-written HIP kernels for gfx950
+ * (MI355X), plus the host-side planner and ratio policy around it.
+ *
+ * One worker's iteration, as the paper states it:
+ *   1. error feedback      A = G + c * residual            Algorithm 1, line 2;
+ *                                                          c from the scheduler
+ *                                                          of Sec. III-D
+ *   2. coarse filter       shard s is sent at iteration t iff (s + t) mod I == 0
+ *                                                          Sec. III-A, Definition 1
+ *   3. pack                selected shards, ascending, contiguous in `send`
+ *   4. residual            selected: 0, otherwise A        Algorithm 1, line 4
+ *   5. exchange + mean     out = (sum over N workers' payloads) / N, unpacked to
+ *                          the dense layout, 0 where nothing was sent
+ *                                                          Sec. II-A, Sec. III-B
+ * Steps 1-4 are covap_compress (one kernel), step 5 is covap_decompress (one
+ * kernel).  The exchange itself (AllReduce) is not part of this library: the
+ * caller hands covap_decompress the N payload rows.
+ *
+ * Conventions
+ *  - Pointers marked [device] are HIP device pointers owned by the caller; the
+ *    library never allocates or frees device memory in a hot-path call and
+ *    never keeps a pointer after the call returns.  [host] pointers are
+ *    ordinary host memory.
+ *  - Device buffers must be 16-byte aligned.  Elements are fp32, or bf16 stored
+ *    as 16-bit patterns (computed in fp32, rounded to nearest-even once).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Hot-path calls are asynchronous: COVAP_OK means "enqueued".
+ *  - Indexing is 0-based for tensors, shards, buckets and iterations.
+ *  - Every function returns a status (or a plain value for pure queries) and
+ *    never aborts; covap_last_error() gives the text of this thread's last
+ *    failure.
+ *  - A plan is immutable after creation and may be shared by threads.  The
+ *    interval I is fixed for the life of a plan (the paper fixes it once, early
+ *    in training); a new I needs a new plan.
+ */
+#ifndef COVAP_H
+#define COVAP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct covap_plan_s covap_plan_t; /* opaque, owned by the library */
+
+typedef enum {
+    COVAP_OK = 0,
+    COVAP_EINVAL = 1,       /* bad argument (null, misaligned, out of range) */
+    COVAP_ENOMEM = 2,       /* host or device allocation failed (plan creation only) */
+    COVAP_EHIP = 3,         /* a HIP call or kernel launch failed */
+    COVAP_ERANGE = 4,       /* index (tensor, shard, bucket) out of range */
+    COVAP_EUNSUPPORTED = 5  /* valid request this build does not implement */
+} covap_status_t;
+
+typedef enum { COVAP_F32 = 0, COVAP_BF16 = 1 } covap_dtype_t;
+
+typedef enum {
+    /* The arena is cut into shards of `shard_elems` elements regardless of
+     * tensor boundaries; the last shard is short.  Buckets are greedy runs of
+     * shards under `bucket_cap_bytes`. */
+    COVAP_SHARD_FIXED = 0,
+    /* Sec. III-C: whole tensors are grouped into buckets of about
+     * `bucket_cap_bytes`; a bucket holding at least twice the reference element
+     * count (the median of the bucket sizes, or `ref_elems` when > 0) is cut
+     * evenly into floor(numel/ref) pieces, at most I.  Shards have different
+     * lengths. */
+    COVAP_SHARD_MEDIAN = 1
+} covap_shard_mode_t;
+
+typedef struct {
+    int32_t dtype;            /* covap_dtype_t */
+    int32_t mode;             /* covap_shard_mode_t */
+    int64_t shard_elems;      /* FIXED mode: 1..2^30, multiple of 4 (fp32) or 8 (bf16) */
+    int64_t bucket_cap_bytes; /* > 0; the paper's default is 25 MiB (Sec. III-A) */
+    int64_t ref_elems;        /* MEDIAN mode: reference count, 0 = use the median */
+    int32_t K;                /* the interval I >= 1 (1 = no compression) */
+    int32_t reserved;         /* must be 0 */
+} covap_plan_opts_t;
+
+/* ---- planning (host) --------------------------------------------------- */
+
+/* Lay `n_tensors` tensors (element counts in tensor_numel [host]) end to end
+ * in one flat arena, cut it into shards and buckets, and fix the interval.
+ * On success *out receives a plan to be released with covap_plan_free.
+ * EINVAL: null argument, n_tensors < 1, a negative count, K < 1, bad shard
+ * size or cap, total elements >= 2^40. */
+covap_status_t covap_plan(const int64_t *tensor_numel, int32_t n_tensors,
+                          const covap_plan_opts_t *opts, covap_plan_t **out);
+void covap_plan_free(covap_plan_t *plan);
+
+/* Pure queries; a null plan gives -1. */
+int64_t covap_plan_total_elems(const covap_plan_t *plan);
+int32_t covap_plan_num_tensors(const covap_plan_t *plan);
+int32_t covap_plan_num_shards(const covap_plan_t *plan);
+int32_t covap_plan_num_buckets(const covap_plan_t *plan);
+int32_t covap_plan_interval(const covap_plan_t *plan);
+/* Arena offset (elements) of tensor i, or -1 when i is out of range. */
+int64_t covap_plan_tensor_offset(const covap_plan_t *plan, int32_t i);
+/* Arena offset, length and bucket of shard s; any out pointer may be null. */
+covap_status_t covap_plan_shard(const covap_plan_t *plan, int32_t s, int64_t *off,
+                                int64_t *len, int32_t *bucket);
+/* Shard range [*sh_lo, *sh_hi) of bucket b. */
+covap_status_t covap_plan_bucket(const covap_plan_t *plan, int32_t b, int32_t *sh_lo,
+                                 int32_t *sh_hi);
+/* 1 if shard s is sent at iteration `step`, 0 if not, -1 on a bad argument. */
+int32_t covap_plan_is_selected(const covap_plan_t *plan, uint64_t step, int32_t s);
+/* Ids of the shards sent at `step`, ascending, into shard_ids[cap] [host]
+ * (may be null to only count).  Returns how many there are. */
+int32_t covap_plan_selected(const covap_plan_t *plan, uint64_t step, int32_t *shard_ids,
+                            int32_t cap);
+/* Elements sent at `step` by bucket b (b = -1: by all buckets). */
+int64_t covap_plan_packed_elems(const covap_plan_t *plan, uint64_t step, int32_t bucket);
+/* Offset in the step's packed layout at which bucket b's payload starts. */
+int64_t covap_plan_packed_base(const covap_plan_t *plan, uint64_t step, int32_t bucket);
+/* Largest covap_plan_packed_elems(step, -1) over all steps: the size to give
+ * send buffers and the row stride of receive buffers. */
+int64_t covap_plan_packed_elems_max(const covap_plan_t *plan);
+
+/* ---- ratio policy and error-feedback scheduler (host) ------------------- */
+
+/* I = ceil(CCR), never below 1 (Sec. III-B).  EINVAL unless 0 < ccr < 2^31. */
+covap_status_t covap_ratio_from_ccr(double ccr, int32_t *K);
+/* CCR = t_comm / t_comp (Sec. II-A), then as above.  Both times > 0, finite. */
+covap_status_t covap_ratio_from_times(double t_comm, double t_comp, int32_t *K);
+/* Compensation coefficient of the error-feedback scheduler (Sec. III-D):
+ *   min(init_value + floor(num_steps / ascend_steps) * ascend_range, 1),
+ * evaluated in double from the fp32 parameters and rounded to fp32.
+ * EINVAL: ascend_steps == 0, non-finite parameter, null out. */
+covap_status_t covap_ef_coeff(float init_value, uint64_t num_steps, uint64_t ascend_steps,
+                              float ascend_range, float *coeff);
+
+/* ---- hot path (device) ------------------------------------------------- */
+
+/* Steps 1-4 for bucket `bucket` (-1 = the whole arena in one launch) at
+ * iteration `step`.
+ *   grad      [device] const, whole arena (total_elems elements), read only
+ *   residual  [device] whole arena, read and overwritten with the new residual
+ *   send      [device] the step's packed layout, indexed from its start: a
+ *             per-bucket call writes only [packed_base, packed_base + packed_elems)
+ *   send_cap_elems     capacity of `send` in elements; EINVAL if the range
+ *                      this call writes does not fit
+ *   ef_coeff  the scheduler's coefficient c; A = fma(c, residual, grad)
+ * `grad`, `residual` and `send` must not overlap.  Selected residual elements
+ * become +0.0 whatever A was. */
+covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                              const void *grad, void *residual, void *send,
+                              int64_t send_cap_elems, float ef_coeff, void *stream);
+
+/* Step 5 for bucket `bucket` (-1 = all) at iteration `step`.
+ *   recv       [device] const, n_workers rows of stride_elems elements each;
+ *              row w is worker w's `send` buffer of this step
+ *   dense_out  [device] whole arena; this call writes every element of the
+ *              bucket's shards: the mean where the shard was sent, +0.0 elsewhere
+ * The sum runs over w = 0, 1, ..., n_workers-1 in that order in fp32 and is
+ * divided by n_workers (IEEE division).  EINVAL: n_workers < 1, stride smaller
+ * than the packed range read, stride not a multiple of 4 (fp32) / 8 (bf16)
+ * elements when n_workers > 1.  dense_out must not overlap recv. */
+covap_status_t covap_decompress(const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                                const void *recv, int32_t n_workers, int64_t stride_elems,
+                                void *dense_out, void *stream);
+
+/* ---- fine-grained top-k sparsifier (contrast point; Sec. I, Table II) --- */
+
+/* Bytes of device workspace topk_compress needs for n elements. */
+size_t topk_workspace_bytes(int64_t n, int32_t dtype);
+
+/* A = fma(c, residual, grad) over n fp32 elements; keep the k entries of
+ * largest magnitude.  Magnitudes are ordered by the bit pattern of |A| read as
+ * an unsigned integer; among equal magnitudes the lowest index is kept.
+ *   out_vals [device] k values, out_idx [device] k indices, ascending index
+ *   residual [device] becomes A with the kept entries set to +0.0
+ *   workspace [device] at least topk_workspace_bytes(n) bytes, 256-byte aligned
+ * EINVAL: k < 0, k > n, n >= 2^32, null/misaligned pointer, small workspace.
+ * EUNSUPPORTED: dtype other than COVAP_F32. */
+covap_status_t topk_compress(const void *grad, void *residual, int64_t n, int64_t k,
+                             int32_t dtype, float ef_coeff, void *out_vals,
+                             uint32_t *out_idx, void *workspace, size_t ws_bytes,
+                             void *stream);
+
+/* ---- measurement helpers ------------------------------------------------ */
+
+/* Plain streaming kernels used to measure the achievable HBM rate next to the
+ * hot path and to calibrate hardware byte counters: dst = src (16-byte
+ * vectors; `bytes` a multiple of 16), and a = b + s*c over n fp32 elements
+ * (n a multiple of 4).  All pointers [device], 16-byte aligned. */
+covap_status_t covap_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
+covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float s, int64_t n,
+                                 void *stream);
+
+/* Launch-shape knobs for tuning sweeps: key is one of "compress_unroll",
+ * "decompress_unroll", "nontemporal".  EINVAL for an unknown key or a value
+ * outside the documented set.  Not thread-safe against running calls. */
+covap_status_t covap_tune_set(const char *key, int32_t value);
+int32_t covap_tune_get(const char *key);
+
+/* Text of the calling thread's most recent error ("" if none). */
+const char *covap_last_error(void);
+/* Library version, "major.minor.patch". */
+const char *covap_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COVAP_H */

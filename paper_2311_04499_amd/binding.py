@@ -1,0 +1,286 @@
+"""Thin ctypes binding over libcovap.so (the C ABI declared in include/covap.h).
+
+Argument marshalling only: every step of the hot path runs in the library's
+HIP kernels.  torch is used for device memory and streams; tensors are passed
+as raw device pointers.  There is no fallback: if the library is not built (or
+cannot be loaded) the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+_CSRC = os.path.join(_HERE, "csrc")
+_INCLUDE = os.path.join(_ROOT, "include")
+LIB_PATH = os.path.join(_HERE, "libcovap.so")
+
+SOURCES = ["plan.cpp", "kernels.hip", "topk.hip"]
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "-ffp-contract=off",                       # the only FMA is the one written as fmaf
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wextra", "-Wno-unused-parameter", "-Wno-unknown-attributes",
+]
+
+COVAP_F32, COVAP_BF16 = 0, 1
+COVAP_SHARD_FIXED, COVAP_SHARD_MEDIAN = 0, 1
+STATUS_NAMES = {0: "COVAP_OK", 1: "COVAP_EINVAL", 2: "COVAP_ENOMEM", 3: "COVAP_EHIP",
+                4: "COVAP_ERANGE", 5: "COVAP_EUNSUPPORTED"}
+
+
+class CovapError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {msg}")
+        self.status = status
+
+
+def build(verbose: bool = False) -> str:
+    """Compile libcovap.so for gfx950 with hipcc (cross-compiles without a GPU)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    srcs = [os.path.join(_CSRC, s) for s in SOURCES if os.path.exists(os.path.join(_CSRC, s))]
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", _INCLUDE, "-I", _CSRC, "-o", LIB_PATH, *srcs]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return LIB_PATH
+
+
+class _PlanOpts(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("mode", C.c_int32), ("shard_elems", C.c_int64),
+                ("bucket_cap_bytes", C.c_int64), ("ref_elems", C.c_int64), ("K", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+_lib = None
+_vp = C.c_void_p
+_i64p = C.POINTER(C.c_int64)
+_i32p = C.POINTER(C.c_int32)
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; "
+                           "g.build()'` first (there is no CPU fallback)")
+    L = C.CDLL(LIB_PATH)
+    L.covap_plan.restype = C.c_int
+    L.covap_plan.argtypes = [_i64p, C.c_int32, C.POINTER(_PlanOpts), C.POINTER(_vp)]
+    L.covap_plan_free.restype = None
+    L.covap_plan_free.argtypes = [_vp]
+    for name in ("covap_plan_total_elems", "covap_plan_packed_elems_max"):
+        getattr(L, name).restype = C.c_int64
+        getattr(L, name).argtypes = [_vp]
+    for name in ("covap_plan_num_tensors", "covap_plan_num_shards", "covap_plan_num_buckets",
+                 "covap_plan_interval"):
+        getattr(L, name).restype = C.c_int32
+        getattr(L, name).argtypes = [_vp]
+    L.covap_plan_tensor_offset.restype = C.c_int64
+    L.covap_plan_tensor_offset.argtypes = [_vp, C.c_int32]
+    L.covap_plan_shard.restype = C.c_int
+    L.covap_plan_shard.argtypes = [_vp, C.c_int32, _i64p, _i64p, _i32p]
+    L.covap_plan_bucket.restype = C.c_int
+    L.covap_plan_bucket.argtypes = [_vp, C.c_int32, _i32p, _i32p]
+    L.covap_plan_is_selected.restype = C.c_int32
+    L.covap_plan_is_selected.argtypes = [_vp, C.c_uint64, C.c_int32]
+    L.covap_plan_selected.restype = C.c_int32
+    L.covap_plan_selected.argtypes = [_vp, C.c_uint64, _i32p, C.c_int32]
+    L.covap_plan_packed_elems.restype = C.c_int64
+    L.covap_plan_packed_elems.argtypes = [_vp, C.c_uint64, C.c_int32]
+    L.covap_plan_packed_base.restype = C.c_int64
+    L.covap_plan_packed_base.argtypes = [_vp, C.c_uint64, C.c_int32]
+    L.covap_ratio_from_ccr.restype = C.c_int
+    L.covap_ratio_from_ccr.argtypes = [C.c_double, _i32p]
+    L.covap_ratio_from_times.restype = C.c_int
+    L.covap_ratio_from_times.argtypes = [C.c_double, C.c_double, _i32p]
+    L.covap_ef_coeff.restype = C.c_int
+    L.covap_ef_coeff.argtypes = [C.c_float, C.c_uint64, C.c_uint64, C.c_float, C.POINTER(C.c_float)]
+    L.covap_compress.restype = C.c_int
+    L.covap_compress.argtypes = [_vp, C.c_uint64, C.c_int32, _vp, _vp, _vp, C.c_int64, C.c_float, _vp]
+    L.covap_decompress.restype = C.c_int
+    L.covap_decompress.argtypes = [_vp, C.c_uint64, C.c_int32, _vp, C.c_int32, C.c_int64, _vp, _vp]
+    L.topk_workspace_bytes.restype = C.c_size_t
+    L.topk_workspace_bytes.argtypes = [C.c_int64, C.c_int32]
+    L.topk_compress.restype = C.c_int
+    L.topk_compress.argtypes = [_vp, _vp, C.c_int64, C.c_int64, C.c_int32, C.c_float, _vp, _vp, _vp,
+                                C.c_size_t, _vp]
+    L.covap_probe_copy.restype = C.c_int
+    L.covap_probe_copy.argtypes = [_vp, _vp, C.c_size_t, _vp]
+    L.covap_probe_triad.restype = C.c_int
+    L.covap_probe_triad.argtypes = [_vp, _vp, _vp, C.c_float, C.c_int64, _vp]
+    L.covap_tune_set.restype = C.c_int
+    L.covap_tune_set.argtypes = [C.c_char_p, C.c_int32]
+    L.covap_tune_get.restype = C.c_int32
+    L.covap_tune_get.argtypes = [C.c_char_p]
+    L.covap_last_error.restype = C.c_char_p
+    L.covap_last_error.argtypes = []
+    L.covap_version.restype = C.c_char_p
+    L.covap_version.argtypes = []
+    _lib = L
+    return L
+
+
+def _check(status: int):
+    if status != 0:
+        raise CovapError(status, lib().covap_last_error().decode())
+
+
+def _ptr(t) -> int:
+    """Device (or host) address of a torch tensor / numpy array / int."""
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return t
+    if hasattr(t, "data_ptr"):
+        if not t.is_contiguous():
+            raise ValueError("tensor must be contiguous")
+        return t.data_ptr()
+    return t.ctypes.data
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+class Plan:
+    """Owner of a covap_plan_t handle."""
+
+    def __init__(self, handle: int, dtype: int):
+        self._h = handle
+        self.dtype = dtype
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            lib().covap_plan_free(self._h)
+            self._h = None
+
+    @property
+    def handle(self) -> int:
+        return self._h
+
+    total_elems = property(lambda self: lib().covap_plan_total_elems(self._h))
+    num_tensors = property(lambda self: lib().covap_plan_num_tensors(self._h))
+    num_shards = property(lambda self: lib().covap_plan_num_shards(self._h))
+    num_buckets = property(lambda self: lib().covap_plan_num_buckets(self._h))
+    interval = property(lambda self: lib().covap_plan_interval(self._h))
+    packed_elems_max = property(lambda self: lib().covap_plan_packed_elems_max(self._h))
+
+    def tensor_offset(self, i: int) -> int:
+        return lib().covap_plan_tensor_offset(self._h, i)
+
+    def shard(self, s: int):
+        off, ln, b = C.c_int64(), C.c_int64(), C.c_int32()
+        _check(lib().covap_plan_shard(self._h, s, C.byref(off), C.byref(ln), C.byref(b)))
+        return off.value, ln.value, b.value
+
+    def bucket(self, b: int):
+        lo, hi = C.c_int32(), C.c_int32()
+        _check(lib().covap_plan_bucket(self._h, b, C.byref(lo), C.byref(hi)))
+        return lo.value, hi.value
+
+    def is_selected(self, step: int, s: int) -> int:
+        return lib().covap_plan_is_selected(self._h, step, s)
+
+    def selected(self, step: int):
+        n = lib().covap_plan_selected(self._h, step, None, 0)
+        ids = (C.c_int32 * max(n, 1))()
+        lib().covap_plan_selected(self._h, step, ids, n)
+        return list(ids[:n])
+
+    def packed_elems(self, step: int, bucket: int = -1) -> int:
+        return lib().covap_plan_packed_elems(self._h, step, bucket)
+
+    def packed_base(self, step: int, bucket: int = -1) -> int:
+        return lib().covap_plan_packed_base(self._h, step, bucket)
+
+
+def covap_plan(tensor_numel: Sequence[int], shard_elems: int, K: int, dtype: int = COVAP_F32,
+               bucket_cap_bytes: int = 25 << 20, mode: int = COVAP_SHARD_FIXED,
+               ref_elems: int = 0) -> Plan:
+    arr = (C.c_int64 * max(len(tensor_numel), 1))(*[int(x) for x in tensor_numel])
+    opts = _PlanOpts(dtype, mode, shard_elems, bucket_cap_bytes, ref_elems, K, 0)
+    h = _vp()
+    _check(lib().covap_plan(arr, len(tensor_numel), C.byref(opts), C.byref(h)))
+    return Plan(h.value, dtype)
+
+
+def covap_compress(plan: Plan, step: int, grad, residual, send, ef_coeff: float = 1.0,
+                   bucket: int = -1, stream=None, send_cap_elems: Optional[int] = None) -> None:
+    cap = send.numel() if send_cap_elems is None else send_cap_elems
+    _check(lib().covap_compress(plan.handle, step, bucket, _ptr(grad), _ptr(residual), _ptr(send),
+                                cap, ef_coeff, _stream(stream)))
+
+
+def covap_decompress(plan: Plan, step: int, recv, dense_out, n_workers: Optional[int] = None,
+                     stride_elems: Optional[int] = None, bucket: int = -1, stream=None) -> None:
+    if n_workers is None:
+        n_workers = recv.shape[0]
+    if stride_elems is None:
+        stride_elems = recv.stride(0) if recv.dim() == 2 else recv.numel()
+    _check(lib().covap_decompress(plan.handle, step, bucket, _ptr(recv), n_workers, stride_elems,
+                                  _ptr(dense_out), _stream(stream)))
+
+
+def topk_workspace_bytes(n: int, dtype: int = COVAP_F32) -> int:
+    return lib().topk_workspace_bytes(n, dtype)
+
+
+def topk_compress(grad, residual, k: int, out_vals, out_idx, workspace, ef_coeff: float = 1.0,
+                  n: Optional[int] = None, dtype: int = COVAP_F32, stream=None,
+                  ws_bytes: Optional[int] = None) -> None:
+    if n is None:
+        n = grad.numel()
+    if ws_bytes is None:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    _check(lib().topk_compress(_ptr(grad), _ptr(residual), n, k, dtype, ef_coeff, _ptr(out_vals),
+                               _ptr(out_idx), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def covap_ratio_from_ccr(ccr: float) -> int:
+    k = C.c_int32()
+    _check(lib().covap_ratio_from_ccr(ccr, C.byref(k)))
+    return k.value
+
+
+def covap_ratio_from_times(t_comm: float, t_comp: float) -> int:
+    k = C.c_int32()
+    _check(lib().covap_ratio_from_times(t_comm, t_comp, C.byref(k)))
+    return k.value
+
+
+def covap_ef_coeff(init_value: float, num_steps: int, ascend_steps: int, ascend_range: float) -> float:
+    c = C.c_float()
+    _check(lib().covap_ef_coeff(init_value, num_steps, ascend_steps, ascend_range, C.byref(c)))
+    return c.value
+
+
+def covap_probe_copy(dst, src, nbytes: int, stream=None) -> None:
+    _check(lib().covap_probe_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
+
+
+def covap_probe_triad(a, b, c, s: float, n: int, stream=None) -> None:
+    _check(lib().covap_probe_triad(_ptr(a), _ptr(b), _ptr(c), s, n, _stream(stream)))
+
+
+def covap_tune_set(key: str, value: int) -> None:
+    _check(lib().covap_tune_set(key.encode(), value))
+
+
+def covap_tune_get(key: str) -> int:
+    return lib().covap_tune_get(key.encode())
+
+
+def covap_version() -> str:
+    return lib().covap_version().decode()

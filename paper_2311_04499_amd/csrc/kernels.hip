@@ -1,0 +1,569 @@
+// COVAP hot-path kernels for gfx950 (MI355X): covap_compress and
+// covap_decompress, plus two plain streaming probes.
+//
+// Both kernels are pure HBM streaming (at most one FMA per 12 bytes moved), so
+// the design is about memory access only:
+//   * every thread moves 16-byte vectors; a 256-thread workgroup owns one
+//     "tile" of 256 * UNROLL consecutive vectors of ONE shard, so the filter's
+//     decision (sent / kept) is uniform over the workgroup and costs a few
+//     scalar integer operations per tile -- never per element;
+//   * all loads of a tile are issued before the first use, so each wave keeps
+//     UNROLL (compress: 2*UNROLL) 16-byte loads in flight;
+//   * data that is not read again in the same iteration (everything here) is
+//     moved with streaming (non-temporal) hints;
+//   * shard starts and packed offsets are multiples of the vector size, so the
+//     vector path is always aligned; a shard's ragged tail (< one vector) goes
+//     through a scalar path in the same launch.
+// No LDS and no MFMA: there is no data reuse and no contraction.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "plan.h"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+
+template <bool NT>
+__device__ __forceinline__ u32x4 ld16(const u32x4 *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+
+template <bool NT>
+__device__ __forceinline__ void st16(u32x4 *p, u32x4 v)
+{
+    if constexpr (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+// ---- element types ---------------------------------------------------------
+
+// fp32 elements: four per 16-byte vector.
+struct ops_f32 {
+    static constexpr int EPV = 4;
+    typedef float elem_t;
+    typedef f32x4 acc_t;
+
+    // A = fma(c, r, g): one rounding (Algorithm 1 line 2 with the scheduler's c)
+    static __device__ __forceinline__ u32x4 ef(u32x4 g, u32x4 r, float c)
+    {
+        f32x4 gf = __builtin_bit_cast(f32x4, g), rf = __builtin_bit_cast(f32x4, r), a;
+        a.x = __builtin_fmaf(c, rf.x, gf.x);
+        a.y = __builtin_fmaf(c, rf.y, gf.y);
+        a.z = __builtin_fmaf(c, rf.z, gf.z);
+        a.w = __builtin_fmaf(c, rf.w, gf.w);
+        return __builtin_bit_cast(u32x4, a);
+    }
+    static __device__ __forceinline__ float ef1(float g, float r, float c)
+    {
+        return __builtin_fmaf(c, r, g);
+    }
+    static __device__ __forceinline__ acc_t widen(u32x4 v) { return __builtin_bit_cast(f32x4, v); }
+    static __device__ __forceinline__ void add(acc_t &acc, u32x4 v)
+    {
+        acc += __builtin_bit_cast(f32x4, v);
+    }
+    static __device__ __forceinline__ float mean1(float acc, float n, float inv, bool pow2)
+    {
+        // dividing by 2^m and multiplying by 2^-m round identically
+        return pow2 ? acc * inv : __fdiv_rn(acc, n);
+    }
+    static __device__ __forceinline__ u32x4 mean(acc_t acc, float n, float inv, bool pow2)
+    {
+        f32x4 o;
+        o.x = mean1(acc.x, n, inv, pow2);
+        o.y = mean1(acc.y, n, inv, pow2);
+        o.z = mean1(acc.z, n, inv, pow2);
+        o.w = mean1(acc.w, n, inv, pow2);
+        return __builtin_bit_cast(u32x4, o);
+    }
+    static __device__ __forceinline__ float widen1(float x) { return x; }
+    static __device__ __forceinline__ float narrow1(float x) { return x; }
+};
+
+// bf16 elements stored as 16-bit patterns: eight per vector, arithmetic in
+// fp32, one round-to-nearest-even back.
+struct ops_bf16 {
+    static constexpr int EPV = 8;
+    typedef uint16_t elem_t;
+    struct acc_t {
+        float v[8];
+    };
+
+    static __device__ __forceinline__ float lo(uint32_t w) { return __uint_as_float(w << 16); }
+    static __device__ __forceinline__ float hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+    static __device__ __forceinline__ uint32_t rne(float f)
+    {
+        uint32_t u = __float_as_uint(f);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
+        return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    }
+    static __device__ __forceinline__ uint32_t pack(float a, float b) { return rne(a) | (rne(b) << 16); }
+
+    static __device__ __forceinline__ u32x4 ef(u32x4 g, u32x4 r, float c)
+    {
+        u32x4 a;
+        a.x = pack(__builtin_fmaf(c, lo(r.x), lo(g.x)), __builtin_fmaf(c, hi(r.x), hi(g.x)));
+        a.y = pack(__builtin_fmaf(c, lo(r.y), lo(g.y)), __builtin_fmaf(c, hi(r.y), hi(g.y)));
+        a.z = pack(__builtin_fmaf(c, lo(r.z), lo(g.z)), __builtin_fmaf(c, hi(r.z), hi(g.z)));
+        a.w = pack(__builtin_fmaf(c, lo(r.w), lo(g.w)), __builtin_fmaf(c, hi(r.w), hi(g.w)));
+        return a;
+    }
+    static __device__ __forceinline__ uint16_t ef1(uint16_t g, uint16_t r, float c)
+    {
+        return (uint16_t)rne(__builtin_fmaf(c, lo(r), lo(g)));
+    }
+    static __device__ __forceinline__ acc_t widen(u32x4 v)
+    {
+        acc_t a;
+        a.v[0] = lo(v.x); a.v[1] = hi(v.x); a.v[2] = lo(v.y); a.v[3] = hi(v.y);
+        a.v[4] = lo(v.z); a.v[5] = hi(v.z); a.v[6] = lo(v.w); a.v[7] = hi(v.w);
+        return a;
+    }
+    static __device__ __forceinline__ void add(acc_t &a, u32x4 v)
+    {
+        a.v[0] += lo(v.x); a.v[1] += hi(v.x); a.v[2] += lo(v.y); a.v[3] += hi(v.y);
+        a.v[4] += lo(v.z); a.v[5] += hi(v.z); a.v[6] += lo(v.w); a.v[7] += hi(v.w);
+    }
+    static __device__ __forceinline__ float mean1(float acc, float n, float inv, bool pow2)
+    {
+        return pow2 ? acc * inv : __fdiv_rn(acc, n);
+    }
+    static __device__ __forceinline__ u32x4 mean(acc_t a, float n, float inv, bool pow2)
+    {
+        u32x4 o;
+        o.x = pack(mean1(a.v[0], n, inv, pow2), mean1(a.v[1], n, inv, pow2));
+        o.y = pack(mean1(a.v[2], n, inv, pow2), mean1(a.v[3], n, inv, pow2));
+        o.z = pack(mean1(a.v[4], n, inv, pow2), mean1(a.v[5], n, inv, pow2));
+        o.w = pack(mean1(a.v[6], n, inv, pow2), mean1(a.v[7], n, inv, pow2));
+        return o;
+    }
+    static __device__ __forceinline__ float widen1(uint16_t x) { return lo(x); }
+    static __device__ __forceinline__ uint16_t narrow1(float x) { return (uint16_t)rne(x); }
+};
+
+// ---- tile geometry -----------------------------------------------------------
+
+// Fixed-size shards: shard s covers [s*S, min((s+1)*S, D)); every shard is cut
+// into tiles_per_shard = ceil(S / TILE) tiles.  Shard s is sent at this step
+// iff s mod K == first_sel (Definition 1 rewritten for a fixed step).  The
+// shards of one residue class all have S elements except possibly the last of
+// the arena, so the packed offset of shard s is (s / K) * S.
+//
+// All per-tile decisions are taken in 32-bit scalar arithmetic (S < 2^31); only
+// the two final offsets are 64-bit products.  64-bit compare-and-select chains
+// are avoided here on purpose: hipcc 7.2 turned `left < TILE ? left : TILE` on
+// int64 into an s_cselect that read a stale SCC, so every ragged tile ran as a
+// full one.
+struct fixed_geom {
+    int64_t S;
+    uint32_t shard_len;  // S
+    uint32_t last_len;   // elements of the last shard of the arena, 1..S
+    uint32_t n_shards;
+    int32_t K;
+    int32_t first_sel;
+    uint32_t tiles_per_shard;
+    uint32_t tile_lo;  // first tile of this launch (per-bucket calls start mid-arena)
+};
+
+struct tile_ref {
+    int64_t off;   // arena element offset
+    int64_t poff;  // packed element offset
+    int32_t n;     // elements in the tile, 1..TILE
+    bool sel;
+};
+
+template <int TILE>
+__device__ __forceinline__ bool resolve_tile(const fixed_geom &g, tile_ref &t)
+{
+    const uint32_t tile = g.tile_lo + blockIdx.x;
+    const uint32_t s = tile / g.tiles_per_shard;
+    const uint32_t j = tile - s * g.tiles_per_shard;
+    const uint32_t sh_len = (s + 1u == g.n_shards) ? g.last_len : g.shard_len;
+    const uint32_t in = j * (uint32_t)TILE;
+    if (in >= sh_len) return false;
+    const uint32_t left = sh_len - in;
+    t.n = (int32_t)(left < (uint32_t)TILE ? left : (uint32_t)TILE);
+    t.off = (int64_t)s * g.S + (int64_t)in;
+    t.sel = (int32_t)(s % (uint32_t)g.K) == g.first_sel;
+    t.poff = (int64_t)(s / (uint32_t)g.K) * g.S + (int64_t)in;
+    return true;
+}
+
+// ---- compress: error feedback + filter + pack + residual -----------------------
+
+template <typename OPS, int UNROLL, bool NT>
+__global__ __launch_bounds__(kThreads) void k_compress(const u32x4 *__restrict__ G, u32x4 *R,
+                                                       u32x4 *__restrict__ send, fixed_geom g,
+                                                       float c)
+{
+    constexpr int EPV = OPS::EPV;
+    constexpr int TILE = kThreads * EPV * UNROLL;
+    tile_ref t;
+    if (!resolve_tile<TILE>(g, t)) return;
+    const int tid = threadIdx.x;
+    const u32x4 *gp = G + t.off / EPV;
+    u32x4 *rp = R + t.off / EPV;
+    u32x4 *sp = send + t.poff / EPV;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+
+    if (t.n == TILE) {
+        u32x4 gv[UNROLL], rv[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) gv[u] = ld16<NT>(gp + u * kThreads + tid);
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) rv[u] = ld16<NT>(rp + u * kThreads + tid);
+        if (t.sel) {
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                st16<NT>(sp + u * kThreads + tid, OPS::ef(gv[u], rv[u], c));
+                st16<NT>(rp + u * kThreads + tid, zero);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+                st16<NT>(rp + u * kThreads + tid, OPS::ef(gv[u], rv[u], c));
+        }
+        return;
+    }
+
+    // ragged tile: whole vectors under a bound, then fewer than EPV scalars
+    const int nv = t.n / EPV;
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int v = u * kThreads + tid;
+        if (v < nv) {
+            const u32x4 a = OPS::ef(ld16<NT>(gp + v), ld16<NT>(rp + v), c);
+            if (t.sel) {
+                st16<NT>(sp + v, a);
+                st16<NT>(rp + v, zero);
+            } else {
+                st16<NT>(rp + v, a);
+            }
+        }
+    }
+    const int rem = t.n - nv * EPV;
+    if (tid < rem) {
+        typedef typename OPS::elem_t E;
+        const int64_t e = (int64_t)nv * EPV + tid;
+        const E a = OPS::ef1(((const E *)gp)[e], ((const E *)rp)[e], c);
+        if (t.sel) {
+            ((E *)sp)[e] = a;
+            ((E *)rp)[e] = (E)0;
+        } else {
+            ((E *)rp)[e] = a;
+        }
+    }
+}
+
+// ---- decompress: N-way mean + unpack + zero fill --------------------------------
+
+// Sum of one packed vector position over the N payload rows, in row order.
+// WU rows are loaded before the first of them is added, so WU 16-byte loads are
+// in flight per thread; the additions keep the order w = 0, 1, ..., N-1.
+template <typename OPS, int WU, bool NT>
+__device__ __forceinline__ typename OPS::acc_t sum_rows(const u32x4 *p, int32_t N,
+                                                        int64_t stride_vec)
+{
+    typename OPS::acc_t acc = OPS::widen(ld16<NT>(p));
+    int32_t w = 1;
+    for (; w + WU <= N; w += WU) {
+        u32x4 x[WU];
+#pragma unroll
+        for (int j = 0; j < WU; ++j) x[j] = ld16<NT>(p + (int64_t)(w + j) * stride_vec);
+#pragma unroll
+        for (int j = 0; j < WU; ++j) OPS::add(acc, x[j]);
+    }
+    for (; w < N; ++w) OPS::add(acc, ld16<NT>(p + (int64_t)w * stride_vec));
+    return acc;
+}
+
+template <typename OPS, int WU, bool NT, int UNROLL>
+__global__ __launch_bounds__(kThreads) void k_decompress(const u32x4 *__restrict__ recv,
+                                                         u32x4 *__restrict__ out, fixed_geom g,
+                                                         int32_t N, int64_t stride_elems,
+                                                         float n_f, float inv_n, int pow2)
+{
+    constexpr int EPV = OPS::EPV;
+    constexpr int TILE = kThreads * EPV * UNROLL;
+    typedef typename OPS::elem_t E;
+    tile_ref t;
+    if (!resolve_tile<TILE>(g, t)) return;
+    const int tid = threadIdx.x;
+    u32x4 *op = out + t.off / EPV;
+    const int nv = t.n / EPV;
+    const int rem = t.n - nv * EPV;
+
+    if (!t.sel) {  // nothing was sent for this shard: the dense result is +0
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int v = u * kThreads + tid;
+            if (v < nv) st16<NT>(op + v, zero);
+        }
+        if (tid < rem) ((E *)op)[(int64_t)nv * EPV + tid] = (E)0;
+        return;
+    }
+
+    const u32x4 *rp = recv + t.poff / EPV;
+    const int64_t stride_vec = stride_elems / EPV;
+#pragma unroll 1
+    for (int u = 0; u < UNROLL; ++u) {
+        const int v = u * kThreads + tid;
+        if (v < nv) {
+            typename OPS::acc_t acc = sum_rows<OPS, WU, NT>(rp + v, N, stride_vec);
+            st16<NT>(op + v, OPS::mean(acc, n_f, inv_n, pow2 != 0));
+        }
+    }
+    if (tid < rem) {
+        const int64_t e = (int64_t)nv * EPV + tid;
+        const E *row = (const E *)rp + e;
+        float acc = OPS::widen1(row[0]);
+        for (int32_t w = 1; w < N; ++w) acc += OPS::widen1(row[(int64_t)w * stride_elems]);
+        ((E *)op)[e] = OPS::narrow1(OPS::mean1(acc, n_f, inv_n, pow2 != 0));
+    }
+}
+
+// ---- probes ------------------------------------------------------------------------
+
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void k_copy(u32x4 *__restrict__ dst,
+                                                   const u32x4 *__restrict__ src, int64_t nvec)
+{
+    constexpr int U = 4;
+    const int64_t base = (int64_t)blockIdx.x * (kThreads * U) + threadIdx.x;
+    if (base + (U - 1) * kThreads < nvec) {
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = ld16<NT>(src + base + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < U; ++u) st16<NT>(dst + base + u * kThreads, v[u]);
+    } else {
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * kThreads;
+            if (i < nvec) st16<NT>(dst + i, ld16<NT>(src + i));
+        }
+    }
+}
+
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void k_triad(u32x4 *__restrict__ a,
+                                                    const u32x4 *__restrict__ b,
+                                                    const u32x4 *__restrict__ c, float s,
+                                                    int64_t nvec)
+{
+    constexpr int U = 4;
+    const int64_t base = (int64_t)blockIdx.x * (kThreads * U) + threadIdx.x;
+    for (int u = 0; u < U; ++u) {
+        const int64_t i = base + u * kThreads;
+        if (i < nvec) st16<NT>(a + i, ops_f32::ef(ld16<NT>(b + i), ld16<NT>(c + i), s));
+    }
+}
+
+// ---- host-side launch helpers ----------------------------------------------------------
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+bool overlap(const void *a, int64_t abytes, const void *b, int64_t bbytes)
+{
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + (uintptr_t)bbytes && b0 < a0 + (uintptr_t)abytes;
+}
+
+fixed_geom make_geom(const covap_plan_s *p, const covap::call_range &cr, int tile_elems,
+                     uint32_t *grid)
+{
+    fixed_geom g;
+    g.S = p->opts.shard_elems;
+    g.shard_len = (uint32_t)g.S;
+    g.n_shards = (uint32_t)p->shards.size();
+    g.last_len = p->shards.empty() ? 0u : (uint32_t)p->shards.back().len;
+    g.K = p->K;
+    g.first_sel = cr.first_sel;
+    g.tiles_per_shard = (uint32_t)((g.S + tile_elems - 1) / tile_elems);
+    g.tile_lo = (uint32_t)cr.sh_lo * g.tiles_per_shard;
+    *grid = (uint32_t)(cr.sh_hi - cr.sh_lo) * g.tiles_per_shard;
+    return g;
+}
+
+covap_status_t check_launch(const char *what)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return covap::fail(COVAP_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+    return COVAP_OK;
+}
+
+template <typename OPS, int UNROLL>
+void launch_compress(bool nt, uint32_t grid, hipStream_t st, const void *G, void *R, void *send,
+                     const fixed_geom &g, float c)
+{
+    if (nt)
+        k_compress<OPS, UNROLL, true><<<grid, kThreads, 0, st>>>((const u32x4 *)G, (u32x4 *)R,
+                                                                 (u32x4 *)send, g, c);
+    else
+        k_compress<OPS, UNROLL, false><<<grid, kThreads, 0, st>>>((const u32x4 *)G, (u32x4 *)R,
+                                                                  (u32x4 *)send, g, c);
+}
+
+template <typename OPS>
+void dispatch_compress(int unroll, bool nt, uint32_t grid, hipStream_t st, const void *G, void *R,
+                       void *send, const fixed_geom &g, float c)
+{
+    switch (unroll) {
+    case 1: launch_compress<OPS, 1>(nt, grid, st, G, R, send, g, c); break;
+    case 2: launch_compress<OPS, 2>(nt, grid, st, G, R, send, g, c); break;
+    case 8: launch_compress<OPS, 8>(nt, grid, st, G, R, send, g, c); break;
+    default: launch_compress<OPS, 4>(nt, grid, st, G, R, send, g, c); break;
+    }
+}
+
+constexpr int kDecompressUnroll = 4;  // vectors per thread per tile
+
+template <typename OPS, int WU>
+void launch_decompress(bool nt, uint32_t grid, hipStream_t st, const void *recv, void *out,
+                       const fixed_geom &g, int32_t N, int64_t stride, float n_f, float inv_n,
+                       int pow2)
+{
+    if (nt)
+        k_decompress<OPS, WU, true, kDecompressUnroll><<<grid, kThreads, 0, st>>>(
+            (const u32x4 *)recv, (u32x4 *)out, g, N, stride, n_f, inv_n, pow2);
+    else
+        k_decompress<OPS, WU, false, kDecompressUnroll><<<grid, kThreads, 0, st>>>(
+            (const u32x4 *)recv, (u32x4 *)out, g, N, stride, n_f, inv_n, pow2);
+}
+
+template <typename OPS>
+void dispatch_decompress(int wu, bool nt, uint32_t grid, hipStream_t st, const void *recv,
+                         void *out, const fixed_geom &g, int32_t N, int64_t stride, float n_f,
+                         float inv_n, int pow2)
+{
+    switch (wu) {
+    case 2: launch_decompress<OPS, 2>(nt, grid, st, recv, out, g, N, stride, n_f, inv_n, pow2); break;
+    case 4: launch_decompress<OPS, 4>(nt, grid, st, recv, out, g, N, stride, n_f, inv_n, pow2); break;
+    case 16: launch_decompress<OPS, 16>(nt, grid, st, recv, out, g, N, stride, n_f, inv_n, pow2); break;
+    default: launch_decompress<OPS, 8>(nt, grid, st, recv, out, g, N, stride, n_f, inv_n, pow2); break;
+    }
+}
+
+}  // namespace
+
+using covap::fail;
+
+extern "C" {
+
+covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                              const void *grad, void *residual, void *send,
+                              int64_t send_cap_elems, float ef_coeff, void *stream)
+{
+    covap::clear_error();
+    covap::call_range cr;
+    const covap_status_t rs = covap::resolve(plan, step, bucket, &cr);
+    if (rs != COVAP_OK) return rs;
+    if (!plan->uniform) return fail(COVAP_EUNSUPPORTED, "covap_compress: plan has no fixed-size shards");
+    if (!grad || !residual || !send) return fail(COVAP_EINVAL, "covap_compress: null device pointer");
+    if (!aligned16(grad) || !aligned16(residual) || !aligned16(send))
+        return fail(COVAP_EINVAL, "covap_compress: device pointers must be 16-byte aligned");
+    if (send_cap_elems < cr.packed_base + cr.packed_elems)
+        return fail(COVAP_EINVAL, "covap_compress: send buffer too small for this step");
+    const int64_t esz = plan->opts.dtype == COVAP_F32 ? 4 : 2;
+    const int64_t abytes = plan->total_elems * esz, sbytes = send_cap_elems * esz;
+    if (overlap(grad, abytes, residual, abytes) || overlap(grad, abytes, send, sbytes) ||
+        overlap(residual, abytes, send, sbytes))
+        return fail(COVAP_EINVAL, "covap_compress: grad, residual and send must not overlap");
+    if (cr.sh_hi == cr.sh_lo) return COVAP_OK;
+
+    const covap::tuning &tn = covap::tune();
+    const int unroll = tn.compress_unroll;
+    uint32_t grid = 0;
+    const fixed_geom g = make_geom(plan, cr, kThreads * plan->elems_per_vec * unroll, &grid);
+    hipStream_t st = (hipStream_t)stream;
+    if (plan->opts.dtype == COVAP_F32)
+        dispatch_compress<ops_f32>(unroll, tn.nontemporal != 0, grid, st, grad, residual, send, g, ef_coeff);
+    else
+        dispatch_compress<ops_bf16>(unroll, tn.nontemporal != 0, grid, st, grad, residual, send, g, ef_coeff);
+    return check_launch("covap_compress");
+}
+
+covap_status_t covap_decompress(const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                                const void *recv, int32_t n_workers, int64_t stride_elems,
+                                void *dense_out, void *stream)
+{
+    covap::clear_error();
+    covap::call_range cr;
+    const covap_status_t rs = covap::resolve(plan, step, bucket, &cr);
+    if (rs != COVAP_OK) return rs;
+    if (!plan->uniform) return fail(COVAP_EUNSUPPORTED, "covap_decompress: plan has no fixed-size shards");
+    if (!recv || !dense_out) return fail(COVAP_EINVAL, "covap_decompress: null device pointer");
+    if (!aligned16(recv) || !aligned16(dense_out))
+        return fail(COVAP_EINVAL, "covap_decompress: device pointers must be 16-byte aligned");
+    if (n_workers < 1) return fail(COVAP_EINVAL, "covap_decompress: n_workers < 1");
+    if (stride_elems < cr.packed_base + cr.packed_elems)
+        return fail(COVAP_EINVAL, "covap_decompress: row stride smaller than the packed payload");
+    if (n_workers > 1 && stride_elems % plan->elems_per_vec != 0)
+        return fail(COVAP_EINVAL, "covap_decompress: row stride must be a multiple of 16 bytes");
+    const int64_t esz = plan->opts.dtype == COVAP_F32 ? 4 : 2;
+    if (overlap(recv, (int64_t)n_workers * stride_elems * esz, dense_out, plan->total_elems * esz))
+        return fail(COVAP_EINVAL, "covap_decompress: recv and dense_out must not overlap");
+    if (cr.sh_hi == cr.sh_lo) return COVAP_OK;
+
+    const covap::tuning &tn = covap::tune();
+    uint32_t grid = 0;
+    const fixed_geom g =
+        make_geom(plan, cr, kThreads * plan->elems_per_vec * kDecompressUnroll, &grid);
+    const int pow2 = (n_workers & (n_workers - 1)) == 0;
+    const float n_f = (float)n_workers, inv_n = 1.0f / n_f;
+    hipStream_t st = (hipStream_t)stream;
+    if (plan->opts.dtype == COVAP_F32)
+        dispatch_decompress<ops_f32>(tn.decompress_unroll, tn.nontemporal != 0, grid, st, recv,
+                                     dense_out, g, n_workers, stride_elems, n_f, inv_n, pow2);
+    else
+        dispatch_decompress<ops_bf16>(tn.decompress_unroll, tn.nontemporal != 0, grid, st, recv,
+                                      dense_out, g, n_workers, stride_elems, n_f, inv_n, pow2);
+    return check_launch("covap_decompress");
+}
+
+covap_status_t covap_probe_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    covap::clear_error();
+    if (!dst || !src || !aligned16(dst) || !aligned16(src) || bytes % 16 != 0)
+        return fail(COVAP_EINVAL, "covap_probe_copy: pointers and size must be 16-byte multiples");
+    if (bytes == 0) return COVAP_OK;
+    const int64_t nvec = (int64_t)(bytes / 16);
+    const int64_t per = kThreads * 4;
+    const uint32_t grid = (uint32_t)((nvec + per - 1) / per);
+    if (covap::tune().nontemporal)
+        k_copy<true><<<grid, kThreads, 0, (hipStream_t)stream>>>((u32x4 *)dst, (const u32x4 *)src, nvec);
+    else
+        k_copy<false><<<grid, kThreads, 0, (hipStream_t)stream>>>((u32x4 *)dst, (const u32x4 *)src, nvec);
+    return check_launch("covap_probe_copy");
+}
+
+covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float s, int64_t n,
+                                 void *stream)
+{
+    covap::clear_error();
+    if (!a || !b || !c || !aligned16(a) || !aligned16(b) || !aligned16(c) || n < 0 || n % 4 != 0)
+        return fail(COVAP_EINVAL, "covap_probe_triad: pointers 16-byte aligned, n a multiple of 4");
+    if (n == 0) return COVAP_OK;
+    const int64_t nvec = n / 4;
+    const int64_t per = kThreads * 4;
+    const uint32_t grid = (uint32_t)((nvec + per - 1) / per);
+    if (covap::tune().nontemporal)
+        k_triad<true><<<grid, kThreads, 0, (hipStream_t)stream>>>((u32x4 *)a, (const u32x4 *)b,
+                                                                  (const u32x4 *)c, s, nvec);
+    else
+        k_triad<false><<<grid, kThreads, 0, (hipStream_t)stream>>>((u32x4 *)a, (const u32x4 *)b,
+                                                                   (const u32x4 *)c, s, nvec);
+    return check_launch("covap_probe_triad");
+}
+
+}  // extern "C"

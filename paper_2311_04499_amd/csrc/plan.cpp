@@ -1,0 +1,323 @@
+// Host side of libcovap: planner (arena layout, shards, buckets, interval),
+// ratio policy and error-feedback scheduler.  Pure host code: nothing here
+// touches the GPU, so plans can be built and queried on a machine without one.
+#include "plan.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+
+namespace covap {
+
+static thread_local std::string g_last_error;
+
+covap_status_t fail(covap_status_t st, const std::string &msg)
+{
+    g_last_error = msg;
+    return st;
+}
+
+void clear_error() { g_last_error.clear(); }
+
+tuning &tune()
+{
+    static tuning t;
+    return t;
+}
+
+covap_status_t resolve(const covap_plan_s *plan, uint64_t step, int32_t bucket, call_range *out)
+{
+    if (!plan) return fail(COVAP_EINVAL, "plan is null");
+    const int32_t nb = (int32_t)plan->buckets.size();
+    if (bucket < -1 || bucket >= nb) return fail(COVAP_ERANGE, "bucket out of range");
+    const int32_t r = (int32_t)(step % (uint64_t)plan->K);
+    out->first_sel = first_selected(step, plan->K);
+    if (bucket < 0) {
+        out->sh_lo = 0;
+        out->sh_hi = (int32_t)plan->shards.size();
+        out->packed_base = 0;
+        out->packed_elems = plan->packed_total[r];
+    } else {
+        const covap_bucket_rec &b = plan->buckets[bucket];
+        out->sh_lo = b.sh_lo;
+        out->sh_hi = b.sh_hi;
+        out->packed_base = b.packed_base[r];
+        out->packed_elems = b.packed_elems[r];
+    }
+    return COVAP_OK;
+}
+
+// Shards -> buckets: consecutive shards are grouped greedily; a bucket closes
+// when the next shard would push it past the cap (Sec. III-A gives only the
+// target size of a communication tensor, about 25 MB).
+static void assign_buckets(covap_plan_s *p, int64_t cap_elems)
+{
+    int32_t b = 0;
+    int64_t fill = 0;
+    for (auto &sh : p->shards) {
+        if (fill > 0 && fill + sh.len > cap_elems) {
+            ++b;
+            fill = 0;
+        }
+        sh.bucket = b;
+        fill += sh.len;
+    }
+}
+
+// Packed layout: at any step the selected shards (one residue class mod K)
+// are stored in ascending shard order, so a shard's packed offset is the
+// total length of the earlier shards of its own class -- the same number at
+// every step that sends it.  Also fills the per-bucket and whole-arena packed
+// sizes by residue.
+static void finish_tables(covap_plan_s *p)
+{
+    const int32_t K = p->K;
+    std::vector<int64_t> class_fill((size_t)K, 0);
+    for (size_t s = 0; s < p->shards.size(); ++s) {
+        int64_t &f = class_fill[s % (size_t)K];
+        p->shards[s].packed_off = f;
+        f += p->shards[s].len;
+    }
+    p->packed_total.assign((size_t)K, 0);
+    p->packed_max = 0;
+    for (int32_t r = 0; r < K; ++r) {  // r = step mod K sends class (K - r) mod K
+        p->packed_total[r] = class_fill[(size_t)((K - r) % K)];
+        p->packed_max = std::max(p->packed_max, p->packed_total[r]);
+    }
+    const int32_t nb = p->shards.empty() ? 0 : p->shards.back().bucket + 1;
+    p->buckets.assign((size_t)nb, covap_bucket_rec());
+    for (auto &b : p->buckets) {
+        b.sh_lo = -1;
+        b.sh_hi = -1;
+        b.packed_base.assign((size_t)K, 0);
+        b.packed_elems.assign((size_t)K, 0);
+    }
+    std::vector<int64_t> run((size_t)K, 0);  // packed elements so far, by class
+    for (size_t s = 0; s < p->shards.size(); ++s) {
+        covap_bucket_rec &b = p->buckets[(size_t)p->shards[s].bucket];
+        if (b.sh_lo < 0) {
+            b.sh_lo = (int32_t)s;
+            for (int32_t r = 0; r < K; ++r) b.packed_base[r] = run[(size_t)((K - r) % K)];
+        }
+        b.sh_hi = (int32_t)s + 1;
+        const int32_t cls = (int32_t)(s % (size_t)K);
+        b.packed_elems[(size_t)((K - cls) % K)] += p->shards[s].len;
+        run[(size_t)cls] += p->shards[s].len;
+    }
+}
+
+}  // namespace covap
+
+using namespace covap;
+
+extern "C" {
+
+covap_status_t covap_plan(const int64_t *tensor_numel, int32_t n_tensors,
+                          const covap_plan_opts_t *opts, covap_plan_t **out)
+{
+    clear_error();
+    if (!tensor_numel || !opts || !out) return fail(COVAP_EINVAL, "covap_plan: null argument");
+    *out = nullptr;
+    if (n_tensors < 1) return fail(COVAP_EINVAL, "covap_plan: n_tensors < 1");
+    if (opts->K < 1) return fail(COVAP_EINVAL, "covap_plan: K < 1");
+    if (opts->reserved != 0) return fail(COVAP_EINVAL, "covap_plan: reserved must be 0");
+    if (opts->dtype != COVAP_F32 && opts->dtype != COVAP_BF16)
+        return fail(COVAP_EINVAL, "covap_plan: unknown dtype");
+    if (opts->bucket_cap_bytes <= 0) return fail(COVAP_EINVAL, "covap_plan: bucket_cap_bytes <= 0");
+    const int32_t epv = opts->dtype == COVAP_F32 ? 4 : 8;
+    const int64_t esz = opts->dtype == COVAP_F32 ? 4 : 2;
+    int64_t total = 0;
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (tensor_numel[i] < 0) return fail(COVAP_EINVAL, "covap_plan: negative element count");
+        total += tensor_numel[i];
+        if (total >= ((int64_t)1 << 40))
+            return fail(COVAP_EINVAL, "covap_plan: total elements >= 2^40");
+    }
+    if (opts->mode == COVAP_SHARD_MEDIAN)
+        return fail(COVAP_EUNSUPPORTED, "covap_plan: median sharding is not built yet");
+    if (opts->mode != COVAP_SHARD_FIXED) return fail(COVAP_EINVAL, "covap_plan: unknown mode");
+    if (opts->shard_elems > ((int64_t)1 << 30))
+        return fail(COVAP_EINVAL, "covap_plan: shard_elems > 2^30");
+    if (opts->shard_elems <= 0 || opts->shard_elems % epv != 0)
+        return fail(COVAP_EINVAL,
+                    "covap_plan: shard_elems must be a positive multiple of the 16-byte vector");
+    if ((total + opts->shard_elems - 1) / opts->shard_elems > (int64_t)0x7fffffff / 2)
+        return fail(COVAP_EINVAL, "covap_plan: too many shards");
+
+    covap_plan_s *p = new (std::nothrow) covap_plan_s();
+    if (!p) return fail(COVAP_ENOMEM, "covap_plan: out of host memory");
+    try {
+        p->opts = *opts;
+        p->K = opts->K;
+        p->elems_per_vec = epv;
+        p->total_elems = total;
+        p->uniform = true;
+        p->tensor_off.resize((size_t)n_tensors);
+        int64_t acc = 0;
+        for (int32_t i = 0; i < n_tensors; ++i) {  // tight packing, in the caller's order
+            p->tensor_off[(size_t)i] = acc;
+            acc += tensor_numel[i];
+        }
+        const int64_t S = opts->shard_elems;
+        for (int64_t b = 0; b < total; b += S) {
+            covap_shard_rec sh;
+            sh.off = b;
+            sh.len = std::min(S, total - b);
+            sh.packed_off = 0;
+            sh.bucket = 0;
+            p->shards.push_back(sh);
+        }
+        assign_buckets(p, std::max<int64_t>(1, opts->bucket_cap_bytes / esz));
+        finish_tables(p);
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return fail(COVAP_ENOMEM, "covap_plan: out of host memory");
+    }
+    *out = p;
+    return COVAP_OK;
+}
+
+void covap_plan_free(covap_plan_t *plan) { delete plan; }
+
+int64_t covap_plan_total_elems(const covap_plan_t *p) { return p ? p->total_elems : -1; }
+int32_t covap_plan_num_tensors(const covap_plan_t *p) { return p ? (int32_t)p->tensor_off.size() : -1; }
+int32_t covap_plan_num_shards(const covap_plan_t *p) { return p ? (int32_t)p->shards.size() : -1; }
+int32_t covap_plan_num_buckets(const covap_plan_t *p) { return p ? (int32_t)p->buckets.size() : -1; }
+int32_t covap_plan_interval(const covap_plan_t *p) { return p ? p->K : -1; }
+
+int64_t covap_plan_tensor_offset(const covap_plan_t *p, int32_t i)
+{
+    if (!p || i < 0 || i >= (int32_t)p->tensor_off.size()) return -1;
+    return p->tensor_off[(size_t)i];
+}
+
+covap_status_t covap_plan_shard(const covap_plan_t *p, int32_t s, int64_t *off, int64_t *len,
+                                int32_t *bucket)
+{
+    clear_error();
+    if (!p) return fail(COVAP_EINVAL, "covap_plan_shard: plan is null");
+    if (s < 0 || s >= (int32_t)p->shards.size())
+        return fail(COVAP_ERANGE, "covap_plan_shard: shard out of range");
+    const covap_shard_rec &sh = p->shards[(size_t)s];
+    if (off) *off = sh.off;
+    if (len) *len = sh.len;
+    if (bucket) *bucket = sh.bucket;
+    return COVAP_OK;
+}
+
+covap_status_t covap_plan_bucket(const covap_plan_t *p, int32_t b, int32_t *sh_lo, int32_t *sh_hi)
+{
+    clear_error();
+    if (!p) return fail(COVAP_EINVAL, "covap_plan_bucket: plan is null");
+    if (b < 0 || b >= (int32_t)p->buckets.size())
+        return fail(COVAP_ERANGE, "covap_plan_bucket: bucket out of range");
+    if (sh_lo) *sh_lo = p->buckets[(size_t)b].sh_lo;
+    if (sh_hi) *sh_hi = p->buckets[(size_t)b].sh_hi;
+    return COVAP_OK;
+}
+
+int32_t covap_plan_is_selected(const covap_plan_t *p, uint64_t step, int32_t s)
+{
+    if (!p || s < 0 || s >= (int32_t)p->shards.size()) return -1;
+    return (s % p->K) == first_selected(step, p->K) ? 1 : 0;
+}
+
+int32_t covap_plan_selected(const covap_plan_t *p, uint64_t step, int32_t *ids, int32_t cap)
+{
+    if (!p) return -1;
+    int32_t n = 0;
+    const int32_t ns = (int32_t)p->shards.size();
+    for (int32_t s = first_selected(step, p->K); s < ns; s += p->K) {
+        if (ids && n < cap) ids[n] = s;
+        ++n;
+    }
+    return n;
+}
+
+int64_t covap_plan_packed_elems(const covap_plan_t *p, uint64_t step, int32_t bucket)
+{
+    call_range cr;
+    if (resolve(p, step, bucket, &cr) != COVAP_OK) return -1;
+    return cr.packed_elems;
+}
+
+int64_t covap_plan_packed_base(const covap_plan_t *p, uint64_t step, int32_t bucket)
+{
+    call_range cr;
+    if (resolve(p, step, bucket, &cr) != COVAP_OK) return -1;
+    return cr.packed_base;
+}
+
+int64_t covap_plan_packed_elems_max(const covap_plan_t *p) { return p ? p->packed_max : -1; }
+
+covap_status_t covap_ratio_from_ccr(double ccr, int32_t *K)
+{
+    clear_error();
+    if (!K) return fail(COVAP_EINVAL, "covap_ratio_from_ccr: null out");
+    if (!(ccr > 0.0) || !std::isfinite(ccr) || ccr >= 2147483648.0)
+        return fail(COVAP_EINVAL, "covap_ratio_from_ccr: CCR must be in (0, 2^31)");
+    const double up = std::ceil(ccr);
+    *K = up < 1.0 ? 1 : (int32_t)up;
+    return COVAP_OK;
+}
+
+covap_status_t covap_ratio_from_times(double t_comm, double t_comp, int32_t *K)
+{
+    clear_error();
+    if (!(t_comm > 0.0) || !(t_comp > 0.0) || !std::isfinite(t_comm) || !std::isfinite(t_comp))
+        return fail(COVAP_EINVAL, "covap_ratio_from_times: times must be positive and finite");
+    return covap_ratio_from_ccr(t_comm / t_comp, K);
+}
+
+covap_status_t covap_ef_coeff(float init_value, uint64_t num_steps, uint64_t ascend_steps,
+                              float ascend_range, float *coeff)
+{
+    clear_error();
+    if (!coeff) return fail(COVAP_EINVAL, "covap_ef_coeff: null out");
+    if (ascend_steps == 0) return fail(COVAP_EINVAL, "covap_ef_coeff: ascend_steps == 0");
+    if (!std::isfinite(init_value) || !std::isfinite(ascend_range))
+        return fail(COVAP_EINVAL, "covap_ef_coeff: non-finite parameter");
+    const double rises = (double)(num_steps / ascend_steps);
+    double v = (double)init_value + rises * (double)ascend_range;
+    if (v > 1.0) v = 1.0;
+    *coeff = (float)v;
+    return COVAP_OK;
+}
+
+covap_status_t covap_tune_set(const char *key, int32_t value)
+{
+    clear_error();
+    if (!key) return fail(COVAP_EINVAL, "covap_tune_set: null key");
+    tuning &t = tune();
+    if (!std::strcmp(key, "compress_unroll")) {
+        if (value != 1 && value != 2 && value != 4 && value != 8)
+            return fail(COVAP_EINVAL, "compress_unroll must be 1, 2, 4 or 8");
+        t.compress_unroll = value;
+    } else if (!std::strcmp(key, "decompress_unroll")) {
+        if (value != 2 && value != 4 && value != 8 && value != 16)
+            return fail(COVAP_EINVAL, "decompress_unroll must be 2, 4, 8 or 16");
+        t.decompress_unroll = value;
+    } else if (!std::strcmp(key, "nontemporal")) {
+        if (value != 0 && value != 1) return fail(COVAP_EINVAL, "nontemporal must be 0 or 1");
+        t.nontemporal = value;
+    } else {
+        return fail(COVAP_EINVAL, "covap_tune_set: unknown key");
+    }
+    return COVAP_OK;
+}
+
+int32_t covap_tune_get(const char *key)
+{
+    if (!key) return -1;
+    const tuning &t = tune();
+    if (!std::strcmp(key, "compress_unroll")) return t.compress_unroll;
+    if (!std::strcmp(key, "decompress_unroll")) return t.decompress_unroll;
+    if (!std::strcmp(key, "nontemporal")) return t.nontemporal;
+    return -1;
+}
+
+const char *covap_last_error(void) { return g_last_error.c_str(); }
+const char *covap_version(void) { return "0.1.0"; }
+
+}  // extern "C"

@@ -1,0 +1,226 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element and bit for bit, on the same seeded inputs.
+
+Bar: selection, packing positions, error feedback, residuals and the N-way mean
+are all bit-exact (the mean keeps the oracle's summation order w = 0..N-1 and
+uses IEEE division).  The only exception is the payload of a NaN, which
+hardware and libm may propagate differently: NaN positions must coincide.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_04499_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2311_04499_amd import binding
+    binding.lib()                      # raises if the HIP library is not built
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return binding
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16).copy()
+    return t.numpy().copy()
+
+
+def bits(a: np.ndarray) -> np.ndarray:
+    if a.dtype == np.float32:
+        return a.view(np.uint32)
+    return a
+
+
+def assert_same(got: np.ndarray, want: np.ndarray, what: str):
+    gb, wb = bits(got), bits(want)
+    if np.array_equal(gb, wb):
+        return
+    if got.dtype == np.float32:
+        nan_g, nan_w = np.isnan(got), np.isnan(want)
+        if np.array_equal(nan_g, nan_w) and np.array_equal(gb[~nan_g], wb[~nan_w]):
+            return
+    bad = np.nonzero(gb != wb)[0]
+    raise AssertionError(f"{what}: {bad.size} of {gb.size} elements differ, first at {bad[0]}: "
+                         f"got {got[bad[0]]!r} want {want[bad[0]]!r}")
+
+
+def make_plans(B, numel, S, K, dtype=torch.float32, cap_bytes=25 << 20):
+    code = B.COVAP_F32 if dtype == torch.float32 else B.COVAP_BF16
+    esz = 4 if dtype == torch.float32 else 2
+    plan = B.covap_plan(numel, S, K, dtype=code, bucket_cap_bytes=cap_bytes)
+    tab = oracle.plan_fixed(numel, S, max(1, cap_bytes // esz))
+    assert plan.total_elems == tab.D and plan.num_shards == tab.n_shards
+    assert plan.num_buckets == tab.n_buckets
+    return plan, tab
+
+
+def run_iterations(B, wl, numel, S, K, N, iters, dtype=torch.float32, c=1.0, per_bucket=False,
+                   cap_bytes=25 << 20, slack=0):
+    """Full-fidelity loop: every one of the N workers compresses its own gradient
+    each iteration; their send buffers are the rows handed to decompress.  Both
+    sides run the same loop on the same inputs and are compared after every call."""
+    plan, tab = make_plans(B, numel, S, K, dtype, cap_bytes)
+    D, P = tab.D, plan.packed_elems_max
+    epv = 4 if dtype == torch.float32 else 8
+    stride = (P + slack + epv - 1) // epv * epv
+    np_dt = np.float32 if dtype == torch.float32 else np.uint16
+    R_gpu = [torch.zeros(D, dtype=dtype, device=DEV) for _ in range(N)]
+    R_cpu = [np.zeros(D, np_dt) for _ in range(N)]
+    for t in range(iters):
+        assert plan.packed_elems(t) == oracle.packed_elems(tab, K, t)
+        assert plan.selected(t) == [s for s in range(tab.n_shards) if oracle.selected(s, t, K)]
+        recv_gpu = torch.full((N, stride), float("nan"), dtype=dtype, device=DEV)
+        recv_cpu = to_np(recv_gpu)
+        buckets = range(tab.n_buckets) if per_bucket else [-1]
+        for w in range(N):
+            G = workloads.gradient(wl, w, t, DEV, dtype)[:D].contiguous()
+            Gn = to_np(G)
+            for b in buckets:
+                B.covap_compress(plan, t, G, R_gpu[w], recv_gpu[w], ef_coeff=c, bucket=b)
+                oracle.compress(tab, K, t, Gn, R_cpu[w], recv_cpu[w], c, bucket=b)
+            torch.cuda.synchronize()
+            assert_same(to_np(recv_gpu[w]), recv_cpu[w], f"send t={t} w={w}")
+            assert_same(to_np(R_gpu[w]), R_cpu[w], f"residual t={t} w={w}")
+        out_gpu = torch.full((D,), float("nan"), dtype=dtype, device=DEV)
+        out_cpu = np.zeros(D, np_dt)
+        for b in buckets:
+            B.covap_decompress(plan, t, recv_gpu, out_gpu, bucket=b)
+            oracle.decompress(tab, K, t, recv_cpu, out_cpu, bucket=b)
+        torch.cuda.synchronize()
+        assert_same(to_np(out_gpu), out_cpu, f"dense t={t}")
+
+
+# ------------------------------------------------------------------ configurations
+
+def test_cfg1_tiny_mlp_full(B):
+    wl = workloads.config(1)
+    run_iterations(B, wl, wl.numel, wl.shard_elems, wl.K, wl.n_workers, wl.iterations)
+
+
+@pytest.mark.parametrize("cfg,numel,S", [
+    (2, [1_000_003, 64 * 64 * 9, 2048 * 512, 1000], 65536),     # several shards + ragged tail
+    (3, [3 * 1048576 + 12328], 1 << 20),
+    (4, [768 * 768] * 3 + [3072 * 768, 768, 2], 1 << 18),
+    (5, [2 * 1048576 + 404480, 1024], 1 << 20),
+])
+def test_scaled_configs(B, cfg, numel, S):
+    wl = workloads.scaled_down(workloads.config(cfg), numel, S)
+    run_iterations(B, wl, numel, S, wl.K, min(wl.n_workers, 8), 2 * wl.K + 1)
+
+
+@pytest.mark.parametrize("c", [0.25, 0.5, 0.3])
+def test_ef_coefficient_sweep(B, c):
+    wl = workloads.scaled_down(workloads.config(1), [70_001], 4096)
+    run_iterations(B, wl, [70_001], 4096, 3, 2, 7, c=c)
+
+
+@pytest.mark.parametrize("N", [1, 3, 5, 7, 24, 64])
+def test_worker_counts(B, N):
+    wl = workloads.scaled_down(workloads.config(1), [40_961], 4096)
+    run_iterations(B, wl, [40_961], 4096, 2, N, 3)
+
+
+@pytest.mark.parametrize("numel,S,K", [
+    ([1], 4, 1), ([3], 4, 2), ([4], 4, 4), ([5], 4, 3), ([4095], 4096, 2), ([4097], 4096, 2),
+    ([8193], 8, 5), ([100], 1 << 20, 16),                       # fewer shards than K
+    ([12_289], 12, 4), ([50_000], 1000, 1), ([65_537], 16384, 7),
+])
+def test_edge_shapes(B, numel, S, K):
+    wl = workloads.scaled_down(workloads.config(1), numel, S)
+    run_iterations(B, wl, numel, S, K, 3, 2 * K + 1, slack=5)
+
+
+def test_per_bucket_calls(B):
+    numel = [300_000, 12_345]
+    wl = workloads.scaled_down(workloads.config(2), numel, 8192)
+    run_iterations(B, wl, numel, 8192, 3, 2, 4, per_bucket=True, cap_bytes=100_000, c=0.5)
+
+
+@pytest.mark.parametrize("key,vals", [("compress_unroll", [1, 2, 8]), ("decompress_unroll", [2, 4, 16]),
+                                      ("nontemporal", [0])])
+def test_launch_shape_knobs(B, key, vals):
+    old = B.covap_tune_get(key)
+    try:
+        for v in vals:
+            B.covap_tune_set(key, v)
+            wl = workloads.scaled_down(workloads.config(1), [100_003], 4096)
+            run_iterations(B, wl, [100_003], 4096, 3, 5, 4)
+    finally:
+        B.covap_tune_set(key, old)
+
+
+@pytest.mark.parametrize("numel,S,K,N", [([100_003], 4096, 3, 4), ([7], 8, 2, 3), ([8 * 4096 + 9], 8192, 4, 5),
+                                         ([768 * 768, 3072 * 768 + 5], 1 << 18, 6, 32)])
+def test_bf16(B, numel, S, K, N):
+    wl = workloads.scaled_down(workloads.config(4), numel, S)
+    run_iterations(B, wl, numel, S, K, N, 2 * K + 1, dtype=torch.bfloat16, c=0.5)
+
+
+def test_special_values(B):
+    """Signed zeros, infinities, NaN, denormals: same bits as the oracle (NaN
+    payload aside), and a sent element leaves residual +0 whatever it was."""
+    D, S, K, N = 4096 * 2 + 6, 4096, 2, 3
+    plan, tab = make_plans(B, [D], S, K)
+    specials = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1e-45, -1e-45, 1e-39, 3.4e38, -3.4e38,
+                         1.17549435e-38, 1.0, -1.0], np.float32)
+    rng = np.random.default_rng(0)
+    Gn = rng.choice(specials, D).astype(np.float32)
+    Rn = rng.choice(specials, D).astype(np.float32)
+    for t in range(2):
+        G = torch.from_numpy(Gn).to(DEV)
+        R = torch.from_numpy(Rn).to(DEV)
+        P = plan.packed_elems_max
+        stride = (P + 3) // 4 * 4
+        send = torch.zeros(stride, device=DEV)
+        Rc, sc = Rn.copy(), np.zeros(stride, np.float32)
+        B.covap_compress(plan, t, G, R, send, ef_coeff=0.5)
+        oracle.compress(tab, K, t, Gn, Rc, sc, 0.5)
+        assert_same(to_np(send), sc, "send")
+        assert_same(to_np(R), Rc, "residual")
+        recv = torch.from_numpy(rng.choice(specials, (N, stride)).astype(np.float32)).to(DEV)
+        out = torch.zeros(D, device=DEV)
+        oc = np.zeros(D, np.float32)
+        B.covap_decompress(plan, t, recv, out)
+        oracle.decompress(tab, K, t, to_np(recv), oc)
+        assert_same(to_np(out), oc, "dense")
+
+
+def test_k1_identity_on_gpu(B):
+    wl = workloads.config(1)
+    plan, tab = make_plans(B, wl.numel, wl.shard_elems, 1)
+    G = workloads.gradient(wl, 0, 0, DEV)
+    R = torch.zeros_like(G)
+    send = torch.zeros_like(G)
+    B.covap_compress(plan, 5, G, R, send)
+    torch.cuda.synchronize()
+    assert torch.equal(send, G) and not R.any()
+
+
+def test_argument_errors(B):
+    plan, _ = make_plans(B, [10_000], 1024, 4)
+    G = torch.zeros(10_000, device=DEV)
+    R = torch.zeros(10_000, device=DEV)
+    send = torch.zeros(plan.packed_elems_max, device=DEV)
+    with pytest.raises(B.CovapError) as e:
+        B.covap_compress(plan, 0, G, R, send, send_cap_elems=10)
+    assert e.value.status == 1
+    with pytest.raises(B.CovapError):
+        B.covap_compress(plan, 0, G[1:], R, send)               # misaligned
+    with pytest.raises(B.CovapError):
+        B.covap_compress(plan, 0, G, G, send)                   # overlap
+    with pytest.raises(B.CovapError) as e:
+        B.covap_compress(plan, 0, G, R, send, bucket=99)
+    assert e.value.status == 4
+    with pytest.raises(B.CovapError):
+        B.covap_decompress(plan, 0, send, G, n_workers=0, stride_elems=send.numel())
+    with pytest.raises(B.CovapError):
+        B.covap_decompress(plan, 0, send, G, n_workers=2, stride_elems=send.numel() // 2 - 1)
+    torch.cuda.synchronize()

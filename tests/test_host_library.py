@@ -1,0 +1,152 @@
+"""CPU-only checks of libcovap: it loads, exports every symbol the header
+declares, and its host logic (planner, filter queries, ratio policy, scheduler,
+argument validation that happens before any GPU work) agrees with the oracle's
+tables.  The two planners share no code; they are compared table against table.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2311_04499_amd import workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2311_04499_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        binding.build()
+    binding.lib()
+    return binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "covap.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b((?:covap|topk)_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported(B):
+    names = declared_functions()
+    assert {"covap_plan", "covap_compress", "covap_decompress", "topk_compress"} <= set(names)
+    L = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), f"{n} is declared in covap.h but not exported"
+    assert re.fullmatch(r"\d+\.\d+\.\d+", B.covap_version())
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_planner_tables_match_oracle(B, cfg):
+    wl = workloads.config(cfg)
+    for dtype, esz in ((B.COVAP_F32, 4), (B.COVAP_BF16, 2)):
+        plan = B.covap_plan(wl.numel, wl.shard_elems, wl.K, dtype=dtype)
+        tab = oracle.plan_fixed(wl.numel, wl.shard_elems, (25 << 20) // esz)
+        assert plan.total_elems == tab.D == wl.D
+        assert plan.num_tensors == len(wl.numel)
+        assert plan.interval == wl.K
+        assert plan.num_shards == tab.n_shards
+        assert plan.num_buckets == tab.n_buckets
+        for i in (0, 1, len(wl.numel) // 2, len(wl.numel) - 1):
+            assert plan.tensor_offset(i) == int(tab.tensor_offsets[i])
+        assert plan.tensor_offset(len(wl.numel)) == -1
+        for s in range(tab.n_shards):
+            assert plan.shard(s) == (int(tab.off[s]), int(tab.len[s]), int(tab.bucket[s]))
+        for b in range(tab.n_buckets):
+            assert plan.bucket(b) == tab.bucket_range(b)
+        pmax = 0
+        for t in list(range(2 * wl.K)) + [10 ** 12 + 7, 2 ** 64 - 1]:
+            sel = plan.selected(t)
+            assert sel == [s for s in range(tab.n_shards) if oracle.selected(s, t, wl.K)]
+            assert all(plan.is_selected(t, s) == 1 for s in sel[:3])
+            assert plan.packed_elems(t) == oracle.packed_elems(tab, wl.K, t)
+            pmax = max(pmax, plan.packed_elems(t))
+            for b in {0, tab.n_buckets // 2, tab.n_buckets - 1}:
+                assert plan.packed_elems(t, b) == oracle.packed_elems(tab, wl.K, t, b)
+                assert plan.packed_base(t, b) == oracle.packed_base(tab, wl.K, t, b)
+        assert plan.packed_elems_max == pmax
+
+
+def test_small_plans_match_oracle_exhaustively(B):
+    for D in (1, 4, 5, 63, 64, 65, 1000):
+        for S in (4, 8, 64):
+            for K in (1, 2, 3, 5, 16):
+                for cap in (16, 100, 1 << 20):
+                    plan = B.covap_plan([D], S, K, bucket_cap_bytes=cap)
+                    tab = oracle.plan_fixed([D], S, max(1, cap // 4))
+                    assert plan.num_buckets == tab.n_buckets
+                    for t in range(K + 1):
+                        for b in range(-1, tab.n_buckets):
+                            assert plan.packed_elems(t, b) == oracle.packed_elems(tab, K, t, b)
+                            if b >= 0:
+                                assert plan.packed_base(t, b) == oracle.packed_base(tab, K, t, b)
+
+
+def test_plan_argument_errors(B):
+    for kwargs in (dict(shard_elems=0), dict(shard_elems=6), dict(K=0), dict(bucket_cap_bytes=0),
+                   dict(dtype=7), dict(mode=9)):
+        args = dict(tensor_numel=[100], shard_elems=8, K=2)
+        args.update(kwargs)
+        with pytest.raises(B.CovapError) as e:
+            B.covap_plan(**args)
+        assert e.value.status == 1
+    with pytest.raises(B.CovapError):
+        B.covap_plan([], 8, 2)
+    with pytest.raises(B.CovapError):
+        B.covap_plan([10, -1], 8, 2)
+    with pytest.raises(B.CovapError):
+        B.covap_plan([100], 12, 2, dtype=B.COVAP_BF16)      # bf16 vectors hold 8 elements
+    p = B.covap_plan([100], 8, 2)
+    with pytest.raises(B.CovapError) as e:
+        p.shard(13)
+    assert e.value.status == 4
+    assert p.packed_elems(0, 5) == -1
+    assert B.lib().covap_plan_total_elems(None) == -1
+
+
+def test_ratio_policy_matches_paper_and_oracle(B, golden):
+    for row in golden("ratio_policy.txt"):
+        assert B.covap_ratio_from_ccr(float(row[0])) == int(row[1])
+    for ccr in (0.01, 0.5, 1.0, 1.0000001, 2.999, 3.0, 6.0, 1e6):
+        assert B.covap_ratio_from_ccr(ccr) == oracle.ratio_from_ccr(ccr)
+    # Table I: T_comm / T_comp of ResNet-101, VGG-19 and Bert
+    assert B.covap_ratio_from_times(280, 135) == 3
+    assert B.covap_ratio_from_times(842, 210) == 5      # 4.0095...: the table rounds CCR to 4.0
+    assert B.covap_ratio_from_times(520, 170) == 4
+    for bad in (0.0, -2.0, float("nan"), float("inf")):
+        with pytest.raises(B.CovapError):
+            B.covap_ratio_from_ccr(bad)
+    with pytest.raises(B.CovapError):
+        B.covap_ratio_from_times(1.0, 0.0)
+
+
+def test_ef_coeff_matches_oracle(B):
+    for init, asc, rng in ((0.1, 100, 0.1), (0.3, 7, 0.05), (1.0, 3, 0.5), (0.0, 1, 0.001)):
+        for n in (0, 1, 6, 7, 99, 100, 899, 900, 12345, 2 ** 40):
+            got = B.covap_ef_coeff(init, n, asc, rng)
+            assert np.float32(got) == np.float32(oracle.ef_coeff(init, n, asc, rng))
+            assert got <= 1.0
+    with pytest.raises(B.CovapError):
+        B.covap_ef_coeff(0.1, 5, 0, 0.1)
+
+
+def test_hot_path_rejects_bad_arguments_before_touching_the_gpu(B):
+    p = B.covap_plan([1000], 64, 4)
+    L = B.lib()
+    assert L.covap_compress(p.handle, 0, -1, None, None, None, 1000, 1.0, None) == 1
+    assert L.covap_compress(None, 0, -1, 16, 32, 48, 1000, 1.0, None) == 1
+    assert L.covap_compress(p.handle, 0, -1, 16, 4096 * 4, 4096 * 8 + 4, 1000, 1.0, None) == 1
+    assert b"aligned" in L.covap_last_error()
+    assert L.covap_decompress(p.handle, 0, 7, 16, 1, 1000, 32, None) == 4
+    assert L.covap_decompress(p.handle, 0, -1, 1 << 20, 0, 1000, 1 << 30, None) == 1
+    assert L.topk_compress(None, None, 10, 11, 0, 1.0, None, None, None, 0, None) != 0
+    with pytest.raises(B.CovapError):
+        B.covap_tune_set("no_such_knob", 1)
+    with pytest.raises(B.CovapError):
+        B.covap_tune_set("compress_unroll", 3)
+    assert B.covap_tune_get("compress_unroll") in (1, 2, 4, 8)
