@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the COVAP hot path on one MI355X.
+
+One "step" = one worker's whole per-iteration path on one synthetic gradient
+set: covap_compress (error feedback + filter + pack + residual) followed by
+covap_decompress (N-way mean + unpack + zero fill) over the N payload rows.
+Inputs are resident in HBM before the timed region.  The default workload is
+the GPT-2-medium-shaped gradient set (355M fp32 elements, shard 2^20, N = 64,
+K = 16) in payload mode: row 0 of the receive buffer is this worker's own
+packed output, rows 1..N-1 are synthetic payloads drawn at packed shape.
+
+Prints ONE JSON line (see README/DESIGN for the fields).  `--gpus N` with
+N > 1 is refused: this build is a single-GPU path with no collectives.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5")
+    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
+    ap.add_argument("--tune", action="append", default=[], help="key=value launch knob")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-topk", action="store_true")
+    ap.add_argument("--no-probes", action="store_true")
+    return ap.parse_args()
+
+
+def read_traffic(kernel: str, workload: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+    return float(m.group(1)) if m else None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding across "
+              "GPUs); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2311_04499_amd import binding as B
+    from paper_2311_04499_amd import workloads
+
+    B.lib()                                    # no fallback: fails if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    for kv in args.tune:
+        k, v = kv.split("=")
+        B.covap_tune_set(k, int(v))
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = workloads.config(args.config)
+    tdtype = torch.float32 if args.dtype == "f32" else torch.bfloat16
+    esz = 4 if args.dtype == "f32" else 2
+    epv = 16 // esz
+    plan = B.covap_plan(wl.numel, wl.shard_elems, wl.K,
+                        dtype=B.COVAP_F32 if args.dtype == "f32" else B.COVAP_BF16)
+    D, N, K = wl.D, wl.n_workers, wl.K
+    P_max = plan.packed_elems_max
+    stride = (P_max + epv - 1) // epv * epv
+
+    # ---- inputs, resident in HBM before anything is timed
+    ring = [workloads.gradient(wl, 0, i, dev, tdtype) for i in range(3)]
+    residual = torch.zeros(D, dtype=tdtype, device=dev)
+    recv = torch.empty(N, stride, dtype=tdtype, device=dev)
+    if N > 1:
+        recv[1:] = workloads.payload_rows(wl, N - 1, stride, 0, dev, tdtype)
+    dense = torch.empty(D, dtype=tdtype, device=dev)
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream()
+
+    def step(t):
+        B.covap_compress(plan, t, ring[t % 3], residual, recv[0], stream=stream)
+        B.covap_decompress(plan, t, recv, dense, n_workers=N, stride_elems=stride, stream=stream)
+
+    for t in range(args.warmup):
+        step(t)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` steps, HIP events around every kernel
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t_first = args.warmup
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    for i in range(args.steps):
+        t = t_first + i
+        ev[i][0].record(stream)
+        B.covap_compress(plan, t, ring[t % 3], residual, recv[0], stream=stream)
+        ev[i][1].record(stream)
+        B.covap_decompress(plan, t, recv, dense, n_workers=N, stride_elems=stride, stream=stream)
+        ev[i][2].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+
+    ms_step = wall * 1e3 / args.steps
+    tc = [e[0].elapsed_time(e[1]) for e in ev]           # ms
+    td = [e[1].elapsed_time(e[2]) for e in ev]
+    tc_avg, td_avg = sum(tc) / len(tc), sum(td) / len(td)
+    steps_t = [t_first + i for i in range(args.steps)]
+    P_avg = sum(plan.packed_elems(t) for t in steps_t) / len(steps_t)
+    bytes_c = esz * (3 * D + P_avg)                      # read G, read R, write R, write packed
+    bytes_d = esz * (N * P_avg + D)                      # read N rows, write dense
+    grad_gbs = esz * D / (ms_step * 1e-3) / 1e9
+    hbm_gbs = (bytes_c + bytes_d) / (ms_step * 1e-3) / 1e9
+
+    dominant = ("covap_decompress", td_avg, bytes_d) if td_avg >= tc_avg else \
+               ("covap_compress", tc_avg, bytes_c)
+    ach = dominant[2] / (dominant[1] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dominant[0], "achieved": round(ach, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                "traffic": read_traffic(dominant[0], wl.name),
+                "bytes_per_launch": round(dominant[2]), "avg_launch_us": round(dominant[1] * 1e3, 2)}
+
+    kernels = {
+        "covap_compress": {"avg_us": round(tc_avg * 1e3, 2), "algorithmic_bytes": round(bytes_c),
+                           "GB/s": round(bytes_c / (tc_avg * 1e-3) / 1e9, 1),
+                           "frac": round(bytes_c / (tc_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "covap_decompress": {"avg_us": round(td_avg * 1e3, 2), "algorithmic_bytes": round(bytes_d),
+                             "GB/s": round(bytes_d / (td_avg * 1e-3) / 1e9, 1),
+                             "frac": round(bytes_d / (td_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+    }
+
+    out = {
+        "metric": "compress+decompress GB/s of gradient processed", "value": round(grad_gbs, 2),
+        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"cfg{wl.cfg_id}:{wl.name}", "elements": D, "shard_elems": wl.shard_elems,
+                   "n_workers": N, "K": K, "mode": "payload"},
+        "hbm_GB/s": round(hbm_gbs, 1), "hbm_frac": round(hbm_gbs / HBM_PEAK_GBS, 4),
+        "overhead_us_per_iter": round(ms_step * 1e3, 1),
+        "roofline": roofline, "kernels": kernels,
+    }
+
+    # ---- achievable streaming rate in the same run (context for the fraction)
+    if not args.no_probes:
+        nb = min(D * esz, 1 << 31) // 16 * 16
+        a = dense.view(torch.uint8)[:nb]
+        b = ring[0].view(torch.uint8)[:nb]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(3):
+            B.covap_probe_copy(a, b, nb, stream=stream)
+        e0.record(stream)
+        reps = 20
+        for _ in range(reps):
+            B.covap_probe_copy(a, b, nb, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        copy_gbs = 2 * nb * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        out["probe_copy_GB/s"] = round(copy_gbs, 1)
+
+    # ---- top-k contrast on the same gradient buffers
+    if not args.no_topk and args.dtype == "f32":
+        try:
+            k = -(-D // 1000)                            # ceil(0.1% of D)
+            ws_bytes = B.topk_workspace_bytes(D)
+            ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+            vals = torch.empty(k, dtype=torch.float32, device=dev)
+            idx = torch.empty(k, dtype=torch.int32, device=dev)
+            res2 = torch.zeros(D, dtype=torch.float32, device=dev)
+            for t in range(3):
+                B.topk_compress(ring[t % 3], res2, k, vals, idx, ws, stream=stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = max(5, min(args.steps, 20))
+            e0.record(stream)
+            for t in range(reps):
+                B.topk_compress(ring[t % 3], res2, k, vals, idx, ws, stream=stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            topk_us = e0.elapsed_time(e1) * 1e3 / reps
+            out["topk"] = {"k": k, "us_per_iter": round(topk_us, 1),
+                           "vs_covap_compress": round(topk_us / (tc_avg * 1e3), 2),
+                           "vs_covap_compress_plus_decompress": round(topk_us / (ms_step * 1e3), 2)}
+            del ws, vals, idx, res2
+        except B.CovapError as e:
+            out["topk"] = {"error": str(e)}
+
+    # ---- CPU oracle on a bounded sample of the same workload (reported, not a target)
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        tab = oracle.plan_fixed(wl.numel, wl.shard_elems, (25 << 20) // esz)
+        t = t_first + args.steps
+        to_np = (lambda x: x.cpu().numpy()) if args.dtype == "f32" else \
+                (lambda x: x.cpu().view(torch.int16).numpy().view(np.uint16))
+        Gn = to_np(ring[t % 3])
+        Rn = to_np(residual).copy()
+        recv_n = to_np(recv).copy()
+        out_n = np.empty(D, Gn.dtype)
+        c0 = time.perf_counter()
+        oracle.compress(tab, K, t, Gn, Rn, recv_n[0])
+        c1 = time.perf_counter()
+        oracle.decompress(tab, K, t, recv_n, out_n)
+        c2 = time.perf_counter()
+        out["cpu_baseline"] = {"value": round(esz * D / (c2 - c0) / 1e9, 4), "unit": "GB/s",
+                               "cores": 1, "kind": "oracle",
+                               "sample": "1 full iteration of the same workload (compress %.2f s + "
+                                         "decompress %.2f s), single thread" % (c1 - c0, c2 - c1),
+                               "host_cpus": os.cpu_count()}
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

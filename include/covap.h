@@ -191,9 +191,15 @@ covap_status_t covap_probe_copy(void *dst, const void *src, size_t bytes, void *
 covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float s, int64_t n,
                                  void *stream);
 
-/* Launch-shape knobs for tuning sweeps: key is one of "compress_unroll",
- * "decompress_unroll", "nontemporal".  EINVAL for an unknown key or a value
- * outside the documented set.  Not thread-safe against running calls. */
+/* Launch-shape knobs for tuning sweeps (the defaults are the measured best on
+ * MI355X).  Keys and allowed values:
+ *   "compress_threads", "decompress_threads"  workgroup size: 64, 128, 256, 512
+ *   "compress_unroll"    16-byte vectors per thread per tile: 1, 2, 4
+ *   "decompress_tile"    16-byte vectors per thread per tile: 1, 2
+ *   "decompress_unroll"  payload rows loaded before they are summed: 2, 4, 8
+ *   "nontemporal"        streaming cache hints on loads and stores: 0, 1
+ * No knob changes any result bit.  EINVAL for an unknown key or value.  Global
+ * to the process and not thread-safe against running calls. */
 covap_status_t covap_tune_set(const char *key, int32_t value);
 int32_t covap_tune_get(const char *key);
 

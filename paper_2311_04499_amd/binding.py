@@ -162,9 +162,9 @@ class Plan:
         self.dtype = dtype
 
     def __del__(self):
-        if getattr(self, "_h", None):
-            lib().covap_plan_free(self._h)
-            self._h = None
+        h, self._h = getattr(self, "_h", None), None
+        if h and _lib is not None:          # at interpreter exit the module may be gone already
+            _lib.covap_plan_free(h)
 
     @property
     def handle(self) -> int:

@@ -18,6 +18,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "plan.h"
 
@@ -26,7 +27,7 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
+constexpr int kProbeThreads = 256;
 
 template <bool NT>
 __device__ __forceinline__ u32x4 ld16(const u32x4 *p)
@@ -200,7 +201,7 @@ __device__ __forceinline__ bool resolve_tile(const fixed_geom &g, tile_ref &t)
 
 // ---- compress: error feedback + filter + pack + residual -----------------------
 
-template <typename OPS, int UNROLL, bool NT>
+template <typename OPS, int kThreads, int UNROLL, bool NT>
 __global__ __launch_bounds__(kThreads) void k_compress(const u32x4 *__restrict__ G, u32x4 *R,
                                                        u32x4 *__restrict__ send, fixed_geom g,
                                                        float c)
@@ -286,7 +287,7 @@ __device__ __forceinline__ typename OPS::acc_t sum_rows(const u32x4 *p, int32_t 
     return acc;
 }
 
-template <typename OPS, int WU, bool NT, int UNROLL>
+template <typename OPS, int kThreads, int UNROLL, int WU, bool NT>
 __global__ __launch_bounds__(kThreads) void k_decompress(const u32x4 *__restrict__ recv,
                                                          u32x4 *__restrict__ out, fixed_geom g,
                                                          int32_t N, int64_t stride_elems,
@@ -335,35 +336,35 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const u32x4 *__restrict
 // ---- probes ------------------------------------------------------------------------
 
 template <bool NT>
-__global__ __launch_bounds__(kThreads) void k_copy(u32x4 *__restrict__ dst,
+__global__ __launch_bounds__(kProbeThreads) void k_copy(u32x4 *__restrict__ dst,
                                                    const u32x4 *__restrict__ src, int64_t nvec)
 {
     constexpr int U = 4;
-    const int64_t base = (int64_t)blockIdx.x * (kThreads * U) + threadIdx.x;
-    if (base + (U - 1) * kThreads < nvec) {
+    const int64_t base = (int64_t)blockIdx.x * (kProbeThreads * U) + threadIdx.x;
+    if (base + (U - 1) * kProbeThreads < nvec) {
         u32x4 v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = ld16<NT>(src + base + u * kThreads);
+        for (int u = 0; u < U; ++u) v[u] = ld16<NT>(src + base + u * kProbeThreads);
 #pragma unroll
-        for (int u = 0; u < U; ++u) st16<NT>(dst + base + u * kThreads, v[u]);
+        for (int u = 0; u < U; ++u) st16<NT>(dst + base + u * kProbeThreads, v[u]);
     } else {
         for (int u = 0; u < U; ++u) {
-            const int64_t i = base + u * kThreads;
+            const int64_t i = base + u * kProbeThreads;
             if (i < nvec) st16<NT>(dst + i, ld16<NT>(src + i));
         }
     }
 }
 
 template <bool NT>
-__global__ __launch_bounds__(kThreads) void k_triad(u32x4 *__restrict__ a,
+__global__ __launch_bounds__(kProbeThreads) void k_triad(u32x4 *__restrict__ a,
                                                     const u32x4 *__restrict__ b,
                                                     const u32x4 *__restrict__ c, float s,
                                                     int64_t nvec)
 {
     constexpr int U = 4;
-    const int64_t base = (int64_t)blockIdx.x * (kThreads * U) + threadIdx.x;
+    const int64_t base = (int64_t)blockIdx.x * (kProbeThreads * U) + threadIdx.x;
     for (int u = 0; u < U; ++u) {
-        const int64_t i = base + u * kThreads;
+        const int64_t i = base + u * kProbeThreads;
         if (i < nvec) st16<NT>(a + i, ops_f32::ef(ld16<NT>(b + i), ld16<NT>(c + i), s));
     }
 }
@@ -402,56 +403,48 @@ covap_status_t check_launch(const char *what)
     return COVAP_OK;
 }
 
-template <typename OPS, int UNROLL>
-void launch_compress(bool nt, uint32_t grid, hipStream_t st, const void *G, void *R, void *send,
-                     const fixed_geom &g, float c)
+// Calls f(std::integral_constant<int, V>) for the V in Vs... that equals v.
+template <int... Vs, typename F>
+bool pick(int v, F &&f)
 {
-    if (nt)
-        k_compress<OPS, UNROLL, true><<<grid, kThreads, 0, st>>>((const u32x4 *)G, (u32x4 *)R,
-                                                                 (u32x4 *)send, g, c);
-    else
-        k_compress<OPS, UNROLL, false><<<grid, kThreads, 0, st>>>((const u32x4 *)G, (u32x4 *)R,
-                                                                  (u32x4 *)send, g, c);
+    return ((v == Vs ? (f(std::integral_constant<int, Vs>{}), true) : false) || ...);
 }
 
 template <typename OPS>
-void dispatch_compress(int unroll, bool nt, uint32_t grid, hipStream_t st, const void *G, void *R,
-                       void *send, const fixed_geom &g, float c)
+bool launch_compress(const covap::tuning &tn, const covap_plan_s *plan, const covap::call_range &cr,
+                     hipStream_t st, const void *G, void *R, void *send, float c)
 {
-    switch (unroll) {
-    case 1: launch_compress<OPS, 1>(nt, grid, st, G, R, send, g, c); break;
-    case 2: launch_compress<OPS, 2>(nt, grid, st, G, R, send, g, c); break;
-    case 8: launch_compress<OPS, 8>(nt, grid, st, G, R, send, g, c); break;
-    default: launch_compress<OPS, 4>(nt, grid, st, G, R, send, g, c); break;
-    }
-}
-
-constexpr int kDecompressUnroll = 4;  // vectors per thread per tile
-
-template <typename OPS, int WU>
-void launch_decompress(bool nt, uint32_t grid, hipStream_t st, const void *recv, void *out,
-                       const fixed_geom &g, int32_t N, int64_t stride, float n_f, float inv_n,
-                       int pow2)
-{
-    if (nt)
-        k_decompress<OPS, WU, true, kDecompressUnroll><<<grid, kThreads, 0, st>>>(
-            (const u32x4 *)recv, (u32x4 *)out, g, N, stride, n_f, inv_n, pow2);
-    else
-        k_decompress<OPS, WU, false, kDecompressUnroll><<<grid, kThreads, 0, st>>>(
-            (const u32x4 *)recv, (u32x4 *)out, g, N, stride, n_f, inv_n, pow2);
+    return pick<64, 128, 256, 512>(tn.compress_threads, [&](auto T) {
+        pick<1, 2, 4>(tn.compress_unroll, [&](auto U) {
+            pick<0, 1>(tn.nontemporal, [&](auto NT) {
+                uint32_t grid = 0;
+                const fixed_geom g = make_geom(plan, cr, T() * OPS::EPV * U(), &grid);
+                k_compress<OPS, T(), U(), NT() != 0><<<grid, T(), 0, st>>>(
+                    (const u32x4 *)G, (u32x4 *)R, (u32x4 *)send, g, c);
+            });
+        });
+    });
 }
 
 template <typename OPS>
-void dispatch_decompress(int wu, bool nt, uint32_t grid, hipStream_t st, const void *recv,
-                         void *out, const fixed_geom &g, int32_t N, int64_t stride, float n_f,
-                         float inv_n, int pow2)
+bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
+                       const covap::call_range &cr, hipStream_t st, const void *recv, void *out,
+                       int32_t N, int64_t stride)
 {
-    switch (wu) {
-    case 2: launch_decompress<OPS, 2>(nt, grid, st, recv, out, g, N, stride, n_f, inv_n, pow2); break;
-    case 4: launch_decompress<OPS, 4>(nt, grid, st, recv, out, g, N, stride, n_f, inv_n, pow2); break;
-    case 16: launch_decompress<OPS, 16>(nt, grid, st, recv, out, g, N, stride, n_f, inv_n, pow2); break;
-    default: launch_decompress<OPS, 8>(nt, grid, st, recv, out, g, N, stride, n_f, inv_n, pow2); break;
-    }
+    const int pow2 = (N & (N - 1)) == 0;
+    const float n_f = (float)N, inv_n = 1.0f / n_f;
+    return pick<64, 128, 256, 512>(tn.decompress_threads, [&](auto T) {
+        pick<1, 2>(tn.decompress_tile, [&](auto U) {
+            pick<2, 4, 8>(tn.decompress_unroll, [&](auto WU) {
+                pick<0, 1>(tn.nontemporal, [&](auto NT) {
+                    uint32_t grid = 0;
+                    const fixed_geom g = make_geom(plan, cr, T() * OPS::EPV * U(), &grid);
+                    k_decompress<OPS, T(), U(), WU(), NT() != 0><<<grid, T(), 0, st>>>(
+                        (const u32x4 *)recv, (u32x4 *)out, g, N, stride, n_f, inv_n, pow2);
+                });
+            });
+        });
+    });
 }
 
 }  // namespace
@@ -482,14 +475,11 @@ covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t b
     if (cr.sh_hi == cr.sh_lo) return COVAP_OK;
 
     const covap::tuning &tn = covap::tune();
-    const int unroll = tn.compress_unroll;
-    uint32_t grid = 0;
-    const fixed_geom g = make_geom(plan, cr, kThreads * plan->elems_per_vec * unroll, &grid);
     hipStream_t st = (hipStream_t)stream;
-    if (plan->opts.dtype == COVAP_F32)
-        dispatch_compress<ops_f32>(unroll, tn.nontemporal != 0, grid, st, grad, residual, send, g, ef_coeff);
-    else
-        dispatch_compress<ops_bf16>(unroll, tn.nontemporal != 0, grid, st, grad, residual, send, g, ef_coeff);
+    const bool ok = plan->opts.dtype == COVAP_F32
+                        ? launch_compress<ops_f32>(tn, plan, cr, st, grad, residual, send, ef_coeff)
+                        : launch_compress<ops_bf16>(tn, plan, cr, st, grad, residual, send, ef_coeff);
+    if (!ok) return fail(COVAP_EINVAL, "covap_compress: launch knobs select no kernel");
     return check_launch("covap_compress");
 }
 
@@ -516,18 +506,11 @@ covap_status_t covap_decompress(const covap_plan_t *plan, uint64_t step, int32_t
     if (cr.sh_hi == cr.sh_lo) return COVAP_OK;
 
     const covap::tuning &tn = covap::tune();
-    uint32_t grid = 0;
-    const fixed_geom g =
-        make_geom(plan, cr, kThreads * plan->elems_per_vec * kDecompressUnroll, &grid);
-    const int pow2 = (n_workers & (n_workers - 1)) == 0;
-    const float n_f = (float)n_workers, inv_n = 1.0f / n_f;
     hipStream_t st = (hipStream_t)stream;
-    if (plan->opts.dtype == COVAP_F32)
-        dispatch_decompress<ops_f32>(tn.decompress_unroll, tn.nontemporal != 0, grid, st, recv,
-                                     dense_out, g, n_workers, stride_elems, n_f, inv_n, pow2);
-    else
-        dispatch_decompress<ops_bf16>(tn.decompress_unroll, tn.nontemporal != 0, grid, st, recv,
-                                      dense_out, g, n_workers, stride_elems, n_f, inv_n, pow2);
+    const bool ok = plan->opts.dtype == COVAP_F32
+                        ? launch_decompress<ops_f32>(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems)
+                        : launch_decompress<ops_bf16>(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems);
+    if (!ok) return fail(COVAP_EINVAL, "covap_decompress: launch knobs select no kernel");
     return check_launch("covap_decompress");
 }
 
@@ -538,12 +521,12 @@ covap_status_t covap_probe_copy(void *dst, const void *src, size_t bytes, void *
         return fail(COVAP_EINVAL, "covap_probe_copy: pointers and size must be 16-byte multiples");
     if (bytes == 0) return COVAP_OK;
     const int64_t nvec = (int64_t)(bytes / 16);
-    const int64_t per = kThreads * 4;
+    const int64_t per = kProbeThreads * 4;
     const uint32_t grid = (uint32_t)((nvec + per - 1) / per);
     if (covap::tune().nontemporal)
-        k_copy<true><<<grid, kThreads, 0, (hipStream_t)stream>>>((u32x4 *)dst, (const u32x4 *)src, nvec);
+        k_copy<true><<<grid, kProbeThreads, 0, (hipStream_t)stream>>>((u32x4 *)dst, (const u32x4 *)src, nvec);
     else
-        k_copy<false><<<grid, kThreads, 0, (hipStream_t)stream>>>((u32x4 *)dst, (const u32x4 *)src, nvec);
+        k_copy<false><<<grid, kProbeThreads, 0, (hipStream_t)stream>>>((u32x4 *)dst, (const u32x4 *)src, nvec);
     return check_launch("covap_probe_copy");
 }
 
@@ -555,13 +538,13 @@ covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float
         return fail(COVAP_EINVAL, "covap_probe_triad: pointers 16-byte aligned, n a multiple of 4");
     if (n == 0) return COVAP_OK;
     const int64_t nvec = n / 4;
-    const int64_t per = kThreads * 4;
+    const int64_t per = kProbeThreads * 4;
     const uint32_t grid = (uint32_t)((nvec + per - 1) / per);
     if (covap::tune().nontemporal)
-        k_triad<true><<<grid, kThreads, 0, (hipStream_t)stream>>>((u32x4 *)a, (const u32x4 *)b,
+        k_triad<true><<<grid, kProbeThreads, 0, (hipStream_t)stream>>>((u32x4 *)a, (const u32x4 *)b,
                                                                   (const u32x4 *)c, s, nvec);
     else
-        k_triad<false><<<grid, kThreads, 0, (hipStream_t)stream>>>((u32x4 *)a, (const u32x4 *)b,
+        k_triad<false><<<grid, kProbeThreads, 0, (hipStream_t)stream>>>((u32x4 *)a, (const u32x4 *)b,
                                                                    (const u32x4 *)c, s, nvec);
     return check_launch("covap_probe_triad");
 }

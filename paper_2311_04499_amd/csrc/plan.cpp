@@ -285,35 +285,43 @@ covap_status_t covap_ef_coeff(float init_value, uint64_t num_steps, uint64_t asc
     return COVAP_OK;
 }
 
+namespace {
+struct knob {
+    const char *key;
+    int covap::tuning::*field;
+    int allowed[5];  // 0-terminated unless the knob allows 0 (then -1-terminated)
+};
+const knob kKnobs[] = {
+    {"compress_threads", &covap::tuning::compress_threads, {64, 128, 256, 512, -1}},
+    {"compress_unroll", &covap::tuning::compress_unroll, {1, 2, 4, -1, -1}},
+    {"decompress_threads", &covap::tuning::decompress_threads, {64, 128, 256, 512, -1}},
+    {"decompress_tile", &covap::tuning::decompress_tile, {1, 2, -1, -1, -1}},
+    {"decompress_unroll", &covap::tuning::decompress_unroll, {2, 4, 8, -1, -1}},
+    {"nontemporal", &covap::tuning::nontemporal, {0, 1, -1, -1, -1}},
+};
+}  // namespace
+
 covap_status_t covap_tune_set(const char *key, int32_t value)
 {
     clear_error();
     if (!key) return fail(COVAP_EINVAL, "covap_tune_set: null key");
-    tuning &t = tune();
-    if (!std::strcmp(key, "compress_unroll")) {
-        if (value != 1 && value != 2 && value != 4 && value != 8)
-            return fail(COVAP_EINVAL, "compress_unroll must be 1, 2, 4 or 8");
-        t.compress_unroll = value;
-    } else if (!std::strcmp(key, "decompress_unroll")) {
-        if (value != 2 && value != 4 && value != 8 && value != 16)
-            return fail(COVAP_EINVAL, "decompress_unroll must be 2, 4, 8 or 16");
-        t.decompress_unroll = value;
-    } else if (!std::strcmp(key, "nontemporal")) {
-        if (value != 0 && value != 1) return fail(COVAP_EINVAL, "nontemporal must be 0 or 1");
-        t.nontemporal = value;
-    } else {
-        return fail(COVAP_EINVAL, "covap_tune_set: unknown key");
+    for (const knob &k : kKnobs) {
+        if (std::strcmp(key, k.key)) continue;
+        for (int a : k.allowed)
+            if (a >= 0 && a == value) {
+                tune().*(k.field) = value;
+                return COVAP_OK;
+            }
+        return fail(COVAP_EINVAL, std::string("covap_tune_set: value not allowed for ") + key);
     }
-    return COVAP_OK;
+    return fail(COVAP_EINVAL, "covap_tune_set: unknown key");
 }
 
 int32_t covap_tune_get(const char *key)
 {
     if (!key) return -1;
-    const tuning &t = tune();
-    if (!std::strcmp(key, "compress_unroll")) return t.compress_unroll;
-    if (!std::strcmp(key, "decompress_unroll")) return t.decompress_unroll;
-    if (!std::strcmp(key, "nontemporal")) return t.nontemporal;
+    for (const knob &k : kKnobs)
+        if (!std::strcmp(key, k.key)) return tune().*(k.field);
     return -1;
 }
 

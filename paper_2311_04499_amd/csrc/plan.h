@@ -56,9 +56,12 @@ struct call_range {
 covap_status_t resolve(const covap_plan_s *plan, uint64_t step, int32_t bucket, call_range *out);
 
 struct tuning {
-    int compress_unroll = 4;    // 16-byte vectors per thread per tile: 1, 2, 4, 8
-    int decompress_unroll = 8;  // payload rows loaded before they are summed: 2, 4, 8, 16
-    int nontemporal = 1;        // 0 = plain loads/stores, 1 = streaming hints
+    int compress_threads = 64;     // workgroup size: 64, 128, 256, 512
+    int compress_unroll = 1;       // 16-byte vectors per thread per tile: 1, 2, 4
+    int decompress_threads = 64;   // workgroup size: 64, 128, 256, 512
+    int decompress_tile = 1;       // 16-byte vectors per thread per tile: 1, 2
+    int decompress_unroll = 4;     // payload rows loaded before they are summed: 2, 4, 8
+    int nontemporal = 1;           // 0 = plain loads/stores, 1 = streaming hints
 };
 tuning &tune();
 

@@ -144,17 +144,37 @@ def test_per_bucket_calls(B):
     run_iterations(B, wl, numel, 8192, 3, 2, 4, per_bucket=True, cap_bytes=100_000, c=0.5)
 
 
-@pytest.mark.parametrize("key,vals", [("compress_unroll", [1, 2, 8]), ("decompress_unroll", [2, 4, 16]),
-                                      ("nontemporal", [0])])
-def test_launch_shape_knobs(B, key, vals):
-    old = B.covap_tune_get(key)
+KNOBS = {"compress_threads": [64, 128, 256, 512], "compress_unroll": [1, 2, 4],
+         "decompress_threads": [64, 128, 256, 512], "decompress_tile": [1, 2],
+         "decompress_unroll": [2, 4, 8], "nontemporal": [0, 1]}
+
+
+@pytest.mark.parametrize("key", list(KNOBS))
+def test_launch_shape_knobs(B, key):
+    """Every launch shape the tuning knobs can select gives the same bits."""
+    old = {k: B.covap_tune_get(k) for k in KNOBS}
     try:
-        for v in vals:
+        for v in KNOBS[key]:
             B.covap_tune_set(key, v)
             wl = workloads.scaled_down(workloads.config(1), [100_003], 4096)
             run_iterations(B, wl, [100_003], 4096, 3, 5, 4)
+            run_iterations(B, wl, [9_001, 12_345], 1000, 5, 3, 6, per_bucket=True, cap_bytes=9000)
+            run_iterations(B, wl, [8 * 4096 + 9], 8192, 4, 3, 5, dtype=torch.bfloat16)
     finally:
-        B.covap_tune_set(key, old)
+        for k, v in old.items():
+            B.covap_tune_set(k, v)
+
+
+def test_largest_launch_shapes_together(B):
+    old = {k: B.covap_tune_get(k) for k in KNOBS}
+    try:
+        for k in KNOBS:
+            B.covap_tune_set(k, KNOBS[k][-1])
+        wl = workloads.scaled_down(workloads.config(1), [300_007], 16384)
+        run_iterations(B, wl, [300_007], 16384, 4, 9, 5)
+    finally:
+        for k, v in old.items():
+            B.covap_tune_set(k, v)
 
 
 @pytest.mark.parametrize("numel,S,K,N", [([100_003], 4096, 3, 4), ([7], 8, 2, 3), ([8 * 4096 + 9], 8192, 4, 5),
