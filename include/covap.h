@@ -195,8 +195,8 @@ covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float
  * MI355X).  Keys and allowed values:
  *   "compress_threads", "decompress_threads"  workgroup size: 64, 128, 256, 512
  *   "compress_unroll"    16-byte vectors per thread per tile: 1, 2, 4
- *   "decompress_tile"    16-byte vectors per thread per tile: 1, 2
- *   "decompress_unroll"  payload rows loaded before they are summed: 2, 4, 8
+ *   "decompress_tile"    16-byte vectors per thread per tile: 1, 2, 4
+ *   "decompress_unroll"  payload rows loaded before they are summed: 1, 2, 4, 8
  *   "nontemporal"        streaming cache hints on loads and stores: 0, 1
  * No knob changes any result bit.  EINVAL for an unknown key or value.  Global
  * to the process and not thread-safe against running calls. */

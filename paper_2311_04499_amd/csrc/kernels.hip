@@ -316,6 +316,36 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const u32x4 *__restrict
 
     const u32x4 *rp = recv + t.poff / EPV;
     const int64_t stride_vec = stride_elems / EPV;
+    if (UNROLL > 1 && t.n == TILE) {
+        // Full tile: walk the rows once for all UNROLL vector positions, so each
+        // visit to a row reads UNROLL * kThreads * 16 contiguous bytes.
+        typename OPS::acc_t acc[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) acc[u] = OPS::widen(ld16<NT>(rp + u * kThreads + tid));
+        int32_t w = 1;
+        for (; w + WU <= N; w += WU) {
+            u32x4 x[WU][UNROLL];
+#pragma unroll
+            for (int j = 0; j < WU; ++j) {
+                const u32x4 *row = rp + (int64_t)(w + j) * stride_vec + tid;
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) x[j][u] = ld16<NT>(row + u * kThreads);
+            }
+#pragma unroll
+            for (int j = 0; j < WU; ++j)
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) OPS::add(acc[u], x[j][u]);
+        }
+        for (; w < N; ++w) {
+            const u32x4 *row = rp + (int64_t)w * stride_vec + tid;
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) OPS::add(acc[u], ld16<NT>(row + u * kThreads));
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            st16<NT>(op + u * kThreads + tid, OPS::mean(acc[u], n_f, inv_n, pow2 != 0));
+        return;
+    }
 #pragma unroll 1
     for (int u = 0; u < UNROLL; ++u) {
         const int v = u * kThreads + tid;
@@ -434,8 +464,8 @@ bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
     const int pow2 = (N & (N - 1)) == 0;
     const float n_f = (float)N, inv_n = 1.0f / n_f;
     return pick<64, 128, 256, 512>(tn.decompress_threads, [&](auto T) {
-        pick<1, 2>(tn.decompress_tile, [&](auto U) {
-            pick<2, 4, 8>(tn.decompress_unroll, [&](auto WU) {
+        pick<1, 2, 4>(tn.decompress_tile, [&](auto U) {
+            pick<1, 2, 4, 8>(tn.decompress_unroll, [&](auto WU) {
                 pick<0, 1>(tn.nontemporal, [&](auto NT) {
                     uint32_t grid = 0;
                     const fixed_geom g = make_geom(plan, cr, T() * OPS::EPV * U(), &grid);

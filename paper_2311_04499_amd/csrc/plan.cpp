@@ -295,8 +295,8 @@ const knob kKnobs[] = {
     {"compress_threads", &covap::tuning::compress_threads, {64, 128, 256, 512, -1}},
     {"compress_unroll", &covap::tuning::compress_unroll, {1, 2, 4, -1, -1}},
     {"decompress_threads", &covap::tuning::decompress_threads, {64, 128, 256, 512, -1}},
-    {"decompress_tile", &covap::tuning::decompress_tile, {1, 2, -1, -1, -1}},
-    {"decompress_unroll", &covap::tuning::decompress_unroll, {2, 4, 8, -1, -1}},
+    {"decompress_tile", &covap::tuning::decompress_tile, {1, 2, 4, -1, -1}},
+    {"decompress_unroll", &covap::tuning::decompress_unroll, {1, 2, 4, 8, -1}},
     {"nontemporal", &covap::tuning::nontemporal, {0, 1, -1, -1, -1}},
 };
 }  // namespace

@@ -59,8 +59,8 @@ struct tuning {
     int compress_threads = 64;     // workgroup size: 64, 128, 256, 512
     int compress_unroll = 1;       // 16-byte vectors per thread per tile: 1, 2, 4
     int decompress_threads = 64;   // workgroup size: 64, 128, 256, 512
-    int decompress_tile = 1;       // 16-byte vectors per thread per tile: 1, 2
-    int decompress_unroll = 4;     // payload rows loaded before they are summed: 2, 4, 8
+    int decompress_tile = 1;       // 16-byte vectors per thread per tile: 1, 2, 4
+    int decompress_unroll = 1;     // payload rows loaded before they are summed: 1, 2, 4, 8
     int nontemporal = 1;           // 0 = plain loads/stores, 1 = streaming hints
 };
 tuning &tune();

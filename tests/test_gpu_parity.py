@@ -145,8 +145,8 @@ def test_per_bucket_calls(B):
 
 
 KNOBS = {"compress_threads": [64, 128, 256, 512], "compress_unroll": [1, 2, 4],
-         "decompress_threads": [64, 128, 256, 512], "decompress_tile": [1, 2],
-         "decompress_unroll": [2, 4, 8], "nontemporal": [0, 1]}
+         "decompress_threads": [64, 128, 256, 512], "decompress_tile": [1, 2, 4],
+         "decompress_unroll": [1, 2, 4, 8], "nontemporal": [0, 1]}
 
 
 @pytest.mark.parametrize("key", list(KNOBS))
