@@ -244,3 +244,33 @@ def test_argument_errors(B):
     with pytest.raises(B.CovapError):
         B.covap_decompress(plan, 0, send, G, n_workers=2, stride_elems=send.numel() // 2 - 1)
     torch.cuda.synchronize()
+
+
+def test_full_size_gpt2_medium_in_bench_configuration(B):
+    """The benchmark's own workload, shapes and launch configuration (payload
+    mode, default knobs), every element compared with the oracle: step 14 sends
+    the short last shard, step 3 does not; the residual carries over."""
+    wl = workloads.config(5)
+    plan, tab = make_plans(B, wl.numel, wl.shard_elems, wl.K)
+    D, N, K = wl.D, wl.n_workers, wl.K
+    stride = (plan.packed_elems_max + 3) // 4 * 4
+    recv = torch.empty(N, stride, device=DEV)
+    recv[1:] = workloads.payload_rows(wl, N - 1, stride, 0, DEV)
+    R = workloads.gradient(wl, 1, 0, DEV)                 # a non-trivial starting residual
+    Rc = to_np(R)
+    out = torch.empty(D, device=DEV)
+    for t in (14, 3):
+        G = workloads.gradient(wl, 0, t, DEV)
+        B.covap_compress(plan, t, G, R, recv[0])
+        B.covap_decompress(plan, t, recv, out, n_workers=N, stride_elems=stride)
+        torch.cuda.synchronize()
+        recv_c = to_np(recv)
+        recv_c[0, :] = np.nan
+        oracle.compress(tab, K, t, to_np(G), Rc, recv_c[0])
+        P = plan.packed_elems(t)
+        assert_same(to_np(recv[0])[:P], recv_c[0, :P], f"send t={t}")
+        assert_same(to_np(R), Rc, f"residual t={t}")
+        out_c = np.empty(D, np.float32)
+        recv_c[0, P:] = to_np(recv[0])[P:]
+        oracle.decompress(tab, K, t, recv_c, out_c)
+        assert_same(to_np(out), out_c, f"dense t={t}")
