@@ -63,11 +63,15 @@ typedef enum {
      * tensor boundaries; the last shard is short.  Buckets are greedy runs of
      * shards under `bucket_cap_bytes`. */
     COVAP_SHARD_FIXED = 0,
-    /* Sec. III-C: whole tensors are grouped into buckets of about
-     * `bucket_cap_bytes`; a bucket holding at least twice the reference element
-     * count (the median of the bucket sizes, or `ref_elems` when > 0) is cut
-     * evenly into floor(numel/ref) pieces, at most I.  Shards have different
-     * lengths. */
+    /* Sec. III-C: whole tensors are grouped, in order, into buckets
+     * (communication tensors) of about `bucket_cap_bytes`; a bucket holding at
+     * least twice the reference element count (the median of the bucket sizes, or
+     * `ref_elems` when > 0) is cut evenly into floor(numel/ref) pieces, at most I.
+     * Every piece is one shard for the filter; shards have different lengths.
+     * Each bucket starts on a 16-byte boundary of the arena (so total_elems may
+     * exceed the sum of the tensor counts by a few padding elements that no call
+     * reads or writes), and in the packed layout every sent shard starts on a
+     * 16-byte boundary too (elements in the gaps are never written or read). */
     COVAP_SHARD_MEDIAN = 1
 } covap_shard_mode_t;
 
@@ -85,6 +89,8 @@ typedef struct {
 
 /* Lay `n_tensors` tensors (element counts in tensor_numel [host]) end to end
  * in one flat arena, cut it into shards and buckets, and fix the interval.
+ * The arena offset of each tensor is the plan's to assign: ask for it with
+ * covap_plan_tensor_offset.
  * On success *out receives a plan to be released with covap_plan_free.
  * EINVAL: null argument, n_tensors < 1, a negative count, K < 1, bad shard
  * size or cap, total elements >= 2^40. */
@@ -112,9 +118,12 @@ int32_t covap_plan_is_selected(const covap_plan_t *plan, uint64_t step, int32_t 
  * (may be null to only count).  Returns how many there are. */
 int32_t covap_plan_selected(const covap_plan_t *plan, uint64_t step, int32_t *shard_ids,
                             int32_t cap);
-/* Elements sent at `step` by bucket b (b = -1: by all buckets). */
+/* Extent, in elements, of the packed range that bucket b's sent shards occupy
+ * at `step` (b = -1: the whole payload); 0 if it sends nothing.  With
+ * fixed-size shards this is the number of elements sent. */
 int64_t covap_plan_packed_elems(const covap_plan_t *plan, uint64_t step, int32_t bucket);
-/* Offset in the step's packed layout at which bucket b's payload starts. */
+/* Offset in the step's packed layout at which bucket b's payload starts
+ * (meaningful when covap_plan_packed_elems(step, b) > 0). */
 int64_t covap_plan_packed_base(const covap_plan_t *plan, uint64_t step, int32_t bucket);
 /* Largest covap_plan_packed_elems(step, -1) over all steps: the size to give
  * send buffers and the row stride of receive buffers. */
@@ -193,10 +202,10 @@ covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float
 
 /* Launch-shape knobs for tuning sweeps (the defaults are the measured best on
  * MI355X).  Keys and allowed values:
- *   "compress_threads", "decompress_threads"  workgroup size: 64, 128, 256, 512
+ *   "compress_threads", "decompress_threads"  workgroup size: 64, 256
  *   "compress_unroll"    16-byte vectors per thread per tile: 1, 2, 4
  *   "decompress_tile"    16-byte vectors per thread per tile: 1, 2, 4
- *   "decompress_unroll"  payload rows loaded before they are summed: 1, 2, 4, 8
+ *   "decompress_unroll"  payload rows loaded before they are summed: 1, 2, 4
  *   "nontemporal"        streaming cache hints on loads and stores: 0, 1
  * No knob changes any result bit.  EINVAL for an unknown key or value.  Global
  * to the process and not thread-safe against running calls. */

@@ -55,8 +55,10 @@ def lib():
         L.orc_plan_even_slices.argtypes = [C.c_int64, C.c_int32, C.c_int64, _i64p]
         L.orc_selected.restype = C.c_int32
         L.orc_selected.argtypes = [C.c_int64, C.c_uint64, C.c_int32]
-        L.orc_packed_elems.restype = C.c_int64
-        L.orc_packed_elems.argtypes = [_i64p, C.c_int64, C.c_int64, C.c_int32, C.c_uint64]
+        L.orc_packed_end.restype = C.c_int64
+        L.orc_packed_end.argtypes = [_i64p, C.c_int64, C.c_int32, C.c_uint64, C.c_int64]
+        L.orc_plan_group_layers.restype = C.c_int32
+        L.orc_plan_group_layers.argtypes = [_i64p, C.c_int32, C.c_int64, _i32p]
         L.orc_f32_to_bf16.restype = C.c_uint16
         L.orc_f32_to_bf16.argtypes = [C.c_float]
         L.orc_bf16_to_f32.restype = C.c_float
@@ -65,11 +67,11 @@ def lib():
             f = getattr(L, "orc_compress_" + name)
             f.restype = C.c_int64
             f.argtypes = [ptr, ptr, ptr, _i64p, _i64p, C.c_int64, C.c_int64, C.c_int32,
-                          C.c_uint64, C.c_float]
+                          C.c_uint64, C.c_float, C.c_int64]
             g = getattr(L, "orc_decompress_" + name)
             g.restype = None
             g.argtypes = [ptr, C.c_int32, C.c_int64, ptr, _i64p, _i64p, C.c_int64, C.c_int64,
-                          C.c_int32, C.c_uint64]
+                          C.c_int32, C.c_uint64, C.c_int64]
         L.orc_topk_f32.restype = C.c_int32
         L.orc_topk_f32.argtypes = [_f32p, _f32p, C.c_int64, C.c_int64, C.c_float, _f32p, _u32p]
         L.orc_ratio_from_ccr.restype = C.c_int32
@@ -93,14 +95,17 @@ def _chk(a: np.ndarray, dtype) -> np.ndarray:
 # ------------------------------------------------------------------ planner
 
 class ShardTable:
-    """Shard list of one arena: off[s], len[s], bucket[s]; D elements in all."""
+    """Shard list of one arena: off[s], len[s], bucket[s]; D elements in all.
+    `align`: every sent shard starts at a multiple of this many elements in the
+    packed layout (1 = plain concatenation)."""
 
-    def __init__(self, off, length, bucket, D, tensor_offsets=None):
+    def __init__(self, off, length, bucket, D, tensor_offsets=None, align=1):
         self.off = np.ascontiguousarray(off, dtype=np.int64)
         self.len = np.ascontiguousarray(length, dtype=np.int64)
         self.bucket = np.ascontiguousarray(bucket, dtype=np.int32)
         self.D = int(D)
         self.tensor_offsets = tensor_offsets
+        self.align = int(align)
 
     @property
     def n_shards(self) -> int:
@@ -131,6 +136,41 @@ def plan_fixed(tensor_numel, shard_elems: int, bucket_cap_elems: int) -> ShardTa
     return ShardTable(off[:n], ln[:n], bucket[:n], D, offs[:len(numel)])
 
 
+def plan_median(tensor_numel, bucket_cap_elems: int, interval: int, ref: int = 0,
+                align: int = 4) -> ShardTable:
+    """Sec. III-C: layers -> communication tensors (greedy, whole layers) ->
+    median-based even slicing capped at the interval.  Every communication
+    tensor starts at a multiple of `align` elements in the arena (each is a
+    buffer of its own in the framework the paper builds on), layers inside it
+    are tight; slices are multiples of `align` except the last of a tensor."""
+    numel = np.ascontiguousarray(tensor_numel, dtype=np.int64)
+    n = len(numel)
+    group_of = np.zeros(max(n, 1), dtype=np.int32)
+    n_groups = lib().orc_plan_group_layers(_p(numel, _i64p), n, bucket_cap_elems, _p(group_of, _i32p))
+    group_numel = np.zeros(n_groups, dtype=np.int64)
+    for i in range(n):
+        group_numel[group_of[i]] += numel[i]
+    parts, _ = median_parts(group_numel, ref, interval)
+    offs = np.zeros(n, dtype=np.int64)
+    off, ln, bucket = [], [], []
+    pos = 0
+    i = 0
+    for g in range(n_groups):
+        pos = (pos + align - 1) // align * align
+        start = pos
+        while i < n and group_of[i] == g:
+            offs[i] = pos
+            pos += int(numel[i])
+            i += 1
+        o = start
+        for l in even_slices(int(group_numel[g]), int(parts[g]), align):
+            off.append(o)
+            ln.append(int(l))
+            bucket.append(g)
+            o += int(l)
+    return ShardTable(off, ln, bucket, pos, offs, align)
+
+
 def median_parts(numel, ref: int, interval: int):
     numel = np.ascontiguousarray(numel, dtype=np.int64)
     parts = np.zeros(len(numel), dtype=np.int32)
@@ -149,14 +189,22 @@ def selected(s: int, t: int, interval: int) -> bool:
     return bool(lib().orc_selected(s, t, interval))
 
 
-def packed_elems(tab: ShardTable, interval: int, t: int, bucket: int = -1) -> int:
-    lo, hi = tab.bucket_range(bucket)
-    return int(lib().orc_packed_elems(_p(tab.len, _i64p), lo, hi, interval, t))
+def _packed_end(tab: ShardTable, interval: int, t: int, sh_hi: int) -> int:
+    return int(lib().orc_packed_end(_p(tab.len, _i64p), sh_hi, interval, t, tab.align))
 
 
 def packed_base(tab: ShardTable, interval: int, t: int, bucket: int) -> int:
+    """Where the bucket's first sent shard starts in the step's packed layout."""
     lo, _ = tab.bucket_range(bucket)
-    return int(lib().orc_packed_elems(_p(tab.len, _i64p), 0, lo, interval, t))
+    a = tab.align
+    return (_packed_end(tab, interval, t, lo) + a - 1) // a * a
+
+
+def packed_elems(tab: ShardTable, interval: int, t: int, bucket: int = -1) -> int:
+    """Extent of the packed range the bucket's sent shards occupy at step t
+    (for the whole arena: the payload size), 0 if it sends nothing."""
+    _, hi = tab.bucket_range(bucket)
+    return max(0, _packed_end(tab, interval, t, hi) - packed_base(tab, interval, t, bucket))
 
 
 # ------------------------------------------------------------------ hot path
@@ -178,7 +226,7 @@ def compress(tab: ShardTable, interval: int, t: int, G, R, send, c: float = 1.0,
     lo, hi = tab.bucket_range(bucket)
     f = getattr(lib(), "orc_compress_" + name)
     return int(f(_p(G, ptr), _p(R, ptr), _p(send, ptr), _p(tab.off, _i64p), _p(tab.len, _i64p),
-                 lo, hi, interval, t, c))
+                 lo, hi, interval, t, c, tab.align))
 
 
 def decompress(tab: ShardTable, interval: int, t: int, recv, out, bucket: int = -1) -> None:
@@ -190,7 +238,7 @@ def decompress(tab: ShardTable, interval: int, t: int, recv, out, bucket: int = 
     lo, hi = tab.bucket_range(bucket)
     f = getattr(lib(), "orc_decompress_" + name)
     f(_p(recv, ptr), recv.shape[0], recv.shape[1], _p(out, ptr), _p(tab.off, _i64p),
-      _p(tab.len, _i64p), lo, hi, interval, t)
+      _p(tab.len, _i64p), lo, hi, interval, t, tab.align)
 
 
 def topk(G, R, k: int, c: float = 1.0):

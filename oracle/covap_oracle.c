@@ -80,6 +80,28 @@ int32_t orc_plan_buckets(const int64_t *len, int64_t n_sh, int64_t cap_elems,
     return n_sh > 0 ? b + 1 : 0;
 }
 
+/* Communication tensors from layers (Sec. II-B, Sec. III-A, Sec. III-C): whole
+ * layers, in the given order, are merged greedily; a communication tensor is
+ * closed when the next layer would push it over cap_elems, and it always holds
+ * at least one layer (a layer larger than the cap is not split here).  Writes
+ * the communication-tensor id of each layer; returns how many there are.  The
+ * paper gives the target size only; the rule is this build's reading. */
+int32_t orc_plan_group_layers(const int64_t *numel, int32_t n, int64_t cap_elems,
+                              int32_t *group_of)
+{
+    int32_t g = 0;
+    int64_t fill = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        if (fill > 0 && fill + numel[i] > cap_elems) {
+            ++g;
+            fill = 0;
+        }
+        group_of[i] = g;
+        fill += numel[i];
+    }
+    return n > 0 ? g + 1 : 0;
+}
+
 /* Median-based tensor sharding (Sec. III-C): given the element counts of the
  * communication tensors, a tensor holding at least twice the reference count
  * is cut evenly into floor(numel/ref) parts, but never more than I parts.
@@ -148,13 +170,17 @@ int32_t orc_selected(int64_t s, uint64_t t, int32_t I)
     return ((a + b) % (uint64_t)I) == 0 ? 1 : 0;
 }
 
-/* Number of elements the selected shards in [sh_lo, sh_hi) hold at step t. */
-int64_t orc_packed_elems(const int64_t *len, int64_t sh_lo, int64_t sh_hi,
-                         int32_t I, uint64_t t)
+/* Packed layout of step t: the shards sent at t, in ascending order, one after
+ * the other; each starts at the next multiple of `align` elements (align = 1:
+ * plain concatenation; with equal-size shards that are multiples of `align`
+ * the two coincide).  Returns the running position after shards [0, sh_hi). */
+static int64_t round_up(int64_t x, int64_t align) { return (x + align - 1) / align * align; }
+
+int64_t orc_packed_end(const int64_t *len, int64_t sh_hi, int32_t I, uint64_t t, int64_t align)
 {
     int64_t p = 0;
-    for (int64_t s = sh_lo; s < sh_hi; ++s)
-        if (orc_selected(s, t, I)) p += len[s];
+    for (int64_t s = 0; s < sh_hi; ++s)
+        if (orc_selected(s, t, I)) p = round_up(p, align) + len[s];
     return p;
 }
 
@@ -195,19 +221,23 @@ float orc_bf16_to_f32(uint16_t h) { return bf16_to_f32(h); }
  *                                      coefficient c (one rounding: fmaf)
  *     selected shard:   send[p++] = a; R[i] = +0   (G' = a, so G - G' = 0)
  *     unselected shard: R[i] = a                   (G' = 0, Definition 1)
- * send is indexed from the start of the step's packed layout over ALL shards:
- * p starts at the packed size of shards [0, sh_lo).  Returns the number of
- * elements written to send.
+ * send is indexed from the start of the step's packed layout over ALL shards
+ * (see orc_packed_end): p starts where shards [0, sh_lo) left it.  Returns the
+ * number of elements written to send.
  */
 int64_t orc_compress_f32(const float *G, float *R, float *send,
-                         const int64_t *off, const int64_t *len,
-                         int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t,
-                         float c)
+                          const int64_t *off, const int64_t *len,
+                          int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t,
+                          float c, int64_t align)
 {
-    int64_t p = orc_packed_elems(len, 0, sh_lo, I, t);
-    int64_t p0 = p;
+    int64_t p = orc_packed_end(len, sh_lo, I, t, align);
+    int64_t written = 0;
     for (int64_t s = sh_lo; s < sh_hi; ++s) {
         int sel = orc_selected(s, t, I);
+        if (sel) {
+            p = round_up(p, align);
+            written += len[s];
+        }
         for (int64_t i = off[s]; i < off[s] + len[s]; ++i) {
             float a = fmaf(c, R[i], G[i]);
             if (sel) {
@@ -218,19 +248,23 @@ int64_t orc_compress_f32(const float *G, float *R, float *send,
             }
         }
     }
-    return p - p0;
+    return written;
 }
 
 /* Same with bf16 storage: operands widen to fp32, one fmaf, one RNE back. */
 int64_t orc_compress_bf16(const uint16_t *G, uint16_t *R, uint16_t *send,
                           const int64_t *off, const int64_t *len,
                           int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t,
-                          float c)
+                          float c, int64_t align)
 {
-    int64_t p = orc_packed_elems(len, 0, sh_lo, I, t);
-    int64_t p0 = p;
+    int64_t p = orc_packed_end(len, sh_lo, I, t, align);
+    int64_t written = 0;
     for (int64_t s = sh_lo; s < sh_hi; ++s) {
         int sel = orc_selected(s, t, I);
+        if (sel) {
+            p = round_up(p, align);
+            written += len[s];
+        }
         for (int64_t i = off[s]; i < off[s] + len[s]; ++i) {
             float a = fmaf(c, bf16_to_f32(R[i]), bf16_to_f32(G[i]));
             uint16_t h = f32_to_bf16(a);
@@ -242,7 +276,7 @@ int64_t orc_compress_bf16(const uint16_t *G, uint16_t *R, uint16_t *send,
             }
         }
     }
-    return p - p0;
+    return written;
 }
 
 /* ------------------------------------------------------------------ */
@@ -258,11 +292,13 @@ int64_t orc_compress_bf16(const uint16_t *G, uint16_t *R, uint16_t *send,
  */
 void orc_decompress_f32(const float *recv, int32_t N, int64_t stride,
                         float *out, const int64_t *off, const int64_t *len,
-                        int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t)
+                        int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t,
+                        int64_t align)
 {
-    int64_t q = orc_packed_elems(len, 0, sh_lo, I, t);
+    int64_t q = orc_packed_end(len, sh_lo, I, t, align);
     for (int64_t s = sh_lo; s < sh_hi; ++s) {
         int sel = orc_selected(s, t, I);
+        if (sel) q = round_up(q, align);
         for (int64_t i = off[s]; i < off[s] + len[s]; ++i) {
             if (sel) {
                 float acc = recv[q];
@@ -279,11 +315,13 @@ void orc_decompress_f32(const float *recv, int32_t N, int64_t stride,
 /* bf16 payloads: fp32 accumulator, one RNE at the end. */
 void orc_decompress_bf16(const uint16_t *recv, int32_t N, int64_t stride,
                          uint16_t *out, const int64_t *off, const int64_t *len,
-                         int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t)
+                         int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t,
+                         int64_t align)
 {
-    int64_t q = orc_packed_elems(len, 0, sh_lo, I, t);
+    int64_t q = orc_packed_end(len, sh_lo, I, t, align);
     for (int64_t s = sh_lo; s < sh_hi; ++s) {
         int sel = orc_selected(s, t, I);
+        if (sel) q = round_up(q, align);
         for (int64_t i = off[s]; i < off[s] + len[s]; ++i) {
             if (sel) {
                 float acc = bf16_to_f32(recv[q]);

@@ -199,12 +199,40 @@ __device__ __forceinline__ bool resolve_tile(const fixed_geom &g, tile_ref &t)
     return true;
 }
 
+// Variable-length shards (median sharding): the records of up to kMaxUnits
+// consecutive shards travel in the kernel arguments, so no device table is ever
+// allocated.  blockIdx.y picks the shard, blockIdx.x the tile inside it.
+constexpr int kMaxUnits = 96;
+
+struct table_geom {
+    int64_t off[kMaxUnits];   // arena offset of each shard (vector aligned)
+    int64_t poff[kMaxUnits];  // packed offset of each shard (vector aligned)
+    uint32_t len[kMaxUnits];  // elements
+    uint32_t unit_lo;         // global index of shard 0 of this launch
+    int32_t K;
+    int32_t first_sel;
+};
+
+template <int TILE>
+__device__ __forceinline__ bool resolve_tile(const table_geom &g, tile_ref &t)
+{
+    const uint32_t u = blockIdx.y;
+    const uint32_t sh_len = g.len[u];
+    const uint32_t in = blockIdx.x * (uint32_t)TILE;
+    if (in >= sh_len) return false;
+    const uint32_t left = sh_len - in;
+    t.n = (int32_t)(left < (uint32_t)TILE ? left : (uint32_t)TILE);
+    t.off = g.off[u] + (int64_t)in;
+    t.sel = (int32_t)((g.unit_lo + u) % (uint32_t)g.K) == g.first_sel;
+    t.poff = g.poff[u] + (int64_t)in;
+    return true;
+}
+
 // ---- compress: error feedback + filter + pack + residual -----------------------
 
-template <typename OPS, int kThreads, int UNROLL, bool NT>
+template <typename OPS, typename GEOM, int kThreads, int UNROLL, bool NT>
 __global__ __launch_bounds__(kThreads) void k_compress(const u32x4 *__restrict__ G, u32x4 *R,
-                                                       u32x4 *__restrict__ send, fixed_geom g,
-                                                       float c)
+                                                       u32x4 *__restrict__ send, GEOM g, float c)
 {
     constexpr int EPV = OPS::EPV;
     constexpr int TILE = kThreads * EPV * UNROLL;
@@ -287,9 +315,9 @@ __device__ __forceinline__ typename OPS::acc_t sum_rows(const u32x4 *p, int32_t 
     return acc;
 }
 
-template <typename OPS, int kThreads, int UNROLL, int WU, bool NT>
+template <typename OPS, typename GEOM, int kThreads, int UNROLL, int WU, bool NT>
 __global__ __launch_bounds__(kThreads) void k_decompress(const u32x4 *__restrict__ recv,
-                                                         u32x4 *__restrict__ out, fixed_geom g,
+                                                         u32x4 *__restrict__ out, GEOM g,
                                                          int32_t N, int64_t stride_elems,
                                                          float n_f, float inv_n, int pow2)
 {
@@ -440,17 +468,53 @@ bool pick(int v, F &&f)
     return ((v == Vs ? (f(std::integral_constant<int, Vs>{}), true) : false) || ...);
 }
 
+// Runs f(geom, grid) once per launch the call needs: one launch for fixed-size
+// shards, one per kMaxUnits shards otherwise.
+template <typename F>
+void for_each_launch(const covap_plan_s *plan, const covap::call_range &cr, int tile_elems, F &&f)
+{
+    if (plan->uniform) {
+        uint32_t grid = 0;
+        const fixed_geom g = make_geom(plan, cr, tile_elems, &grid);
+        f(g, dim3(grid));
+        return;
+    }
+    for (int32_t lo = cr.sh_lo; lo < cr.sh_hi; lo += kMaxUnits) {
+        const int32_t hi = lo + kMaxUnits < cr.sh_hi ? lo + kMaxUnits : cr.sh_hi;
+        table_geom g;
+        g.unit_lo = (uint32_t)lo;
+        g.K = plan->K;
+        g.first_sel = cr.first_sel;
+        int64_t longest = 0;
+        for (int32_t s = lo; s < hi; ++s) {
+            const covap_shard_rec &sh = plan->shards[(size_t)s];
+            g.off[s - lo] = sh.off;
+            g.poff[s - lo] = sh.packed_off;
+            g.len[s - lo] = (uint32_t)sh.len;
+            longest = sh.len > longest ? sh.len : longest;
+        }
+        for (int32_t u = hi - lo; u < kMaxUnits; ++u) {
+            g.off[u] = 0;
+            g.poff[u] = 0;
+            g.len[u] = 0u;
+        }
+        const uint32_t tiles = (uint32_t)((longest + tile_elems - 1) / tile_elems);
+        if (tiles) f(g, dim3(tiles, (uint32_t)(hi - lo)));
+    }
+}
+
 template <typename OPS>
 bool launch_compress(const covap::tuning &tn, const covap_plan_s *plan, const covap::call_range &cr,
                      hipStream_t st, const void *G, void *R, void *send, float c)
 {
-    return pick<64, 128, 256, 512>(tn.compress_threads, [&](auto T) {
+    return pick<64, 256>(tn.compress_threads, [&](auto T) {
         pick<1, 2, 4>(tn.compress_unroll, [&](auto U) {
             pick<0, 1>(tn.nontemporal, [&](auto NT) {
-                uint32_t grid = 0;
-                const fixed_geom g = make_geom(plan, cr, T() * OPS::EPV * U(), &grid);
-                k_compress<OPS, T(), U(), NT() != 0><<<grid, T(), 0, st>>>(
-                    (const u32x4 *)G, (u32x4 *)R, (u32x4 *)send, g, c);
+                for_each_launch(plan, cr, T() * OPS::EPV * U(), [&](const auto &g, dim3 grid) {
+                    typedef std::decay_t<decltype(g)> GEOM;
+                    k_compress<OPS, GEOM, T(), U(), NT() != 0><<<grid, T(), 0, st>>>(
+                        (const u32x4 *)G, (u32x4 *)R, (u32x4 *)send, g, c);
+                });
             });
         });
     });
@@ -463,14 +527,15 @@ bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
 {
     const int pow2 = (N & (N - 1)) == 0;
     const float n_f = (float)N, inv_n = 1.0f / n_f;
-    return pick<64, 128, 256, 512>(tn.decompress_threads, [&](auto T) {
+    return pick<64, 256>(tn.decompress_threads, [&](auto T) {
         pick<1, 2, 4>(tn.decompress_tile, [&](auto U) {
-            pick<1, 2, 4, 8>(tn.decompress_unroll, [&](auto WU) {
+            pick<1, 2, 4>(tn.decompress_unroll, [&](auto WU) {
                 pick<0, 1>(tn.nontemporal, [&](auto NT) {
-                    uint32_t grid = 0;
-                    const fixed_geom g = make_geom(plan, cr, T() * OPS::EPV * U(), &grid);
-                    k_decompress<OPS, T(), U(), WU(), NT() != 0><<<grid, T(), 0, st>>>(
-                        (const u32x4 *)recv, (u32x4 *)out, g, N, stride, n_f, inv_n, pow2);
+                    for_each_launch(plan, cr, T() * OPS::EPV * U(), [&](const auto &g, dim3 grid) {
+                        typedef std::decay_t<decltype(g)> GEOM;
+                        k_decompress<OPS, GEOM, T(), U(), WU(), NT() != 0><<<grid, T(), 0, st>>>(
+                            (const u32x4 *)recv, (u32x4 *)out, g, N, stride, n_f, inv_n, pow2);
+                    });
                 });
             });
         });
@@ -491,7 +556,6 @@ covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t b
     covap::call_range cr;
     const covap_status_t rs = covap::resolve(plan, step, bucket, &cr);
     if (rs != COVAP_OK) return rs;
-    if (!plan->uniform) return fail(COVAP_EUNSUPPORTED, "covap_compress: plan has no fixed-size shards");
     if (!grad || !residual || !send) return fail(COVAP_EINVAL, "covap_compress: null device pointer");
     if (!aligned16(grad) || !aligned16(residual) || !aligned16(send))
         return fail(COVAP_EINVAL, "covap_compress: device pointers must be 16-byte aligned");
@@ -521,7 +585,6 @@ covap_status_t covap_decompress(const covap_plan_t *plan, uint64_t step, int32_t
     covap::call_range cr;
     const covap_status_t rs = covap::resolve(plan, step, bucket, &cr);
     if (rs != COVAP_OK) return rs;
-    if (!plan->uniform) return fail(COVAP_EUNSUPPORTED, "covap_decompress: plan has no fixed-size shards");
     if (!recv || !dense_out) return fail(COVAP_EINVAL, "covap_decompress: null device pointer");
     if (!aligned16(recv) || !aligned16(dense_out))
         return fail(COVAP_EINVAL, "covap_decompress: device pointers must be 16-byte aligned");

@@ -65,26 +65,19 @@ static void assign_buckets(covap_plan_s *p, int64_t cap_elems)
     }
 }
 
-// Packed layout: at any step the selected shards (one residue class mod K)
-// are stored in ascending shard order, so a shard's packed offset is the
-// total length of the earlier shards of its own class -- the same number at
-// every step that sends it.  Also fills the per-bucket and whole-arena packed
-// sizes by residue.
+static int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// Packed layout: at any step the selected shards (one residue class mod K) are
+// stored in ascending shard order, each starting at the next multiple of the
+// 16-byte vector.  A shard's packed offset therefore depends only on the
+// earlier shards of its own class -- the same number at every step that sends
+// it.  With fixed-size shards no padding ever appears (only the arena's last
+// shard can be ragged).  Also fills the per-bucket and whole-arena packed
+// extents by residue.
 static void finish_tables(covap_plan_s *p)
 {
     const int32_t K = p->K;
-    std::vector<int64_t> class_fill((size_t)K, 0);
-    for (size_t s = 0; s < p->shards.size(); ++s) {
-        int64_t &f = class_fill[s % (size_t)K];
-        p->shards[s].packed_off = f;
-        f += p->shards[s].len;
-    }
-    p->packed_total.assign((size_t)K, 0);
-    p->packed_max = 0;
-    for (int32_t r = 0; r < K; ++r) {  // r = step mod K sends class (K - r) mod K
-        p->packed_total[r] = class_fill[(size_t)((K - r) % K)];
-        p->packed_max = std::max(p->packed_max, p->packed_total[r]);
-    }
+    const int64_t al = p->elems_per_vec;
     const int32_t nb = p->shards.empty() ? 0 : p->shards.back().bucket + 1;
     p->buckets.assign((size_t)nb, covap_bucket_rec());
     for (auto &b : p->buckets) {
@@ -93,18 +86,112 @@ static void finish_tables(covap_plan_s *p)
         b.packed_base.assign((size_t)K, 0);
         b.packed_elems.assign((size_t)K, 0);
     }
-    std::vector<int64_t> run((size_t)K, 0);  // packed elements so far, by class
+    std::vector<int64_t> end((size_t)K, 0);  // running end of each class's packed layout
     for (size_t s = 0; s < p->shards.size(); ++s) {
-        covap_bucket_rec &b = p->buckets[(size_t)p->shards[s].bucket];
-        if (b.sh_lo < 0) {
+        covap_shard_rec &sh = p->shards[s];
+        covap_bucket_rec &b = p->buckets[(size_t)sh.bucket];
+        if (b.sh_lo < 0) {  // first shard of its bucket: where would each class continue?
             b.sh_lo = (int32_t)s;
-            for (int32_t r = 0; r < K; ++r) b.packed_base[r] = run[(size_t)((K - r) % K)];
+            for (int32_t r = 0; r < K; ++r)  // r = step mod K sends class (K - r) mod K
+                b.packed_base[(size_t)r] = round_up(end[(size_t)((K - r) % K)], al);
         }
         b.sh_hi = (int32_t)s + 1;
-        const int32_t cls = (int32_t)(s % (size_t)K);
-        b.packed_elems[(size_t)((K - cls) % K)] += p->shards[s].len;
-        run[(size_t)cls] += p->shards[s].len;
+        const size_t cls = s % (size_t)K;
+        sh.packed_off = round_up(end[cls], al);
+        end[cls] = sh.packed_off + sh.len;
+        const size_t r = (size_t)((K - (int32_t)cls) % K);
+        b.packed_elems[r] = end[cls] - b.packed_base[r];
     }
+    p->packed_total.assign((size_t)K, 0);
+    p->packed_max = 0;
+    for (int32_t r = 0; r < K; ++r) {
+        p->packed_total[(size_t)r] = end[(size_t)((K - r) % K)];
+        p->packed_max = std::max(p->packed_max, p->packed_total[(size_t)r]);
+    }
+}
+
+// Fixed-size shards over a tightly packed arena.
+static void build_fixed(covap_plan_s *p, const int64_t *numel, int32_t n, int64_t cap_elems)
+{
+    p->uniform = true;
+    int64_t acc = 0;
+    for (int32_t i = 0; i < n; ++i) {  // tight packing, in the caller's order
+        p->tensor_off[(size_t)i] = acc;
+        acc += numel[i];
+    }
+    p->total_elems = acc;
+    const int64_t S = p->opts.shard_elems;
+    for (int64_t b = 0; b < acc; b += S) {
+        covap_shard_rec sh;
+        sh.off = b;
+        sh.len = std::min(S, acc - b);
+        sh.packed_off = 0;
+        sh.bucket = 0;
+        p->shards.push_back(sh);
+    }
+    assign_buckets(p, cap_elems);
+}
+
+// Sec. III-C.  Layers are merged, in order, into communication tensors of about
+// the cap (whole layers only; a layer above the cap stands alone).  The median of
+// their element counts (or the caller's reference count) decides the cut: a
+// tensor with at least twice that many elements is sliced evenly into
+// floor(numel / ref) pieces, never more than K.  Every piece is one shard for the
+// filter.  Each communication tensor starts on a 16-byte boundary of the arena
+// (they are separate buffers in the framework the paper builds on), layers inside
+// it are tight; pieces are multiples of the vector except a tensor's last.
+static void build_median(covap_plan_s *p, const int64_t *numel, int32_t n, int64_t cap_elems)
+{
+    p->uniform = false;
+    const int64_t al = p->elems_per_vec;
+    std::vector<int32_t> group_of((size_t)n);
+    std::vector<int64_t> group_numel;
+    int64_t fill = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        if (group_numel.empty() || (fill > 0 && fill + numel[i] > cap_elems)) {
+            group_numel.push_back(0);
+            fill = 0;
+        }
+        group_of[(size_t)i] = (int32_t)group_numel.size() - 1;
+        group_numel.back() += numel[i];
+        fill += numel[i];
+    }
+    int64_t ref = p->opts.ref_elems;
+    if (ref <= 0) {
+        std::vector<int64_t> sorted(group_numel);
+        std::sort(sorted.begin(), sorted.end());
+        const size_t m = sorted.size();
+        ref = (m % 2) ? sorted[m / 2] : (sorted[m / 2 - 1] + sorted[m / 2]) / 2;
+        if (ref <= 0) ref = 1;
+    }
+    int64_t pos = 0;
+    int32_t i = 0;
+    for (size_t g = 0; g < group_numel.size(); ++g) {
+        pos = round_up(pos, al);
+        const int64_t start = pos;
+        while (i < n && group_of[(size_t)i] == (int32_t)g) {
+            p->tensor_off[(size_t)i] = pos;
+            pos += numel[i];
+            ++i;
+        }
+        const int64_t total = group_numel[g];
+        int64_t parts = total / ref;
+        if (parts > p->K) parts = p->K;
+        if (parts < 2) parts = 1;
+        const int64_t piece = round_up((total + parts - 1) / parts, al);
+        int64_t left = total, o = start;
+        for (int64_t k = 0; k < parts && left > 0; ++k) {
+            covap_shard_rec sh;
+            sh.off = o;
+            sh.len = (k == parts - 1 || left < piece) ? left : piece;
+            sh.packed_off = 0;
+            sh.bucket = (int32_t)g;
+            p->shards.push_back(sh);
+            o += sh.len;
+            left -= sh.len;
+        }
+    }
+    p->total_elems = pos;
 }
 
 }  // namespace covap
@@ -134,16 +221,19 @@ covap_status_t covap_plan(const int64_t *tensor_numel, int32_t n_tensors,
         if (total >= ((int64_t)1 << 40))
             return fail(COVAP_EINVAL, "covap_plan: total elements >= 2^40");
     }
-    if (opts->mode == COVAP_SHARD_MEDIAN)
-        return fail(COVAP_EUNSUPPORTED, "covap_plan: median sharding is not built yet");
-    if (opts->mode != COVAP_SHARD_FIXED) return fail(COVAP_EINVAL, "covap_plan: unknown mode");
-    if (opts->shard_elems > ((int64_t)1 << 30))
-        return fail(COVAP_EINVAL, "covap_plan: shard_elems > 2^30");
-    if (opts->shard_elems <= 0 || opts->shard_elems % epv != 0)
-        return fail(COVAP_EINVAL,
-                    "covap_plan: shard_elems must be a positive multiple of the 16-byte vector");
-    if ((total + opts->shard_elems - 1) / opts->shard_elems > (int64_t)0x7fffffff / 2)
-        return fail(COVAP_EINVAL, "covap_plan: too many shards");
+    if (opts->mode != COVAP_SHARD_FIXED && opts->mode != COVAP_SHARD_MEDIAN)
+        return fail(COVAP_EINVAL, "covap_plan: unknown mode");
+    if (opts->mode == COVAP_SHARD_FIXED) {
+        if (opts->shard_elems > ((int64_t)1 << 30))
+            return fail(COVAP_EINVAL, "covap_plan: shard_elems > 2^30");
+        if (opts->shard_elems <= 0 || opts->shard_elems % epv != 0)
+            return fail(COVAP_EINVAL,
+                        "covap_plan: shard_elems must be a positive multiple of the 16-byte vector");
+        if ((total + opts->shard_elems - 1) / opts->shard_elems > (int64_t)0x7fffffff / 2)
+            return fail(COVAP_EINVAL, "covap_plan: too many shards");
+    } else if (opts->ref_elems < 0) {
+        return fail(COVAP_EINVAL, "covap_plan: ref_elems < 0");
+    }
 
     covap_plan_s *p = new (std::nothrow) covap_plan_s();
     if (!p) return fail(COVAP_ENOMEM, "covap_plan: out of host memory");
@@ -151,24 +241,17 @@ covap_status_t covap_plan(const int64_t *tensor_numel, int32_t n_tensors,
         p->opts = *opts;
         p->K = opts->K;
         p->elems_per_vec = epv;
-        p->total_elems = total;
-        p->uniform = true;
         p->tensor_off.resize((size_t)n_tensors);
-        int64_t acc = 0;
-        for (int32_t i = 0; i < n_tensors; ++i) {  // tight packing, in the caller's order
-            p->tensor_off[(size_t)i] = acc;
-            acc += tensor_numel[i];
-        }
-        const int64_t S = opts->shard_elems;
-        for (int64_t b = 0; b < total; b += S) {
-            covap_shard_rec sh;
-            sh.off = b;
-            sh.len = std::min(S, total - b);
-            sh.packed_off = 0;
-            sh.bucket = 0;
-            p->shards.push_back(sh);
-        }
-        assign_buckets(p, std::max<int64_t>(1, opts->bucket_cap_bytes / esz));
+        const int64_t cap_elems = std::max<int64_t>(1, opts->bucket_cap_bytes / esz);
+        if (opts->mode == COVAP_SHARD_FIXED)
+            build_fixed(p, tensor_numel, n_tensors, cap_elems);
+        else
+            build_median(p, tensor_numel, n_tensors, cap_elems);
+        for (const covap_shard_rec &sh : p->shards)
+            if (sh.len > ((int64_t)1 << 31) - 1) {
+                delete p;
+                return fail(COVAP_EINVAL, "covap_plan: a shard exceeds 2^31 - 1 elements");
+            }
         finish_tables(p);
     } catch (const std::bad_alloc &) {
         delete p;
@@ -292,11 +375,11 @@ struct knob {
     int allowed[5];  // 0-terminated unless the knob allows 0 (then -1-terminated)
 };
 const knob kKnobs[] = {
-    {"compress_threads", &covap::tuning::compress_threads, {64, 128, 256, 512, -1}},
+    {"compress_threads", &covap::tuning::compress_threads, {64, 256, -1, -1, -1}},
     {"compress_unroll", &covap::tuning::compress_unroll, {1, 2, 4, -1, -1}},
-    {"decompress_threads", &covap::tuning::decompress_threads, {64, 128, 256, 512, -1}},
+    {"decompress_threads", &covap::tuning::decompress_threads, {64, 256, -1, -1, -1}},
     {"decompress_tile", &covap::tuning::decompress_tile, {1, 2, 4, -1, -1}},
-    {"decompress_unroll", &covap::tuning::decompress_unroll, {1, 2, 4, 8, -1}},
+    {"decompress_unroll", &covap::tuning::decompress_unroll, {1, 2, 4, -1, -1}},
     {"nontemporal", &covap::tuning::nontemporal, {0, 1, -1, -1, -1}},
 };
 }  // namespace

@@ -56,11 +56,11 @@ struct call_range {
 covap_status_t resolve(const covap_plan_s *plan, uint64_t step, int32_t bucket, call_range *out);
 
 struct tuning {
-    int compress_threads = 64;     // workgroup size: 64, 128, 256, 512
+    int compress_threads = 64;     // workgroup size: 64, 256
     int compress_unroll = 1;       // 16-byte vectors per thread per tile: 1, 2, 4
-    int decompress_threads = 64;   // workgroup size: 64, 128, 256, 512
+    int decompress_threads = 64;   // workgroup size: 64, 256
     int decompress_tile = 1;       // 16-byte vectors per thread per tile: 1, 2, 4
-    int decompress_unroll = 1;     // payload rows loaded before they are summed: 1, 2, 4, 8
+    int decompress_unroll = 1;     // payload rows loaded before they are summed: 1, 2, 4
     int nontemporal = 1;           // 0 = plain loads/stores, 1 = streaming hints
 };
 tuning &tune();

@@ -62,12 +62,23 @@ def make_plans(B, numel, S, K, dtype=torch.float32, cap_bytes=25 << 20):
     return plan, tab
 
 
+def make_median_plans(B, numel, K, dtype=torch.float32, cap_bytes=25 << 20, ref=0):
+    code = B.COVAP_F32 if dtype == torch.float32 else B.COVAP_BF16
+    esz = 4 if dtype == torch.float32 else 2
+    plan = B.covap_plan(numel, 0, K, dtype=code, bucket_cap_bytes=cap_bytes,
+                        mode=B.COVAP_SHARD_MEDIAN, ref_elems=ref)
+    tab = oracle.plan_median(numel, max(1, cap_bytes // esz), K, ref, 16 // esz)
+    assert plan.total_elems == tab.D and plan.num_shards == tab.n_shards
+    assert plan.num_buckets == tab.n_buckets
+    return plan, tab
+
+
 def run_iterations(B, wl, numel, S, K, N, iters, dtype=torch.float32, c=1.0, per_bucket=False,
-                   cap_bytes=25 << 20, slack=0):
+                   cap_bytes=25 << 20, slack=0, plans=None):
     """Full-fidelity loop: every one of the N workers compresses its own gradient
     each iteration; their send buffers are the rows handed to decompress.  Both
     sides run the same loop on the same inputs and are compared after every call."""
-    plan, tab = make_plans(B, numel, S, K, dtype, cap_bytes)
+    plan, tab = plans if plans is not None else make_plans(B, numel, S, K, dtype, cap_bytes)
     D, P = tab.D, plan.packed_elems_max
     epv = 4 if dtype == torch.float32 else 8
     stride = (P + slack + epv - 1) // epv * epv
@@ -81,7 +92,10 @@ def run_iterations(B, wl, numel, S, K, N, iters, dtype=torch.float32, c=1.0, per
         recv_cpu = to_np(recv_gpu)
         buckets = range(tab.n_buckets) if per_bucket else [-1]
         for w in range(N):
-            G = workloads.gradient(wl, w, t, DEV, dtype)[:D].contiguous()
+            G = workloads.gradient(wl, w, t, DEV, dtype)
+            if G.numel() < D:                                   # arena with alignment padding
+                G = torch.cat([G, torch.ones(D - G.numel(), dtype=dtype, device=DEV)])
+            G = G[:D].contiguous()
             Gn = to_np(G)
             for b in buckets:
                 B.covap_compress(plan, t, G, R_gpu[w], recv_gpu[w], ef_coeff=c, bucket=b)
@@ -90,7 +104,7 @@ def run_iterations(B, wl, numel, S, K, N, iters, dtype=torch.float32, c=1.0, per
             assert_same(to_np(recv_gpu[w]), recv_cpu[w], f"send t={t} w={w}")
             assert_same(to_np(R_gpu[w]), R_cpu[w], f"residual t={t} w={w}")
         out_gpu = torch.full((D,), float("nan"), dtype=dtype, device=DEV)
-        out_cpu = np.zeros(D, np_dt)
+        out_cpu = to_np(out_gpu)                                # padding elements stay as they were
         for b in buckets:
             B.covap_decompress(plan, t, recv_gpu, out_gpu, bucket=b)
             oracle.decompress(tab, K, t, recv_cpu, out_cpu, bucket=b)
@@ -144,9 +158,9 @@ def test_per_bucket_calls(B):
     run_iterations(B, wl, numel, 8192, 3, 2, 4, per_bucket=True, cap_bytes=100_000, c=0.5)
 
 
-KNOBS = {"compress_threads": [64, 128, 256, 512], "compress_unroll": [1, 2, 4],
-         "decompress_threads": [64, 128, 256, 512], "decompress_tile": [1, 2, 4],
-         "decompress_unroll": [1, 2, 4, 8], "nontemporal": [0, 1]}
+KNOBS = {"compress_threads": [64, 256], "compress_unroll": [1, 2, 4],
+         "decompress_threads": [64, 256], "decompress_tile": [1, 2, 4],
+         "decompress_unroll": [1, 2, 4], "nontemporal": [0, 1]}
 
 
 @pytest.mark.parametrize("key", list(KNOBS))
@@ -274,3 +288,41 @@ def test_full_size_gpt2_medium_in_bench_configuration(B):
         recv_c[0, P:] = to_np(recv[0])[P:]
         oracle.decompress(tab, K, t, recv_c, out_c)
         assert_same(to_np(out), out_c, f"dense t={t}")
+
+
+# ------------------------------------------------------------------ median sharding (Sec. III-C)
+
+MEDIAN_CASES = [
+    # layers, K, cap_bytes, ref
+    ([41_011, 167_813, 1_074_805, 70_794, 76_697, 5_551], 4, 4, 55_903),      # Table V / 100, one layer per tensor
+    ([41_011, 167_813, 1_074_805, 70_794, 76_697, 5_551], 8, 4, 0),
+    ([1_003, 2_001, 30_007, 5, 4_099, 17, 90_001, 3], 3, 20_000, 0),           # ragged everywhere
+    ([257] * 300, 5, 4, 0),                                                    # more shards than one launch carries
+    ([100_000, 7], 16, 1 << 20, 1_000),                                        # capped at K pieces
+]
+
+
+@pytest.mark.parametrize("layers,K,cap,ref", MEDIAN_CASES)
+def test_median_sharded_plans(B, layers, K, cap, ref):
+    wl = workloads.scaled_down(workloads.config(3), layers, 4096)
+    plans = make_median_plans(B, layers, K, cap_bytes=cap, ref=ref)
+    run_iterations(B, wl, layers, 0, K, 3, 2 * K + 1, c=0.5, plans=plans, slack=3)
+    plans = make_median_plans(B, layers, K, cap_bytes=cap, ref=ref)
+    run_iterations(B, wl, layers, 0, K, 2, K + 1, per_bucket=True, plans=plans)
+
+
+def test_median_sharded_bf16_and_knobs(B):
+    layers = [1_003, 2_001, 30_007, 5, 4_099, 17, 90_001, 3]
+    wl = workloads.scaled_down(workloads.config(3), layers, 4096)
+    old = {k: B.covap_tune_get(k) for k in KNOBS}
+    try:
+        for k in KNOBS:
+            B.covap_tune_set(k, KNOBS[k][-1])
+        for dtype in (torch.float32, torch.bfloat16):
+            plans = make_median_plans(B, layers, 4, dtype=dtype, cap_bytes=40_000)
+            run_iterations(B, wl, layers, 0, 4, 5, 6, dtype=dtype, plans=plans)
+    finally:
+        for k, v in old.items():
+            B.covap_tune_set(k, v)
+    plans = make_median_plans(B, layers, 4, dtype=torch.bfloat16, cap_bytes=40_000)
+    run_iterations(B, wl, layers, 0, 4, 3, 9, dtype=torch.bfloat16, plans=plans, c=0.25)

@@ -87,6 +87,40 @@ def test_small_plans_match_oracle_exhaustively(B):
                                 assert plan.packed_base(t, b) == oracle.packed_base(tab, K, t, b)
 
 
+@pytest.mark.parametrize("layers,K,cap,ref", [
+    ([4101096, 16781312, 107480576, 7079424, 7669760, 555072], 100, 4, 5590260),   # Table V, Sec. III-C
+    ([4101096, 16781312, 107480576, 7079424, 7669760, 555072], 4, 4, 5590260),
+    ([4101096, 16781312, 107480576, 7079424, 7669760, 555072], 16, 4, 0),
+    ([1_003, 2_001, 30_007, 5, 4_099, 17, 90_001, 3], 3, 20_000, 0),
+    ([257] * 300, 5, 4, 0),
+    (None, 8, 25 << 20, 0),                                                        # VGG-19 layer list
+])
+def test_median_planner_tables_match_oracle(B, layers, K, cap, ref):
+    if layers is None:
+        layers = workloads.config(3).numel
+    for dtype, esz in ((B.COVAP_F32, 4), (B.COVAP_BF16, 2)):
+        plan = B.covap_plan(layers, 0, K, dtype=dtype, bucket_cap_bytes=cap,
+                            mode=B.COVAP_SHARD_MEDIAN, ref_elems=ref)
+        tab = oracle.plan_median(layers, max(1, cap // esz), K, ref, 16 // esz)
+        assert plan.total_elems == tab.D
+        assert plan.num_shards == tab.n_shards and plan.num_buckets == tab.n_buckets
+        for i in range(len(layers)):
+            assert plan.tensor_offset(i) == int(tab.tensor_offsets[i])
+        for s in range(tab.n_shards):
+            assert plan.shard(s) == (int(tab.off[s]), int(tab.len[s]), int(tab.bucket[s]))
+        pmax = 0
+        for t in range(2 * K):
+            assert plan.packed_elems(t) == oracle.packed_elems(tab, K, t)
+            pmax = max(pmax, plan.packed_elems(t))
+            for b in range(tab.n_buckets):
+                assert plan.packed_elems(t, b) == oracle.packed_elems(tab, K, t, b), (t, b)
+                if plan.packed_elems(t, b):
+                    assert plan.packed_base(t, b) == oracle.packed_base(tab, K, t, b), (t, b)
+        assert plan.packed_elems_max == pmax
+    if ref == 5590260 and K == 100:
+        assert plan.num_shards == 26                    # the count Sec. III-C prints
+
+
 def test_plan_argument_errors(B):
     for kwargs in (dict(shard_elems=0), dict(shard_elems=6), dict(K=0), dict(bucket_cap_bytes=0),
                    dict(dtype=7), dict(mode=9)):
@@ -150,4 +184,4 @@ def test_hot_path_rejects_bad_arguments_before_touching_the_gpu(B):
     with pytest.raises(B.CovapError):
         B.covap_tune_set("compress_unroll", 3)
     assert B.covap_tune_get("compress_unroll") in (1, 2, 4)
-    assert B.covap_tune_get("compress_threads") in (64, 128, 256, 512)
+    assert B.covap_tune_get("compress_threads") in (64, 256)

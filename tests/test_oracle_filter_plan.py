@@ -187,3 +187,45 @@ def test_ef_coefficient_closed_form():
     vals = [oracle.ef_coeff(0.3, n, 10, 0.05) for n in range(300)]
     assert all(b >= a for a, b in zip(vals, vals[1:]))
     assert math.isclose(vals[25], 0.3 + 2 * 0.05, rel_tol=1e-6)
+
+
+def test_median_plan_structure(golden):
+    """Sec. III-C on Table V's six communication tensors (one layer each here):
+    26 units; every tensor's pieces tile it exactly; pieces of one tensor are
+    even up to the alignment; starts are aligned; the filter then runs over
+    the global unit index."""
+    rows = golden("vgg19_tensors.txt")
+    numel = [int(r[1]) for r in rows]
+    want_parts = [int(r[2]) for r in rows]
+    tab = oracle.plan_median(numel, 1, 1000, 5590260, 4)
+    assert tab.n_shards == 26 and tab.n_buckets == 6
+    assert tab.D == sum(numel)                          # every count is a multiple of 4: no padding
+    for g, (n, parts) in enumerate(zip(numel, want_parts)):
+        lo, hi = tab.bucket_range(g)
+        assert hi - lo == parts
+        assert int(tab.len[lo:hi].sum()) == n
+        assert int(tab.off[lo]) == int(tab.tensor_offsets[g])
+        assert np.all(tab.off[lo + 1:hi] == tab.off[lo:hi - 1] + tab.len[lo:hi - 1])
+        assert np.all(tab.len[lo:hi - 1] == tab.len[lo]) and tab.len[hi - 1] <= tab.len[lo]
+        assert tab.len[lo] - n / parts < 5
+    assert np.all(tab.off % 4 == 0)
+    # balance: the sharded sizes differ by far less than the unsharded ones did
+    assert max(numel) / min(numel) > 190 and tab.len.max() / np.median(tab.len) < 1.5
+    # cap at the interval
+    tab4 = oracle.plan_median(numel, 1, 4, 5590260, 4)
+    assert [tab4.bucket_range(g)[1] - tab4.bucket_range(g)[0] for g in range(6)] == [1, 3, 4, 1, 1, 1]
+    # coverage still holds over the global unit index
+    for t0 in (0, 5):
+        assert sum(oracle.packed_elems(tab4, 4, t) for t in range(t0, t0 + 4)) >= tab4.D
+
+
+def test_median_plan_grouping_and_padding():
+    layers = [10, 3, 5, 100, 7, 2, 2, 2]
+    tab = oracle.plan_median(layers, 16, 2, 0, 4)
+    # greedy whole layers under 16 elements: [10,3] [5] [100] [7,2,2,2]
+    assert tab.n_buckets == 4
+    assert list(tab.tensor_offsets) == [0, 10, 16, 24, 124, 131, 133, 135]   # groups start on multiples of 4
+    assert tab.D == 137
+    # group sizes 13, 5, 100, 13 -> median 13 -> the third is cut into min(floor(100/13), 2) = 2 pieces
+    assert [int(x) for x in tab.len] == [13, 5, 52, 48, 13]
+    assert [int(x) for x in tab.off] == [0, 16, 24, 76, 124]

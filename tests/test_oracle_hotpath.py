@@ -371,3 +371,60 @@ def test_bf16_compress_and_average_against_torch():
         avg = (acc / N).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)[:n]
         want, _ = scatter_packed(tab, I, t, avg, tab.D)
         assert np.array_equal(out, want)
+
+
+# ------------------------------------------------------------------ variable-length shards
+
+def aligned_positions(tab, I, t):
+    """Independent statement of the packed layout: sent shards in ascending order,
+    each starting at the next multiple of tab.align."""
+    pos, p = {}, 0
+    for s in range(tab.n_shards):
+        if (s + t) % I == 0:
+            p = -(-p // tab.align) * tab.align
+            pos[s] = p
+            p += int(tab.len[s])
+    return pos, p
+
+
+@pytest.mark.parametrize("layers,I,cap,ref", [([1003, 2001, 30007, 5, 4099, 17, 90001, 3], 3, 5000, 0),
+                                             ([41011, 167813, 1074805, 70794, 76697, 5551], 4, 1, 55903)])
+def test_median_plan_compress_decompress_identities(layers, I, cap, ref):
+    tab = oracle.plan_median(layers, cap, I, ref, 4)
+    covered = np.zeros(tab.D, bool)
+    for s in range(tab.n_shards):
+        covered[int(tab.off[s]):int(tab.off[s] + tab.len[s])] = True
+    rng = np.random.default_rng(8)
+    R = np.zeros(tab.D, np.float32)
+    N = 3
+    for t in range(2 * I + 1):
+        G = rng.standard_normal(tab.D).astype(np.float32)
+        R_old = R.copy()
+        pos, end = aligned_positions(tab, I, t)
+        assert end == oracle.packed_elems(tab, I, t)
+        send = np.full(end + 8, np.nan, np.float32)
+        wrote = oracle.compress(tab, I, t, G, R, send, 0.5)
+        assert wrote == sum(int(tab.len[s]) for s in pos)
+        A = (G.astype(np.float64) + 0.5 * R_old.astype(np.float64)).astype(np.float32)
+        touched = np.zeros(end + 8, bool)
+        for s in range(tab.n_shards):
+            o, l = int(tab.off[s]), int(tab.len[s])
+            if s in pos:
+                assert np.array_equal(bits(send[pos[s]:pos[s] + l]), bits(A[o:o + l]))
+                assert not bits(R[o:o + l]).any()
+                touched[pos[s]:pos[s] + l] = True
+            else:
+                assert np.array_equal(bits(R[o:o + l]), bits(A[o:o + l]))
+        assert np.all(np.isnan(send[~touched]))                  # gaps and the tail stay untouched
+        assert np.array_equal(bits(R[~covered]), bits(R_old[~covered]))   # arena padding is never written
+        recv = np.stack([send * (w + 1) for w in range(N)])
+        out = np.full(tab.D, np.nan, np.float32)
+        oracle.decompress(tab, I, t, recv, out)
+        for s in range(tab.n_shards):
+            o, l = int(tab.off[s]), int(tab.len[s])
+            if s in pos:
+                x = send[pos[s]:pos[s] + l]
+                assert np.array_equal(out[o:o + l], ((x + x * 2) + x * 3) / np.float32(3))
+            else:
+                assert not bits(out[o:o + l]).any()
+        assert np.all(np.isnan(out[~covered]))
