@@ -33,6 +33,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
+    ap.add_argument("--shard-mode", choices=["fixed", "median"], default="fixed",
+                    help="fixed-size shards (default) or the median sharding of Sec. III-C")
     ap.add_argument("--tune", action="append", default=[], help="key=value launch knob")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-topk", action="store_true")
@@ -75,13 +77,16 @@ def main():
     esz = 4 if args.dtype == "f32" else 2
     epv = 16 // esz
     plan = B.covap_plan(wl.numel, wl.shard_elems, wl.K,
-                        dtype=B.COVAP_F32 if args.dtype == "f32" else B.COVAP_BF16)
-    D, N, K = wl.D, wl.n_workers, wl.K
+                        dtype=B.COVAP_F32 if args.dtype == "f32" else B.COVAP_BF16,
+                        mode=B.COVAP_SHARD_FIXED if args.shard_mode == "fixed" else B.COVAP_SHARD_MEDIAN)
+    D, N, K = plan.total_elems, wl.n_workers, wl.K
     P_max = plan.packed_elems_max
     stride = (P_max + epv - 1) // epv * epv
 
     # ---- inputs, resident in HBM before anything is timed
     ring = [workloads.gradient(wl, 0, i, dev, tdtype) for i in range(3)]
+    if D > wl.D:                               # median mode may pad bucket starts to 16 bytes
+        ring = [torch.cat([g, g.new_zeros(D - wl.D)]) for g in ring]
     residual = torch.zeros(D, dtype=tdtype, device=dev)
     recv = torch.empty(N, stride, dtype=tdtype, device=dev)
     if N > 1:
@@ -148,7 +153,8 @@ def main():
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": f"cfg{wl.cfg_id}:{wl.name}", "elements": D, "shard_elems": wl.shard_elems,
-                   "n_workers": N, "K": K, "mode": "payload"},
+                   "n_workers": N, "K": K, "mode": "payload", "sharding": args.shard_mode,
+                   "shards": plan.num_shards},
         "hbm_GB/s": round(hbm_gbs, 1), "hbm_frac": round(hbm_gbs / HBM_PEAK_GBS, 4),
         "overhead_us_per_iter": round(ms_step * 1e3, 1),
         "roofline": roofline, "kernels": kernels,
@@ -201,7 +207,8 @@ def main():
     if not args.no_cpu_baseline:
         import numpy as np
         import oracle
-        tab = oracle.plan_fixed(wl.numel, wl.shard_elems, (25 << 20) // esz)
+        tab = oracle.plan_fixed(wl.numel, wl.shard_elems, (25 << 20) // esz) if args.shard_mode == "fixed" \
+            else oracle.plan_median(wl.numel, (25 << 20) // esz, K, 0, epv)
         t = t_first + args.steps
         to_np = (lambda x: x.cpu().numpy()) if args.dtype == "f32" else \
                 (lambda x: x.cpu().view(torch.int16).numpy().view(np.uint16))

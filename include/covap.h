@@ -93,7 +93,7 @@ typedef struct {
  * covap_plan_tensor_offset.
  * On success *out receives a plan to be released with covap_plan_free.
  * EINVAL: null argument, n_tensors < 1, a negative count, K < 1, bad shard
- * size or cap, total elements >= 2^40. */
+ * size or cap, total elements >= 2^38. */
 covap_status_t covap_plan(const int64_t *tensor_numel, int32_t n_tensors,
                           const covap_plan_opts_t *opts, covap_plan_t **out);
 void covap_plan_free(covap_plan_t *plan);

@@ -218,8 +218,8 @@ covap_status_t covap_plan(const int64_t *tensor_numel, int32_t n_tensors,
     for (int32_t i = 0; i < n_tensors; ++i) {
         if (tensor_numel[i] < 0) return fail(COVAP_EINVAL, "covap_plan: negative element count");
         total += tensor_numel[i];
-        if (total >= ((int64_t)1 << 40))
-            return fail(COVAP_EINVAL, "covap_plan: total elements >= 2^40");
+        if (total >= ((int64_t)1 << 38))  // keeps every grid below 2^31 workgroups
+            return fail(COVAP_EINVAL, "covap_plan: total elements >= 2^38");
     }
     if (opts->mode != COVAP_SHARD_FIXED && opts->mode != COVAP_SHARD_MEDIAN)
         return fail(COVAP_EINVAL, "covap_plan: unknown mode");
