@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-topk", action="store_true")
     ap.add_argument("--no-probes", action="store_true")
+    ap.add_argument("--no-streamed", action="store_true",
+                    help="skip the per-bucket / HIP-graph / overlap measurements")
     return ap.parse_args()
 
 
@@ -202,6 +204,92 @@ def main():
             del ws, vals, idx, res2
         except B.CovapError as e:
             out["topk"] = {"error": str(e)}
+
+    # ---- per-bucket streamed mode: one launch per communication bucket, as a DDP hook
+    # would issue them while backward is still running (Sec. II-B); eager launches,
+    # HIP graphs (one per residue of the step), and overlap with a synthetic backward
+    if not args.no_streamed:
+        nb = plan.num_buckets
+
+        def per_bucket(t):
+            for b in range(nb):
+                B.covap_compress(plan, t, ring[0], residual, recv[0], bucket=b)
+            for b in range(nb):
+                B.covap_decompress(plan, t, recv, dense, n_workers=N, stride_elems=stride, bucket=b)
+
+        def timed(fn, reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            w0 = time.perf_counter()
+            e0.record()
+            for t in range(reps):
+                fn(t)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps, (time.perf_counter() - w0) * 1e6 / reps
+
+        reps = max(K, min(args.steps, 2 * K))
+        per_bucket(0)
+        eager_gpu_us, eager_wall_us = timed(per_bucket, reps)
+        sres = {"buckets": nb, "launches_per_step": 2 * nb,
+                "eager_us_per_step": round(eager_wall_us, 1),
+                "whole_arena_us_per_step": round(ms_step * 1e3, 1)}
+        try:
+            graphs = []
+            side = torch.cuda.Stream()
+            for r in range(K):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    per_bucket(r)
+                graphs.append(g)
+            for g in graphs:
+                g.replay()
+            _, graph_wall_us = timed(lambda t: graphs[t % K].replay(), reps)
+            sres["graph_us_per_step"] = round(graph_wall_us, 1)
+        except Exception as e:                              # reported, never hidden
+            sres["graph_error"] = repr(e)[:200]
+
+        # overlap: backward = one bf16 GEMM per bucket on the main stream; compress of
+        # bucket b runs on a side stream as soon as "its gradient is ready"
+        try:
+            m = 4096
+            xa = torch.randn(m, m, device=dev, dtype=torch.bfloat16)
+            xb = torch.randn(m, m, device=dev, dtype=torch.bfloat16)
+            xc = torch.empty(m, m, device=dev, dtype=torch.bfloat16)
+            side = torch.cuda.Stream()
+            ready = [torch.cuda.Event() for _ in range(nb)]
+            done = torch.cuda.Event()
+
+            def backward_only(t):
+                for b in range(nb):
+                    torch.mm(xa, xb, out=xc)
+
+            def compress_only(t):
+                for b in range(nb):
+                    B.covap_compress(plan, t, ring[0], residual, recv[0], bucket=b)
+
+            def overlapped(t):
+                for b in range(nb):
+                    torch.mm(xa, xb, out=xc)
+                    ready[b].record()
+                    side.wait_event(ready[b])
+                    B.covap_compress(plan, t, ring[0], residual, recv[0], bucket=b, stream=side)
+                done.record(side)
+                torch.cuda.current_stream().wait_event(done)
+
+            for f in (backward_only, compress_only, overlapped):
+                f(0)
+            bw_us, _ = timed(backward_only, reps)
+            co_us, _ = timed(compress_only, reps)
+            ov_us, _ = timed(overlapped, reps)
+            sres["overlap"] = {"backward_us": round(bw_us, 1), "compress_us": round(co_us, 1),
+                               "both_overlapped_us": round(ov_us, 1),
+                               "exposed_compress_us": round(ov_us - bw_us, 1),
+                               "hidden_frac": round(1.0 - max(ov_us - bw_us, 0.0) / co_us, 3)}
+            del xa, xb, xc
+        except Exception as e:
+            sres["overlap_error"] = repr(e)[:200]
+        out["streamed"] = sres
 
     # ---- CPU oracle on a bounded sample of the same workload (reported, not a target)
     if not args.no_cpu_baseline:

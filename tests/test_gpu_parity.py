@@ -326,3 +326,47 @@ def test_median_sharded_bf16_and_knobs(B):
             B.covap_tune_set(k, v)
     plans = make_median_plans(B, layers, 4, dtype=torch.bfloat16, cap_bytes=40_000)
     run_iterations(B, wl, layers, 0, 4, 3, 9, dtype=torch.bfloat16, plans=plans, c=0.25)
+
+
+# ------------------------------------------------------------------ HIP graph capture
+
+def test_per_bucket_calls_under_hip_graph_replay(B):
+    """Per-bucket launches captured once per residue of the step and replayed: every
+    replay, with eager work and synchronisations in between, must give the bits the
+    oracle gives for that step (the launches use no memset nodes and no allocation)."""
+    numel, S, K, N = [300_000, 12_345], 8192, 3, 4
+    wl = workloads.scaled_down(workloads.config(2), numel, S)
+    plan, tab = make_plans(B, numel, S, K, cap_bytes=100_000)
+    D = tab.D
+    stride = (plan.packed_elems_max + 3) // 4 * 4
+    G = torch.empty(D, device=DEV)
+    R = torch.zeros(D, device=DEV)
+    recv = torch.zeros(N, stride, device=DEV)
+    out = torch.zeros(D, device=DEV)
+    side = torch.cuda.Stream()
+    graphs = []
+    for r in range(K):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for b in range(tab.n_buckets):
+                B.covap_compress(plan, r, G, R, recv[0], ef_coeff=0.5, bucket=b)
+            for b in range(tab.n_buckets):
+                B.covap_decompress(plan, r, recv, out, bucket=b)
+        graphs.append(g)
+    R.zero_()
+    Rc = np.zeros(D, np.float32)
+    for t in range(3 * K + 1):
+        G.copy_(workloads.gradient(wl, 0, t, DEV))
+        recv.copy_(workloads.payload_rows(wl, N, stride, t, DEV, first_worker=0))
+        recv_c = to_np(recv)
+        torch.cuda.synchronize()
+        graphs[t % K].replay()
+        scratch = torch.randn(1000, device=DEV).sum().item()       # eager work between replays
+        torch.cuda.synchronize()
+        oracle.compress(tab, K, t, to_np(G), Rc, recv_c[0], 0.5)
+        out_c = np.zeros(D, np.float32)
+        oracle.decompress(tab, K, t, recv_c, out_c)
+        assert_same(to_np(recv[0]), recv_c[0], f"send t={t}")
+        assert_same(to_np(R), Rc, f"residual t={t}")
+        assert_same(to_np(out), out_c, f"dense t={t}")
+        assert scratch == scratch
