@@ -32,7 +32,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5")
-    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
+    ap.add_argument("--dtype", choices=["f32", "bf16", "bf16_res32"], default="f32",
+                    help="element type; bf16_res32 = bf16 gradients and payload, fp32 residual")
     ap.add_argument("--shard-mode", choices=["fixed", "median"], default="fixed",
                     help="fixed-size shards (default) or the median sharding of Sec. III-C")
     ap.add_argument("--tune", action="append", default=[], help="key=value launch knob")
@@ -76,10 +77,13 @@ def main():
     torch.cuda.set_device(0)
     wl = workloads.config(args.config)
     tdtype = torch.float32 if args.dtype == "f32" else torch.bfloat16
+    rdtype = torch.bfloat16 if args.dtype == "bf16" else torch.float32     # residual
     esz = 4 if args.dtype == "f32" else 2
+    rsz = 2 if args.dtype == "bf16" else 4
     epv = 16 // esz
     plan = B.covap_plan(wl.numel, wl.shard_elems, wl.K,
-                        dtype=B.COVAP_F32 if args.dtype == "f32" else B.COVAP_BF16,
+                        dtype={"f32": B.COVAP_F32, "bf16": B.COVAP_BF16,
+                               "bf16_res32": B.COVAP_BF16_RES32}[args.dtype],
                         mode=B.COVAP_SHARD_FIXED if args.shard_mode == "fixed" else B.COVAP_SHARD_MEDIAN)
     D, N, K = plan.total_elems, wl.n_workers, wl.K
     P_max = plan.packed_elems_max
@@ -89,7 +93,7 @@ def main():
     ring = [workloads.gradient(wl, 0, i, dev, tdtype) for i in range(3)]
     if D > wl.D:                               # median mode may pad bucket starts to 16 bytes
         ring = [torch.cat([g, g.new_zeros(D - wl.D)]) for g in ring]
-    residual = torch.zeros(D, dtype=tdtype, device=dev)
+    residual = torch.zeros(D, dtype=rdtype, device=dev)
     recv = torch.empty(N, stride, dtype=tdtype, device=dev)
     if N > 1:
         recv[1:] = workloads.payload_rows(wl, N - 1, stride, 0, dev, tdtype)
@@ -127,7 +131,7 @@ def main():
     tc_avg, td_avg = sum(tc) / len(tc), sum(td) / len(td)
     steps_t = [t_first + i for i in range(args.steps)]
     P_avg = sum(plan.packed_elems(t) for t in steps_t) / len(steps_t)
-    bytes_c = esz * (3 * D + P_avg)                      # read G, read R, write R, write packed
+    bytes_c = esz * (D + P_avg) + rsz * 2 * D            # read G, read R, write R, write packed
     bytes_d = esz * (N * P_avg + D)                      # read N rows, write dense
     grad_gbs = esz * D / (ms_step * 1e-3) / 1e9
     hbm_gbs = (bytes_c + bytes_d) / (ms_step * 1e-3) / 1e9
@@ -298,8 +302,8 @@ def main():
         tab = oracle.plan_fixed(wl.numel, wl.shard_elems, (25 << 20) // esz) if args.shard_mode == "fixed" \
             else oracle.plan_median(wl.numel, (25 << 20) // esz, K, 0, epv)
         t = t_first + args.steps
-        to_np = (lambda x: x.cpu().numpy()) if args.dtype == "f32" else \
-                (lambda x: x.cpu().view(torch.int16).numpy().view(np.uint16))
+        to_np = lambda x: x.cpu().numpy() if x.dtype == torch.float32 else \
+            x.cpu().view(torch.int16).numpy().view(np.uint16)
         Gn = to_np(ring[t % 3])
         Rn = to_np(residual).copy()
         recv_n = to_np(recv).copy()

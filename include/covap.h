@@ -24,7 +24,8 @@
  *    never keeps a pointer after the call returns.  [host] pointers are
  *    ordinary host memory.
  *  - Device buffers must be 16-byte aligned.  Elements are fp32, or bf16 stored
- *    as 16-bit patterns (computed in fp32, rounded to nearest-even once).
+ *    as 16-bit patterns (computed in fp32, rounded to nearest-even once); with
+ *    COVAP_BF16_RES32 the residual buffer alone is fp32.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Hot-path calls are asynchronous: COVAP_OK means "enqueued".
  *  - Indexing is 0-based for tensors, shards, buckets and iterations.
@@ -56,7 +57,14 @@ typedef enum {
     COVAP_EUNSUPPORTED = 5  /* valid request this build does not implement */
 } covap_status_t;
 
-typedef enum { COVAP_F32 = 0, COVAP_BF16 = 1 } covap_dtype_t;
+typedef enum {
+    COVAP_F32 = 0,        /* gradients, residual, payload, dense output: fp32 */
+    COVAP_BF16 = 1,       /* all four bf16 (computed in fp32, rounded once) */
+    /* gradients, payload and dense output bf16, residual fp32: Algorithm 1 with the
+     * bf16 rounding as the quantiser of line 3 -- a sent element leaves
+     * residual = A - bf16(A) (exact), a kept element leaves residual = A. */
+    COVAP_BF16_RES32 = 2
+} covap_dtype_t;
 
 typedef enum {
     /* The arena is cut into shards of `shard_elems` elements regardless of
@@ -154,7 +162,7 @@ covap_status_t covap_ef_coeff(float init_value, uint64_t num_steps, uint64_t asc
  *                      this call writes does not fit
  *   ef_coeff  the scheduler's coefficient c; A = fma(c, residual, grad)
  * `grad`, `residual` and `send` must not overlap.  Selected residual elements
- * become +0.0 whatever A was. */
+ * become +0.0 whatever A was (COVAP_BF16_RES32: A - bf16(A)). */
 covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t bucket,
                               const void *grad, void *residual, void *send,
                               int64_t send_cap_elems, float ef_coeff, void *stream);

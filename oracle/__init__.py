@@ -72,6 +72,9 @@ def lib():
             g.restype = None
             g.argtypes = [ptr, C.c_int32, C.c_int64, ptr, _i64p, _i64p, C.c_int64, C.c_int64,
                           C.c_int32, C.c_uint64, C.c_int64]
+        L.orc_compress_bf16_res32.restype = C.c_int64
+        L.orc_compress_bf16_res32.argtypes = [_u16p, _f32p, _u16p, _i64p, _i64p, C.c_int64, C.c_int64,
+                                              C.c_int32, C.c_uint64, C.c_float, C.c_int64]
         L.orc_topk_f32.restype = C.c_int32
         L.orc_topk_f32.argtypes = [_f32p, _f32p, C.c_int64, C.c_int64, C.c_float, _f32p, _u32p]
         L.orc_ratio_from_ccr.restype = C.c_int32
@@ -219,11 +222,17 @@ def _kind(a: np.ndarray):
 
 def compress(tab: ShardTable, interval: int, t: int, G, R, send, c: float = 1.0,
              bucket: int = -1) -> int:
-    """In place: R becomes the new residual, send receives the packed shards."""
+    """In place: R becomes the new residual, send receives the packed shards.
+    G/send uint16 (bf16 patterns) with R float32 selects the mixed-precision form."""
+    lo, hi = tab.bucket_range(bucket)
+    if G.dtype == np.uint16 and R.dtype == np.float32:
+        _chk(G, np.uint16), _chk(send, np.uint16), _chk(R, np.float32)
+        return int(lib().orc_compress_bf16_res32(
+            _p(G, _u16p), _p(R, _f32p), _p(send, _u16p), _p(tab.off, _i64p), _p(tab.len, _i64p),
+            lo, hi, interval, t, c, tab.align))
     name, ptr = _kind(G)
     for a in (G, R, send):
         _chk(a, G.dtype)
-    lo, hi = tab.bucket_range(bucket)
     f = getattr(lib(), "orc_compress_" + name)
     return int(f(_p(G, ptr), _p(R, ptr), _p(send, ptr), _p(tab.off, _i64p), _p(tab.len, _i64p),
                  lo, hi, interval, t, c, tab.align))

@@ -279,6 +279,41 @@ int64_t orc_compress_bf16(const uint16_t *G, uint16_t *R, uint16_t *send,
     return written;
 }
 
+/* Mixed precision: bf16 gradients and payload, fp32 residual.  Algorithm 1 with
+ * the quantiser in line 3 made explicit:
+ *     a  = G[i] + c * R[i]                 fp32, one rounding (fmaf)
+ *     sent shard:   G' = bf16(a) (round to nearest even); send[p++] = G';
+ *                   R[i] = a - G'          line 4: what rounding lost stays local
+ *                                          (the difference is exact in fp32)
+ *     kept shard:   R[i] = a               nothing is lost to rounding
+ */
+int64_t orc_compress_bf16_res32(const uint16_t *G, float *R, uint16_t *send,
+                                const int64_t *off, const int64_t *len,
+                                int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t,
+                                float c, int64_t align)
+{
+    int64_t p = orc_packed_end(len, sh_lo, I, t, align);
+    int64_t written = 0;
+    for (int64_t s = sh_lo; s < sh_hi; ++s) {
+        int sel = orc_selected(s, t, I);
+        if (sel) {
+            p = round_up(p, align);
+            written += len[s];
+        }
+        for (int64_t i = off[s]; i < off[s] + len[s]; ++i) {
+            float a = fmaf(c, R[i], bf16_to_f32(G[i]));
+            if (sel) {
+                uint16_t h = f32_to_bf16(a);
+                send[p++] = h;
+                R[i] = a - bf16_to_f32(h);
+            } else {
+                R[i] = a;
+            }
+        }
+    }
+    return written;
+}
+
 /* ------------------------------------------------------------------ */
 /* Decompress: N-way average + unpack (Sec. II-A AllReduce + DP mean)  */
 /* ------------------------------------------------------------------ */

@@ -52,6 +52,7 @@ __device__ __forceinline__ void st16(u32x4 *p, u32x4 v)
 // fp32 elements: four per 16-byte vector.
 struct ops_f32 {
     static constexpr int EPV = 4;
+    static constexpr bool MIXED = false;
     typedef float elem_t;
     typedef f32x4 acc_t;
 
@@ -96,6 +97,7 @@ struct ops_f32 {
 // fp32, one round-to-nearest-even back.
 struct ops_bf16 {
     static constexpr int EPV = 8;
+    static constexpr bool MIXED = false;
     typedef uint16_t elem_t;
     struct acc_t {
         float v[8];
@@ -151,6 +153,13 @@ struct ops_bf16 {
     }
     static __device__ __forceinline__ float widen1(uint16_t x) { return lo(x); }
     static __device__ __forceinline__ uint16_t narrow1(float x) { return (uint16_t)rne(x); }
+};
+
+// bf16 gradients and payload with an fp32 residual.  Decompress is that of
+// ops_bf16; compress has its own tile routine (compress_tile_mixed) because the
+// residual stream is twice as wide as the other two.
+struct ops_bf16_res32 : ops_bf16 {
+    static constexpr bool MIXED = true;
 };
 
 // ---- tile geometry -----------------------------------------------------------
@@ -307,6 +316,74 @@ __device__ __forceinline__ void compress_tile(const u32x4 *__restrict__ G, u32x4
     }
 }
 
+// Mixed precision tile: per step a thread owns four consecutive elements -- one
+// 8-byte vector of bf16 gradients and one 16-byte vector of fp32 residuals -- so
+// every load and store instruction of a wave still covers one contiguous run.
+// A sent element leaves residual = A - bf16(A), the part rounding dropped
+// (exact: both lie in the same or adjacent binade and share the low bits).
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <int kThreads, int UNROLL, bool NT>
+__device__ __forceinline__ void compress_tile_mixed(const uint16_t *__restrict__ G, float *R,
+                                                    uint16_t *__restrict__ send,
+                                                    const tile_ref &t, float c)
+{
+    constexpr int SLOTS = 2 * UNROLL;  // 4-element slots per thread; tile = kThreads * 8 * UNROLL
+    const int tid = threadIdx.x;
+    const u32x2 *gp = (const u32x2 *)(G + t.off);
+    f32x4 *rp = (f32x4 *)(R + t.off);
+    u32x2 *sp = (u32x2 *)(send + t.poff);
+    const int nq = t.n / 4;
+#pragma unroll
+    for (int u = 0; u < SLOTS; ++u) {
+        const int q = u * kThreads + tid;
+        if (q < nq) {
+            u32x2 g;
+            f32x4 r;
+            if constexpr (NT) {
+                g = __builtin_nontemporal_load(gp + q);
+                r = __builtin_nontemporal_load(rp + q);
+            } else {
+                g = gp[q];
+                r = rp[q];
+            }
+            f32x4 a;
+            a.x = __builtin_fmaf(c, r.x, ops_bf16::lo(g.x));
+            a.y = __builtin_fmaf(c, r.y, ops_bf16::hi(g.x));
+            a.z = __builtin_fmaf(c, r.z, ops_bf16::lo(g.y));
+            a.w = __builtin_fmaf(c, r.w, ops_bf16::hi(g.y));
+            if (t.sel) {
+                u32x2 h;
+                h.x = ops_bf16::pack(a.x, a.y);
+                h.y = ops_bf16::pack(a.z, a.w);
+                a.x -= ops_bf16::lo(h.x);
+                a.y -= ops_bf16::hi(h.x);
+                a.z -= ops_bf16::lo(h.y);
+                a.w -= ops_bf16::hi(h.y);
+                if constexpr (NT)
+                    __builtin_nontemporal_store(h, sp + q);
+                else
+                    sp[q] = h;
+            }
+            if constexpr (NT)
+                __builtin_nontemporal_store(a, rp + q);
+            else
+                rp[q] = a;
+        }
+    }
+    const int rem = t.n - nq * 4;
+    if (tid < rem) {
+        const int64_t e = (int64_t)nq * 4 + tid;
+        float a = __builtin_fmaf(c, R[t.off + e], ops_bf16::lo(G[t.off + e]));
+        if (t.sel) {
+            const uint16_t h = (uint16_t)ops_bf16::rne(a);
+            send[t.poff + e] = h;
+            a -= ops_bf16::lo(h);
+        }
+        R[t.off + e] = a;
+    }
+}
+
 template <typename OPS, typename GEOM, int kThreads, int UNROLL, bool NT>
 __global__ __launch_bounds__(kThreads) void k_compress(const u32x4 *__restrict__ G, u32x4 *R,
                                                        u32x4 *__restrict__ send, GEOM g, float c)
@@ -314,7 +391,10 @@ __global__ __launch_bounds__(kThreads) void k_compress(const u32x4 *__restrict__
     constexpr int TILE = kThreads * OPS::EPV * UNROLL;
     tile_ref t;
     if (!resolve_tile<TILE>(g, t)) return;
-    compress_tile<OPS, kThreads, UNROLL, NT>(G, R, send, t, c);
+    if constexpr (OPS::MIXED)
+        compress_tile_mixed<kThreads, UNROLL, NT>((const uint16_t *)G, (float *)R, (uint16_t *)send, t, c);
+    else
+        compress_tile<OPS, kThreads, UNROLL, NT>(G, R, send, t, c);
 }
 
 // ---- decompress: N-way mean + unpack + zero fill --------------------------------
@@ -634,17 +714,23 @@ covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t b
     if (send_cap_elems < cr.packed_base + cr.packed_elems)
         return fail(COVAP_EINVAL, "covap_compress: send buffer too small for this step");
     const int64_t esz = plan->opts.dtype == COVAP_F32 ? 4 : 2;
+    const int64_t rsz = plan->opts.dtype == COVAP_BF16 ? 2 : 4;  // residual element size
     const int64_t abytes = plan->total_elems * esz, sbytes = send_cap_elems * esz;
-    if (overlap(grad, abytes, residual, abytes) || overlap(grad, abytes, send, sbytes) ||
-        overlap(residual, abytes, send, sbytes))
+    const int64_t rbytes = plan->total_elems * rsz;
+    if (overlap(grad, abytes, residual, rbytes) || overlap(grad, abytes, send, sbytes) ||
+        overlap(residual, rbytes, send, sbytes))
         return fail(COVAP_EINVAL, "covap_compress: grad, residual and send must not overlap");
     if (cr.sh_hi == cr.sh_lo) return COVAP_OK;
 
     const covap::tuning &tn = covap::tune();
     hipStream_t st = (hipStream_t)stream;
-    const bool ok = plan->opts.dtype == COVAP_F32
-                        ? launch_compress<ops_f32>(tn, plan, cr, st, grad, residual, send, ef_coeff)
-                        : launch_compress<ops_bf16>(tn, plan, cr, st, grad, residual, send, ef_coeff);
+    bool ok;
+    if (plan->opts.dtype == COVAP_F32)
+        ok = launch_compress<ops_f32>(tn, plan, cr, st, grad, residual, send, ef_coeff);
+    else if (plan->opts.dtype == COVAP_BF16)
+        ok = launch_compress<ops_bf16>(tn, plan, cr, st, grad, residual, send, ef_coeff);
+    else
+        ok = launch_compress<ops_bf16_res32>(tn, plan, cr, st, grad, residual, send, ef_coeff);
     if (!ok) return fail(COVAP_EINVAL, "covap_compress: launch knobs select no kernel");
     return check_launch("covap_compress");
 }

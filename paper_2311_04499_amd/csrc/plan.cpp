@@ -209,7 +209,7 @@ covap_status_t covap_plan(const int64_t *tensor_numel, int32_t n_tensors,
     if (n_tensors < 1) return fail(COVAP_EINVAL, "covap_plan: n_tensors < 1");
     if (opts->K < 1) return fail(COVAP_EINVAL, "covap_plan: K < 1");
     if (opts->reserved != 0) return fail(COVAP_EINVAL, "covap_plan: reserved must be 0");
-    if (opts->dtype != COVAP_F32 && opts->dtype != COVAP_BF16)
+    if (opts->dtype != COVAP_F32 && opts->dtype != COVAP_BF16 && opts->dtype != COVAP_BF16_RES32)
         return fail(COVAP_EINVAL, "covap_plan: unknown dtype");
     if (opts->bucket_cap_bytes <= 0) return fail(COVAP_EINVAL, "covap_plan: bucket_cap_bytes <= 0");
     const int32_t epv = opts->dtype == COVAP_F32 ? 4 : 8;

@@ -370,3 +370,94 @@ def test_per_bucket_calls_under_hip_graph_replay(B):
         assert_same(to_np(R), Rc, f"residual t={t}")
         assert_same(to_np(out), out_c, f"dense t={t}")
         assert scratch == scratch
+
+
+# ------------------------------------------------------------------ bf16 gradients, fp32 residual
+
+@pytest.mark.parametrize("numel,S,K,c", [([100_003], 4096, 3, 1.0), ([7], 8, 2, 0.5), ([8 * 4096 + 9], 8192, 4, 0.3),
+                                         ([768 * 768, 3072 * 768 + 5], 1 << 18, 6, 1.0)])
+def test_mixed_precision_bf16_with_fp32_residual(B, numel, S, K, c):
+    wl = workloads.scaled_down(workloads.config(4), numel, S)
+    plan = B.covap_plan(numel, S, K, dtype=B.COVAP_BF16_RES32)
+    tab = oracle.plan_fixed(numel, S, (25 << 20) // 2)
+    D, N = tab.D, 3
+    stride = (plan.packed_elems_max + 7) // 8 * 8
+    R = torch.zeros(D, dtype=torch.float32, device=DEV)
+    Rc = np.zeros(D, np.float32)
+    old = {k: B.covap_tune_get(k) for k in ("compress_threads", "compress_unroll", "nontemporal")}
+    try:
+        for t in range(2 * K + 1):
+            B.covap_tune_set("compress_threads", (64, 256)[t % 2])
+            B.covap_tune_set("compress_unroll", (1, 2, 4)[t % 3])
+            B.covap_tune_set("nontemporal", (t // 2) % 2)
+            G = workloads.gradient(wl, 0, t, DEV, torch.bfloat16)
+            recv = torch.full((N, stride), float("nan"), dtype=torch.bfloat16, device=DEV)
+            recv_c = to_np(recv)
+            B.covap_compress(plan, t, G, R, recv[0], ef_coeff=c)
+            oracle.compress(tab, K, t, to_np(G), Rc, recv_c[0], c)
+            torch.cuda.synchronize()
+            assert_same(to_np(recv[0]), recv_c[0], f"send t={t}")
+            assert_same(to_np(R), Rc, f"residual t={t}")
+            recv[1:] = workloads.payload_rows(wl, N - 1, stride, t, DEV, torch.bfloat16)
+            recv_c = to_np(recv)
+            out = torch.zeros(D, dtype=torch.bfloat16, device=DEV)
+            out_c = np.zeros(D, np.uint16)
+            B.covap_decompress(plan, t, recv, out)
+            oracle.decompress(tab, K, t, recv_c, out_c)
+            torch.cuda.synchronize()
+            assert_same(to_np(out), out_c, f"dense t={t}")
+    finally:
+        for k, v in old.items():
+            B.covap_tune_set(k, v)
+
+
+def test_mixed_precision_on_median_shards(B):
+    layers = [1_003, 2_001, 30_007, 5, 4_099, 17, 90_001, 3]
+    wl = workloads.scaled_down(workloads.config(3), layers, 4096)
+    K = 4
+    plan = B.covap_plan(layers, 0, K, dtype=B.COVAP_BF16_RES32, bucket_cap_bytes=40_000,
+                        mode=B.COVAP_SHARD_MEDIAN)
+    tab = oracle.plan_median(layers, 20_000, K, 0, 8)
+    D = tab.D
+    assert plan.total_elems == D
+    R = torch.zeros(D, device=DEV)
+    Rc = np.zeros(D, np.float32)
+    stride = (plan.packed_elems_max + 7) // 8 * 8
+    for t in range(2 * K + 1):
+        G = workloads.gradient(wl, 0, t, DEV, torch.bfloat16)
+        G = torch.cat([G, torch.ones(D - G.numel(), dtype=torch.bfloat16, device=DEV)])
+        send = torch.full((stride,), float("nan"), dtype=torch.bfloat16, device=DEV)
+        sc = to_np(send)
+        B.covap_compress(plan, t, G, R, send, ef_coeff=0.5)
+        oracle.compress(tab, K, t, to_np(G), Rc, sc, 0.5)
+        torch.cuda.synchronize()
+        assert_same(to_np(send), sc, f"send t={t}")
+        assert_same(to_np(R), Rc, f"residual t={t}")
+
+
+def test_scheduler_driven_run(B):
+    """A whole schedule of the error-feedback scheduler (Sec. III-D): the
+    coefficient comes from covap_ef_coeff on one side and the oracle's formula on
+    the other, step by step, while it climbs from 0.25 to 1."""
+    numel, S, K, N = [150_001], 4096, 4, 2
+    wl = workloads.scaled_down(workloads.config(1), numel, S)
+    plan, tab = make_plans(B, numel, S, K)
+    D = tab.D
+    stride = (plan.packed_elems_max + 3) // 4 * 4
+    R = torch.zeros(D, device=DEV)
+    Rc = np.zeros(D, np.float32)
+    seen = set()
+    for t in range(26):
+        c = B.covap_ef_coeff(0.25, t, 3, 0.125)
+        cc = oracle.ef_coeff(0.25, t, 3, 0.125)
+        assert np.float32(c) == np.float32(cc)
+        seen.add(c)
+        G = workloads.gradient(wl, 0, t, DEV)
+        send = torch.zeros(stride, device=DEV)
+        sc = np.zeros(stride, np.float32)
+        B.covap_compress(plan, t, G, R, send, ef_coeff=c)
+        oracle.compress(tab, K, t, to_np(G), Rc, sc, cc)
+        torch.cuda.synchronize()
+        assert_same(to_np(send), sc, f"send t={t}")
+        assert_same(to_np(R), Rc, f"residual t={t}")
+    assert min(seen) == 0.25 and max(seen) == 1.0 and len(seen) == 7

@@ -428,3 +428,57 @@ def test_median_plan_compress_decompress_identities(layers, I, cap, ref):
             else:
                 assert not bits(out[o:o + l]).any()
         assert np.all(np.isnan(out[~covered]))
+
+
+# ------------------------------------------------------------------ bf16 gradients, fp32 residual
+
+def bf16_bits(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().view(torch.int16).numpy().view(np.uint16).copy()
+
+
+def test_mixed_precision_residual_keeps_the_rounding_error():
+    """Algorithm 1 with bf16 rounding as the quantiser: sent = bf16(A) (checked
+    against torch's cast), residual = A - sent exactly, kept shards hold A in full
+    fp32 precision."""
+    tab = oracle.plan_fixed([4096 * 3 + 40], 1024, 1 << 30)
+    I = 3
+    g = torch.Generator().manual_seed(5)
+    R = np.zeros(tab.D, np.float32)
+    for t in range(2 * I + 1):
+        Gt = (torch.randn(tab.D, generator=g) * 1e-3).to(torch.bfloat16)
+        R_old = R.copy()
+        send = np.full(tab.D, 0xffff, np.uint16)
+        n = oracle.compress(tab, I, t, bf16_bits(Gt), R, send, 0.5)
+        A = (Gt.double().numpy() + 0.5 * R_old.astype(np.float64)).astype(np.float32)
+        m = keep_mask(tab, I, t, tab.D)
+        dense, p = scatter_packed(tab, I, t, send, tab.D)
+        assert p == n
+        want_h = bf16_bits(torch.from_numpy(A).to(torch.bfloat16))
+        assert np.array_equal(dense[m], want_h[m])
+        sent_f32 = (dense.astype(np.uint32) << 16).view(np.float32)
+        assert np.array_equal(bits(R[m]), bits((A - sent_f32)[m]))
+        assert np.array_equal(sent_f32[m] + R[m], A[m])              # nothing is lost: exact
+        assert np.all(np.abs(R[m]) <= np.abs(A[m]) * 2.0 ** -8 + 1e-45)
+        assert np.array_equal(bits(R[~m]), bits(A[~m]))
+
+
+def test_mixed_precision_conservation_integer_data():
+    """Integers up to a few thousand do not fit bf16's 8-bit significand, so the
+    payload is rounded -- and still, with c = 1, everything sent plus the residual
+    equals the sum of all gradients exactly."""
+    tab = oracle.plan_fixed([3000, 500, 77], 128, 1 << 30)
+    I, T = 4, 13
+    R = np.zeros(tab.D, np.float32)
+    total_sent = np.zeros(tab.D, np.float64)
+    total_grad = np.zeros(tab.D, np.float64)
+    rounded = 0
+    for t in range(T):
+        Gt = workloads.integer_valued(tab.D, seed=300 + t, lo=-200, hi=200).to(torch.bfloat16)
+        total_grad += Gt.double().numpy()
+        send = np.zeros(tab.D, np.uint16)
+        oracle.compress(tab, I, t, bf16_bits(Gt), R, send)
+        dense, _ = scatter_packed(tab, I, t, send, tab.D)
+        total_sent += (dense.astype(np.uint32) << 16).view(np.float32)
+        rounded += int((R[keep_mask(tab, I, t, tab.D)] != 0).sum())
+    assert np.array_equal(total_sent + R, total_grad)
+    assert rounded > 0                                               # the case is not vacuous
