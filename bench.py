@@ -209,6 +209,51 @@ def main():
         except B.CovapError as e:
             out["topk"] = {"error": str(e)}
 
+    # ---- Random-k (k = 1 %) and FP16 contrast kernels on the same gradient buffers
+    if not args.no_topk and args.dtype == "f32":
+        def timed_us(fn, reps=10):
+            for t in range(2):
+                fn(t)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for t in range(reps):
+                fn(t)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps
+
+        try:
+            res2 = torch.zeros(D, dtype=torch.float32, device=dev)
+            k1 = -(-D // 100)
+            g = torch.Generator(device=dev)
+            g.manual_seed(workloads.seed_for(wl.cfg_id, 0, 0, stream=2))
+            # distinct coordinates from a shared seed: one per stride-100 cell
+            ridx = (torch.arange(k1, device=dev, dtype=torch.int64) * 100 +
+                    torch.randint(0, 100, (k1,), generator=g, device=dev)).clamp_(max=D - 1)
+            ridx = torch.unique(ridx).to(torch.int32)
+            rvals = torch.empty(ridx.numel(), dtype=torch.float32, device=dev)
+            us = timed_us(lambda t: B.randk_compress(ring[t % 3], res2, ridx, rvals, stream=stream))
+            out["randk"] = {"k": int(ridx.numel()), "us_per_iter": round(us, 1),
+                            "vs_covap_compress": round(us / (tc_avg * 1e3), 2)}
+            half = torch.empty(D, dtype=torch.float16, device=dev)
+            us = timed_us(lambda t: B.fp16_compress(ring[t % 3], res2, half, stream=stream))
+            out["fp16"] = {"compress_us_per_iter": round(us, 1),
+                           "vs_covap_compress": round(us / (tc_avg * 1e3), 2)}
+            del half, res2, rvals, ridx
+            if "topk" in out and "k" in out["topk"]:
+                kk = out["topk"]["k"]
+                sv = torch.randn(N, kk, device=dev)
+                si = torch.stack([torch.sort(torch.randperm(D, device=dev)[:kk]).values.to(torch.int32)
+                                  for _ in range(min(N, 4))])
+                si = si.repeat((N + si.shape[0] - 1) // si.shape[0], 1)[:N].contiguous()
+                us = timed_us(lambda t: B.sparse_decompress(sv, si, dense, stream=stream), reps=5)
+                out["topk"]["decompress_us_per_iter"] = round(us, 1)
+                out["topk"]["compress_plus_decompress_vs_covap"] = round(
+                    (out["topk"]["us_per_iter"] + us) / (ms_step * 1e3), 2)
+                del sv, si
+        except B.CovapError as e:
+            out["contrast_error"] = str(e)
+
     # ---- per-bucket streamed mode: one launch per communication bucket, as a DDP hook
     # would issue them while backward is still running (Sec. II-B); eager launches,
     # HIP graphs (one per residue of the step), and overlap with a synthetic backward

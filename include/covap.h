@@ -198,6 +198,42 @@ covap_status_t topk_compress(const void *grad, void *residual, int64_t n, int64_
                              uint32_t *out_idx, void *workspace, size_t ws_bytes,
                              void *stream);
 
+/* ---- further contrast points without data dependencies (Sec. II-C, Table III) --- */
+
+/* Random-k sparsifier with error feedback.  The k coordinates are the caller's
+ * to draw (from a seed all workers share, so every worker sends the same set):
+ *   idx [device] k indices, all distinct, each < n
+ *   A = fma(c, residual, grad) over n fp32 elements; out_vals[j] = A[idx[j]];
+ *   residual [device] becomes A with the sent coordinates set to +0.0
+ * EINVAL: k < 0, k > n, n >= 2^32, null or misaligned pointer. */
+covap_status_t randk_compress(const void *grad, void *residual, int64_t n, const uint32_t *idx,
+                              int64_t k, float ef_coeff, void *out_vals, void *stream);
+
+/* FP16 quantiser with error feedback over n fp32 elements:
+ *   A = fma(c, residual, grad); out_half[i] = fp16(A[i]) (round to nearest even);
+ *   residual[i] = A[i] - fp16(A[i]).  All pointers [device], 16-byte aligned. */
+covap_status_t fp16_compress(const void *grad, void *residual, int64_t n, float ef_coeff,
+                             void *out_half, void *stream);
+
+/* Mean of n_workers fp16 payload rows (row w at recv + w * stride_elems halves):
+ *   dense_out[i] = (sum over w = 0..n_workers-1, in that order, in fp32) / n_workers
+ * dense_out [device] n fp32 elements.  EINVAL: stride < n, stride not a
+ * multiple of 8 when n_workers > 1, null or misaligned pointer. */
+covap_status_t fp16_decompress(const void *recv, int32_t n_workers, int64_t stride_elems,
+                               int64_t n, void *dense_out, void *stream);
+
+/* Mean of n_workers sparse payloads, k (value, index) pairs each (row w at
+ * vals + w * stride_elems and idx + w * stride_elems), as produced by
+ * topk_compress or randk_compress:
+ *   dense_out = 0; for w = 0..n_workers-1 in order: dense_out[idx] += val;
+ *   dense_out /= n_workers
+ * Indices inside one row must be distinct (rows may overlap freely).  The
+ * additions into one element happen in worker order, so the result is
+ * deterministic.  dense_out [device] n fp32 elements, fully written. */
+covap_status_t sparse_decompress(const void *vals, const uint32_t *idx, int32_t n_workers,
+                                 int64_t k, int64_t stride_elems, int64_t n, void *dense_out,
+                                 void *stream);
+
 /* ---- measurement helpers ------------------------------------------------ */
 
 /* Plain streaming kernels used to measure the achievable HBM rate next to the

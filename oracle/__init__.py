@@ -77,6 +77,18 @@ def lib():
                                               C.c_int32, C.c_uint64, C.c_float, C.c_int64]
         L.orc_topk_f32.restype = C.c_int32
         L.orc_topk_f32.argtypes = [_f32p, _f32p, C.c_int64, C.c_int64, C.c_float, _f32p, _u32p]
+        L.orc_randk_f32.restype = C.c_int32
+        L.orc_randk_f32.argtypes = [_f32p, _f32p, C.c_int64, _u32p, C.c_int64, C.c_float, _f32p]
+        L.orc_f32_to_f16.restype = C.c_uint16
+        L.orc_f32_to_f16.argtypes = [C.c_float]
+        L.orc_f16_to_f32.restype = C.c_float
+        L.orc_f16_to_f32.argtypes = [C.c_uint16]
+        L.orc_fp16_compress.restype = None
+        L.orc_fp16_compress.argtypes = [_f32p, _f32p, C.c_int64, C.c_float, _u16p]
+        L.orc_fp16_mean.restype = None
+        L.orc_fp16_mean.argtypes = [_u16p, C.c_int32, C.c_int64, C.c_int64, _f32p]
+        L.orc_sparse_mean.restype = None
+        L.orc_sparse_mean.argtypes = [_f32p, _u32p, C.c_int32, C.c_int64, C.c_int64, C.c_int64, _f32p]
         L.orc_ratio_from_ccr.restype = C.c_int32
         L.orc_ratio_from_ccr.argtypes = [C.c_double, _i32p]
         L.orc_ef_coeff.restype = C.c_float
@@ -261,6 +273,47 @@ def topk(G, R, k: int, c: float = 1.0):
     if rc != 0:
         raise ValueError("orc_topk_f32: bad n or k")
     return vals[:k], idx[:k]
+
+
+def randk(G, R, idx, c: float = 1.0):
+    """In place on R.  idx: uint32, distinct.  Returns vals[k]."""
+    _chk(G, np.float32), _chk(R, np.float32), _chk(idx, np.uint32)
+    vals = np.zeros(max(len(idx), 1), np.float32)
+    if lib().orc_randk_f32(_p(G, _f32p), _p(R, _f32p), G.shape[0], _p(idx, _u32p), len(idx), c,
+                           _p(vals, _f32p)) != 0:
+        raise ValueError("orc_randk_f32: bad n or k")
+    return vals[:len(idx)]
+
+
+def fp16_compress(G, R, c: float = 1.0):
+    """In place on R.  Returns the fp16 payload as uint16 bit patterns."""
+    _chk(G, np.float32), _chk(R, np.float32)
+    out = np.zeros(G.shape[0], np.uint16)
+    lib().orc_fp16_compress(_p(G, _f32p), _p(R, _f32p), G.shape[0], c, _p(out, _u16p))
+    return out
+
+
+def fp16_mean(recv, n: int):
+    _chk(recv, np.uint16)
+    out = np.zeros(n, np.float32)
+    lib().orc_fp16_mean(_p(recv, _u16p), recv.shape[0], recv.shape[1], n, _p(out, _f32p))
+    return out
+
+
+def sparse_mean(vals, idx, k: int, n: int):
+    _chk(vals, np.float32), _chk(idx, np.uint32)
+    out = np.zeros(n, np.float32)
+    lib().orc_sparse_mean(_p(vals, _f32p), _p(idx, _u32p), vals.shape[0], k, vals.shape[1], n,
+                          _p(out, _f32p))
+    return out
+
+
+def f32_to_f16(x: float) -> int:
+    return int(lib().orc_f32_to_f16(x))
+
+
+def f16_to_f32(h: int) -> float:
+    return float(lib().orc_f16_to_f32(h))
 
 
 def f32_to_bf16(x: float) -> int:

@@ -428,6 +428,105 @@ int32_t orc_topk_f32(const float *G, float *R, int64_t n, int64_t k, float c,
 }
 
 /* ------------------------------------------------------------------ */
+/* Random-k and FP16 (contrast points without data dependency; Sec. II-C, */
+/* Table III), each under Algorithm 1's error feedback, and their means  */
+/* ------------------------------------------------------------------ */
+
+/* Random-k: the k coordinates idx[] (distinct) are given -- all workers draw
+ * them from a shared seed.  a = G + c*R; vals[j] = a[idx[j]]; R = a with the
+ * sent coordinates set to +0. */
+int32_t orc_randk_f32(const float *G, float *R, int64_t n, const uint32_t *idx, int64_t k,
+                      float c, float *vals)
+{
+    if (n < 0 || k < 0 || k > n) return -1;
+    for (int64_t i = 0; i < n; ++i) R[i] = fmaf(c, R[i], G[i]);
+    for (int64_t j = 0; j < k; ++j) {
+        vals[j] = R[idx[j]];
+        R[idx[j]] = 0.0f;
+    }
+    return 0;
+}
+
+/* fp32 -> fp16, round to nearest even, with gradual underflow and overflow to
+ * infinity (IEEE 754 binary16); own implementation. */
+static uint16_t f32_to_f16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    uint32_t mag = u & 0x7fffffffu;
+    if (mag > 0x7f800000u) return (uint16_t)(sign | 0x7e00u);            /* NaN */
+    if (mag >= 0x47800000u) return (uint16_t)(sign | 0x7c00u);           /* >= 65536 (and Inf) -> Inf */
+    if (mag < 0x33000000u) return sign;                                  /* < 2^-25 -> 0 */
+    int32_t e = (int32_t)(mag >> 23) - 127;                              /* unbiased exponent */
+    uint32_t m = (mag & 0x7fffffu) | 0x800000u;                          /* 24-bit significand */
+    int shift = e >= -14 ? 13 : 13 + (-14 - e);                          /* bits to drop */
+    uint32_t keep = m >> shift;
+    uint32_t drop = m & ((1u << shift) - 1u);
+    uint32_t half = 1u << (shift - 1);
+    if (drop > half || (drop == half && (keep & 1u))) keep += 1u;
+    uint32_t h;
+    if (e >= -14)
+        h = ((uint32_t)(e + 15) << 10) + (keep - 0x400u);                /* carry may bump the exponent: intended */
+    else
+        h = keep;                                                        /* subnormal (or the smallest normal on carry) */
+    return (uint16_t)(sign | h);                                         /* 0x7c00 on overflow by rounding */
+}
+
+static float f16_to_f32(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t e = (h >> 10) & 0x1fu, m = h & 0x3ffu;
+    float v;
+    if (e == 0x1fu) {
+        uint32_t u = sign | 0x7f800000u | (m << 13);
+        memcpy(&v, &u, 4);
+        return v;
+    }
+    v = e ? ldexpf((float)(m | 0x400u), (int)e - 25) : ldexpf((float)m, -24);
+    return sign ? -v : v;
+}
+
+uint16_t orc_f32_to_f16(float f) { return f32_to_f16(f); }
+float orc_f16_to_f32(uint16_t h) { return f16_to_f32(h); }
+
+/* FP16 quantiser: a = G + c*R; out[i] = fp16(a); R[i] = a - fp16(a). */
+void orc_fp16_compress(const float *G, float *R, int64_t n, float c, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        float a = fmaf(c, R[i], G[i]);
+        uint16_t h = f32_to_f16(a);
+        out[i] = h;
+        R[i] = a - f16_to_f32(h);
+    }
+}
+
+/* Mean of N fp16 payload rows: fp32 left fold over w = 0..N-1, then / N. */
+void orc_fp16_mean(const uint16_t *recv, int32_t N, int64_t stride, int64_t n, float *out)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        float acc = f16_to_f32(recv[i]);
+        for (int32_t w = 1; w < N; ++w) acc += f16_to_f32(recv[(int64_t)w * stride + i]);
+        out[i] = acc / (float)N;
+    }
+}
+
+/* Mean of N sparse payloads of k (value, index) pairs: the dense sum is built
+ * worker by worker (w = 0..N-1), then divided by N (not when N = 1). */
+void orc_sparse_mean(const float *vals, const uint32_t *idx, int32_t N, int64_t k, int64_t stride,
+                     int64_t n, float *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = 0.0f;
+    for (int32_t w = 0; w < N; ++w)
+        for (int64_t j = 0; j < k; ++j) {
+            int64_t at = (int64_t)w * stride + j;
+            out[idx[at]] = out[idx[at]] + vals[at];
+        }
+    if (N > 1)
+        for (int64_t i = 0; i < n; ++i) out[i] = out[i] / (float)N;
+}
+
+/* ------------------------------------------------------------------ */
 /* Host policy                                                         */
 /* ------------------------------------------------------------------ */
 

@@ -18,7 +18,7 @@ _CSRC = os.path.join(_HERE, "csrc")
 _INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_HERE, "libcovap.so")
 
-SOURCES = ["plan.cpp", "kernels.hip", "topk.hip"]
+SOURCES = ["plan.cpp", "kernels.hip", "topk.hip", "contrast.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -111,6 +111,14 @@ def lib():
     L.topk_compress.restype = C.c_int
     L.topk_compress.argtypes = [_vp, _vp, C.c_int64, C.c_int64, C.c_int32, C.c_float, _vp, _vp, _vp,
                                 C.c_size_t, _vp]
+    L.randk_compress.restype = C.c_int
+    L.randk_compress.argtypes = [_vp, _vp, C.c_int64, _vp, C.c_int64, C.c_float, _vp, _vp]
+    L.fp16_compress.restype = C.c_int
+    L.fp16_compress.argtypes = [_vp, _vp, C.c_int64, C.c_float, _vp, _vp]
+    L.fp16_decompress.restype = C.c_int
+    L.fp16_decompress.argtypes = [_vp, C.c_int32, C.c_int64, C.c_int64, _vp, _vp]
+    L.sparse_decompress.restype = C.c_int
+    L.sparse_decompress.argtypes = [_vp, _vp, C.c_int32, C.c_int64, C.c_int64, C.c_int64, _vp, _vp]
     L.covap_probe_copy.restype = C.c_int
     L.covap_probe_copy.argtypes = [_vp, _vp, C.c_size_t, _vp]
     L.covap_probe_triad.restype = C.c_int
@@ -246,6 +254,39 @@ def topk_compress(grad, residual, k: int, out_vals, out_idx, workspace, ef_coeff
         ws_bytes = workspace.numel() * workspace.element_size()
     _check(lib().topk_compress(_ptr(grad), _ptr(residual), n, k, dtype, ef_coeff, _ptr(out_vals),
                                _ptr(out_idx), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def randk_compress(grad, residual, idx, out_vals, ef_coeff: float = 1.0, n: Optional[int] = None,
+                   k: Optional[int] = None, stream=None) -> None:
+    n = grad.numel() if n is None else n
+    k = idx.numel() if k is None else k
+    _check(lib().randk_compress(_ptr(grad), _ptr(residual), n, _ptr(idx), k, ef_coeff,
+                                _ptr(out_vals), _stream(stream)))
+
+
+def fp16_compress(grad, residual, out_half, ef_coeff: float = 1.0, n: Optional[int] = None,
+                  stream=None) -> None:
+    n = grad.numel() if n is None else n
+    _check(lib().fp16_compress(_ptr(grad), _ptr(residual), n, ef_coeff, _ptr(out_half), _stream(stream)))
+
+
+def fp16_decompress(recv, dense_out, n: Optional[int] = None, n_workers: Optional[int] = None,
+                    stride_elems: Optional[int] = None, stream=None) -> None:
+    n_workers = recv.shape[0] if n_workers is None else n_workers
+    stride_elems = recv.stride(0) if stride_elems is None else stride_elems
+    n = dense_out.numel() if n is None else n
+    _check(lib().fp16_decompress(_ptr(recv), n_workers, stride_elems, n, _ptr(dense_out), _stream(stream)))
+
+
+def sparse_decompress(vals, idx, dense_out, k: Optional[int] = None, n: Optional[int] = None,
+                      n_workers: Optional[int] = None, stride_elems: Optional[int] = None,
+                      stream=None) -> None:
+    n_workers = vals.shape[0] if n_workers is None else n_workers
+    stride_elems = vals.stride(0) if stride_elems is None else stride_elems
+    k = vals.shape[1] if k is None else k
+    n = dense_out.numel() if n is None else n
+    _check(lib().sparse_decompress(_ptr(vals), _ptr(idx), n_workers, k, stride_elems, n,
+                                   _ptr(dense_out), _stream(stream)))
 
 
 def covap_ratio_from_ccr(ccr: float) -> int:
