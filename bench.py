@@ -254,6 +254,24 @@ def main():
         except B.CovapError as e:
             out["contrast_error"] = str(e)
 
+    # ---- aliased-residual compress (the producer accumulates; never the headline number:
+    # the error-feedback addition is then paid for inside the producer)
+    if args.dtype != "bf16_res32":
+        acc_buf = ring[1].clone()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for t in range(K):
+            B.covap_compress_aliased(plan, t, acc_buf, recv[0], stream=stream)
+        e0.record(stream)
+        for t in range(2 * K):
+            B.covap_compress_aliased(plan, t, acc_buf, recv[0], stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (2 * K)
+        P_period = sum(plan.packed_elems(t) for t in range(K)) / K
+        out["aliased_compress"] = {"us_per_iter": round(us, 2), "algorithmic_bytes": round(3 * esz * P_period),
+                                   "GB/s": round(3 * esz * P_period / (us * 1e-6) / 1e9, 1)}
+        del acc_buf
+
     # ---- per-bucket streamed mode: one launch per communication bucket, as a DDP hook
     # would issue them while backward is still running (Sec. II-B); eager launches,
     # HIP graphs (one per residue of the step), and overlap with a synthetic backward

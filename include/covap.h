@@ -167,6 +167,20 @@ covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t b
                               const void *grad, void *residual, void *send,
                               int64_t send_cap_elems, float ef_coeff, void *stream);
 
+/* Aliased-residual form of steps 1-4, for callers whose gradient-accumulation
+ * buffer doubles as the residual: the producer adds every new gradient into
+ * `accum` (that addition IS Algorithm 1 line 2 with c = 1), and this call only
+ * moves the sent shards of `accum` to `send` and clears them; shards that are
+ * not sent are neither read nor written, so the call touches 3 * packed_elems
+ * elements instead of 3 * total + packed.  Same packed layout and the same bits
+ * as covap_compress(ef_coeff = 1) fed with the last gradient and the previous
+ * residual.  Not available for COVAP_BF16_RES32 (EUNSUPPORTED), nor for c != 1.
+ *   accum  [device] whole arena, read and written (sent shards only)
+ *   send   [device] as in covap_compress */
+covap_status_t covap_compress_aliased(const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                                      void *accum, void *send, int64_t send_cap_elems,
+                                      void *stream);
+
 /* Step 5 for bucket `bucket` (-1 = all) at iteration `step`.
  *   recv       [device] const, n_workers rows of stride_elems elements each;
  *              row w is worker w's `send` buffer of this step

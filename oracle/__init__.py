@@ -75,6 +75,9 @@ def lib():
         L.orc_compress_bf16_res32.restype = C.c_int64
         L.orc_compress_bf16_res32.argtypes = [_u16p, _f32p, _u16p, _i64p, _i64p, C.c_int64, C.c_int64,
                                               C.c_int32, C.c_uint64, C.c_float, C.c_int64]
+        L.orc_compress_aliased.restype = C.c_int64
+        L.orc_compress_aliased.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _i64p, _i64p, C.c_int64,
+                                           C.c_int64, C.c_int32, C.c_uint64, C.c_int64]
         L.orc_topk_f32.restype = C.c_int32
         L.orc_topk_f32.argtypes = [_f32p, _f32p, C.c_int64, C.c_int64, C.c_float, _f32p, _u32p]
         L.orc_randk_f32.restype = C.c_int32
@@ -248,6 +251,15 @@ def compress(tab: ShardTable, interval: int, t: int, G, R, send, c: float = 1.0,
     f = getattr(lib(), "orc_compress_" + name)
     return int(f(_p(G, ptr), _p(R, ptr), _p(send, ptr), _p(tab.off, _i64p), _p(tab.len, _i64p),
                  lo, hi, interval, t, c, tab.align))
+
+
+def compress_aliased(tab: ShardTable, interval: int, t: int, accum, send, bucket: int = -1) -> int:
+    """In place: sent shards of accum move to send and are cleared."""
+    _chk(accum, accum.dtype), _chk(send, accum.dtype)
+    lo, hi = tab.bucket_range(bucket)
+    return int(lib().orc_compress_aliased(accum.ctypes.data, send.ctypes.data, accum.dtype.itemsize,
+                                          _p(tab.off, _i64p), _p(tab.len, _i64p), lo, hi, interval, t,
+                                          tab.align))
 
 
 def decompress(tab: ShardTable, interval: int, t: int, recv, out, bucket: int = -1) -> None:

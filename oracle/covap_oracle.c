@@ -314,6 +314,31 @@ int64_t orc_compress_bf16_res32(const uint16_t *G, float *R, uint16_t *send,
     return written;
 }
 
+/* Aliased-residual form: the caller's accumulation buffer already holds
+ * G + residual (the producer added the new gradient into it: Algorithm 1 line 2
+ * with c = 1).  Sent shards move to the payload and are cleared; the others are
+ * left alone (their content IS the new residual).  esz = element size in bytes
+ * (the operation only moves bit patterns). */
+int64_t orc_compress_aliased(void *accum, void *send, int32_t esz,
+                             const int64_t *off, const int64_t *len,
+                             int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t, int64_t align)
+{
+    int64_t p = orc_packed_end(len, sh_lo, I, t, align);
+    int64_t written = 0;
+    unsigned char *a = (unsigned char *)accum, *o = (unsigned char *)send;
+    for (int64_t s = sh_lo; s < sh_hi; ++s) {
+        if (!orc_selected(s, t, I)) continue;
+        p = round_up(p, align);
+        written += len[s];
+        for (int64_t i = off[s]; i < off[s] + len[s]; ++i) {
+            memcpy(o + p * esz, a + i * esz, (size_t)esz);
+            memset(a + i * esz, 0, (size_t)esz);
+            ++p;
+        }
+    }
+    return written;
+}
+
 /* ------------------------------------------------------------------ */
 /* Decompress: N-way average + unpack (Sec. II-A AllReduce + DP mean)  */
 /* ------------------------------------------------------------------ */

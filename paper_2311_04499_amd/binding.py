@@ -104,6 +104,8 @@ def lib():
     L.covap_ef_coeff.argtypes = [C.c_float, C.c_uint64, C.c_uint64, C.c_float, C.POINTER(C.c_float)]
     L.covap_compress.restype = C.c_int
     L.covap_compress.argtypes = [_vp, C.c_uint64, C.c_int32, _vp, _vp, _vp, C.c_int64, C.c_float, _vp]
+    L.covap_compress_aliased.restype = C.c_int
+    L.covap_compress_aliased.argtypes = [_vp, C.c_uint64, C.c_int32, _vp, _vp, C.c_int64, _vp]
     L.covap_decompress.restype = C.c_int
     L.covap_decompress.argtypes = [_vp, C.c_uint64, C.c_int32, _vp, C.c_int32, C.c_int64, _vp, _vp]
     L.topk_workspace_bytes.restype = C.c_size_t
@@ -229,6 +231,13 @@ def covap_compress(plan: Plan, step: int, grad, residual, send, ef_coeff: float 
     cap = send.numel() if send_cap_elems is None else send_cap_elems
     _check(lib().covap_compress(plan.handle, step, bucket, _ptr(grad), _ptr(residual), _ptr(send),
                                 cap, ef_coeff, _stream(stream)))
+
+
+def covap_compress_aliased(plan: Plan, step: int, accum, send, bucket: int = -1, stream=None,
+                           send_cap_elems: Optional[int] = None) -> None:
+    cap = send.numel() if send_cap_elems is None else send_cap_elems
+    _check(lib().covap_compress_aliased(plan.handle, step, bucket, _ptr(accum), _ptr(send), cap,
+                                        _stream(stream)))
 
 
 def covap_decompress(plan: Plan, step: int, recv, dense_out, n_workers: Optional[int] = None,

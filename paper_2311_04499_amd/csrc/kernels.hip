@@ -183,7 +183,8 @@ struct fixed_geom {
     int32_t K;
     int32_t first_sel;
     uint32_t tiles_per_shard;
-    uint32_t sh_lo;        // first shard of this call (per-bucket calls start mid-arena)
+    uint32_t sh_lo;        // first shard this launch covers (per-bucket calls start mid-arena)
+    uint32_t sh_step;      // 1: every shard from sh_lo on; K: only the sent ones
 };
 
 struct tile_ref {
@@ -199,7 +200,7 @@ __device__ __forceinline__ bool resolve_tile(const fixed_geom &g, tile_ref &t)
     const uint32_t tile = blockIdx.x;
     const uint32_t q = tile / g.tiles_per_shard;
     const uint32_t j = tile - q * g.tiles_per_shard;
-    const uint32_t s = g.sh_lo + q;
+    const uint32_t s = g.sh_lo + q * g.sh_step;
     const uint32_t sh_len = (s + 1u == g.n_shards) ? g.last_len : g.shard_len;
     const uint32_t in = j * (uint32_t)TILE;
     if (in >= sh_len) return false;
@@ -397,6 +398,43 @@ __global__ __launch_bounds__(kThreads) void k_compress(const u32x4 *__restrict__
         compress_tile<OPS, kThreads, UNROLL, NT>(G, R, send, t, c);
 }
 
+// ---- take: aliased-residual form of compress ------------------------------------------
+//
+// When the caller's gradient-accumulation buffer doubles as the residual (the
+// producer adds each new gradient into it, which is Algorithm 1 line 2 with
+// c = 1), all that is left of compress is: move the sent shards to the payload
+// and clear them.  Shards that are not sent are not touched at all, so the call
+// moves 3 * P_t elements instead of 3 * D + P_t.  Pure byte movement: ESZ is the
+// element size (4 or 2) and only matters for a shard's ragged tail.
+template <typename GEOM, int ESZ, bool NT>
+__global__ __launch_bounds__(64) void k_take(u32x4 *acc, u32x4 *__restrict__ send, GEOM g)
+{
+    constexpr int EPV = 16 / ESZ;
+    constexpr int TILE = 64 * EPV;
+    tile_ref t;
+    if (!resolve_tile<TILE>(g, t)) return;
+    const int tid = threadIdx.x;
+    u32x4 *ap = acc + t.off / EPV;
+    u32x4 *sp = send + t.poff / EPV;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    const int nv = t.n / EPV;
+    if (tid < nv) {
+        st16<NT>(sp + tid, ld16<NT>(ap + tid));
+        st16<NT>(ap + tid, zero);
+    }
+    const int rem = t.n - nv * EPV;
+    if (tid < rem) {
+        const int64_t e = (int64_t)nv * EPV + tid;
+        if constexpr (ESZ == 4) {
+            ((uint32_t *)sp)[e] = ((const uint32_t *)ap)[e];
+            ((uint32_t *)ap)[e] = 0u;
+        } else {
+            ((uint16_t *)sp)[e] = ((const uint16_t *)ap)[e];
+            ((uint16_t *)ap)[e] = (uint16_t)0;
+        }
+    }
+}
+
 // ---- decompress: N-way mean + unpack + zero fill --------------------------------
 
 // Sum of one packed vector position over the N payload rows, in row order.
@@ -552,7 +590,7 @@ bool overlap(const void *a, int64_t abytes, const void *b, int64_t bbytes)
 }
 
 fixed_geom make_geom(const covap_plan_s *p, const covap::call_range &cr, int tile_elems,
-                     uint32_t *grid)
+                     bool sent_only, uint32_t *grid)
 {
     fixed_geom g;
     g.S = p->opts.shard_elems;
@@ -562,8 +600,17 @@ fixed_geom make_geom(const covap_plan_s *p, const covap::call_range &cr, int til
     g.K = p->K;
     g.first_sel = cr.first_sel;
     g.tiles_per_shard = (uint32_t)((g.S + tile_elems - 1) / tile_elems);
-    g.sh_lo = (uint32_t)cr.sh_lo;
-    *grid = (uint32_t)(cr.sh_hi - cr.sh_lo) * g.tiles_per_shard;
+    const uint32_t K = (uint32_t)g.K, lo = (uint32_t)cr.sh_lo, n = (uint32_t)(cr.sh_hi - cr.sh_lo);
+    if (sent_only) {
+        const uint32_t phase = ((uint32_t)cr.first_sel + K - lo % K) % K;  // offset of the first sent shard
+        g.sh_lo = lo + phase;
+        g.sh_step = K;
+        *grid = (phase < n ? (n - phase + K - 1) / K : 0u) * g.tiles_per_shard;
+    } else {
+        g.sh_lo = lo;
+        g.sh_step = 1u;
+        *grid = n * g.tiles_per_shard;
+    }
     return g;
 }
 
@@ -583,14 +630,16 @@ bool pick(int v, F &&f)
 }
 
 // Runs f(geom, grid) once per launch the call needs: one launch for fixed-size
-// shards, one per kMaxUnits shards otherwise.
+// shards, one per kMaxUnits segments otherwise.  sent_only: cover only the shards
+// sent at this step.
 template <typename F>
-void for_each_launch(const covap_plan_s *plan, const covap::call_range &cr, int tile_elems, F &&f)
+void for_each_launch(const covap_plan_s *plan, const covap::call_range &cr, int tile_elems,
+                     bool sent_only, F &&f)
 {
     if (plan->uniform) {
         uint32_t grid = 0;
-        const fixed_geom g = make_geom(plan, cr, tile_elems, &grid);
-        f(g, dim3(grid));
+        const fixed_geom g = make_geom(plan, cr, tile_elems, sent_only, &grid);
+        if (grid) f(g, dim3(grid));
         return;
     }
     // Cut every shard into segments of at most kSegTiles tiles and order the
@@ -611,6 +660,7 @@ void for_each_launch(const covap_plan_s *plan, const covap::call_range &cr, int 
     for (int32_t s = cr.sh_lo; s < cr.sh_hi; ++s) {
         const covap_shard_rec &sh = plan->shards[(size_t)s];
         const bool is_sent = s % K == cr.first_sel;
+        if (sent_only && !is_sent) continue;
         for (int64_t in = 0; in < sh.len; in += seg_elems) {
             seg g;
             g.off = sh.off + in;
@@ -662,7 +712,7 @@ bool launch_compress(const covap::tuning &tn, const covap_plan_s *plan, const co
     return pick<64, 256>(tn.compress_threads, [&](auto T) {
         pick<1, 2, 4>(tn.compress_unroll, [&](auto U) {
             pick<0, 1>(tn.nontemporal, [&](auto NT) {
-                for_each_launch(plan, cr, T() * OPS::EPV * U(), [&](const auto &g, dim3 grid) {
+                for_each_launch(plan, cr, T() * OPS::EPV * U(), false, [&](const auto &g, dim3 grid) {
                     typedef std::decay_t<decltype(g)> GEOM;
                     k_compress<OPS, GEOM, T(), U(), NT() != 0><<<grid, T(), 0, st>>>(
                         (const u32x4 *)G, (u32x4 *)R, (u32x4 *)send, g, c);
@@ -683,7 +733,7 @@ bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
         pick<1, 2, 4>(tn.decompress_tile, [&](auto U) {
             pick<1, 2, 4>(tn.decompress_unroll, [&](auto WU) {
                 pick<0, 1>(tn.nontemporal, [&](auto NT) {
-                    for_each_launch(plan, cr, T() * OPS::EPV * U(), [&](const auto &g, dim3 grid) {
+                    for_each_launch(plan, cr, T() * OPS::EPV * U(), false, [&](const auto &g, dim3 grid) {
                         typedef std::decay_t<decltype(g)> GEOM;
                         k_decompress<OPS, GEOM, T(), U(), WU(), NT() != 0><<<grid, T(), 0, st>>>(
                             (const u32x4 *)recv, (u32x4 *)out, g, N, stride, n_f, inv_n, pow2);
@@ -733,6 +783,41 @@ covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t b
         ok = launch_compress<ops_bf16_res32>(tn, plan, cr, st, grad, residual, send, ef_coeff);
     if (!ok) return fail(COVAP_EINVAL, "covap_compress: launch knobs select no kernel");
     return check_launch("covap_compress");
+}
+
+covap_status_t covap_compress_aliased(const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                                      void *accum, void *send, int64_t send_cap_elems,
+                                      void *stream)
+{
+    covap::clear_error();
+    covap::call_range cr;
+    const covap_status_t rs = covap::resolve(plan, step, bucket, &cr);
+    if (rs != COVAP_OK) return rs;
+    if (plan->opts.dtype == COVAP_BF16_RES32)
+        return fail(COVAP_EUNSUPPORTED,
+                    "covap_compress_aliased: gradient and residual must share one element type");
+    if (!accum || !send) return fail(COVAP_EINVAL, "covap_compress_aliased: null device pointer");
+    if (!aligned16(accum) || !aligned16(send))
+        return fail(COVAP_EINVAL, "covap_compress_aliased: device pointers must be 16-byte aligned");
+    if (send_cap_elems < cr.packed_base + cr.packed_elems)
+        return fail(COVAP_EINVAL, "covap_compress_aliased: send buffer too small for this step");
+    const int64_t esz = plan->opts.dtype == COVAP_F32 ? 4 : 2;
+    if (overlap(accum, plan->total_elems * esz, send, send_cap_elems * esz))
+        return fail(COVAP_EINVAL, "covap_compress_aliased: accum and send must not overlap");
+    if (cr.sh_hi == cr.sh_lo) return COVAP_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const bool nt = covap::tune().nontemporal != 0;
+    for_each_launch(plan, cr, 64 * plan->elems_per_vec, true, [&](const auto &g, dim3 grid) {
+        typedef std::decay_t<decltype(g)> GEOM;
+        if (esz == 4) {
+            if (nt) k_take<GEOM, 4, true><<<grid, 64, 0, st>>>((u32x4 *)accum, (u32x4 *)send, g);
+            else k_take<GEOM, 4, false><<<grid, 64, 0, st>>>((u32x4 *)accum, (u32x4 *)send, g);
+        } else {
+            if (nt) k_take<GEOM, 2, true><<<grid, 64, 0, st>>>((u32x4 *)accum, (u32x4 *)send, g);
+            else k_take<GEOM, 2, false><<<grid, 64, 0, st>>>((u32x4 *)accum, (u32x4 *)send, g);
+        }
+    });
+    return check_launch("covap_compress_aliased");
 }
 
 covap_status_t covap_decompress(const covap_plan_t *plan, uint64_t step, int32_t bucket,

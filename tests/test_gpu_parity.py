@@ -461,3 +461,60 @@ def test_scheduler_driven_run(B):
         assert_same(to_np(send), sc, f"send t={t}")
         assert_same(to_np(R), Rc, f"residual t={t}")
     assert min(seen) == 0.25 and max(seen) == 1.0 and len(seen) == 7
+
+
+# ------------------------------------------------------------------ aliased residual
+
+@pytest.mark.parametrize("mode,numel,S,K,dtype", [
+    ("fixed", [100_003], 4096, 3, torch.float32), ("fixed", [7], 4, 2, torch.float32),
+    ("fixed", [8 * 4096 + 9], 8192, 4, torch.bfloat16), ("fixed", [300_000, 12_345], 8192, 16, torch.float32),
+    ("median", [1_003, 2_001, 30_007, 5, 4_099, 17, 90_001, 3], 0, 3, torch.float32),
+    ("median", [257] * 300, 0, 5, torch.bfloat16),
+])
+def test_aliased_residual_compress(B, mode, numel, S, K, dtype):
+    """covap_compress_aliased against the oracle, and against covap_compress itself
+    (c = 1) when the accumulation buffer is fed the way a producer would."""
+    wl = workloads.scaled_down(workloads.config(1), numel, 4096)
+    if mode == "fixed":
+        plan, tab = make_plans(B, numel, S, K, dtype, cap_bytes=60_000)
+    else:
+        plan, tab = make_median_plans(B, numel, K, dtype, cap_bytes=20_000)
+    D = tab.D
+    epv = 4 if dtype == torch.float32 else 8
+    stride = (plan.packed_elems_max + epv - 1) // epv * epv
+    acc = torch.zeros(D, dtype=dtype, device=DEV)
+    acc_c = to_np(acc)
+    R = torch.zeros(D, dtype=dtype, device=DEV)
+    covered = np.zeros(D, bool)                                  # arena padding belongs to no shard
+    for s_ in range(tab.n_shards):
+        covered[int(tab.off[s_]):int(tab.off[s_] + tab.len[s_])] = True
+    covered_t = torch.from_numpy(covered).to(DEV)
+    for t in range(2 * K + 1):
+        G = workloads.gradient(wl, 0, t, DEV, dtype)
+        if G.numel() < D:
+            G = torch.cat([G, torch.zeros(D - G.numel(), dtype=dtype, device=DEV)])
+        G = G * covered_t
+        acc = (G.float() + acc.float()).to(dtype)               # the producer accumulates
+        acc_c = to_np(acc)
+        send_a = torch.full((stride,), float("nan"), dtype=dtype, device=DEV)
+        send_c = to_np(send_a)
+        send_r = torch.full((stride,), float("nan"), dtype=dtype, device=DEV)
+        per_bucket = t % 2 == 1
+        for b in (range(tab.n_buckets) if per_bucket else [-1]):
+            B.covap_compress_aliased(plan, t, acc, send_a, bucket=b)
+            oracle.compress_aliased(tab, K, t, acc_c, send_c, bucket=b)
+        B.covap_compress(plan, t, G, R, send_r)
+        torch.cuda.synchronize()
+        assert_same(to_np(send_a), send_c, f"send t={t}")
+        assert_same(to_np(acc), acc_c, f"accum t={t}")
+        assert_same(to_np(send_a), to_np(send_r), f"aliased vs plain payload t={t}")
+        assert_same(to_np(acc), to_np(R), f"aliased buffer vs plain residual t={t}")
+
+
+def test_aliased_rejects_mixed_precision(B):
+    plan = B.covap_plan([1000], 64, 2, dtype=B.COVAP_BF16_RES32)
+    a = torch.zeros(1000, dtype=torch.bfloat16, device=DEV)
+    s = torch.zeros(1000, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(B.CovapError) as e:
+        B.covap_compress_aliased(plan, 0, a, s)
+    assert e.value.status == 5

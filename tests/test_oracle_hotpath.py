@@ -482,3 +482,28 @@ def test_mixed_precision_conservation_integer_data():
         rounded += int((R[keep_mask(tab, I, t, tab.D)] != 0).sum())
     assert np.array_equal(total_sent + R, total_grad)
     assert rounded > 0                                               # the case is not vacuous
+
+
+# ------------------------------------------------------------------ aliased residual
+
+@pytest.mark.parametrize("numel,S,I", CASES)
+def test_aliased_form_equals_algorithm_1_at_c1(numel, S, I):
+    """If the producer adds each gradient into one buffer, taking the sent
+    shards out of it is the whole of compress: same payload, and the buffer then
+    holds the residual Algorithm 1 would hold (c = 1)."""
+    tab = oracle.plan_fixed(numel, S, 1 << 30)
+    rng = np.random.default_rng(12)
+    R = np.zeros(tab.D, np.float32)
+    acc = np.zeros(tab.D, np.float32)
+    for t in range(2 * I + 2):
+        G = rng.standard_normal(tab.D).astype(np.float32)
+        acc = G + acc                                            # the producer's accumulation
+        s1 = np.full(tab.D, np.nan, np.float32)
+        s2 = np.full(tab.D, np.nan, np.float32)
+        n1 = oracle.compress(tab, I, t, G, R, s1)
+        n2 = oracle.compress_aliased(tab, I, t, acc, s2)
+        assert n1 == n2
+        assert np.array_equal(bits(s1), bits(s2))
+        assert np.array_equal(bits(R), bits(acc))
+        m = keep_mask(tab, I, t, tab.D)
+        assert not bits(acc[m]).any()
