@@ -9,8 +9,12 @@ the GPT-2-medium-shaped gradient set (355M fp32 elements, shard 2^20, N = 64,
 K = 16) in payload mode: row 0 of the receive buffer is this worker's own
 packed output, rows 1..N-1 are synthetic payloads drawn at packed shape.
 
-Prints ONE JSON line (see README/DESIGN for the fields).  `--gpus N` with
-N > 1 is refused: this build is a single-GPU path with no collectives.
+Prints ONE JSON line: metric / value (GB/s of gradient processed) / ms_per_step,
+`roofline` for the slower of the two kernels (algorithmic HBM bytes over its
+HIP-event duration, against the 8 TB/s peak), `kernels` (both), `cpu_baseline`
+(the CPU oracle on one full iteration), and the contrast and streamed-mode
+measurements.  `--gpus N` with N > 1 is refused: this build is a single-GPU
+path with no collectives.
 """
 import argparse
 import json
