@@ -371,9 +371,12 @@ def main():
         t = t_first + args.steps
         to_np = lambda x: x.cpu().numpy() if x.dtype == torch.float32 else \
             x.cpu().view(torch.int16).numpy().view(np.uint16)
+        # inputs are generated, never taken from the GPU path's outputs: a gradient, a residual
+        # of the same scale, and the synthetic payload rows (row 0 is filled by the oracle itself)
         Gn = to_np(ring[t % 3])
-        Rn = to_np(residual).copy()
+        Rn = to_np(ring[(t + 1) % 3].to(rdtype)).copy()
         recv_n = to_np(recv).copy()
+        recv_n[0] = 0
         out_n = np.empty(D, Gn.dtype)
         c0 = time.perf_counter()
         oracle.compress(tab, K, t, Gn, Rn, recv_n[0])

@@ -518,3 +518,42 @@ def test_aliased_rejects_mixed_precision(B):
     with pytest.raises(B.CovapError) as e:
         B.covap_compress_aliased(plan, 0, a, s)
     assert e.value.status == 5
+
+
+# ------------------------------------------------------------------ the other configurations at full size
+
+@pytest.mark.parametrize("cfg,dtype", [(2, torch.float32), (3, torch.float32), (4, torch.float32),
+                                       (4, torch.bfloat16)])
+def test_full_size_configurations(B, cfg, dtype):
+    """ResNet-50-, VGG-19- and BERT-base-shaped sets at their real sizes, shard
+    sizes, worker counts and intervals (BERT's from CCR = 6), payload mode, two
+    steps with the residual carried over; every element against the oracle."""
+    wl = workloads.config(cfg)
+    K = B.covap_ratio_from_ccr(6.0) if cfg == 4 else wl.K
+    assert K == wl.K
+    plan, tab = make_plans(B, wl.numel, wl.shard_elems, K, dtype)
+    D, N = wl.D, wl.n_workers
+    epv = 4 if dtype == torch.float32 else 8
+    stride = (plan.packed_elems_max + epv - 1) // epv * epv
+    recv = torch.empty(N, stride, dtype=dtype, device=DEV)
+    recv[1:] = workloads.payload_rows(wl, N - 1, stride, 0, DEV, dtype)
+    R = torch.zeros(D, dtype=dtype, device=DEV)
+    Rc = to_np(R)
+    out = torch.empty(D, dtype=dtype, device=DEV)
+    last = tab.n_shards - 1
+    t_last = (K - last % K) % K                              # the step that sends the short last shard
+    for t in (t_last + K - 1, t_last + K):                   # one step before it, then that step
+        G = workloads.gradient(wl, 0, t, DEV, dtype)
+        B.covap_compress(plan, t, G, R, recv[0])
+        B.covap_decompress(plan, t, recv, out, n_workers=N, stride_elems=stride)
+        torch.cuda.synchronize()
+        P = plan.packed_elems(t)
+        recv_c = to_np(recv)
+        sent_gpu = recv_c[0, :P].copy()
+        oracle.compress(tab, K, t, to_np(G), Rc, recv_c[0])
+        assert_same(sent_gpu, recv_c[0, :P], f"send t={t}")
+        assert_same(to_np(R), Rc, f"residual t={t}")
+        out_c = np.empty(D, recv_c.dtype)
+        oracle.decompress(tab, K, t, recv_c, out_c)
+        assert_same(to_np(out), out_c, f"dense t={t}")
+    assert plan.is_selected(t, last) == 1
