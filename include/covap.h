@@ -265,6 +265,8 @@ covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float
  *   "decompress_tile"    16-byte vectors per thread per tile: 1, 2, 4
  *   "decompress_unroll"  payload rows loaded before they are summed: 1, 2, 4
  *   "nontemporal"        streaming cache hints on loads and stores: 0, 1
+ *   "decompress_lds_pad" bytes of unused LDS reserved per decompress workgroup, which
+ *                        caps its occupancy: 0, 6144, 8192
  * No knob changes any result bit.  EINVAL for an unknown key or value.  Global
  * to the process and not thread-safe against running calls. */
 covap_status_t covap_tune_set(const char *key, int32_t value);

@@ -735,7 +735,8 @@ bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
                 pick<0, 1>(tn.nontemporal, [&](auto NT) {
                     for_each_launch(plan, cr, T() * OPS::EPV * U(), false, [&](const auto &g, dim3 grid) {
                         typedef std::decay_t<decltype(g)> GEOM;
-                        k_decompress<OPS, GEOM, T(), U(), WU(), NT() != 0><<<grid, T(), 0, st>>>(
+                        // the LDS reservation is never touched: it only caps occupancy
+                        k_decompress<OPS, GEOM, T(), U(), WU(), NT() != 0><<<grid, T(), (size_t)tn.decompress_lds_pad, st>>>(
                             (const u32x4 *)recv, (u32x4 *)out, g, N, stride, n_f, inv_n, pow2);
                     });
                 });

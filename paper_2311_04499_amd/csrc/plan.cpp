@@ -381,6 +381,7 @@ const knob kKnobs[] = {
     {"decompress_tile", &covap::tuning::decompress_tile, {1, 2, 4, -1, -1}},
     {"decompress_unroll", &covap::tuning::decompress_unroll, {1, 2, 4, -1, -1}},
     {"nontemporal", &covap::tuning::nontemporal, {0, 1, -1, -1, -1}},
+    {"decompress_lds_pad", &covap::tuning::decompress_lds_pad, {0, 6144, 8192, -1, -1}},
 };
 }  // namespace
 

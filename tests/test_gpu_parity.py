@@ -160,7 +160,8 @@ def test_per_bucket_calls(B):
 
 KNOBS = {"compress_threads": [64, 256], "compress_unroll": [1, 2, 4],
          "decompress_threads": [64, 256], "decompress_tile": [1, 2, 4],
-         "decompress_unroll": [1, 2, 4], "nontemporal": [0, 1]}
+         "decompress_unroll": [1, 2, 4], "nontemporal": [0, 1],
+         "decompress_lds_pad": [0, 8192, 6144]}
 
 
 @pytest.mark.parametrize("key", list(KNOBS))
