@@ -558,3 +558,64 @@ def test_full_size_configurations(B, cfg, dtype):
         oracle.decompress(tab, K, t, recv_c, out_c)
         assert_same(to_np(out), out_c, f"dense t={t}")
     assert plan.is_selected(t, last) == 1
+
+
+# ------------------------------------------------------------------ more corners
+
+@pytest.mark.parametrize("numel,S,K,N", [
+    ([50_001], 4096, 1000, 2),          # interval far larger than the shard count
+    ([50_001], 4096, 13, 130),          # many workers, not a power of two
+    ([4096 * 40], 4096, 40, 1),         # exactly one shard per step, single worker
+    ([123_457], 4, 3, 2),               # smallest legal shard: tens of thousands of shards
+])
+def test_extreme_intervals_and_worker_counts(B, numel, S, K, N):
+    wl = workloads.scaled_down(workloads.config(1), numel, S)
+    plan, tab = make_plans(B, numel, S, K)
+    D = tab.D
+    stride = (plan.packed_elems_max + 64 + 3) // 4 * 4        # stride larger than the payload
+    R = torch.zeros(D, device=DEV)
+    Rc = np.zeros(D, np.float32)
+    for t in [0, 1, K - 1, K, 10 ** 15 + 3]:
+        G = workloads.gradient(wl, 0, t % 1000, DEV)
+        recv = workloads.payload_rows(wl, N, stride, t % 1000, DEV, first_worker=0)
+        recv_c = to_np(recv)
+        B.covap_compress(plan, t, G, R, recv[0], ef_coeff=0.5)
+        oracle.compress(tab, K, t, to_np(G), Rc, recv_c[0], 0.5)
+        out = torch.full((D,), float("nan"), device=DEV)
+        out_c = np.zeros(D, np.float32)
+        B.covap_decompress(plan, t, recv, out, n_workers=N, stride_elems=stride)
+        oracle.decompress(tab, K, t, recv_c, out_c)
+        torch.cuda.synchronize()
+        assert_same(to_np(recv[0]), recv_c[0], f"send t={t}")
+        assert_same(to_np(R), Rc, f"residual t={t}")
+        assert_same(to_np(out), out_c, f"dense t={t}")
+
+
+def test_two_streams_run_independent_plans(B):
+    """Two plans driven from two HIP streams at once give the results each gives alone
+    (the library keeps no state between calls besides the immutable plans)."""
+    cases = [([200_003], 4096, 3), ([150_001, 77], 8192, 5)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    state = []
+    for (numel, S, K), st in zip(cases, streams):
+        wl = workloads.scaled_down(workloads.config(1), numel, S)
+        plan, tab = make_plans(B, numel, S, K)
+        D = tab.D
+        stride = (plan.packed_elems_max + 3) // 4 * 4
+        state.append(dict(wl=wl, plan=plan, tab=tab, K=K, D=D, stride=stride,
+                          R=torch.zeros(D, device=DEV), Rc=np.zeros(D, np.float32)))
+    torch.cuda.synchronize()
+    for t in range(6):
+        pending = []
+        for s_, st in zip(state, streams):
+            G = workloads.gradient(s_["wl"], 0, t, DEV)
+            send = torch.zeros(s_["stride"], device=DEV)
+            torch.cuda.synchronize()
+            B.covap_compress(s_["plan"], t, G, s_["R"], send, stream=st)
+            pending.append((s_, G, send))
+        torch.cuda.synchronize()
+        for s_, G, send in pending:
+            sc = np.zeros(s_["stride"], np.float32)
+            oracle.compress(s_["tab"], s_["K"], t, to_np(G), s_["Rc"], sc)
+            assert_same(to_np(send), sc, f"send t={t}")
+            assert_same(to_np(s_["R"]), s_["Rc"], f"residual t={t}")
