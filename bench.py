@@ -148,11 +148,17 @@ def main():
                 "traffic": read_traffic(dominant[0], wl.name),
                 "bytes_per_launch": round(dominant[2]), "avg_launch_us": round(dominant[1] * 1e3, 2)}
 
+    def pct(xs, q):
+        ys = sorted(xs)
+        return round(ys[min(len(ys) - 1, int(q * len(ys)))] * 1e3, 2)
+
     kernels = {
-        "covap_compress": {"avg_us": round(tc_avg * 1e3, 2), "algorithmic_bytes": round(bytes_c),
+        "covap_compress": {"avg_us": round(tc_avg * 1e3, 2), "p10_us": pct(tc, 0.1), "median_us": pct(tc, 0.5),
+                           "p90_us": pct(tc, 0.9), "algorithmic_bytes": round(bytes_c),
                            "GB/s": round(bytes_c / (tc_avg * 1e-3) / 1e9, 1),
                            "frac": round(bytes_c / (tc_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
-        "covap_decompress": {"avg_us": round(td_avg * 1e3, 2), "algorithmic_bytes": round(bytes_d),
+        "covap_decompress": {"avg_us": round(td_avg * 1e3, 2), "p10_us": pct(td, 0.1), "median_us": pct(td, 0.5),
+                             "p90_us": pct(td, 0.9), "algorithmic_bytes": round(bytes_d),
                              "GB/s": round(bytes_d / (td_avg * 1e-3) / 1e9, 1),
                              "frac": round(bytes_d / (td_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
     }
