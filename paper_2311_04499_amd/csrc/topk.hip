@@ -1,15 +1,22 @@
 // Fine-grained top-k sparsifier with error feedback: the contrast point to the
 // coarse filter (Sec. I and Table II: "most of the overhead in Top-k comes from
-// the topk() operator").  Exact, deterministic, no sampling:
+// the topk() operator").  Exact, deterministic, no sampling.
 //
 //   pass 1   A = fma(c, R, G); R <- A; histogram of key bits 30..20        (reads 2D, writes D)
-//   pass 2   histogram of bits 19..9 among keys whose bits 30..20 match    (reads D)
-//   pass 3   histogram of bits 8..0 among keys whose bits 30..9 match      (reads D)
-//            -> threshold key T and the number of ties to keep
-//   pass 4   per tile: how many keys > T, how many == T                    (reads D)
-//            3-phase exclusive scan of the tile counts (tiny)
-//   pass 5   ordered compaction: (value, index) in ascending index,
-//            R <- +0 at kept entries                                       (reads the tiles that keep something)
+//            -> the bin b1 that holds the k-th largest key
+//   collect  one more read of R: every element whose bin is >= b1 is copied, in
+//            index order, into a 32-entry slot array of its 1024-element tile, and
+//            the histogram of bits 19..9 among bin b1 is taken on the way    (reads D)
+//   then everything works on the slots only (about 0.3 % of the data): histogram
+//   of bits 8..0 -> threshold key T and the number of ties to keep; per-tile
+//   counts; 3-phase exclusive scan; ordered write of (value, index), R <- +0 there.
+//
+// If any tile has more than 32 such elements (heavily clustered or tied data) a
+// flag is raised on the device and the general path runs instead: two more
+// full histogram passes, a counting pass and a compaction pass over R (4 more
+// reads of D).  The host launches both tails; every kernel of the tail that is
+// not taken returns at once, so no host round trip is needed.  Both tails give
+// the same bits.
 //
 // key = bit pattern of |A| as an unsigned integer: a total order on magnitudes
 // (NaN above Inf).  Among keys equal to T the lowest indices are kept, which
@@ -43,11 +50,36 @@ struct topk_state {
     uint32_t k_rem;      // how many are still to be taken from the current bin
     uint32_t threshold;  // T, valid after level 3
     uint32_t ties;       // number of keys == T to keep, valid after level 3
+    uint32_t overflow;   // != 0: some tile did not fit its slots, the general tail runs
+    uint32_t pad[3];
 };
+
+constexpr int kSlots = 32;  // slot entries per 1024-element tile
+// Histograms may be kept as several partial copies ("slices") that the pick
+// kernel adds up.  Global atomics run at about 1.5 G/s on this chip whatever the
+// address spread (320 k of them cost 200 us), so the slot passes, whose entries are
+// few, build LDS histograms and store them as slices without any global atomic;
+// the full-data passes flush one LDS histogram per workgroup (a few dozen
+// non-empty bins each) and need no slicing.
+constexpr int kHistSlices = 1;    // full-data passes: workgroup w adds into slice w mod kHistSlices
+constexpr int kSlotGrid = 64;     // slot passes: one slice per workgroup, written with plain stores
+constexpr int kSlotThreads = 512;
+constexpr int kHistRows = 3 * kHistSlices + 2 * kSlotGrid;  // rows of 2048 counters in the workspace
+enum { kAlways = 0, kSlotTail = 1, kGeneralTail = 2 };
+
+// True if a kernel of tail `gate` has nothing to do.
+__device__ __forceinline__ bool skip_tail(const topk_state *st, int gate)
+{
+    const uint32_t ov = st->overflow;
+    return (gate == kSlotTail && ov != 0u) || (gate == kGeneralTail && ov == 0u);
+}
 
 struct topk_ws {
     topk_state *state;
-    uint32_t *hist;       // [3][2048]
+    uint32_t *hist;       // [kHistRows][2048]: level 1 | general tail levels 2, 3 | slot tail levels 2, 3
+    uint32_t *slot_cnt;   // [ntiles]
+    uint32_t *slot_idx;   // [ntiles][kSlots]
+    uint32_t *slot_bits;  // [ntiles][kSlots]  bit patterns of A
     uint32_t *cnt_gt;     // [ntiles]  -> exclusive prefix after the scan
     uint32_t *cnt_eq;     // [ntiles]
     uint32_t *chunk_gt;   // [nchunks] -> exclusive prefix
@@ -67,7 +99,10 @@ size_t ws_layout(int64_t n, void *base, topk_ws *out)
         return at;
     };
     const size_t o_state = take(sizeof(topk_state));
-    const size_t o_hist = take(3 * 2048 * sizeof(uint32_t));
+    const size_t o_hist = take((size_t)kHistRows * 2048 * sizeof(uint32_t));
+    const size_t o_scnt = take((size_t)ntiles * 4);
+    const size_t o_sidx = take((size_t)ntiles * kSlots * 4);
+    const size_t o_sbits = take((size_t)ntiles * kSlots * 4);
     const size_t o_gt = take((size_t)ntiles * 4);
     const size_t o_eq = take((size_t)ntiles * 4);
     const size_t o_cgt = take((size_t)nchunks * 4);
@@ -76,6 +111,9 @@ size_t ws_layout(int64_t n, void *base, topk_ws *out)
         char *b = (char *)base;
         out->state = (topk_state *)(b + o_state);
         out->hist = (uint32_t *)(b + o_hist);
+        out->slot_cnt = (uint32_t *)(b + o_scnt);
+        out->slot_idx = (uint32_t *)(b + o_sidx);
+        out->slot_bits = (uint32_t *)(b + o_sbits);
         out->cnt_gt = (uint32_t *)(b + o_gt);
         out->cnt_eq = (uint32_t *)(b + o_eq);
         out->chunk_gt = (uint32_t *)(b + o_cgt);
@@ -108,12 +146,14 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x)
 
 __global__ void k_topk_init(topk_state *st, uint32_t *hist, uint32_t k)
 {
-    for (int i = threadIdx.x; i < 3 * 2048; i += blockDim.x) hist[i] = 0u;
-    if (threadIdx.x == 0) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < kHistRows * 2048; i += gridDim.x * blockDim.x)
+        hist[i] = 0u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
         st->prefix = 0u;
         st->k_rem = k;
         st->threshold = 0u;
         st->ties = 0u;
+        st->overflow = 0u;
     }
 }
 
@@ -134,12 +174,14 @@ __global__ __launch_bounds__(kHistThreads) void k_topk_hist(const float *__restr
     constexpr int HI_SHIFT = LEVEL == 2 ? 20 : 9;  // bits above this digit (levels 2, 3)
     __shared__ uint32_t lds[kHistWaves][BINS];
     const int tid = threadIdx.x;
+    uint32_t want = 0u;
+    if constexpr (LEVEL > 1) {
+        if (skip_tail(st, kGeneralTail)) return;  // same answer for every thread of the grid
+        want = st->prefix >> HI_SHIFT;
+    }
     uint32_t *mine = lds[tid >> 6];
     for (int i = tid; i < kHistWaves * BINS; i += kHistThreads) (&lds[0][0])[i] = 0u;
     __syncthreads();
-
-    uint32_t want = 0u;
-    if constexpr (LEVEL > 1) want = st->prefix >> HI_SHIFT;
 
     const int64_t nvec = n / 4;
     const int64_t stride = (int64_t)gridDim.x * kHistThreads;
@@ -186,38 +228,61 @@ __global__ __launch_bounds__(kHistThreads) void k_topk_hist(const float *__restr
         uint32_t s = 0u;
 #pragma unroll
         for (int w = 0; w < kHistWaves; ++w) s += lds[w][b];
-        if (s) atomicAdd(&hist[b], s);
+        if (s) atomicAdd(&hist[(blockIdx.x % kHistSlices) * 2048 + b], s);
     }
 }
 
 // Finds the digit at which the count from the top reaches k_rem: the largest b
 // with sum_{j >= b} hist[j] >= k_rem.  One workgroup of 256 threads.
-template <int LEVEL>
-__global__ __launch_bounds__(256) void k_topk_pick(topk_state *st, const uint32_t *__restrict__ hist)
+constexpr int kPickThreads = 1024;  // all of them add up the slices; the first 256 then scan
+
+template <int LEVEL, int GATE>
+__global__ __launch_bounds__(kPickThreads) void k_topk_pick(topk_state *st,
+                                                           const uint32_t *__restrict__ hist,
+                                                           int nslices)
 {
+    if (skip_tail(st, GATE)) return;
     constexpr int BINS = LEVEL == 3 ? kBins3 : kBins12;
     constexpr int PER = BINS / 256;
     constexpr int SHIFT = LEVEL == 1 ? 20 : (LEVEL == 2 ? 9 : 0);
     __shared__ uint32_t part[256];
+    __shared__ uint32_t total[BINS];
     const int tid = threadIdx.x;
     const uint32_t k_rem = st->k_rem;
-    // thread t owns bins [BINS - (t+1)*PER, BINS - t*PER): thread 0 the top ones
+    for (int bin = tid; bin < BINS; bin += kPickThreads) {  // neighbouring threads read neighbouring counters
+        uint32_t c[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+        int sl = 0;
+        for (; sl + 8 <= nslices; sl += 8) {  // eight independent loads in flight
+#pragma unroll
+            for (int j = 0; j < 8; ++j) c[j] += hist[(sl + j) * 2048 + bin];
+        }
+        for (; sl < nslices; ++sl) c[0] += hist[sl * 2048 + bin];
+        total[bin] = ((c[0] + c[1]) + (c[2] + c[3])) + ((c[4] + c[5]) + (c[6] + c[7]));
+    }
+    __syncthreads();
+    // The scan is the work of the first 256 threads; the others only keep every
+    // barrier complete (a barrier must be reached by all threads of the workgroup).
+    const bool scanner = tid < 256;
+    // scanner t owns bins [BINS - (t+1)*PER, BINS - t*PER): thread 0 the top ones
     uint32_t h[PER];
     uint32_t mine = 0u;
+    if (scanner) {
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {
-        h[j] = hist[BINS - 1 - (tid * PER + j)];  // descending bin order
-        mine += h[j];
+        for (int j = 0; j < PER; ++j) {
+            h[j] = total[BINS - 1 - (tid * PER + j)];  // descending bin order
+            mine += h[j];
+        }
+        part[tid] = mine;
     }
-    part[tid] = mine;
     __syncthreads();
-    // inclusive scan over threads (Hillis-Steele in LDS)
+    // inclusive scan over the scanners (Hillis-Steele in LDS)
     for (int d = 1; d < 256; d <<= 1) {
-        const uint32_t y = tid >= d ? part[tid - d] : 0u;
+        const uint32_t y = (scanner && tid >= d) ? part[tid - d] : 0u;
         __syncthreads();
-        part[tid] += y;
+        if (scanner) part[tid] += y;
         __syncthreads();
     }
+    if (!scanner) return;  // no barrier follows
     const uint32_t incl = part[tid], excl = incl - mine;
     if (k_rem > 0u && excl < k_rem && k_rem <= incl) {  // exactly one thread
         uint32_t above = excl;
@@ -260,32 +325,35 @@ __device__ __forceinline__ u32x4 load_keys(const float *R, int64_t n, int64_t e,
     return k;
 }
 
-__global__ __launch_bounds__(64) void k_topk_count(const float *__restrict__ R, int64_t n,
+__global__ __launch_bounds__(64) void k_topk_count(const float *__restrict__ R, int64_t n, int64_t ntiles,
                                                    const topk_state *__restrict__ st,
                                                    uint32_t *__restrict__ cnt_gt,
                                                    uint32_t *__restrict__ cnt_eq)
 {
+    if (skip_tail(st, kGeneralTail)) return;
     const uint32_t T = st->threshold;
     const int lane = threadIdx.x;
-    const int64_t base = (int64_t)blockIdx.x * kTile;
-    uint32_t gt = 0u, eq = 0u;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t base = tile * kTile;
+        uint32_t gt = 0u, eq = 0u;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
-        uint32_t valid;
-        const u32x4 k = load_keys(R, n, e, &valid);
+        for (int u = 0; u < 4; ++u) {
+            const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
+            uint32_t valid;
+            const u32x4 k = load_keys(R, n, e, &valid);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool ok = (valid >> j) & 1u;
-            gt += (ok && k[j] > T) ? 1u : 0u;
-            eq += (ok && k[j] == T) ? 1u : 0u;
+            for (int j = 0; j < 4; ++j) {
+                const bool ok = (valid >> j) & 1u;
+                gt += (ok && k[j] > T) ? 1u : 0u;
+                eq += (ok && k[j] == T) ? 1u : 0u;
+            }
         }
-    }
-    gt = wave_sum(gt);
-    eq = wave_sum(eq);
-    if (lane == 0) {
-        cnt_gt[blockIdx.x] = gt;
-        cnt_eq[blockIdx.x] = eq;
+        gt = wave_sum(gt);
+        eq = wave_sum(eq);
+        if (lane == 0) {
+            cnt_gt[tile] = gt;
+            cnt_eq[tile] = eq;
+        }
     }
 }
 
@@ -380,59 +448,216 @@ __global__ __launch_bounds__(64) void k_topk_write(float *R, int64_t n,
                                                    const uint32_t *__restrict__ chunk_gt,
                                                    const uint32_t *__restrict__ chunk_eq,
                                                    int64_t ntiles, float *__restrict__ vals,
-                                                   uint32_t *__restrict__ idx)
+                                                   uint32_t *__restrict__ idx, uint32_t kmax)
 {
+    if (skip_tail(st, kGeneralTail)) return;
     const uint32_t T = st->threshold, ties = st->ties;
     const int lane = threadIdx.x;
-    const int64_t tile = blockIdx.x;
-    const int64_t chunk = tile / kScanChunk;
-    const uint32_t gt_before = chunk_gt[chunk] + cnt_gt[tile];
-    uint32_t eq_before = chunk_eq[chunk] + cnt_eq[tile];
-    // how many this tile keeps: known from the prefixes of the next tile, but a
-    // cheap local test is enough to skip tiles that hold nothing at or above T
-    uint32_t out_pos = gt_before + (eq_before < ties ? eq_before : ties);
-    const int64_t base = tile * kTile;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t chunk = tile / kScanChunk;
+        const uint32_t gt_before = chunk_gt[chunk] + cnt_gt[tile];
+        uint32_t eq_before = chunk_eq[chunk] + cnt_eq[tile];
+        uint32_t out_pos = gt_before + (eq_before < ties ? eq_before : ties);
+        const int64_t base = tile * kTile;
 #pragma unroll 1
+        for (int u = 0; u < 4; ++u) {
+            const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
+            uint32_t valid;
+            const u32x4 k = load_keys(R, n, e, &valid);
+            uint32_t gtm = 0u, eqm = 0u;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool ok = (valid >> j) & 1u;
+                gtm |= (ok && k[j] > T) ? (1u << j) : 0u;
+                eqm |= (ok && k[j] == T) ? (1u << j) : 0u;
+            }
+            if (__ballot((gtm | eqm) != 0u) == 0ull) continue;  // nothing to keep in this round
+            const uint32_t eq_cnt = __popc(eqm);
+            const uint32_t eq_incl = wave_incl_scan(eq_cnt);
+            const uint32_t eq_total = __shfl(eq_incl, 63, 64);
+            uint32_t eq_rank = eq_before + eq_incl - eq_cnt;  // rank of this lane's first tie
+            uint32_t selm = gtm;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if ((eqm >> j) & 1u) {
+                    if (eq_rank < ties) selm |= 1u << j;
+                    ++eq_rank;
+                }
+            }
+            const uint32_t sel_cnt = __popc(selm);
+            const uint32_t sel_incl = wave_incl_scan(sel_cnt);
+            const uint32_t sel_total = __shfl(sel_incl, 63, 64);
+            uint32_t pos = out_pos + sel_incl - sel_cnt;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (((selm >> j) & 1u) && pos < kmax) {  // pos < kmax always holds (see above)
+                    const int64_t i = e + j;
+                    vals[pos] = R[i];
+                    idx[pos] = (uint32_t)i;
+                    R[i] = 0.0f;
+                    ++pos;
+                }
+            }
+            eq_before += eq_total;
+            out_pos += sel_total;
+        }
+    }
+}
+
+// ---- slot tail -------------------------------------------------------------------------
+
+// One wave per 1024-element tile: copies (index, bits) of every element whose
+// level-1 bin is >= the bin of the k-th largest key into the tile's slots, in
+// index order.
+__global__ __launch_bounds__(64) void k_topk_collect(const float *__restrict__ R, int64_t n,
+                                                     topk_state *st, uint32_t *__restrict__ slot_cnt,
+                                                     uint32_t *__restrict__ slot_idx,
+                                                     uint32_t *__restrict__ slot_bits)
+{
+    const uint32_t b1 = st->prefix >> 20;
+    const int lane = threadIdx.x;
+    const int64_t tile = blockIdx.x;
+    const int64_t base = tile * kTile;
+    uint32_t running = 0u;
+    u32x4 raws[4];
+    uint32_t valids[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {  // all four loads are in flight before the first is used
+        const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
+        raws[u] = u32x4{0u, 0u, 0u, 0u};
+        valids[u] = 0u;
+        if (e + 4 <= n) {
+            raws[u] = __builtin_nontemporal_load((const u32x4 *)(R + e));
+            valids[u] = 0xfu;
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (e + j < n) {
+                    raws[u][j] = __float_as_uint(R[e + j]);
+                    valids[u] |= 1u << j;
+                }
+        }
+    }
+#pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
-        uint32_t valid;
-        const u32x4 k = load_keys(R, n, e, &valid);
-        uint32_t gtm = 0u, eqm = 0u;
+        const u32x4 raw = raws[u];
+        const uint32_t valid = valids[u];
+        uint32_t m = 0u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            m |= (((valid >> j) & 1u) && ((raw[j] & kAbs) >> 20) >= b1) ? (1u << j) : 0u;
+        if (__ballot(m != 0u) == 0ull) continue;
+        const uint32_t cnt = __popc(m);
+        const uint32_t incl = wave_incl_scan(cnt);
+        const uint32_t total = __shfl(incl, 63, 64);
+        uint32_t pos = running + incl - cnt;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const bool ok = (valid >> j) & 1u;
-            gtm |= (ok && k[j] > T) ? (1u << j) : 0u;
-            eqm |= (ok && k[j] == T) ? (1u << j) : 0u;
-        }
-        if (__ballot((gtm | eqm) != 0u) == 0ull) continue;  // nothing to keep in this round
-        const uint32_t eq_cnt = __popc(eqm);
-        const uint32_t eq_incl = wave_incl_scan(eq_cnt);
-        const uint32_t eq_total = __shfl(eq_incl, 63, 64);
-        uint32_t eq_rank = eq_before + eq_incl - eq_cnt;  // rank of this lane's first tie
-        uint32_t selm = gtm;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if ((eqm >> j) & 1u) {
-                if (eq_rank < ties) selm |= 1u << j;
-                ++eq_rank;
-            }
-        }
-        const uint32_t sel_cnt = __popc(selm);
-        const uint32_t sel_incl = wave_incl_scan(sel_cnt);
-        const uint32_t sel_total = __shfl(sel_incl, 63, 64);
-        uint32_t pos = out_pos + sel_incl - sel_cnt;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if ((selm >> j) & 1u) {
-                const int64_t i = e + j;
-                vals[pos] = R[i];
-                idx[pos] = (uint32_t)i;
-                R[i] = 0.0f;
+            if ((m >> j) & 1u) {
+                if (pos < (uint32_t)kSlots) {
+                    slot_idx[tile * kSlots + pos] = (uint32_t)(e + j);
+                    slot_bits[tile * kSlots + pos] = raw[j];
+                }
                 ++pos;
             }
         }
-        eq_before += eq_total;
-        out_pos += sel_total;
+        running += total;
+    }
+    if (lane == 0) {
+        slot_cnt[tile] = running < (uint32_t)kSlots ? running : (uint32_t)kSlots;
+        if (running > (uint32_t)kSlots) atomicOr(&st->overflow, 1u);
+    }
+}
+
+// The remaining slot-tail kernels give one thread to each tile (a tile holds
+// four entries on average).
+
+// Histogram of the next digit over the slot entries: a few large workgroups, each
+// with an LDS histogram that it stores as its own slice.
+template <int LEVEL>
+__global__ __launch_bounds__(kSlotThreads) void k_topk_slots_hist(const topk_state *__restrict__ st,
+                                                                  const uint32_t *__restrict__ slot_cnt,
+                                                                  const uint32_t *__restrict__ slot_bits,
+                                                                  int64_t ntiles,
+                                                                  uint32_t *__restrict__ hist)
+{
+    if (skip_tail(st, kSlotTail)) return;
+    constexpr int BINS = LEVEL == 3 ? kBins3 : kBins12;
+    constexpr int SHIFT = LEVEL == 2 ? 9 : 0;
+    constexpr int HI_SHIFT = LEVEL == 2 ? 20 : 9;
+    __shared__ uint32_t lds[BINS];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < BINS; i += kSlotThreads) lds[i] = 0u;
+    __syncthreads();
+    const uint32_t want = st->prefix >> HI_SHIFT;
+    for (int64_t tile = (int64_t)blockIdx.x * kSlotThreads + tid; tile < ntiles;
+         tile += (int64_t)gridDim.x * kSlotThreads) {
+        const uint32_t cnt = slot_cnt[tile];
+        for (uint32_t i = 0; i < cnt; ++i) {
+            const uint32_t key = slot_bits[tile * kSlots + i] & kAbs;
+            if ((key >> HI_SHIFT) == want) atomicAdd(&lds[(key >> SHIFT) & (BINS - 1)], 1u);
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < BINS; i += kSlotThreads) hist[blockIdx.x * 2048 + i] = lds[i];
+}
+
+__global__ __launch_bounds__(256) void k_topk_slots_count(const topk_state *__restrict__ st,
+                                                          const uint32_t *__restrict__ slot_cnt,
+                                                          const uint32_t *__restrict__ slot_bits,
+                                                          int64_t ntiles, uint32_t *__restrict__ cnt_gt,
+                                                          uint32_t *__restrict__ cnt_eq)
+{
+    if (skip_tail(st, kSlotTail)) return;
+    const int64_t tile = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (tile >= ntiles) return;
+    const uint32_t T = st->threshold;
+    const uint32_t cnt = slot_cnt[tile];
+    uint32_t gt = 0u, eq = 0u;
+    for (uint32_t i = 0; i < cnt; ++i) {
+        const uint32_t key = slot_bits[tile * kSlots + i] & kAbs;
+        gt += key > T ? 1u : 0u;
+        eq += key == T ? 1u : 0u;
+    }
+    cnt_gt[tile] = gt;
+    cnt_eq[tile] = eq;
+}
+
+__global__ __launch_bounds__(256) void k_topk_slots_write(float *R, const topk_state *__restrict__ st,
+                                                          const uint32_t *__restrict__ slot_cnt,
+                                                          const uint32_t *__restrict__ slot_idx,
+                                                          const uint32_t *__restrict__ slot_bits,
+                                                          const uint32_t *__restrict__ cnt_gt,
+                                                          const uint32_t *__restrict__ cnt_eq,
+                                                          const uint32_t *__restrict__ chunk_gt,
+                                                          const uint32_t *__restrict__ chunk_eq,
+                                                          int64_t ntiles, float *__restrict__ vals,
+                                                          uint32_t *__restrict__ idx, uint32_t kmax)
+{
+    if (skip_tail(st, kSlotTail)) return;
+    const int64_t tile = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (tile >= ntiles) return;
+    const uint32_t cnt = slot_cnt[tile];
+    if (cnt == 0u) return;
+    const uint32_t T = st->threshold, ties = st->ties;
+    const int64_t chunk = tile / kScanChunk;
+    uint32_t eq_before = chunk_eq[chunk] + cnt_eq[tile];
+    uint32_t pos = chunk_gt[chunk] + cnt_gt[tile] + (eq_before < ties ? eq_before : ties);
+    for (uint32_t i = 0; i < cnt; ++i) {  // entries are in ascending index order
+        const uint32_t bits = slot_bits[tile * kSlots + i];
+        const uint32_t key = bits & kAbs;
+        bool keep = key > T;
+        if (key == T) {
+            keep = eq_before < ties;
+            ++eq_before;
+        }
+        if (keep && pos < kmax) {  // pos < kmax always holds; the test keeps a corrupted workspace harmless
+            const uint32_t at = slot_idx[tile * kSlots + i];
+            vals[pos] = __uint_as_float(bits);
+            idx[pos] = at;
+            R[at] = 0.0f;
+            ++pos;
+        }
     }
 }
 
@@ -483,19 +708,37 @@ covap_status_t topk_compress(const void *grad, void *residual, int64_t n, int64_
     int64_t hist_grid = div_up(nvec > 0 ? nvec : 1, kHistThreads);
     if (hist_grid > 2048) hist_grid = 2048;
 
-    k_topk_init<<<1, 256, 0, st>>>(ws.state, ws.hist, (uint32_t)k);
-    k_topk_hist<1><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(G, R, n, ef_coeff, ws.state, ws.hist);
+    uint32_t *h1 = ws.hist, *h2g = h1 + kHistSlices * 2048, *h3g = h2g + kHistSlices * 2048,
+             *h2s = h3g + kHistSlices * 2048, *h3s = h2s + kSlotGrid * 2048;
+    const uint32_t per_tile_grid = (uint32_t)div_up(ntiles, 256);
+    // the general tail's tile kernels walk the tiles with a bounded grid, so that
+    // they cost next to nothing when they are not taken
+    const uint32_t tail_grid = (uint32_t)(ntiles < 16384 ? ntiles : 16384);
+    k_topk_init<<<64, 256, 0, st>>>(ws.state, ws.hist, (uint32_t)k);
+    k_topk_hist<1><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(G, R, n, ef_coeff, ws.state, h1);
     if (k > 0) {
-        k_topk_pick<1><<<1, 256, 0, st>>>(ws.state, ws.hist);
-        k_topk_hist<2><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(G, R, n, ef_coeff, ws.state, ws.hist + 2048);
-        k_topk_pick<2><<<1, 256, 0, st>>>(ws.state, ws.hist + 2048);
-        k_topk_hist<3><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(G, R, n, ef_coeff, ws.state, ws.hist + 4096);
-        k_topk_pick<3><<<1, 256, 0, st>>>(ws.state, ws.hist + 4096);
-        k_topk_count<<<(uint32_t)ntiles, 64, 0, st>>>(R, n, ws.state, ws.cnt_gt, ws.cnt_eq);
+        k_topk_pick<1, kAlways><<<1, kPickThreads, 0, st>>>(ws.state, h1, kHistSlices);
+        k_topk_collect<<<(uint32_t)ntiles, 64, 0, st>>>(R, n, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits);
+        // slot tail (returns at once if a tile overflowed its slots)
+        k_topk_slots_hist<2><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, h2s);
+        k_topk_pick<2, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h2s, kSlotGrid);
+        k_topk_slots_hist<3><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, h3s);
+        k_topk_pick<3, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h3s, kSlotGrid);
+        k_topk_slots_count<<<per_tile_grid, 256, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.cnt_gt, ws.cnt_eq);
+        // general tail (returns at once otherwise)
+        k_topk_hist<2><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(G, R, n, ef_coeff, ws.state, h2g);
+        k_topk_pick<2, kGeneralTail><<<1, kPickThreads, 0, st>>>(ws.state, h2g, kHistSlices);
+        k_topk_hist<3><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(G, R, n, ef_coeff, ws.state, h3g);
+        k_topk_pick<3, kGeneralTail><<<1, kPickThreads, 0, st>>>(ws.state, h3g, kHistSlices);
+        k_topk_count<<<tail_grid, 64, 0, st>>>(R, n, ntiles, ws.state, ws.cnt_gt, ws.cnt_eq);
+        // common: exclusive scan of the per-tile counts, then the ordered write
         k_topk_scan_a<<<(uint32_t)nchunks, 256, 0, st>>>(ws.cnt_gt, ws.cnt_eq, ntiles, ws.chunk_gt, ws.chunk_eq);
         k_topk_scan_b<<<1, 256, 0, st>>>(ws.chunk_gt, ws.chunk_eq, nchunks);
-        k_topk_write<<<(uint32_t)ntiles, 64, 0, st>>>(R, n, ws.state, ws.cnt_gt, ws.cnt_eq, ws.chunk_gt,
-                                                     ws.chunk_eq, ntiles, (float *)out_vals, out_idx);
+        k_topk_slots_write<<<per_tile_grid, 256, 0, st>>>(R, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.cnt_gt,
+                                                          ws.cnt_eq, ws.chunk_gt, ws.chunk_eq, ntiles,
+                                                          (float *)out_vals, out_idx, (uint32_t)k);
+        k_topk_write<<<tail_grid, 64, 0, st>>>(R, n, ws.state, ws.cnt_gt, ws.cnt_eq, ws.chunk_gt,
+                                                     ws.chunk_eq, ntiles, (float *)out_vals, out_idx, (uint32_t)k);
     }
     return check("topk_compress");
 }

@@ -151,3 +151,43 @@ def test_argument_errors(B):
         B.topk_compress(G, R, 10, vals, idx, ws, dtype=B.COVAP_BF16)
     assert e.value.status == 5
     torch.cuda.synchronize()
+
+
+def tail_taken(ws):
+    """Word 4 of the workspace is the device flag that says a tile overflowed its
+    slots, i.e. that the general tail produced the result."""
+    return "general" if int(ws.view(torch.int32)[4].item()) != 0 else "slots"
+
+
+@pytest.mark.parametrize("kind,want", [("normal", "slots"), ("student_t", "slots"), ("clustered", "general"),
+                                       ("ties", "general"), ("k_large", "general")])
+def test_both_tails_are_exercised_and_agree_with_the_oracle(B, kind, want):
+    n = 1_200_003
+    k = n // 1000
+    rng = np.random.default_rng(11)
+    if kind == "normal":
+        Gn = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    elif kind == "student_t":
+        Gn = (rng.standard_t(3, n) * 1e-3).astype(np.float32)
+    elif kind == "clustered":                              # all the large values sit in a few tiles
+        Gn = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+        Gn[5000:9000] *= 100.0
+    elif kind == "ties":
+        Gn = rng.integers(-3, 4, n).astype(np.float32)
+    else:
+        Gn = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+        k = n // 3
+    Rn = (rng.standard_normal(n) * 1e-4).astype(np.float32)
+    G = torch.from_numpy(Gn).to(DEV)
+    R = torch.from_numpy(Rn).to(DEV)
+    ws = torch.empty(B.topk_workspace_bytes(n), dtype=torch.uint8, device=DEV)
+    vals = torch.empty(k, device=DEV)
+    idx = torch.empty(k, dtype=torch.int32, device=DEV)
+    B.topk_compress(G, R, k, vals, idx, ws)
+    torch.cuda.synchronize()
+    assert tail_taken(ws) == want
+    Rc = Rn.copy()
+    ov, oi = oracle.topk(Gn, Rc, k)
+    assert np.array_equal(idx.cpu().numpy().view(np.uint32), oi)
+    assert np.array_equal(vals.cpu().numpy().view(np.uint32), ov.view(np.uint32))
+    assert np.array_equal(R.cpu().numpy().view(np.uint32), Rc.view(np.uint32))
