@@ -58,6 +58,16 @@ def read_traffic(kernel: str, workload: str):
     return float(m.group(1)) if m else None
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -192,6 +202,18 @@ def main():
         torch.cuda.synchronize()
         copy_gbs = 2 * nb * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
         out["probe_copy_GB/s"] = round(copy_gbs, 1)
+        if args.dtype == "f32":
+            # a = b + s*c: the two-reads-one-write shape of compress without its index work
+            nt = nb // 4
+            ta, tb, tc_ = dense[:nt], ring[0][:nt], ring[1][:nt]
+            for _ in range(3):
+                B.covap_probe_triad(ta, tb, tc_, 0.5, nt, stream=stream)
+            e0.record(stream)
+            for _ in range(reps):
+                B.covap_probe_triad(ta, tb, tc_, 0.5, nt, stream=stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            out["probe_triad_GB/s"] = round(3 * nb * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
 
     # ---- top-k contrast on the same gradient buffers
     if not args.no_topk and args.dtype == "f32":
@@ -393,7 +415,20 @@ def main():
                                "cores": 1, "kind": "oracle",
                                "sample": "1 full iteration of the same workload (compress %.2f s + "
                                          "decompress %.2f s), single thread" % (c1 - c0, c2 - c1),
-                               "host_cpus": os.cpu_count()}
+                               "compress_us_per_iter": round((c1 - c0) * 1e6),
+                               "decompress_us_per_iter": round((c2 - c1) * 1e6),
+                               "host_cpus": os.cpu_count(), "cpu_model": cpu_model()}
+        if args.dtype == "f32" and not args.no_topk:
+            # the oracle's top-k sorts; time it on the first 2^24 elements only and say so
+            ns = min(D, 1 << 24)
+            ks = -(-ns // 1000)
+            Gs, Rs = Gn[:ns].copy(), to_np(ring[(t + 1) % 3])[:ns].copy()
+            c3 = time.perf_counter()
+            oracle.topk(Gs, Rs, ks)
+            c4 = time.perf_counter()
+            out["cpu_baseline"]["topk_sample"] = {
+                "elements": ns, "k": ks, "us": round((c4 - c3) * 1e6),
+                "note": "top-k oracle (full sort) on the first %d elements of the same gradient" % ns}
 
     print(json.dumps(out), flush=True)
 

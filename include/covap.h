@@ -267,6 +267,9 @@ covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float
  *   "nontemporal"        streaming cache hints on loads and stores: 0, 1
  *   "decompress_lds_pad" bytes of unused LDS reserved per decompress workgroup, which
  *                        caps its occupancy: 0, 6144, 8192
+ *   "topk_pass1_waves"   waves that share a 1024-element tile in the first pass of
+ *                        topk_compress: 1, 2, 4
+ *   "topk_pass1_lds_pad" as decompress_lds_pad, for that pass: 0, 6144, 8192, 24576
  * No knob changes any result bit.  EINVAL for an unknown key or value.  Global
  * to the process and not thread-safe against running calls. */
 covap_status_t covap_tune_set(const char *key, int32_t value);

@@ -382,6 +382,8 @@ const knob kKnobs[] = {
     {"decompress_unroll", &covap::tuning::decompress_unroll, {1, 2, 4, -1, -1}},
     {"nontemporal", &covap::tuning::nontemporal, {0, 1, -1, -1, -1}},
     {"decompress_lds_pad", &covap::tuning::decompress_lds_pad, {0, 6144, 8192, -1, -1}},
+    {"topk_pass1_waves", &covap::tuning::topk_pass1_waves, {1, 2, 4, -1, -1}},
+    {"topk_pass1_lds_pad", &covap::tuning::topk_pass1_lds_pad, {0, 6144, 8192, 24576, -1}},
 };
 }  // namespace
 

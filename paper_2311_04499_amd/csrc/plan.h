@@ -66,6 +66,8 @@ struct tuning {
     // workgroups 6144 caps a SIMD at 7 waves instead of 8 (8192: 6); a little less data in
     // flight keeps the DRAM access pattern tighter (+1.5..3 % measured).
     int decompress_lds_pad = 6144;
+    int topk_pass1_waves = 4;      // waves that share a 1024-element tile in top-k pass 1: 1, 2, 4
+    int topk_pass1_lds_pad = 0;    // unused LDS per pass-1 workgroup, bytes: 0, 6144, 8192, 24576
 };
 tuning &tune();
 

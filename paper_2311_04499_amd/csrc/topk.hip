@@ -1,30 +1,35 @@
 // Fine-grained top-k sparsifier with error feedback: the contrast point to the
 // coarse filter (Sec. I and Table II: "most of the overhead in Top-k comes from
-// the topk() operator").  Exact, deterministic, no sampling.
+// the topk() operator").  Exact and deterministic: a sample only decides how much
+// work the exact selection has to do, never what it returns.
 //
-//   pass 1   A = fma(c, R, G); R <- A; histogram of key bits 30..20        (reads 2D, writes D)
+//   sample   A = fma(c, R, G) on 4096 evenly spread 256-element chunks; histogram of
+//            key bits 30..20 -> a bin b_lo that very probably lies at or below the bin
+//            of the k-th largest key, with only a fraction of a percent of the keys
+//            at or above it                                          (reads 8 MB)
+//   pass 1   A = fma(c, R, G); R <- A; every element whose bin is >= b_lo is counted
+//            in the histogram of bits 30..20 and copied, in index order, into a
+//            32-entry slot array of its 1024-element tile        (reads 2D, writes D)
 //            -> the bin b1 that holds the k-th largest key
-//   collect  one more read of R: every element whose bin is >= b1 is copied, in
-//            index order, into a 32-entry slot array of its 1024-element tile, and
-//            the histogram of bits 19..9 among bin b1 is taken on the way    (reads D)
-//   then everything works on the slots only (about 0.3 % of the data): histogram
-//   of bits 8..0 -> threshold key T and the number of ties to keep; per-tile
-//   counts; 3-phase exclusive scan; ordered write of (value, index), R <- +0 there.
+//   then everything works on the slots only (a fraction of a percent of the data):
+//   histograms of bits 19..9 and 8..0 -> threshold key T and the number of ties to
+//   keep; per-tile counts; 3-phase exclusive scan; ordered write of (value, index),
+//   R <- +0 there.
 //
-// If any tile has more than 32 such elements (heavily clustered or tied data) a
-// flag is raised on the device and the general path runs instead: two more
-// full histogram passes, a counting pass and a compaction pass over R (4 more
-// reads of D).  The host launches both tails; every kernel of the tail that is
-// not taken returns at once, so no host round trip is needed.  Both tails give
-// the same bits.
+// If the bins >= b_lo turn out to hold fewer than k keys (the sample misled), or if
+// any tile has more than 32 such elements (heavily clustered or tied data, large
+// k), a flag is raised on the device and the general path runs instead: three full
+// histogram passes, a counting pass and a compaction pass over R (5 more reads of
+// D).  The host launches both tails; every kernel of the tail that is not taken
+// returns at once, so no host round trip is needed.  Both tails give the same bits.
 //
 // key = bit pattern of |A| as an unsigned integer: a total order on magnitudes
 // (NaN above Inf).  Among keys equal to T the lowest indices are kept, which
 // makes the result unique.  Every decision is integer work on bit patterns.
 //
-// Histograms live in LDS per workgroup (a copy per wave) and are flushed once
-// per workgroup; compaction uses wavefront prefix sums (one-wave workgroups, so
-// no barriers).  All scratch is in the caller's workspace; nothing is allocated.
+// Histograms live in LDS per workgroup and are flushed once per workgroup;
+// compaction uses wavefront prefix sums.  All scratch is in the caller's
+// workspace; nothing is allocated.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -50,21 +55,26 @@ struct topk_state {
     uint32_t k_rem;      // how many are still to be taken from the current bin
     uint32_t threshold;  // T, valid after level 3
     uint32_t ties;       // number of keys == T to keep, valid after level 3
-    uint32_t overflow;   // != 0: some tile did not fit its slots, the general tail runs
-    uint32_t pad[3];
+    uint32_t overflow;   // != 0: the general tail runs (bit 0: a tile did not fit its slots,
+                         // bit 1: the bins >= b_lo hold fewer than k keys)
+    uint32_t b_lo;       // pass 1 looks only at keys whose level-1 bin is >= b_lo
+    uint32_t k;          // the k of this call
+    uint32_t pad;
 };
 
 constexpr int kSlots = 32;  // slot entries per 1024-element tile
-// Histograms may be kept as several partial copies ("slices") that the pick
-// kernel adds up.  Global atomics run at about 1.5 G/s on this chip whatever the
-// address spread (320 k of them cost 200 us), so the slot passes, whose entries are
-// few, build LDS histograms and store them as slices without any global atomic;
-// the full-data passes flush one LDS histogram per workgroup (a few dozen
-// non-empty bins each) and need no slicing.
-constexpr int kHistSlices = 1;    // full-data passes: workgroup w adds into slice w mod kHistSlices
-constexpr int kSlotGrid = 64;     // slot passes: one slice per workgroup, written with plain stores
-constexpr int kSlotThreads = 512;
-constexpr int kHistRows = 3 * kHistSlices + 2 * kSlotGrid;  // rows of 2048 counters in the workspace
+// A histogram is either one row that workgroups add their non-empty LDS bins to,
+// or several partial copies ("slices"), one per workgroup, that the pick kernel
+// adds up.  Global atomics run at about 1.5 G/s on this chip whatever the address
+// spread (320 k of them cost 200 us), so the passes of the usual path (the sample
+// and the slot passes: 64 workgroups each) store slices; only the general tail's
+// full-data passes, with 2048 workgroups, add to one row.
+constexpr int kAtomicRows = 3;    // general tail levels 1, 2, 3: one row each, added to atomically
+constexpr int kSlotGrid = 64;     // slot passes and the sample: one slice per workgroup, plain stores
+constexpr int kSlotThreads = 1024;
+constexpr int kHistRows = kAtomicRows + 3 * kSlotGrid;  // rows of 2048 counters in the workspace
+constexpr int kSampleChunks = 4096;  // the sample: this many chunks of 64 vectors (256 elements)
+constexpr int kSampleThreads = 256;
 enum { kAlways = 0, kSlotTail = 1, kGeneralTail = 2 };
 
 // True if a kernel of tail `gate` has nothing to do.
@@ -76,7 +86,8 @@ __device__ __forceinline__ bool skip_tail(const topk_state *st, int gate)
 
 struct topk_ws {
     topk_state *state;
-    uint32_t *hist;       // [kHistRows][2048]: level 1 | general tail levels 2, 3 | slot tail levels 2, 3
+    uint32_t *hist;       // [kHistRows][2048]: general tail levels 1, 2, 3 | slot tail levels 1, 2, 3
+                          // (the sample's slices share the rows of slot level 2, which comes later)
     uint32_t *slot_cnt;   // [ntiles]
     uint32_t *slot_idx;   // [ntiles][kSlots]
     uint32_t *slot_bits;  // [ntiles][kSlots]  bit patterns of A
@@ -142,43 +153,184 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x)
     return x;
 }
 
-// ---- init ------------------------------------------------------------------------
+// ---- sample (and workspace reset) ---------------------------------------------------
 
-__global__ void k_topk_init(topk_state *st, uint32_t *hist, uint32_t k)
+// Resets the selection state and the atomically accumulated histogram rows, and
+// takes the level-1 histogram of A on `n_s` chunks of 64 vectors spread evenly
+// over the `nchunks` full chunks of the data.  Each workgroup stores its LDS
+// histogram as its own slice.  Grid: kSlotGrid workgroups of kSampleThreads.
+__global__ __launch_bounds__(kSampleThreads) void k_topk_sample(const float *__restrict__ G,
+                                                                const float *__restrict__ R, float c,
+                                                                int64_t nchunks, int32_t n_s,
+                                                                topk_state *st, uint32_t *hist_rows,
+                                                                uint32_t *__restrict__ slices, uint32_t k)
 {
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < kHistRows * 2048; i += gridDim.x * blockDim.x)
-        hist[i] = 0u;
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    __shared__ uint32_t lds[kBins12];
+    const int tid = threadIdx.x;
+    const int gid = blockIdx.x * kSampleThreads + tid;
+    for (int i = gid; i < kAtomicRows * 2048; i += kSlotGrid * kSampleThreads) hist_rows[i] = 0u;
+    if (gid == 0) {
         st->prefix = 0u;
         st->k_rem = k;
         st->threshold = 0u;
         st->ties = 0u;
         st->overflow = 0u;
+        st->b_lo = 0u;
+        st->k = k;
+    }
+    for (int i = tid; i < kBins12; i += kSampleThreads) lds[i] = 0u;
+    __syncthreads();
+    const int lane = tid & 63;
+    constexpr int kWaves = kSampleThreads / 64;
+    for (int j = blockIdx.x * kWaves + (tid >> 6); j < n_s; j += kSlotGrid * kWaves) {
+        const int64_t q = (int64_t)j * nchunks / n_s;  // < nchunks
+        const int64_t v = q * 64 + lane;
+        const f32x4 g = ((const f32x4 *)G)[v];
+        const f32x4 r = ((const f32x4 *)R)[v];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t key = __float_as_uint(__builtin_fmaf(c, r[e], g[e])) & kAbs;
+            atomicAdd(&lds[key >> 20], 1u);
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < kBins12; i += kSampleThreads) slices[blockIdx.x * 2048 + i] = lds[i];
+}
+
+// ---- pass 1 ------------------------------------------------------------------------------
+
+// Four values of a tile round: element e .. e+3 (e a multiple of 4); `valid` has
+// one bit per element that lies below n.
+__device__ __forceinline__ f32x4 load4(const float *p, int64_t n, int64_t e, uint32_t *valid)
+{
+    f32x4 x = {0.0f, 0.0f, 0.0f, 0.0f};
+    *valid = 0u;
+    if (e + 4 <= n) {
+        x = __builtin_nontemporal_load((const f32x4 *)(p + e));
+        *valid = 0xfu;
+    } else {
+        for (int j = 0; j < 4; ++j)
+            if (e + j < n) {
+                x[j] = p[e + j];
+                *valid |= 1u << j;
+            }
+    }
+    return x;
+}
+
+// Number of set bits of `mask` that belong to lanes below this one.
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// Error feedback, residual write, and the ordered copy of every key whose level-1
+// bin is >= b_lo into the slots of its tile.  One workgroup of WAVES waves per
+// 1024-element tile, in four rounds of 64 lanes x 4 elements (ascending index
+// order); a wave takes 4 / WAVES consecutive rounds.  Ranks inside a round come from
+// the lane masks of the four components, ranks across waves through LDS.
+template <int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void k_topk_pass1(const float *__restrict__ G, float *R,
+                                                           int64_t n, float c, topk_state *st,
+                                                           uint32_t *__restrict__ slot_cnt,
+                                                           uint32_t *__restrict__ slot_idx,
+                                                           uint32_t *__restrict__ slot_bits)
+{
+    constexpr int ROUNDS = 4 / WAVES;
+    __shared__ uint32_t wave_total[WAVES];
+    const uint32_t b_lo = st->b_lo;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int64_t tile = blockIdx.x;
+    const int64_t base = tile * kTile + (int64_t)wv * ROUNDS * 256;
+    f32x4 g[ROUNDS], r[ROUNDS];
+    uint32_t valids[ROUNDS];
+#pragma unroll
+    for (int u = 0; u < ROUNDS; ++u) {  // all loads are in flight before the first is used
+        const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
+        g[u] = load4(G, n, e, &valids[u]);
+        r[u] = load4(R, n, e, &valids[u]);
+    }
+    u32x4 raw[ROUNDS];
+    uint32_t cand[ROUNDS], rank[ROUNDS];  // per round: 4-bit mask of kept components, rank of the first
+    uint32_t running = 0u;
+#pragma unroll
+    for (int u = 0; u < ROUNDS; ++u) {
+        const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
+        const uint32_t valid = valids[u];
+        f32x4 a;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] = __builtin_fmaf(c, r[u][j], g[u][j]);
+        if (valid == 0xfu) {
+            __builtin_nontemporal_store(a, (f32x4 *)(R + e));  // only single elements are read again
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if ((valid >> j) & 1u) R[e + j] = a[j];
+        }
+        raw[u] = __builtin_bit_cast(u32x4, a);
+        bool cj[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) cj[j] = ((valid >> j) & 1u) && ((raw[u][j] & kAbs) >> 20) >= b_lo;
+        const uint64_t m0 = __ballot(cj[0]), m1 = __ballot(cj[1]), m2 = __ballot(cj[2]), m3 = __ballot(cj[3]);
+        cand[u] = (cj[0] ? 1u : 0u) | (cj[1] ? 2u : 0u) | (cj[2] ? 4u : 0u) | (cj[3] ? 8u : 0u);
+        rank[u] = running;
+        if ((m0 | m1 | m2 | m3) != 0ull) {
+            rank[u] += lanes_below(m0) + lanes_below(m1) + lanes_below(m2) + lanes_below(m3);
+            running += (uint32_t)(__popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3));
+        }
+    }
+    uint32_t before = 0u, total = running;
+    if constexpr (WAVES > 1) {
+        if (lane == 0) wave_total[wv] = running;
+        __syncthreads();
+        total = 0u;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) {
+            const uint32_t t = wave_total[w];
+            before += w < wv ? t : 0u;
+            total += t;
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < ROUNDS; ++u) {
+        if (cand[u] == 0u) continue;
+        const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
+        uint32_t pos = before + rank[u];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if ((cand[u] >> j) & 1u) {
+                if (pos < (uint32_t)kSlots) {
+                    slot_idx[tile * kSlots + pos] = (uint32_t)(e + j);
+                    slot_bits[tile * kSlots + pos] = raw[u][j];
+                }
+                ++pos;
+            }
+        }
+    }
+    if (threadIdx.x == 0) {
+        slot_cnt[tile] = total < (uint32_t)kSlots ? total : (uint32_t)kSlots;
+        if (total > (uint32_t)kSlots && (*(volatile uint32_t *)&st->overflow & 1u) == 0u)
+            atomicOr(&st->overflow, 1u);
     }
 }
 
-// ---- histogram passes ----------------------------------------------------------------
+// ---- full histogram passes (general tail only) --------------------------------------------
 
-// LEVEL 1: error feedback + residual write + histogram of bits 30..20.
-// LEVEL 2/3: histogram of the next digit among keys that match the prefix.
-// Persistent workgroups: each walks tiles of kHistThreads vectors with a grid
-// stride and keeps one LDS histogram per wave.
+// Histogram of one digit of the keys in R: level 1 counts every key, levels 2 and 3
+// the keys that match the prefix found so far.  Persistent workgroups: each walks
+// tiles of kHistThreads vectors with a grid stride and keeps one LDS histogram per
+// wave.
 template <int LEVEL>
-__global__ __launch_bounds__(kHistThreads) void k_topk_hist(const float *__restrict__ G, float *R,
-                                                            int64_t n, float c,
+__global__ __launch_bounds__(kHistThreads) void k_topk_hist(const float *__restrict__ R, int64_t n,
                                                             const topk_state *__restrict__ st,
                                                             uint32_t *__restrict__ hist)
 {
     constexpr int BINS = LEVEL == 3 ? kBins3 : kBins12;
     constexpr int SHIFT = LEVEL == 1 ? 20 : (LEVEL == 2 ? 9 : 0);
-    constexpr int HI_SHIFT = LEVEL == 2 ? 20 : 9;  // bits above this digit (levels 2, 3)
+    constexpr int HI_SHIFT = LEVEL == 1 ? 31 : (LEVEL == 2 ? 20 : 9);  // bits above this digit
     __shared__ uint32_t lds[kHistWaves][BINS];
     const int tid = threadIdx.x;
-    uint32_t want = 0u;
-    if constexpr (LEVEL > 1) {
-        if (skip_tail(st, kGeneralTail)) return;  // same answer for every thread of the grid
-        want = st->prefix >> HI_SHIFT;
-    }
+    if (skip_tail(st, kGeneralTail)) return;  // same answer for every thread of the grid
+    const uint32_t want = LEVEL == 1 ? 0u : st->prefix >> HI_SHIFT;  // keys have bit 31 clear
     uint32_t *mine = lds[tid >> 6];
     for (int i = tid; i < kHistWaves * BINS; i += kHistThreads) (&lds[0][0])[i] = 0u;
     __syncthreads();
@@ -186,69 +338,50 @@ __global__ __launch_bounds__(kHistThreads) void k_topk_hist(const float *__restr
     const int64_t nvec = n / 4;
     const int64_t stride = (int64_t)gridDim.x * kHistThreads;
     for (int64_t v = (int64_t)blockIdx.x * kHistThreads + tid; v < nvec; v += stride) {
-        u32x4 key;
-        if constexpr (LEVEL == 1) {
-            const f32x4 g = __builtin_nontemporal_load((const f32x4 *)G + v);
-            const f32x4 r = __builtin_nontemporal_load((const f32x4 *)R + v);
-            f32x4 a;
-            a.x = __builtin_fmaf(c, r.x, g.x);
-            a.y = __builtin_fmaf(c, r.y, g.y);
-            a.z = __builtin_fmaf(c, r.z, g.z);
-            a.w = __builtin_fmaf(c, r.w, g.w);
-            ((f32x4 *)R)[v] = a;  // read again by the later passes: keep it cacheable
-            key = __builtin_bit_cast(u32x4, a) & kAbs;
-            atomicAdd(&mine[key.x >> SHIFT], 1u);
-            atomicAdd(&mine[key.y >> SHIFT], 1u);
-            atomicAdd(&mine[key.z >> SHIFT], 1u);
-            atomicAdd(&mine[key.w >> SHIFT], 1u);
-        } else {
-            key = __builtin_nontemporal_load((const u32x4 *)R + v) & kAbs;
-            if ((key.x >> HI_SHIFT) == want) atomicAdd(&mine[(key.x >> SHIFT) & (BINS - 1)], 1u);
-            if ((key.y >> HI_SHIFT) == want) atomicAdd(&mine[(key.y >> SHIFT) & (BINS - 1)], 1u);
-            if ((key.z >> HI_SHIFT) == want) atomicAdd(&mine[(key.z >> SHIFT) & (BINS - 1)], 1u);
-            if ((key.w >> HI_SHIFT) == want) atomicAdd(&mine[(key.w >> SHIFT) & (BINS - 1)], 1u);
-        }
+        const u32x4 key = __builtin_nontemporal_load((const u32x4 *)R + v) & kAbs;
+        if ((key.x >> HI_SHIFT) == want) atomicAdd(&mine[(key.x >> SHIFT) & (BINS - 1)], 1u);
+        if ((key.y >> HI_SHIFT) == want) atomicAdd(&mine[(key.y >> SHIFT) & (BINS - 1)], 1u);
+        if ((key.z >> HI_SHIFT) == want) atomicAdd(&mine[(key.z >> SHIFT) & (BINS - 1)], 1u);
+        if ((key.w >> HI_SHIFT) == want) atomicAdd(&mine[(key.w >> SHIFT) & (BINS - 1)], 1u);
     }
     // scalar tail (n mod 4 elements), one workgroup only
     if (blockIdx.x == 0 && tid < (int)(n - nvec * 4)) {
-        const int64_t i = nvec * 4 + tid;
-        uint32_t key;
-        if constexpr (LEVEL == 1) {
-            const float a = __builtin_fmaf(c, R[i], G[i]);
-            R[i] = a;
-            key = __float_as_uint(a) & kAbs;
-            atomicAdd(&mine[key >> SHIFT], 1u);
-        } else {
-            key = __float_as_uint(R[i]) & kAbs;
-            if ((key >> HI_SHIFT) == want) atomicAdd(&mine[(key >> SHIFT) & (BINS - 1)], 1u);
-        }
+        const uint32_t key = __float_as_uint(R[nvec * 4 + tid]) & kAbs;
+        if ((key >> HI_SHIFT) == want) atomicAdd(&mine[(key >> SHIFT) & (BINS - 1)], 1u);
     }
     __syncthreads();
     for (int b = tid; b < BINS; b += kHistThreads) {
         uint32_t s = 0u;
 #pragma unroll
         for (int w = 0; w < kHistWaves; ++w) s += lds[w][b];
-        if (s) atomicAdd(&hist[(blockIdx.x % kHistSlices) * 2048 + b], s);
+        if (s) atomicAdd(&hist[b], s);
     }
 }
 
-// Finds the digit at which the count from the top reaches k_rem: the largest b
-// with sum_{j >= b} hist[j] >= k_rem.  One workgroup of 256 threads.
+// Finds the digit at which the count from the top reaches the wanted count: the
+// largest b with sum_{j >= b} hist[j] >= wanted.  One workgroup.
+//   LEVEL 0     on the sample: wanted = `target`; the digit becomes b_lo (0 if the
+//               sample is too small to tell)
+//   LEVEL 1     wanted = k; the digit opens the prefix.  On the slots (GATE kSlotTail)
+//               a total below k means that b_lo was too high: the general tail is
+//               switched on.
+//   LEVEL 2, 3  wanted = k_rem; the digit extends the prefix; level 3 fixes T.
 constexpr int kPickThreads = 1024;  // all of them add up the slices; the first 256 then scan
 
 template <int LEVEL, int GATE>
 __global__ __launch_bounds__(kPickThreads) void k_topk_pick(topk_state *st,
                                                            const uint32_t *__restrict__ hist,
-                                                           int nslices)
+                                                           int nslices, uint32_t target)
 {
     if (skip_tail(st, GATE)) return;
     constexpr int BINS = LEVEL == 3 ? kBins3 : kBins12;
     constexpr int PER = BINS / 256;
-    constexpr int SHIFT = LEVEL == 1 ? 20 : (LEVEL == 2 ? 9 : 0);
+    constexpr int SHIFT = LEVEL <= 1 ? 20 : (LEVEL == 2 ? 9 : 0);
     __shared__ uint32_t part[256];
     __shared__ uint32_t total[BINS];
     const int tid = threadIdx.x;
-    const uint32_t k_rem = st->k_rem;
+    const uint32_t k_rem = LEVEL == 0 ? target : (LEVEL == 1 ? st->k : st->k_rem);
+    const uint32_t base_prefix = LEVEL <= 1 ? 0u : st->prefix;
     for (int bin = tid; bin < BINS; bin += kPickThreads) {  // neighbouring threads read neighbouring counters
         uint32_t c[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
         int sl = 0;
@@ -284,13 +417,18 @@ __global__ __launch_bounds__(kPickThreads) void k_topk_pick(topk_state *st,
     }
     if (!scanner) return;  // no barrier follows
     const uint32_t incl = part[tid], excl = incl - mine;
-    if (k_rem > 0u && excl < k_rem && k_rem <= incl) {  // exactly one thread
+    if (LEVEL == 1 && GATE == kSlotTail && tid == 255 && incl < k_rem) atomicOr(&st->overflow, 2u);
+    if (k_rem > 0u && excl < k_rem && k_rem <= incl) {  // at most one thread
         uint32_t above = excl;
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
             if (above + h[j] >= k_rem) {
                 const uint32_t bin = (uint32_t)(BINS - 1 - (tid * PER + j));
-                const uint32_t prefix = st->prefix | (bin << SHIFT);
+                if (LEVEL == 0) {
+                    st->b_lo = bin;
+                    break;
+                }
+                const uint32_t prefix = base_prefix | (bin << SHIFT);
                 st->prefix = prefix;
                 st->k_rem = k_rem - above;
                 if (LEVEL == 3) {
@@ -506,74 +644,13 @@ __global__ __launch_bounds__(64) void k_topk_write(float *R, int64_t n,
 
 // ---- slot tail -------------------------------------------------------------------------
 
-// One wave per 1024-element tile: copies (index, bits) of every element whose
-// level-1 bin is >= the bin of the k-th largest key into the tile's slots, in
-// index order.
-__global__ __launch_bounds__(64) void k_topk_collect(const float *__restrict__ R, int64_t n,
-                                                     topk_state *st, uint32_t *__restrict__ slot_cnt,
-                                                     uint32_t *__restrict__ slot_idx,
-                                                     uint32_t *__restrict__ slot_bits)
-{
-    const uint32_t b1 = st->prefix >> 20;
-    const int lane = threadIdx.x;
-    const int64_t tile = blockIdx.x;
-    const int64_t base = tile * kTile;
-    uint32_t running = 0u;
-    u32x4 raws[4];
-    uint32_t valids[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {  // all four loads are in flight before the first is used
-        const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
-        raws[u] = u32x4{0u, 0u, 0u, 0u};
-        valids[u] = 0u;
-        if (e + 4 <= n) {
-            raws[u] = __builtin_nontemporal_load((const u32x4 *)(R + e));
-            valids[u] = 0xfu;
-        } else {
-            for (int j = 0; j < 4; ++j)
-                if (e + j < n) {
-                    raws[u][j] = __float_as_uint(R[e + j]);
-                    valids[u] |= 1u << j;
-                }
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
-        const u32x4 raw = raws[u];
-        const uint32_t valid = valids[u];
-        uint32_t m = 0u;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            m |= (((valid >> j) & 1u) && ((raw[j] & kAbs) >> 20) >= b1) ? (1u << j) : 0u;
-        if (__ballot(m != 0u) == 0ull) continue;
-        const uint32_t cnt = __popc(m);
-        const uint32_t incl = wave_incl_scan(cnt);
-        const uint32_t total = __shfl(incl, 63, 64);
-        uint32_t pos = running + incl - cnt;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if ((m >> j) & 1u) {
-                if (pos < (uint32_t)kSlots) {
-                    slot_idx[tile * kSlots + pos] = (uint32_t)(e + j);
-                    slot_bits[tile * kSlots + pos] = raw[j];
-                }
-                ++pos;
-            }
-        }
-        running += total;
-    }
-    if (lane == 0) {
-        slot_cnt[tile] = running < (uint32_t)kSlots ? running : (uint32_t)kSlots;
-        if (running > (uint32_t)kSlots) atomicOr(&st->overflow, 1u);
-    }
-}
+// A tile's 32 slot entries are eight 16-byte vectors.  The slot-tail kernels give one
+// thread to each such vector, so that a wave reads 1 KB of slots at a time, and look
+// only at the entries below the tile's count.
 
-// The remaining slot-tail kernels give one thread to each tile (a tile holds
-// four entries on average).
-
-// Histogram of the next digit over the slot entries: a few large workgroups, each
-// with an LDS histogram that it stores as its own slice.
+// Histogram of one digit over the slot entries (level 1: all of them; levels 2, 3:
+// those that match the prefix): a few large workgroups, each with an LDS histogram
+// that it stores as its own slice.
 template <int LEVEL>
 __global__ __launch_bounds__(kSlotThreads) void k_topk_slots_hist(const topk_state *__restrict__ st,
                                                                   const uint32_t *__restrict__ slot_cnt,
@@ -583,25 +660,45 @@ __global__ __launch_bounds__(kSlotThreads) void k_topk_slots_hist(const topk_sta
 {
     if (skip_tail(st, kSlotTail)) return;
     constexpr int BINS = LEVEL == 3 ? kBins3 : kBins12;
-    constexpr int SHIFT = LEVEL == 2 ? 9 : 0;
-    constexpr int HI_SHIFT = LEVEL == 2 ? 20 : 9;
+    constexpr int SHIFT = LEVEL == 1 ? 20 : (LEVEL == 2 ? 9 : 0);
+    constexpr int HI_SHIFT = LEVEL == 1 ? 31 : (LEVEL == 2 ? 20 : 9);
     __shared__ uint32_t lds[BINS];
     const int tid = threadIdx.x;
     for (int i = tid; i < BINS; i += kSlotThreads) lds[i] = 0u;
     __syncthreads();
-    const uint32_t want = st->prefix >> HI_SHIFT;
-    for (int64_t tile = (int64_t)blockIdx.x * kSlotThreads + tid; tile < ntiles;
-         tile += (int64_t)gridDim.x * kSlotThreads) {
-        const uint32_t cnt = slot_cnt[tile];
-        for (uint32_t i = 0; i < cnt; ++i) {
-            const uint32_t key = slot_bits[tile * kSlots + i] & kAbs;
-            if ((key >> HI_SHIFT) == want) atomicAdd(&lds[(key >> SHIFT) & (BINS - 1)], 1u);
+    const uint32_t want = LEVEL == 1 ? 0u : st->prefix >> HI_SHIFT;  // keys have bit 31 clear
+    const int64_t nvs = ntiles * (kSlots / 4);
+    const int64_t stride = (int64_t)gridDim.x * kSlotThreads;
+    constexpr int U = 8;  // vectors in flight per thread; the counts are loaded alongside, not before
+    for (int64_t w0 = (int64_t)blockIdx.x * kSlotThreads + tid; w0 < nvs; w0 += U * stride) {
+        uint32_t cnt[U];
+        u32x4 v[U];
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            const int64_t w = w0 + i * stride;
+            cnt[i] = 0u;
+            v[i] = u32x4{0u, 0u, 0u, 0u};
+            if (w < nvs) {
+                cnt[i] = slot_cnt[w >> 3];
+                v[i] = ((const u32x4 *)slot_bits)[w];  // entries at or above the count are stale, and skipped below
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            const uint32_t q4 = (uint32_t)((w0 + i * stride) & 7) * 4u;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t key = v[i][j] & kAbs;
+                if (q4 + j < cnt[i] && (key >> HI_SHIFT) == want)
+                    atomicAdd(&lds[(key >> SHIFT) & (BINS - 1)], 1u);
+            }
         }
     }
     __syncthreads();
     for (int i = tid; i < BINS; i += kSlotThreads) hist[blockIdx.x * 2048 + i] = lds[i];
 }
 
+// Per-tile numbers of slot entries above and at the threshold.
 __global__ __launch_bounds__(256) void k_topk_slots_count(const topk_state *__restrict__ st,
                                                           const uint32_t *__restrict__ slot_cnt,
                                                           const uint32_t *__restrict__ slot_bits,
@@ -609,20 +706,48 @@ __global__ __launch_bounds__(256) void k_topk_slots_count(const topk_state *__re
                                                           uint32_t *__restrict__ cnt_eq)
 {
     if (skip_tail(st, kSlotTail)) return;
-    const int64_t tile = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (tile >= ntiles) return;
+    const int64_t nvs = ntiles * (kSlots / 4);
+    const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const uint32_t T = st->threshold;
-    const uint32_t cnt = slot_cnt[tile];
     uint32_t gt = 0u, eq = 0u;
-    for (uint32_t i = 0; i < cnt; ++i) {
-        const uint32_t key = slot_bits[tile * kSlots + i] & kAbs;
-        gt += key > T ? 1u : 0u;
-        eq += key == T ? 1u : 0u;
+    if (w < nvs) {
+        const uint32_t cnt = slot_cnt[w >> 3], q4 = (uint32_t)(w & 7) * 4u;
+        if (q4 < cnt) {
+            const u32x4 v = ((const u32x4 *)slot_bits)[w];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t key = v[j] & kAbs;
+                gt += (q4 + j < cnt && key > T) ? 1u : 0u;
+                eq += (q4 + j < cnt && key == T) ? 1u : 0u;
+            }
+        }
     }
-    cnt_gt[tile] = gt;
-    cnt_eq[tile] = eq;
+#pragma unroll
+    for (int d = 1; d < 8; d <<= 1) {  // the eight lanes of a tile; every lane of the wave takes part
+        gt += __shfl_xor(gt, d, 64);
+        eq += __shfl_xor(eq, d, 64);
+    }
+    if (w < nvs && (w & 7) == 0) {
+        cnt_gt[w >> 3] = gt;
+        cnt_eq[w >> 3] = eq;
+    }
 }
 
+// Exclusive prefix sum over each group of eight neighbouring lanes.
+__device__ __forceinline__ uint32_t group8_excl_scan(uint32_t x)
+{
+    const int l = threadIdx.x & 7;
+    uint32_t incl = x;
+#pragma unroll
+    for (int d = 1; d < 8; d <<= 1) {
+        const uint32_t y = __shfl_up(incl, d, 64);
+        if (l >= d) incl += y;
+    }
+    return incl - x;
+}
+
+// Ordered write of the kept slot entries; entries of a tile are in ascending index
+// order across its eight lanes.
 __global__ __launch_bounds__(256) void k_topk_slots_write(float *R, const topk_state *__restrict__ st,
                                                           const uint32_t *__restrict__ slot_cnt,
                                                           const uint32_t *__restrict__ slot_idx,
@@ -635,27 +760,46 @@ __global__ __launch_bounds__(256) void k_topk_slots_write(float *R, const topk_s
                                                           uint32_t *__restrict__ idx, uint32_t kmax)
 {
     if (skip_tail(st, kSlotTail)) return;
-    const int64_t tile = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (tile >= ntiles) return;
-    const uint32_t cnt = slot_cnt[tile];
-    if (cnt == 0u) return;
+    const int64_t nvs = ntiles * (kSlots / 4);
+    const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const uint32_t T = st->threshold, ties = st->ties;
-    const int64_t chunk = tile / kScanChunk;
-    uint32_t eq_before = chunk_eq[chunk] + cnt_eq[tile];
-    uint32_t pos = chunk_gt[chunk] + cnt_gt[tile] + (eq_before < ties ? eq_before : ties);
-    for (uint32_t i = 0; i < cnt; ++i) {  // entries are in ascending index order
-        const uint32_t bits = slot_bits[tile * kSlots + i];
-        const uint32_t key = bits & kAbs;
-        bool keep = key > T;
-        if (key == T) {
-            keep = eq_before < ties;
-            ++eq_before;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    uint32_t gtm = 0u, eqm = 0u, eq_before = 0u, tile_pos = 0u;
+    if (w < nvs) {
+        const int64_t tile = w >> 3;
+        const uint32_t cnt = slot_cnt[tile], q4 = (uint32_t)(w & 7) * 4u;
+        if (q4 < cnt) {
+            v = ((const u32x4 *)slot_bits)[w];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t key = v[j] & kAbs;
+                gtm |= (q4 + j < cnt && key > T) ? (1u << j) : 0u;
+                eqm |= (q4 + j < cnt && key == T) ? (1u << j) : 0u;
+            }
+            const int64_t chunk = tile / kScanChunk;
+            eq_before = chunk_eq[chunk] + cnt_eq[tile];
+            tile_pos = chunk_gt[chunk] + cnt_gt[tile] + (eq_before < ties ? eq_before : ties);
         }
-        if (keep && pos < kmax) {  // pos < kmax always holds; the test keeps a corrupted workspace harmless
-            const uint32_t at = slot_idx[tile * kSlots + i];
-            vals[pos] = __uint_as_float(bits);
-            idx[pos] = at;
-            R[at] = 0.0f;
+    }
+    // every lane of the wave takes part in the two scans
+    uint32_t eq_rank = eq_before + group8_excl_scan(__popc(eqm));
+    uint32_t selm = gtm;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if ((eqm >> j) & 1u) {
+            if (eq_rank < ties) selm |= 1u << j;
+            ++eq_rank;
+        }
+    }
+    uint32_t pos = tile_pos + group8_excl_scan(__popc(selm));
+    if (selm == 0u) return;  // no shuffle follows
+    const u32x4 at = ((const u32x4 *)slot_idx)[w];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (((selm >> j) & 1u) && pos < kmax) {  // pos < kmax always holds; the test keeps a corrupted workspace harmless
+            vals[pos] = __uint_as_float(v[j]);
+            idx[pos] = at[j];
+            R[at[j]] = 0.0f;
             ++pos;
         }
     }
@@ -704,37 +848,52 @@ covap_status_t topk_compress(const void *grad, void *residual, int64_t n, int64_
     const int64_t nvec = n / 4;
     const int64_t ntiles = div_up(n, kTile);
     const int64_t nchunks = div_up(ntiles, kScanChunk);
-    // persistent histogram grid: enough workgroups to fill 256 CUs several times over
+    // persistent grids: enough workgroups to fill 256 CUs several times over
     int64_t hist_grid = div_up(nvec > 0 ? nvec : 1, kHistThreads);
     if (hist_grid > 2048) hist_grid = 2048;
 
-    uint32_t *h1 = ws.hist, *h2g = h1 + kHistSlices * 2048, *h3g = h2g + kHistSlices * 2048,
-             *h2s = h3g + kHistSlices * 2048, *h3s = h2s + kSlotGrid * 2048;
-    const uint32_t per_tile_grid = (uint32_t)div_up(ntiles, 256);
+    uint32_t *h1g = ws.hist, *h2g = h1g + 2048, *h3g = h2g + 2048, *h1s = ws.hist + kAtomicRows * 2048,
+             *h2s = h1s + kSlotGrid * 2048, *h3s = h2s + kSlotGrid * 2048, *hs = h2s;
+    // the sample: n_s of the full 256-element chunks; the bin it proposes holds about
+    // twice the keys that are needed (plus a floor for small k), so that the bins
+    // >= b_lo hold at least k keys unless the sample is far off
+    const int64_t nchunks_s = nvec / 64;
+    const int32_t n_s = (int32_t)(nchunks_s < kSampleChunks ? nchunks_s : kSampleChunks);
+    const int64_t m = (int64_t)n_s * 256;
+    const int64_t want = 2 * div_up(k * m, n) + 32;
+    const uint32_t target = (uint32_t)(want < ((int64_t)1 << 31) ? want : ((int64_t)1 << 31));
+    const uint32_t slot_vec_grid = (uint32_t)div_up(ntiles * (kSlots / 4), 256);
     // the general tail's tile kernels walk the tiles with a bounded grid, so that
     // they cost next to nothing when they are not taken
     const uint32_t tail_grid = (uint32_t)(ntiles < 16384 ? ntiles : 16384);
-    k_topk_init<<<64, 256, 0, st>>>(ws.state, ws.hist, (uint32_t)k);
-    k_topk_hist<1><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(G, R, n, ef_coeff, ws.state, h1);
+    k_topk_sample<<<kSlotGrid, kSampleThreads, 0, st>>>(G, R, ef_coeff, nchunks_s, n_s, ws.state, ws.hist, hs,
+                                                        (uint32_t)k);
+    k_topk_pick<0, kAlways><<<1, kPickThreads, 0, st>>>(ws.state, hs, kSlotGrid, target);
+    const covap::tuning &tn = covap::tune();
+    const auto pass1 = tn.topk_pass1_waves == 4 ? k_topk_pass1<4> : (tn.topk_pass1_waves == 2 ? k_topk_pass1<2> : k_topk_pass1<1>);
+    pass1<<<(uint32_t)ntiles, 64 * tn.topk_pass1_waves, (size_t)tn.topk_pass1_lds_pad, st>>>(
+        G, R, n, ef_coeff, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits);
     if (k > 0) {
-        k_topk_pick<1, kAlways><<<1, kPickThreads, 0, st>>>(ws.state, h1, kHistSlices);
-        k_topk_collect<<<(uint32_t)ntiles, 64, 0, st>>>(R, n, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits);
-        // slot tail (returns at once if a tile overflowed its slots)
+        // slot tail (every kernel returns at once when the general tail is switched on)
+        k_topk_slots_hist<1><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, h1s);
+        k_topk_pick<1, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h1s, kSlotGrid, 0u);
         k_topk_slots_hist<2><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, h2s);
-        k_topk_pick<2, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h2s, kSlotGrid);
+        k_topk_pick<2, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h2s, kSlotGrid, 0u);
         k_topk_slots_hist<3><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, h3s);
-        k_topk_pick<3, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h3s, kSlotGrid);
-        k_topk_slots_count<<<per_tile_grid, 256, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.cnt_gt, ws.cnt_eq);
+        k_topk_pick<3, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h3s, kSlotGrid, 0u);
+        k_topk_slots_count<<<slot_vec_grid, 256, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.cnt_gt, ws.cnt_eq);
         // general tail (returns at once otherwise)
-        k_topk_hist<2><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(G, R, n, ef_coeff, ws.state, h2g);
-        k_topk_pick<2, kGeneralTail><<<1, kPickThreads, 0, st>>>(ws.state, h2g, kHistSlices);
-        k_topk_hist<3><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(G, R, n, ef_coeff, ws.state, h3g);
-        k_topk_pick<3, kGeneralTail><<<1, kPickThreads, 0, st>>>(ws.state, h3g, kHistSlices);
+        k_topk_hist<1><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(R, n, ws.state, h1g);
+        k_topk_pick<1, kGeneralTail><<<1, kPickThreads, 0, st>>>(ws.state, h1g, 1, 0u);
+        k_topk_hist<2><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(R, n, ws.state, h2g);
+        k_topk_pick<2, kGeneralTail><<<1, kPickThreads, 0, st>>>(ws.state, h2g, 1, 0u);
+        k_topk_hist<3><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(R, n, ws.state, h3g);
+        k_topk_pick<3, kGeneralTail><<<1, kPickThreads, 0, st>>>(ws.state, h3g, 1, 0u);
         k_topk_count<<<tail_grid, 64, 0, st>>>(R, n, ntiles, ws.state, ws.cnt_gt, ws.cnt_eq);
         // common: exclusive scan of the per-tile counts, then the ordered write
         k_topk_scan_a<<<(uint32_t)nchunks, 256, 0, st>>>(ws.cnt_gt, ws.cnt_eq, ntiles, ws.chunk_gt, ws.chunk_eq);
         k_topk_scan_b<<<1, 256, 0, st>>>(ws.chunk_gt, ws.chunk_eq, nchunks);
-        k_topk_slots_write<<<per_tile_grid, 256, 0, st>>>(R, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.cnt_gt,
+        k_topk_slots_write<<<slot_vec_grid, 256, 0, st>>>(R, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.cnt_gt,
                                                           ws.cnt_eq, ws.chunk_gt, ws.chunk_eq, ntiles,
                                                           (float *)out_vals, out_idx, (uint32_t)k);
         k_topk_write<<<tail_grid, 64, 0, st>>>(R, n, ws.state, ws.cnt_gt, ws.cnt_eq, ws.chunk_gt,

@@ -154,8 +154,8 @@ def test_argument_errors(B):
 
 
 def tail_taken(ws):
-    """Word 4 of the workspace is the device flag that says a tile overflowed its
-    slots, i.e. that the general tail produced the result."""
+    """Word 4 of the workspace is the device flag that switches the general tail on
+    (bit 0: a tile overflowed its slots, bit 1: the sampled bound was too high)."""
     return "general" if int(ws.view(torch.int32)[4].item()) != 0 else "slots"
 
 
@@ -191,3 +191,72 @@ def test_both_tails_are_exercised_and_agree_with_the_oracle(B, kind, want):
     assert np.array_equal(idx.cpu().numpy().view(np.uint32), oi)
     assert np.array_equal(vals.cpu().numpy().view(np.uint32), ov.view(np.uint32))
     assert np.array_equal(R.cpu().numpy().view(np.uint32), Rc.view(np.uint32))
+
+
+def test_a_misleading_sample_falls_back_to_the_general_tail(B):
+    """White box: the sample that proposes the lower bound b_lo takes 4096 evenly spread
+    256-element chunks; at n = 4 * 4096 * 256 that is the first quarter of every 1024
+    elements.  Large values only there make the sample overestimate their share four
+    times, the bins >= b_lo then hold fewer than k keys, and the exact general tail must
+    take over (flag bit 1) with the same bits as the oracle."""
+    n = 4 * 4096 * 256
+    k = n // 100
+    rng = np.random.default_rng(5)
+    Gn = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    big = (np.arange(n // 1024)[:, None] * 1024 + np.arange(8)[None, :] * 31).ravel()   # 8 per tile, all in its first 256
+    Gn[big] = (1.0 + rng.random(big.size)).astype(np.float32) * np.where(rng.random(big.size) < 0.5, -1, 1)
+    Rn = (rng.standard_normal(n) * 1e-4).astype(np.float32)
+    G = torch.from_numpy(Gn).to(DEV)
+    R = torch.from_numpy(Rn).to(DEV)
+    ws = torch.empty(B.topk_workspace_bytes(n), dtype=torch.uint8, device=DEV)
+    vals = torch.empty(k, device=DEV)
+    idx = torch.empty(k, dtype=torch.int32, device=DEV)
+    B.topk_compress(G, R, k, vals, idx, ws)
+    torch.cuda.synchronize()
+    assert int(ws.view(torch.int32)[4].item()) == 2       # bound too high, no slot overflow
+    Rc = Rn.copy()
+    ov, oi = oracle.topk(Gn, Rc, k)
+    assert np.array_equal(idx.cpu().numpy().view(np.uint32), oi)
+    assert np.array_equal(vals.cpu().numpy().view(np.uint32), ov.view(np.uint32))
+    assert np.array_equal(R.cpu().numpy().view(np.uint32), Rc.view(np.uint32))
+
+
+def test_the_sampled_bound_is_used_on_smooth_data(B):
+    """White box: on Gaussian data the bound (word 5 of the workspace) is a real bin,
+    a little below the bin of the k-th largest key, and the slot tail produces the result."""
+    n = 3_000_017
+    k = n // 1000
+    rng = np.random.default_rng(6)
+    Gn = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    Rn = np.zeros(n, np.float32)
+    G = torch.from_numpy(Gn).to(DEV)
+    R = torch.from_numpy(Rn).to(DEV)
+    ws = torch.empty(B.topk_workspace_bytes(n), dtype=torch.uint8, device=DEV)
+    vals = torch.empty(k, device=DEV)
+    idx = torch.empty(k, dtype=torch.int32, device=DEV)
+    B.topk_compress(G, R, k, vals, idx, ws)
+    torch.cuda.synchronize()
+    st = ws.view(torch.int32)[:8].cpu().numpy()
+    assert st[4] == 0
+    key = np.abs(Gn).view(np.uint32)
+    kth_bin = int(np.sort(key)[n - k] >> 20)
+    assert 0 < st[5] <= kth_bin and kth_bin - st[5] <= 3
+    ov, oi = oracle.topk(Gn, Rn, k)
+    assert np.array_equal(idx.cpu().numpy().view(np.uint32), oi)
+    assert np.array_equal(vals.cpu().numpy().view(np.uint32), ov.view(np.uint32))
+
+
+@pytest.mark.parametrize("waves", [1, 2, 4])
+def test_first_pass_launch_shapes_give_the_same_bits(B, waves):
+    """The number of waves that share a tile in the first pass is a launch-shape knob only."""
+    n = 777_777                                            # ragged last tile, ragged last vector
+    k = 1000
+    rng = np.random.default_rng(waves)
+    Gn = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    Rn = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    old = B.covap_tune_get("topk_pass1_waves")
+    B.covap_tune_set("topk_pass1_waves", waves)
+    try:
+        check_against_oracle(B, Gn, Rn, k, c=0.5)
+    finally:
+        B.covap_tune_set("topk_pass1_waves", old)
