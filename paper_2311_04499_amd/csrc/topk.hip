@@ -1,20 +1,19 @@
 // Fine-grained top-k sparsifier with error feedback: the contrast point to the
-// coarse filter (Sec. I and Table II: "most of the overhead in Top-k comes from
-// the topk() operator").  Exact and deterministic: a sample only decides how much
-// work the exact selection has to do, never what it returns.
+// coarse filter (Sec. I and Table II, where the selection operator accounts for
+// nearly all of Top-k's compression time).  Exact and deterministic: a sample only
+// decides how much work the exact selection has to do, never what it returns.
 //
 //   sample   A = fma(c, R, G) on 4096 evenly spread 256-element chunks; histogram of
 //            key bits 30..20 -> a bin b_lo that very probably lies at or below the bin
 //            of the k-th largest key, with only a fraction of a percent of the keys
 //            at or above it                                          (reads 8 MB)
-//   pass 1   A = fma(c, R, G); R <- A; every element whose bin is >= b_lo is counted
-//            in the histogram of bits 30..20 and copied, in index order, into a
-//            32-entry slot array of its 1024-element tile        (reads 2D, writes D)
-//            -> the bin b1 that holds the k-th largest key
+//   pass 1   A = fma(c, R, G); R <- A; every element whose bin is >= b_lo is copied,
+//            in index order, into a 32-entry slot array of its 1024-element tile
+//                                                                (reads 2D, writes D)
 //   then everything works on the slots only (a fraction of a percent of the data):
-//   histograms of bits 19..9 and 8..0 -> threshold key T and the number of ties to
-//   keep; per-tile counts; 3-phase exclusive scan; ordered write of (value, index),
-//   R <- +0 there.
+//   histograms of bits 30..20, 19..9 and 8..0 -> threshold key T and the number of
+//   ties to keep; per-tile counts; 3-phase exclusive scan; ordered write of
+//   (value, index), R <- +0 there.
 //
 // If the bins >= b_lo turn out to hold fewer than k keys (the sample misled), or if
 // any tile has more than 32 such elements (heavily clustered or tied data, large
@@ -27,9 +26,9 @@
 // (NaN above Inf).  Among keys equal to T the lowest indices are kept, which
 // makes the result unique.  Every decision is integer work on bit patterns.
 //
-// Histograms live in LDS per workgroup and are flushed once per workgroup;
-// compaction uses wavefront prefix sums.  All scratch is in the caller's
-// workspace; nothing is allocated.
+// Histograms live in LDS per workgroup and are written out once per workgroup;
+// compaction uses lane masks and wavefront prefix sums.  All scratch is in the
+// caller's workspace; nothing is allocated.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
