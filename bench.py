@@ -36,7 +36,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5")
-    ap.add_argument("--dtype", choices=["f32", "bf16", "bf16_res32"], default="f32",
+    ap.add_argument("--dtype", choices=["f32", "bf16", "bf16_res32", "f32_pay16"], default="f32",
                     help="element type; bf16_res32 = bf16 gradients and payload, fp32 residual")
     ap.add_argument("--shard-mode", choices=["fixed", "median"], default="fixed",
                     help="fixed-size shards (default) or the median sharding of Sec. III-C")
@@ -90,14 +90,17 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = workloads.config(args.config)
-    tdtype = torch.float32 if args.dtype == "f32" else torch.bfloat16
-    rdtype = torch.bfloat16 if args.dtype == "bf16" else torch.float32     # residual
-    esz = 4 if args.dtype == "f32" else 2
+    # gradient / dense result, residual, payload: element types and sizes
+    tdtype = torch.float32 if args.dtype in ("f32", "f32_pay16") else torch.bfloat16
+    rdtype = torch.bfloat16 if args.dtype == "bf16" else torch.float32
+    pdtype = {"f32": torch.float32, "f32_pay16": torch.float16}.get(args.dtype, torch.bfloat16)
+    esz = 4 if args.dtype in ("f32", "f32_pay16") else 2
     rsz = 2 if args.dtype == "bf16" else 4
-    epv = 16 // esz
+    psz = 4 if args.dtype == "f32" else 2
+    epv = 16 // psz
     plan = B.covap_plan(wl.numel, wl.shard_elems, wl.K,
-                        dtype={"f32": B.COVAP_F32, "bf16": B.COVAP_BF16,
-                               "bf16_res32": B.COVAP_BF16_RES32}[args.dtype],
+                        dtype={"f32": B.COVAP_F32, "bf16": B.COVAP_BF16, "bf16_res32": B.COVAP_BF16_RES32,
+                               "f32_pay16": B.COVAP_F32_PAY16}[args.dtype],
                         mode=B.COVAP_SHARD_FIXED if args.shard_mode == "fixed" else B.COVAP_SHARD_MEDIAN)
     D, N, K = plan.total_elems, wl.n_workers, wl.K
     P_max = plan.packed_elems_max
@@ -108,9 +111,9 @@ def main():
     if D > wl.D:                               # median mode may pad bucket starts to 16 bytes
         ring = [torch.cat([g, g.new_zeros(D - wl.D)]) for g in ring]
     residual = torch.zeros(D, dtype=rdtype, device=dev)
-    recv = torch.empty(N, stride, dtype=tdtype, device=dev)
+    recv = torch.empty(N, stride, dtype=pdtype, device=dev)
     if N > 1:
-        recv[1:] = workloads.payload_rows(wl, N - 1, stride, 0, dev, tdtype)
+        recv[1:] = workloads.payload_rows(wl, N - 1, stride, 0, dev, pdtype)
     dense = torch.empty(D, dtype=tdtype, device=dev)
     torch.cuda.synchronize()
 
@@ -145,8 +148,8 @@ def main():
     tc_avg, td_avg = sum(tc) / len(tc), sum(td) / len(td)
     steps_t = [t_first + i for i in range(args.steps)]
     P_avg = sum(plan.packed_elems(t) for t in steps_t) / len(steps_t)
-    bytes_c = esz * (D + P_avg) + rsz * 2 * D            # read G, read R, write R, write packed
-    bytes_d = esz * (N * P_avg + D)                      # read N rows, write dense
+    bytes_c = esz * D + psz * P_avg + rsz * 2 * D        # read G, read R, write R, write packed
+    bytes_d = psz * N * P_avg + esz * D                  # read N rows, write dense
     grad_gbs = esz * D / (ms_step * 1e-3) / 1e9
     hbm_gbs = (bytes_c + bytes_d) / (ms_step * 1e-3) / 1e9
 
@@ -155,7 +158,9 @@ def main():
     ach = dominant[2] / (dominant[1] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant[0], "achieved": round(ach, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-                "traffic": read_traffic(dominant[0], wl.name),
+                # the committed counter summaries cover the default element type and sharding only
+                "traffic": read_traffic(dominant[0], wl.name)
+                if args.dtype == "f32" and args.shard_mode == "fixed" and not args.tune else None,
                 "bytes_per_launch": round(dominant[2]), "avg_launch_us": round(dominant[1] * 1e3, 2)}
 
     def pct(xs, q):
@@ -288,7 +293,7 @@ def main():
 
     # ---- aliased-residual compress (the producer accumulates; never the headline number:
     # the error-feedback addition is then paid for inside the producer)
-    if args.dtype != "bf16_res32":
+    if args.dtype not in ("bf16_res32", "f32_pay16"):
         acc_buf = ring[1].clone()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         for t in range(K):

@@ -25,7 +25,8 @@
  *    ordinary host memory.
  *  - Device buffers must be 16-byte aligned.  Elements are fp32, or bf16 stored
  *    as 16-bit patterns (computed in fp32, rounded to nearest-even once); with
- *    COVAP_BF16_RES32 the residual buffer alone is fp32.
+ *    COVAP_BF16_RES32 the residual buffer alone is fp32; with COVAP_F32_PAY16 the
+ *    payload buffers alone are 16-bit (IEEE half).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Hot-path calls are asynchronous: COVAP_OK means "enqueued".
  *  - Indexing is 0-based for tensors, shards, buckets and iterations.
@@ -63,7 +64,14 @@ typedef enum {
     /* gradients, payload and dense output bf16, residual fp32: Algorithm 1 with the
      * bf16 rounding as the quantiser of line 3 -- a sent element leaves
      * residual = A - bf16(A) (exact), a kept element leaves residual = A. */
-    COVAP_BF16_RES32 = 2
+    COVAP_BF16_RES32 = 2,
+    /* gradients, residual and dense output fp32, payload IEEE half precision: the
+     * coarse filter combined with the FP16 scheme of Table II as the quantiser of
+     * Algorithm 1 line 3 -- a sent element travels as fp16(A) (round to nearest
+     * even, overflow to Inf) and leaves residual = A - fp16(A); a kept element
+     * leaves residual = A.  The mean is taken in fp32 over the widened halves.
+     * Shard sizes and row strides count elements and must be multiples of 8. */
+    COVAP_F32_PAY16 = 3
 } covap_dtype_t;
 
 typedef enum {
@@ -162,7 +170,8 @@ covap_status_t covap_ef_coeff(float init_value, uint64_t num_steps, uint64_t asc
  *                      this call writes does not fit
  *   ef_coeff  the scheduler's coefficient c; A = fma(c, residual, grad)
  * `grad`, `residual` and `send` must not overlap.  Selected residual elements
- * become +0.0 whatever A was (COVAP_BF16_RES32: A - bf16(A)). */
+ * become +0.0 whatever A was (COVAP_BF16_RES32: A - bf16(A); COVAP_F32_PAY16:
+ * A - fp16(A)). */
 covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t bucket,
                               const void *grad, void *residual, void *send,
                               int64_t send_cap_elems, float ef_coeff, void *stream);
@@ -174,7 +183,8 @@ covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t b
  * not sent are neither read nor written, so the call touches 3 * packed_elems
  * elements instead of 3 * total + packed.  Same packed layout and the same bits
  * as covap_compress(ef_coeff = 1) fed with the last gradient and the previous
- * residual.  Not available for COVAP_BF16_RES32 (EUNSUPPORTED), nor for c != 1.
+ * residual.  Not available for COVAP_BF16_RES32 and COVAP_F32_PAY16
+ * (EUNSUPPORTED), nor for c != 1.
  *   accum  [device] whole arena, read and written (sent shards only)
  *   send   [device] as in covap_compress */
 covap_status_t covap_compress_aliased(const covap_plan_t *plan, uint64_t step, int32_t bucket,

@@ -86,6 +86,12 @@ def lib():
         L.orc_f32_to_f16.argtypes = [C.c_float]
         L.orc_f16_to_f32.restype = C.c_float
         L.orc_f16_to_f32.argtypes = [C.c_uint16]
+        L.orc_compress_f32_pay16.restype = C.c_int64
+        L.orc_compress_f32_pay16.argtypes = [_f32p, _f32p, _u16p, _i64p, _i64p, C.c_int64, C.c_int64,
+                                             C.c_int32, C.c_uint64, C.c_float, C.c_int64]
+        L.orc_decompress_pay16.restype = None
+        L.orc_decompress_pay16.argtypes = [_u16p, C.c_int32, C.c_int64, _f32p, _i64p, _i64p, C.c_int64,
+                                           C.c_int64, C.c_int32, C.c_uint64, C.c_int64]
         L.orc_fp16_compress.restype = None
         L.orc_fp16_compress.argtypes = [_f32p, _f32p, C.c_int64, C.c_float, _u16p]
         L.orc_fp16_mean.restype = None
@@ -238,8 +244,14 @@ def _kind(a: np.ndarray):
 def compress(tab: ShardTable, interval: int, t: int, G, R, send, c: float = 1.0,
              bucket: int = -1) -> int:
     """In place: R becomes the new residual, send receives the packed shards.
-    G/send uint16 (bf16 patterns) with R float32 selects the mixed-precision form."""
+    G/send uint16 (bf16 patterns) with R float32 selects the mixed-precision form;
+    G/R float32 with send uint16 (fp16 patterns) the half-payload form."""
     lo, hi = tab.bucket_range(bucket)
+    if G.dtype == np.float32 and send.dtype == np.uint16:
+        _chk(G, np.float32), _chk(R, np.float32), _chk(send, np.uint16)
+        return int(lib().orc_compress_f32_pay16(
+            _p(G, _f32p), _p(R, _f32p), _p(send, _u16p), _p(tab.off, _i64p), _p(tab.len, _i64p),
+            lo, hi, interval, t, c, tab.align))
     if G.dtype == np.uint16 and R.dtype == np.float32:
         _chk(G, np.uint16), _chk(send, np.uint16), _chk(R, np.float32)
         return int(lib().orc_compress_bf16_res32(
@@ -263,7 +275,15 @@ def compress_aliased(tab: ShardTable, interval: int, t: int, accum, send, bucket
 
 
 def decompress(tab: ShardTable, interval: int, t: int, recv, out, bucket: int = -1) -> None:
-    """recv: [N, stride] packed payload rows; out: dense arena, fully written."""
+    """recv: [N, stride] packed payload rows; out: dense arena, fully written.
+    recv uint16 with out float32 selects the half-payload form."""
+    if recv.dtype == np.uint16 and out.dtype == np.float32:
+        _chk(recv, np.uint16), _chk(out, np.float32)
+        assert recv.ndim == 2
+        lo, hi = tab.bucket_range(bucket)
+        lib().orc_decompress_pay16(_p(recv, _u16p), recv.shape[0], recv.shape[1], _p(out, _f32p),
+                                   _p(tab.off, _i64p), _p(tab.len, _i64p), lo, hi, interval, t, tab.align)
+        return
     name, ptr = _kind(recv)
     _chk(recv, recv.dtype)
     _chk(out, recv.dtype)

@@ -5,7 +5,7 @@
  * gradient-compression path computes, written from the paper
  * (arXiv 2311.04499).  Only tests, the smoke check and the benchmark's
  * cpu_baseline leg may call it.  It shares no code with the HIP library: it
- * has its own planner, its own filter, its own bf16 conversion.
+ * has its own planner, its own filter, its own bf16 and fp16 conversions.
  *
  * Every function walks the data in the order the paper states the operation:
  * shard by shard, element by element, worker by worker.  No blocking, fusion
@@ -533,6 +533,68 @@ void orc_fp16_mean(const uint16_t *recv, int32_t N, int64_t stride, int64_t n, f
         float acc = f16_to_f32(recv[i]);
         for (int32_t w = 1; w < N; ++w) acc += f16_to_f32(recv[(int64_t)w * stride + i]);
         out[i] = acc / (float)N;
+    }
+}
+
+/*
+ * Half-precision payload on the coarse filter: the FP16 scheme (Sec. II-C,
+ * Table II) takes the place of the compressor in Algorithm 1 line 3 for the
+ * shards the filter sends.  Gradients, residual and the dense result stay fp32.
+ *     a = G[i] + c * R[i]                          (one rounding: fmaf)
+ *     sent shard:   send[p++] = fp16(a)            round to nearest even
+ *                   R[i] = a - fp32(send)          what the quantiser dropped
+ *     kept shard:   R[i] = a
+ * Packed layout as in orc_compress_f32.
+ */
+int64_t orc_compress_f32_pay16(const float *G, float *R, uint16_t *send,
+                               const int64_t *off, const int64_t *len,
+                               int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t,
+                               float c, int64_t align)
+{
+    int64_t p = orc_packed_end(len, sh_lo, I, t, align);
+    int64_t written = 0;
+    for (int64_t s = sh_lo; s < sh_hi; ++s) {
+        int sel = orc_selected(s, t, I);
+        if (sel) {
+            p = round_up(p, align);
+            written += len[s];
+        }
+        for (int64_t i = off[s]; i < off[s] + len[s]; ++i) {
+            float a = fmaf(c, R[i], G[i]);
+            if (sel) {
+                uint16_t h = f32_to_f16(a);
+                send[p++] = h;
+                R[i] = a - f16_to_f32(h);
+            } else {
+                R[i] = a;
+            }
+        }
+    }
+    return written;
+}
+
+/* Matching dense mean: fp32 left fold over the widened halves of rows
+ * w = 0..N-1, IEEE division by N; +0 where nothing was sent. */
+void orc_decompress_pay16(const uint16_t *recv, int32_t N, int64_t stride,
+                          float *out, const int64_t *off, const int64_t *len,
+                          int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t,
+                          int64_t align)
+{
+    int64_t q = orc_packed_end(len, sh_lo, I, t, align);
+    for (int64_t s = sh_lo; s < sh_hi; ++s) {
+        int sel = orc_selected(s, t, I);
+        if (sel) q = round_up(q, align);
+        for (int64_t i = off[s]; i < off[s] + len[s]; ++i) {
+            if (sel) {
+                float acc = f16_to_f32(recv[q]);
+                for (int32_t w = 1; w < N; ++w)
+                    acc += f16_to_f32(recv[(int64_t)w * stride + q]);
+                out[i] = acc / (float)N;
+                ++q;
+            } else {
+                out[i] = 0.0f;
+            }
+        }
     }
 }
 

@@ -27,7 +27,7 @@ HIPCC_FLAGS = [
     "-Wall", "-Wextra", "-Wno-unused-parameter", "-Wno-unknown-attributes",
 ]
 
-COVAP_F32, COVAP_BF16, COVAP_BF16_RES32 = 0, 1, 2
+COVAP_F32, COVAP_BF16, COVAP_BF16_RES32, COVAP_F32_PAY16 = 0, 1, 2, 3
 COVAP_SHARD_FIXED, COVAP_SHARD_MEDIAN = 0, 1
 STATUS_NAMES = {0: "COVAP_OK", 1: "COVAP_EINVAL", 2: "COVAP_ENOMEM", 3: "COVAP_EHIP",
                 4: "COVAP_ERANGE", 5: "COVAP_EUNSUPPORTED"}

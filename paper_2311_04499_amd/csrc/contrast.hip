@@ -9,6 +9,7 @@
 
 #include <cstdint>
 
+#include "half_util.h"
 #include "plan.h"
 
 namespace {
@@ -19,23 +20,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 64;  // one wave per workgroup, one vector per thread (measured best)
 
-// Pins a value in a register.  Without it the compiler folds fp16(fma(c, r, g))
-// into one v_fma_mixlo_f16, which rounds the exact sum straight to fp16 and so
-// differs from "round to fp32, then to fp16" whenever the fp32 value is a tie.
-__device__ __forceinline__ float pinned(float x)
-{
-    asm volatile("" : "+v"(x));
-    return x;
-}
-
-__device__ __forceinline__ uint32_t pack_half2(float a, float b)
-{
-    // round to nearest even; fp16 denormals are produced, overflow gives Inf
-    return (uint32_t)__half_as_ushort(__float2half_rn(a)) |
-           ((uint32_t)__half_as_ushort(__float2half_rn(b)) << 16);
-}
-__device__ __forceinline__ float half_lo(uint32_t w) { return __half2float(__ushort_as_half((uint16_t)(w & 0xffffu))); }
-__device__ __forceinline__ float half_hi(uint32_t w) { return __half2float(__ushort_as_half((uint16_t)(w >> 16))); }
+using covap_dev::half_hi;
+using covap_dev::half_lo;
+using covap_dev::pack_half2;
+using covap_dev::pinned;
 
 // R <- fma(c, R, G) over n fp32 elements (Algorithm 1 line 2 alone).
 __global__ __launch_bounds__(kThreads) void k_ef_accumulate(const float *__restrict__ G, float *R,

@@ -22,6 +22,7 @@
 #include <type_traits>
 #include <vector>
 
+#include "half_util.h"
 #include "plan.h"
 
 namespace {
@@ -53,6 +54,7 @@ __device__ __forceinline__ void st16(u32x4 *p, u32x4 v)
 struct ops_f32 {
     static constexpr int EPV = 4;
     static constexpr bool MIXED = false;
+    static constexpr bool PAY16 = false;
     typedef float elem_t;
     typedef f32x4 acc_t;
 
@@ -98,6 +100,7 @@ struct ops_f32 {
 struct ops_bf16 {
     static constexpr int EPV = 8;
     static constexpr bool MIXED = false;
+    static constexpr bool PAY16 = false;
     typedef uint16_t elem_t;
     struct acc_t {
         float v[8];
@@ -160,6 +163,13 @@ struct ops_bf16 {
 // residual stream is twice as wide as the other two.
 struct ops_bf16_res32 : ops_bf16 {
     static constexpr bool MIXED = true;
+};
+
+// fp32 gradients, residual and dense output with an IEEE half-precision payload.
+// Compress has its own tile routine (compress_tile_pay16: the payload stream is
+// half as wide as the other two) and decompress its own kernel (k_decompress_pay16).
+struct ops_f32_pay16 : ops_f32 {
+    static constexpr bool PAY16 = true;
 };
 
 // ---- tile geometry -----------------------------------------------------------
@@ -385,6 +395,79 @@ __device__ __forceinline__ void compress_tile_mixed(const uint16_t *__restrict__
     }
 }
 
+// Half-payload tile: per step a thread owns four consecutive elements -- 16-byte
+// vectors of fp32 gradients and residuals, one 8-byte vector of halves -- so every
+// load and store instruction of a wave covers one contiguous run.  A sent element
+// leaves residual = A - fp16(A), what the quantiser dropped (Algorithm 1 line 4
+// with the FP16 scheme of Table II as the compressor of line 3).
+template <int kThreads, int UNROLL, bool NT>
+__device__ __forceinline__ void compress_tile_pay16(const float *__restrict__ G, float *R,
+                                                    uint16_t *__restrict__ send,
+                                                    const tile_ref &t, float c)
+{
+    using covap_dev::half_hi;
+    using covap_dev::half_lo;
+    using covap_dev::pack_half2;
+    using covap_dev::pinned;
+    const int tid = threadIdx.x;
+    const f32x4 *gp = (const f32x4 *)(G + t.off);
+    f32x4 *rp = (f32x4 *)(R + t.off);
+    u32x2 *sp = (u32x2 *)(send + t.poff);
+    const int nq = t.n / 4;
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const int q = u * kThreads + tid;
+        if (q < nq) {
+            f32x4 g, r;
+            if constexpr (NT) {
+                g = __builtin_nontemporal_load(gp + q);
+                r = __builtin_nontemporal_load(rp + q);
+            } else {
+                g = gp[q];
+                r = rp[q];
+            }
+            f32x4 a;
+            a.x = __builtin_fmaf(c, r.x, g.x);
+            a.y = __builtin_fmaf(c, r.y, g.y);
+            a.z = __builtin_fmaf(c, r.z, g.z);
+            a.w = __builtin_fmaf(c, r.w, g.w);
+            if (t.sel) {
+                // the fp32 value must exist before it is narrowed (see pinned())
+                a.x = pinned(a.x);
+                a.y = pinned(a.y);
+                a.z = pinned(a.z);
+                a.w = pinned(a.w);
+                u32x2 h;
+                h.x = pack_half2(a.x, a.y);
+                h.y = pack_half2(a.z, a.w);
+                a.x -= half_lo(h.x);
+                a.y -= half_hi(h.x);
+                a.z -= half_lo(h.y);
+                a.w -= half_hi(h.y);
+                if constexpr (NT)
+                    __builtin_nontemporal_store(h, sp + q);
+                else
+                    sp[q] = h;
+            }
+            if constexpr (NT)
+                __builtin_nontemporal_store(a, rp + q);
+            else
+                rp[q] = a;
+        }
+    }
+    const int rem = t.n - nq * 4;
+    if (tid < rem) {
+        const int64_t e = (int64_t)nq * 4 + tid;
+        float a = pinned(__builtin_fmaf(c, R[t.off + e], G[t.off + e]));
+        if (t.sel) {
+            const __half h = __float2half_rn(a);
+            send[t.poff + e] = __half_as_ushort(h);
+            a -= __half2float(h);
+        }
+        R[t.off + e] = a;
+    }
+}
+
 template <typename OPS, typename GEOM, int kThreads, int UNROLL, bool NT>
 __global__ __launch_bounds__(kThreads) void k_compress(const u32x4 *__restrict__ G, u32x4 *R,
                                                        u32x4 *__restrict__ send, GEOM g, float c)
@@ -394,6 +477,8 @@ __global__ __launch_bounds__(kThreads) void k_compress(const u32x4 *__restrict__
     if (!resolve_tile<TILE>(g, t)) return;
     if constexpr (OPS::MIXED)
         compress_tile_mixed<kThreads, UNROLL, NT>((const uint16_t *)G, (float *)R, (uint16_t *)send, t, c);
+    else if constexpr (OPS::PAY16)
+        compress_tile_pay16<kThreads, UNROLL, NT>((const float *)G, (float *)R, (uint16_t *)send, t, c);
     else
         compress_tile<OPS, kThreads, UNROLL, NT>(G, R, send, t, c);
 }
@@ -541,6 +626,86 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const u32x4 *__restrict
     tile_ref t;
     if (!resolve_tile<TILE>(g, t)) return;
     decompress_tile<OPS, kThreads, UNROLL, WU, NT>(recv, out, t, N, stride_elems, n_f, inv_n, pow2);
+}
+
+// Half payload into an fp32 dense result.  A tile is kThreads * 8 elements: a
+// thread sums one 16-byte vector of eight halves over the N rows (fp32
+// accumulators, row order) and writes two 16-byte vectors of means.
+template <typename GEOM, int kThreads, int WU, bool NT>
+__global__ __launch_bounds__(kThreads) void k_decompress_pay16(const u32x4 *__restrict__ recv,
+                                                               float *__restrict__ out, GEOM g,
+                                                               int32_t N, int64_t stride_elems,
+                                                               float n_f, float inv_n, int pow2)
+{
+    using covap_dev::half_hi;
+    using covap_dev::half_lo;
+    constexpr int TILE = kThreads * 8;
+    tile_ref t;
+    if (!resolve_tile<TILE>(g, t)) return;
+    const int tid = threadIdx.x;
+    float *o = out + t.off;
+    if (!t.sel) {  // nothing was sent for this shard: the dense result is +0
+        const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+        const int nv = t.n / 4;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int v = u * kThreads + tid;
+            if (v < nv) {
+                if constexpr (NT)
+                    __builtin_nontemporal_store(zero, (f32x4 *)o + v);
+                else
+                    ((f32x4 *)o)[v] = zero;
+            }
+        }
+        if (tid < t.n - nv * 4) o[nv * 4 + tid] = 0.0f;
+        return;
+    }
+    const uint16_t *rp = (const uint16_t *)recv + t.poff;
+    const int nv = t.n / 8;
+    if (tid < nv) {
+        const u32x4 *p = (const u32x4 *)rp + tid;
+        const int64_t stride_vec = stride_elems / 8;
+        float acc[8];
+        {
+            const u32x4 x = ld16<NT>(p);
+            acc[0] = half_lo(x.x); acc[1] = half_hi(x.x); acc[2] = half_lo(x.y); acc[3] = half_hi(x.y);
+            acc[4] = half_lo(x.z); acc[5] = half_hi(x.z); acc[6] = half_lo(x.w); acc[7] = half_hi(x.w);
+        }
+        auto add = [&](const u32x4 x) {
+            acc[0] += half_lo(x.x); acc[1] += half_hi(x.x); acc[2] += half_lo(x.y); acc[3] += half_hi(x.y);
+            acc[4] += half_lo(x.z); acc[5] += half_hi(x.z); acc[6] += half_lo(x.w); acc[7] += half_hi(x.w);
+        };
+        int32_t w = 1;
+        for (; w + WU <= N; w += WU) {
+            u32x4 x[WU];
+#pragma unroll
+            for (int j = 0; j < WU; ++j) x[j] = ld16<NT>(p + (int64_t)(w + j) * stride_vec);
+#pragma unroll
+            for (int j = 0; j < WU; ++j) add(x[j]);
+        }
+        for (; w < N; ++w) add(ld16<NT>(p + (int64_t)w * stride_vec));
+        f32x4 lo4, hi4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            lo4[j] = ops_f32::mean1(acc[j], n_f, inv_n, pow2 != 0);
+            hi4[j] = ops_f32::mean1(acc[4 + j], n_f, inv_n, pow2 != 0);
+        }
+        if constexpr (NT) {
+            __builtin_nontemporal_store(lo4, (f32x4 *)o + 2 * tid);
+            __builtin_nontemporal_store(hi4, (f32x4 *)o + 2 * tid + 1);
+        } else {
+            ((f32x4 *)o)[2 * tid] = lo4;
+            ((f32x4 *)o)[2 * tid + 1] = hi4;
+        }
+    }
+    const int rem = t.n - nv * 8;
+    if (tid < rem) {
+        const int64_t e = (int64_t)nv * 8 + tid;
+        const uint16_t *row = rp + e;
+        float acc = __half2float(__ushort_as_half(row[0]));
+        for (int32_t w = 1; w < N; ++w) acc += __half2float(__ushort_as_half(row[(int64_t)w * stride_elems]));
+        o[e] = ops_f32::mean1(acc, n_f, inv_n, pow2 != 0);
+    }
 }
 
 // ---- probes ------------------------------------------------------------------------
@@ -745,6 +910,32 @@ bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
     });
 }
 
+// Half-payload decompress: the tile knob does not apply (a tile is always one
+// 16-byte payload vector per thread).
+bool launch_decompress_pay16(const covap::tuning &tn, const covap_plan_s *plan,
+                             const covap::call_range &cr, hipStream_t st, const void *recv, void *out,
+                             int32_t N, int64_t stride)
+{
+    const int pow2 = (N & (N - 1)) == 0;
+    const float n_f = (float)N, inv_n = 1.0f / n_f;
+    return pick<64, 256>(tn.decompress_threads, [&](auto T) {
+        pick<1, 2, 4>(tn.decompress_unroll, [&](auto WU) {
+            pick<0, 1>(tn.nontemporal, [&](auto NT) {
+                for_each_launch(plan, cr, T() * 8, false, [&](const auto &g, dim3 grid) {
+                    typedef std::decay_t<decltype(g)> GEOM;
+                    k_decompress_pay16<GEOM, T(), WU(), NT() != 0><<<grid, T(), (size_t)tn.decompress_lds_pad, st>>>(
+                        (const u32x4 *)recv, (float *)out, g, N, stride, n_f, inv_n, pow2);
+                });
+            });
+        });
+    });
+}
+
+// Element sizes in bytes of the four buffers of a plan's element type.
+int64_t grad_esz(int32_t dtype) { return dtype == COVAP_F32 || dtype == COVAP_F32_PAY16 ? 4 : 2; }
+int64_t residual_esz(int32_t dtype) { return dtype == COVAP_BF16 ? 2 : 4; }
+int64_t payload_esz(int32_t dtype) { return dtype == COVAP_F32 ? 4 : 2; }
+
 }  // namespace
 
 using covap::fail;
@@ -764,10 +955,9 @@ covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t b
         return fail(COVAP_EINVAL, "covap_compress: device pointers must be 16-byte aligned");
     if (send_cap_elems < cr.packed_base + cr.packed_elems)
         return fail(COVAP_EINVAL, "covap_compress: send buffer too small for this step");
-    const int64_t esz = plan->opts.dtype == COVAP_F32 ? 4 : 2;
-    const int64_t rsz = plan->opts.dtype == COVAP_BF16 ? 2 : 4;  // residual element size
-    const int64_t abytes = plan->total_elems * esz, sbytes = send_cap_elems * esz;
-    const int64_t rbytes = plan->total_elems * rsz;
+    const int32_t dt = plan->opts.dtype;
+    const int64_t abytes = plan->total_elems * grad_esz(dt), sbytes = send_cap_elems * payload_esz(dt);
+    const int64_t rbytes = plan->total_elems * residual_esz(dt);
     if (overlap(grad, abytes, residual, rbytes) || overlap(grad, abytes, send, sbytes) ||
         overlap(residual, rbytes, send, sbytes))
         return fail(COVAP_EINVAL, "covap_compress: grad, residual and send must not overlap");
@@ -780,8 +970,10 @@ covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t b
         ok = launch_compress<ops_f32>(tn, plan, cr, st, grad, residual, send, ef_coeff);
     else if (plan->opts.dtype == COVAP_BF16)
         ok = launch_compress<ops_bf16>(tn, plan, cr, st, grad, residual, send, ef_coeff);
-    else
+    else if (plan->opts.dtype == COVAP_BF16_RES32)
         ok = launch_compress<ops_bf16_res32>(tn, plan, cr, st, grad, residual, send, ef_coeff);
+    else
+        ok = launch_compress<ops_f32_pay16>(tn, plan, cr, st, grad, residual, send, ef_coeff);
     if (!ok) return fail(COVAP_EINVAL, "covap_compress: launch knobs select no kernel");
     return check_launch("covap_compress");
 }
@@ -794,9 +986,9 @@ covap_status_t covap_compress_aliased(const covap_plan_t *plan, uint64_t step, i
     covap::call_range cr;
     const covap_status_t rs = covap::resolve(plan, step, bucket, &cr);
     if (rs != COVAP_OK) return rs;
-    if (plan->opts.dtype == COVAP_BF16_RES32)
+    if (plan->opts.dtype == COVAP_BF16_RES32 || plan->opts.dtype == COVAP_F32_PAY16)
         return fail(COVAP_EUNSUPPORTED,
-                    "covap_compress_aliased: gradient and residual must share one element type");
+                    "covap_compress_aliased: gradient, residual and payload must share one element type");
     if (!accum || !send) return fail(COVAP_EINVAL, "covap_compress_aliased: null device pointer");
     if (!aligned16(accum) || !aligned16(send))
         return fail(COVAP_EINVAL, "covap_compress_aliased: device pointers must be 16-byte aligned");
@@ -837,16 +1029,21 @@ covap_status_t covap_decompress(const covap_plan_t *plan, uint64_t step, int32_t
         return fail(COVAP_EINVAL, "covap_decompress: row stride smaller than the packed payload");
     if (n_workers > 1 && stride_elems % plan->elems_per_vec != 0)
         return fail(COVAP_EINVAL, "covap_decompress: row stride must be a multiple of 16 bytes");
-    const int64_t esz = plan->opts.dtype == COVAP_F32 ? 4 : 2;
-    if (overlap(recv, (int64_t)n_workers * stride_elems * esz, dense_out, plan->total_elems * esz))
+    const int32_t dt = plan->opts.dtype;
+    if (overlap(recv, (int64_t)n_workers * stride_elems * payload_esz(dt), dense_out,
+                plan->total_elems * grad_esz(dt)))
         return fail(COVAP_EINVAL, "covap_decompress: recv and dense_out must not overlap");
     if (cr.sh_hi == cr.sh_lo) return COVAP_OK;
 
     const covap::tuning &tn = covap::tune();
     hipStream_t st = (hipStream_t)stream;
-    const bool ok = plan->opts.dtype == COVAP_F32
-                        ? launch_decompress<ops_f32>(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems)
-                        : launch_decompress<ops_bf16>(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems);
+    bool ok;
+    if (dt == COVAP_F32)
+        ok = launch_decompress<ops_f32>(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems);
+    else if (dt == COVAP_F32_PAY16)
+        ok = launch_decompress_pay16(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems);
+    else
+        ok = launch_decompress<ops_bf16>(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems);
     if (!ok) return fail(COVAP_EINVAL, "covap_decompress: launch knobs select no kernel");
     return check_launch("covap_decompress");
 }

@@ -209,11 +209,13 @@ covap_status_t covap_plan(const int64_t *tensor_numel, int32_t n_tensors,
     if (n_tensors < 1) return fail(COVAP_EINVAL, "covap_plan: n_tensors < 1");
     if (opts->K < 1) return fail(COVAP_EINVAL, "covap_plan: K < 1");
     if (opts->reserved != 0) return fail(COVAP_EINVAL, "covap_plan: reserved must be 0");
-    if (opts->dtype != COVAP_F32 && opts->dtype != COVAP_BF16 && opts->dtype != COVAP_BF16_RES32)
+    if (opts->dtype != COVAP_F32 && opts->dtype != COVAP_BF16 && opts->dtype != COVAP_BF16_RES32 &&
+        opts->dtype != COVAP_F32_PAY16)
         return fail(COVAP_EINVAL, "covap_plan: unknown dtype");
     if (opts->bucket_cap_bytes <= 0) return fail(COVAP_EINVAL, "covap_plan: bucket_cap_bytes <= 0");
+    // alignment unit of shard starts and packed offsets: 16 bytes of the narrowest buffer
     const int32_t epv = opts->dtype == COVAP_F32 ? 4 : 8;
-    const int64_t esz = opts->dtype == COVAP_F32 ? 4 : 2;
+    const int64_t esz = opts->dtype == COVAP_F32 || opts->dtype == COVAP_F32_PAY16 ? 4 : 2;  // gradient element
     int64_t total = 0;
     for (int32_t i = 0; i < n_tensors; ++i) {
         if (tensor_numel[i] < 0) return fail(COVAP_EINVAL, "covap_plan: negative element count");

@@ -1,0 +1,190 @@
+"""GPU parity for the half-payload element type (fp32 gradients, residual and dense
+result; IEEE fp16 payload): covap_compress / covap_decompress through the C ABI
+against the oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_04499_amd import workloads
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2311_04499_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return binding
+
+
+def half_bits(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16).copy()
+
+
+def same_bits(got: np.ndarray, want: np.ndarray, what: str):
+    g = got.view(np.uint32) if got.dtype == np.float32 else got
+    w = want.view(np.uint32) if want.dtype == np.float32 else want
+    if got.dtype == np.float32:                            # NaN payload bits are not specified
+        nan_g, nan_w = np.isnan(got), np.isnan(want)
+        assert np.array_equal(nan_g, nan_w), f"{what}: NaN positions differ"
+        g, w = g[~nan_g], w[~nan_w]
+    bad = np.nonzero(g != w)[0]
+    assert bad.size == 0, f"{what}: {bad.size} of {g.size} differ, first at {bad[0]}: {g[bad[0]]:#x} vs {w[bad[0]]:#x}"
+
+
+KNOBS = ("compress_threads", "compress_unroll", "decompress_threads", "decompress_unroll", "nontemporal")
+
+
+@pytest.mark.parametrize("numel,S,K,N,c", [
+    ([100_003], 4096, 3, 3, 1.0), ([7], 8, 2, 1, 0.5), ([8 * 4096 + 9], 8192, 4, 5, 0.3),
+    ([768 * 768, 3072 * 768 + 5], 1 << 18, 6, 64, 1.0), ([1000, 37, 5000, 8], 256, 4, 7, 1.0)])
+def test_half_payload_iterations(B, numel, S, K, N, c):
+    """Several iterations with the residual carried over, launch-shape knobs cycling."""
+    wl = workloads.scaled_down(workloads.config(5), numel, S)
+    plan = B.covap_plan(numel, S, K, dtype=B.COVAP_F32_PAY16)
+    tab = oracle.plan_fixed(numel, S, (25 << 20) // 4)
+    D = tab.D
+    assert plan.total_elems == D and plan.num_shards == tab.n_shards
+    stride = (plan.packed_elems_max + 7) // 8 * 8 + 8
+    R = torch.zeros(D, device=DEV)
+    Rc = np.zeros(D, np.float32)
+    old = {k: B.covap_tune_get(k) for k in KNOBS}
+    try:
+        for t in range(2 * K + 1):
+            B.covap_tune_set("compress_threads", (64, 256)[t % 2])
+            B.covap_tune_set("compress_unroll", (1, 2, 4)[t % 3])
+            B.covap_tune_set("decompress_threads", (64, 256)[(t // 2) % 2])
+            B.covap_tune_set("decompress_unroll", (1, 2, 4)[(t + 1) % 3])
+            B.covap_tune_set("nontemporal", (t // 3) % 2)
+            G = workloads.gradient(wl, 0, t, DEV)
+            recv = torch.full((N, stride), float("nan"), dtype=torch.float16, device=DEV)
+            recv_c = half_bits(recv)
+            assert plan.packed_elems(t) == oracle.packed_elems(tab, K, t)
+            B.covap_compress(plan, t, G, R, recv[0], ef_coeff=c)
+            oracle.compress(tab, K, t, G.cpu().numpy(), Rc, recv_c[0], c)
+            torch.cuda.synchronize()
+            same_bits(half_bits(recv[0]), recv_c[0], f"send t={t}")
+            same_bits(R.cpu().numpy(), Rc, f"residual t={t}")
+            if N > 1:
+                recv[1:] = workloads.payload_rows(wl, N - 1, stride, t, DEV, torch.float16)
+            recv_c = half_bits(recv)
+            out = torch.full((D,), float("nan"), device=DEV)
+            out_c = np.empty(D, np.float32)
+            B.covap_decompress(plan, t, recv, out)
+            oracle.decompress(tab, K, t, recv_c, out_c)
+            torch.cuda.synchronize()
+            same_bits(out.cpu().numpy(), out_c, f"dense t={t}")
+    finally:
+        for k, v in old.items():
+            B.covap_tune_set(k, v)
+
+
+def test_half_payload_special_values(B):
+    """Overflow to Inf, fp16 subnormals, signed zeros, fp32 ties at the fp16 rounding
+    boundary, NaN: the payload and the residual match the oracle's IEEE conversions."""
+    S, K = 64, 2
+    specials = np.array([70000.0, -70000.0, 65504.0, 65519.9, 65520.0, 1e-8, -1e-8, 6e-8, 0.0, -0.0,
+                         2.0 ** -14, 2.0 ** -24, 2.0 ** -25, 3 * 2.0 ** -25, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11,
+                         np.inf, -np.inf, np.nan, 1e-40, 3.14159], np.float32)
+    rng = np.random.default_rng(3)
+    Gn = rng.choice(specials, 4 * S + 13).astype(np.float32)
+    # residual + gradient that tie exactly at an fp16 rounding boundary only after the fp32 rounding
+    Gn[:8] = np.float32(1.0 + 2.0 ** -11)
+    Rn = np.zeros_like(Gn)
+    Rn[:8] = np.float32(2.0 ** -26)
+    plan = B.covap_plan([Gn.size], S, K, dtype=B.COVAP_F32_PAY16)
+    tab = oracle.plan_fixed([Gn.size], S, 1 << 30)
+    for t in range(K):
+        G = torch.from_numpy(Gn).to(DEV)
+        R = torch.from_numpy(Rn).to(DEV)
+        Rc = Rn.copy()
+        send = torch.zeros(plan.packed_elems_max + 8, dtype=torch.float16, device=DEV)
+        sc = half_bits(send)
+        B.covap_compress(plan, t, G, R, send)
+        oracle.compress(tab, K, t, Gn, Rc, sc)
+        torch.cuda.synchronize()
+        got, P = half_bits(send), plan.packed_elems(t)
+        nan_w = (sc[:P] & 0x7fff) > 0x7c00
+        assert np.array_equal((got[:P] & 0x7fff) > 0x7c00, nan_w)
+        assert np.array_equal(got[:P][~nan_w], sc[:P][~nan_w])
+        same_bits(R.cpu().numpy(), Rc, f"residual t={t}")
+
+
+def test_half_payload_on_median_shards_and_buckets(B):
+    layers = [1_003, 2_001, 30_007, 5, 4_099, 17, 90_001, 3]
+    wl = workloads.scaled_down(workloads.config(3), layers, 4096)
+    K, N = 4, 4
+    plan = B.covap_plan(layers, 0, K, dtype=B.COVAP_F32_PAY16, bucket_cap_bytes=80_000,
+                        mode=B.COVAP_SHARD_MEDIAN)
+    tab = oracle.plan_median(layers, 20_000, K, 0, 8)
+    D = tab.D
+    assert plan.total_elems == D and plan.num_buckets == tab.n_buckets
+    R = torch.zeros(D, device=DEV)
+    Rc = np.zeros(D, np.float32)
+    stride = (plan.packed_elems_max + 7) // 8 * 8
+    for t in range(2 * K + 1):
+        G = workloads.gradient(wl, 0, t, DEV)
+        G = torch.cat([G, torch.ones(D - G.numel(), device=DEV)])
+        recv = workloads.payload_rows(wl, N, stride, t, DEV, torch.float16, first_worker=0)
+        recv_c = half_bits(recv)
+        for b in range(plan.num_buckets):                          # one call per bucket, as a hook would
+            B.covap_compress(plan, t, G, R, recv[0], ef_coeff=0.5, bucket=b)
+        oracle.compress(tab, K, t, G.cpu().numpy(), Rc, recv_c[0], 0.5)
+        torch.cuda.synchronize()
+        same_bits(half_bits(recv[0]), recv_c[0], f"send t={t}")
+        same_bits(R.cpu().numpy(), Rc, f"residual t={t}")
+        out = torch.zeros(D, device=DEV)
+        out_c = np.zeros(D, np.float32)
+        for b in range(plan.num_buckets):
+            B.covap_decompress(plan, t, recv, out, bucket=b)
+        oracle.decompress(tab, K, t, recv_c, out_c)
+        torch.cuda.synchronize()
+        same_bits(out.cpu().numpy(), out_c, f"dense t={t}")
+
+
+def test_half_payload_full_size_gpt2_medium(B):
+    """The benchmark's workload at full size (payload mode, default knobs), every
+    element against the oracle, on the step that sends the short last shard."""
+    wl = workloads.config(5)
+    K, N, D = wl.K, wl.n_workers, wl.D
+    plan = B.covap_plan(wl.numel, wl.shard_elems, K, dtype=B.COVAP_F32_PAY16)
+    tab = oracle.plan_fixed(wl.numel, wl.shard_elems, (25 << 20) // 4)
+    stride = (plan.packed_elems_max + 7) // 8 * 8
+    recv = torch.empty(N, stride, dtype=torch.float16, device=DEV)
+    recv[1:] = workloads.payload_rows(wl, N - 1, stride, 0, DEV, torch.float16)
+    R = workloads.gradient(wl, 1, 0, DEV)
+    Rc = R.cpu().numpy()
+    out = torch.empty(D, device=DEV)
+    t = 14
+    G = workloads.gradient(wl, 0, t, DEV)
+    B.covap_compress(plan, t, G, R, recv[0])
+    B.covap_decompress(plan, t, recv, out, n_workers=N, stride_elems=stride)
+    torch.cuda.synchronize()
+    P = plan.packed_elems(t)
+    recv_c = half_bits(recv)
+    sent_gpu = recv_c[0, :P].copy()
+    oracle.compress(tab, K, t, G.cpu().numpy(), Rc, recv_c[0])
+    same_bits(sent_gpu, recv_c[0, :P], "send")
+    same_bits(R.cpu().numpy(), Rc, "residual")
+    out_c = np.empty(D, np.float32)
+    oracle.decompress(tab, K, t, recv_c, out_c)
+    same_bits(out.cpu().numpy(), out_c, "dense")
+
+
+def test_half_payload_argument_errors(B):
+    plan = B.covap_plan([4096], 512, 2, dtype=B.COVAP_F32_PAY16)
+    G = torch.zeros(4096, device=DEV)
+    R = torch.zeros(4096, device=DEV)
+    send = torch.zeros(4096, dtype=torch.float16, device=DEV)
+    with pytest.raises(B.CovapError) as e:
+        B.covap_compress_aliased(plan, 0, G, send)
+    assert e.value.status == 5
+    with pytest.raises(B.CovapError):
+        B.covap_compress(plan, 0, G, R, send, send_cap_elems=100)
+    recv = torch.zeros(3, 2052, dtype=torch.float16, device=DEV)
+    with pytest.raises(B.CovapError):
+        B.covap_decompress(plan, 0, recv, G)                       # row stride not a multiple of 8
+    torch.cuda.synchronize()

@@ -98,10 +98,11 @@ def test_small_plans_match_oracle_exhaustively(B):
 def test_median_planner_tables_match_oracle(B, layers, K, cap, ref):
     if layers is None:
         layers = workloads.config(3).numel
-    for dtype, esz in ((B.COVAP_F32, 4), (B.COVAP_BF16, 2)):
+    # (element type, bytes per gradient element, alignment unit in elements)
+    for dtype, esz, align in ((B.COVAP_F32, 4, 4), (B.COVAP_BF16, 2, 8), (B.COVAP_F32_PAY16, 4, 8)):
         plan = B.covap_plan(layers, 0, K, dtype=dtype, bucket_cap_bytes=cap,
                             mode=B.COVAP_SHARD_MEDIAN, ref_elems=ref)
-        tab = oracle.plan_median(layers, max(1, cap // esz), K, ref, 16 // esz)
+        tab = oracle.plan_median(layers, max(1, cap // esz), K, ref, align)
         assert plan.total_elems == tab.D
         assert plan.num_shards == tab.n_shards and plan.num_buckets == tab.n_buckets
         for i in range(len(layers)):
@@ -135,6 +136,8 @@ def test_plan_argument_errors(B):
         B.covap_plan([10, -1], 8, 2)
     with pytest.raises(B.CovapError):
         B.covap_plan([100], 12, 2, dtype=B.COVAP_BF16)      # bf16 vectors hold 8 elements
+    with pytest.raises(B.CovapError):
+        B.covap_plan([100], 12, 2, dtype=B.COVAP_F32_PAY16)  # so do vectors of half payload
     p = B.covap_plan([100], 8, 2)
     with pytest.raises(B.CovapError) as e:
         p.shard(13)

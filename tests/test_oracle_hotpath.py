@@ -507,3 +507,107 @@ def test_aliased_form_equals_algorithm_1_at_c1(numel, S, I):
         assert np.array_equal(bits(R), bits(acc))
         m = keep_mask(tab, I, t, tab.D)
         assert not bits(acc[m]).any()
+
+
+# ------------------------------------------------------------------ half-precision payload
+
+def test_half_payload_residual_keeps_the_quantisation_error():
+    """The FP16 scheme (Table II) as the quantiser of Algorithm 1 line 3 on the
+    shards the filter sends: sent = fp16(A) (checked against numpy's cast), residual
+    = A - sent exactly, kept shards hold A untouched."""
+    tab = oracle.plan_fixed([4096 * 3 + 40], 1024, 1 << 30)
+    I = 3
+    rng = np.random.default_rng(5)
+    R = np.zeros(tab.D, np.float32)
+    for t in range(2 * I + 1):
+        G = (rng.standard_normal(tab.D) * 1e-3).astype(np.float32)
+        R_old = R.copy()
+        send = np.full(tab.D, 0xffff, np.uint16)
+        n = oracle.compress(tab, I, t, G, R, send, 0.5)
+        A = (G.astype(np.float64) + 0.5 * R_old.astype(np.float64)).astype(np.float32)
+        m = keep_mask(tab, I, t, tab.D)
+        dense, p = scatter_packed(tab, I, t, send, tab.D)
+        assert p == n == int(m.sum())
+        with np.errstate(over="ignore"):
+            want_h = A.astype(np.float16).view(np.uint16)
+        assert np.array_equal(dense[m], want_h[m])
+        sent_f32 = dense.view(np.float16).astype(np.float32)
+        assert np.array_equal(bits(R[m]), bits((A - sent_f32)[m]))
+        assert np.array_equal(sent_f32[m] + R[m], A[m])              # nothing is lost: exact
+        assert np.all(np.abs(R[m]) <= np.maximum(np.abs(A[m]) * 2.0 ** -11, 2.0 ** -25))
+        assert np.array_equal(bits(R[~m]), bits(A[~m]))
+        assert np.all(send[p:] == 0xffff)                            # nothing written past the payload
+
+
+def test_half_payload_equals_fp16_of_the_fp32_payload():
+    """Same filter, same packed layout: with equal inputs the half payload is the
+    fp16 cast of the fp32 path's payload, position by position."""
+    tab = oracle.plan_fixed([1000, 37, 5000, 8], 256, 1 << 30)
+    I = 4
+    rng = np.random.default_rng(6)
+    for t in range(I):
+        G = rng.standard_normal(tab.D).astype(np.float32)
+        R0 = rng.standard_normal(tab.D).astype(np.float32)
+        R1, R2 = R0.copy(), R0.copy()
+        s32 = np.zeros(tab.D, np.float32)
+        s16 = np.zeros(tab.D, np.uint16)
+        n1 = oracle.compress(tab, I, t, G, R1, s32)
+        n2 = oracle.compress(tab, I, t, G, R2, s16)
+        assert n1 == n2
+        assert np.array_equal(s32[:n1].astype(np.float16).view(np.uint16), s16[:n2])
+        m = keep_mask(tab, I, t, tab.D)
+        assert np.array_equal(bits(R1[~m]), bits(R2[~m]))
+
+
+def test_half_payload_conservation_and_overflow():
+    """Integers up to 2048 are exact in fp16, larger ones are rounded; with c = 1
+    everything sent plus the residual still equals the sum of all gradients exactly.
+    A magnitude beyond 65504 travels as Inf and leaves an infinite residual of the
+    opposite sign (IEEE, no clamping)."""
+    tab = oracle.plan_fixed([3000, 500, 77], 128, 1 << 30)
+    I, T = 4, 13
+    R = np.zeros(tab.D, np.float32)
+    total_sent = np.zeros(tab.D, np.float64)
+    total_grad = np.zeros(tab.D, np.float64)
+    rounded = 0
+    for t in range(T):
+        G = workloads.integer_valued(tab.D, seed=500 + t, lo=-3000, hi=3000).numpy()
+        total_grad += G
+        send = np.zeros(tab.D, np.uint16)
+        oracle.compress(tab, I, t, G, R, send)
+        dense, _ = scatter_packed(tab, I, t, send, tab.D)
+        total_sent += dense.view(np.float16).astype(np.float32)
+        rounded += int((R[keep_mask(tab, I, t, tab.D)] != 0).sum())
+    assert np.array_equal(total_sent + R, total_grad)
+    assert rounded > 0
+    tab = oracle.plan_fixed([8], 8, 1 << 30)
+    G = np.array([70000.0, -70000.0, 65504.0, 65519.9, 65520.0, 1e-8, -1e-8, 6e-8], np.float32)
+    R = np.zeros(8, np.float32)
+    send = np.zeros(8, np.uint16)
+    oracle.compress(tab, 1, 0, G, R, send)
+    assert list(send) == [0x7c00, 0xfc00, 0x7bff, 0x7bff, 0x7c00, 0x0000, 0x8000, 0x0001]
+    assert R[0] == -np.inf and R[1] == np.inf and R[2] == 0 and R[5] == np.float32(1e-8)
+
+
+def test_half_payload_average_against_numpy_left_fold():
+    """Dense mean of N half payloads: fp32 left fold over numpy's widening cast, IEEE
+    division, +0 where nothing was sent; exact closed form on small integers."""
+    tab = oracle.plan_fixed([700, 300, 41], 64, 1 << 30)
+    I, N = 3, 5
+    rng = np.random.default_rng(8)
+    for t in range(I):
+        P = oracle.packed_elems(tab, I, t)
+        stride = P + 16
+        recv = rng.standard_normal((N, stride)).astype(np.float16).view(np.uint16)
+        out = np.full(tab.D, np.nan, np.float32)
+        oracle.decompress(tab, I, t, recv, out)
+        acc = recv[0].view(np.float16).astype(np.float32)
+        for w in range(1, N):
+            acc = acc + recv[w].view(np.float16).astype(np.float32)
+        want, p = scatter_packed(tab, I, t, acc / np.float32(N), tab.D)
+        assert p == P
+        assert np.array_equal(bits(out), bits(want))
+        ints = np.tile(np.arange(1, N + 1, dtype=np.float16)[:, None], (1, stride)).view(np.uint16)
+        oracle.decompress(tab, I, t, ints, out)
+        m = keep_mask(tab, I, t, tab.D)
+        assert np.all(out[m] == np.float32((N + 1) / 2)) and not bits(out[~m]).any()
