@@ -104,7 +104,7 @@ def main():
                         mode=B.COVAP_SHARD_FIXED if args.shard_mode == "fixed" else B.COVAP_SHARD_MEDIAN)
     D, N, K = plan.total_elems, wl.n_workers, wl.K
     P_max = plan.packed_elems_max
-    stride = (P_max + epv - 1) // epv * epv
+    stride = (P_max + 1023) // 1024 * 1024          # rows start on 2 KiB boundaries at least
 
     # ---- inputs, resident in HBM before anything is timed
     ring = [workloads.gradient(wl, 0, i, dev, tdtype) for i in range(3)]
@@ -400,7 +400,7 @@ def main():
         import numpy as np
         import oracle
         tab = oracle.plan_fixed(wl.numel, wl.shard_elems, (25 << 20) // esz) if args.shard_mode == "fixed" \
-            else oracle.plan_median(wl.numel, (25 << 20) // esz, K, 0, epv)
+            else oracle.plan_median(wl.numel, (25 << 20) // esz, K, 0, 1024 // psz)
         t = t_first + args.steps
         to_np = lambda x: x.cpu().numpy() if x.dtype == torch.float32 else \
             x.cpu().view(torch.int16).numpy().view(np.uint16)

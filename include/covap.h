@@ -84,10 +84,12 @@ typedef enum {
      * least twice the reference element count (the median of the bucket sizes, or
      * `ref_elems` when > 0) is cut evenly into floor(numel/ref) pieces, at most I.
      * Every piece is one shard for the filter; shards have different lengths.
-     * Each bucket starts on a 16-byte boundary of the arena (so total_elems may
-     * exceed the sum of the tensor counts by a few padding elements that no call
-     * reads or writes), and in the packed layout every sent shard starts on a
-     * 16-byte boundary too (elements in the gaps are never written or read). */
+     * Each bucket starts on a 1 KiB boundary of the arena -- 256 elements for
+     * COVAP_F32, 512 for the other element types, see covap_plan_align_elems() --
+     * (so total_elems may exceed the sum of the tensor counts by padding elements
+     * that no call reads or writes), pieces are multiples of that unit, and in the
+     * packed layout every sent shard starts on such a boundary too (elements in
+     * the gaps are never written or read). */
     COVAP_SHARD_MEDIAN = 1
 } covap_shard_mode_t;
 
@@ -120,6 +122,11 @@ int32_t covap_plan_num_tensors(const covap_plan_t *plan);
 int32_t covap_plan_num_shards(const covap_plan_t *plan);
 int32_t covap_plan_num_buckets(const covap_plan_t *plan);
 int32_t covap_plan_interval(const covap_plan_t *plan);
+/* Alignment unit, in elements, of shard starts in the arena and in the packed
+ * layout: the 16-byte vector for COVAP_SHARD_FIXED (where no padding ever
+ * appears), 1 KiB of the narrowest buffer for COVAP_SHARD_MEDIAN.  Row strides
+ * that are multiples of 1 KiB keep every payload row aligned alike (faster). */
+int32_t covap_plan_align_elems(const covap_plan_t *plan);
 /* Arena offset (elements) of tensor i, or -1 when i is out of range. */
 int64_t covap_plan_tensor_offset(const covap_plan_t *plan, int32_t i);
 /* Arena offset, length and bucket of shard s; any out pointer may be null. */

@@ -79,7 +79,7 @@ def lib():
         getattr(L, name).restype = C.c_int64
         getattr(L, name).argtypes = [_vp]
     for name in ("covap_plan_num_tensors", "covap_plan_num_shards", "covap_plan_num_buckets",
-                 "covap_plan_interval"):
+                 "covap_plan_interval", "covap_plan_align_elems"):
         getattr(L, name).restype = C.c_int32
         getattr(L, name).argtypes = [_vp]
     L.covap_plan_tensor_offset.restype = C.c_int64
@@ -185,6 +185,7 @@ class Plan:
     num_shards = property(lambda self: lib().covap_plan_num_shards(self._h))
     num_buckets = property(lambda self: lib().covap_plan_num_buckets(self._h))
     interval = property(lambda self: lib().covap_plan_interval(self._h))
+    align_elems = property(lambda self: lib().covap_plan_align_elems(self._h))
     packed_elems_max = property(lambda self: lib().covap_plan_packed_elems_max(self._h))
 
     def tensor_offset(self, i: int) -> int:

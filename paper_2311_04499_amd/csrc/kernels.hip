@@ -226,8 +226,7 @@ __device__ __forceinline__ bool resolve_tile(const fixed_geom &g, tile_ref &t)
 // into segments and passes the records of up to kMaxUnits segments in the kernel
 // arguments, so no device table is ever allocated.  The grid is one-dimensional
 // and holds exactly the tiles of these segments; a workgroup finds its segment
-// by a scalar binary search over the tile prefix (7 steps on kernel-argument
-// words).
+// by a two-level scalar search over the tile prefix.
 constexpr int kMaxUnits = 128;
 constexpr int kSegTiles = 4096;  // longest run of tiles of one kind (sent / not sent) in a launch
 
@@ -243,14 +242,18 @@ template <int TILE>
 __device__ __forceinline__ bool resolve_tile(const table_geom &g, tile_ref &t)
 {
     const uint32_t tile = blockIdx.x;
-    uint32_t lo = 0, hi = g.n_units;  // invariant: first[lo] <= tile < first[hi]
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (g.first[mid] <= tile)
-            lo = mid;
-        else
-            hi = mid;
-    }
+    // Two-level scalar search, three dependent kernel-argument reads in all (a plain
+    // binary search needs eight, and a zero-fill workgroup lives hardly longer than
+    // that): eight pivots at fixed positions, then the 16 entries of one block.
+    // Unused entries hold the grid size, which no tile index reaches.
+    static_assert(kMaxUnits % 16 == 0, "blocks of 16 units");
+    uint32_t blk = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxUnits / 16; ++i) blk += g.first[16 * i] <= tile ? 1u : 0u;
+    const uint32_t *f = g.first + 16 * blk;
+    uint32_t lo = 16 * blk;
+#pragma unroll
+    for (int j = 1; j < 16; ++j) lo += f[j] <= tile ? 1u : 0u;
     const uint32_t u = lo;
     const uint32_t word = g.len[u];
     const uint32_t sh_len = word & 0x7fffffffu;
@@ -953,7 +956,7 @@ covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t b
     if (!grad || !residual || !send) return fail(COVAP_EINVAL, "covap_compress: null device pointer");
     if (!aligned16(grad) || !aligned16(residual) || !aligned16(send))
         return fail(COVAP_EINVAL, "covap_compress: device pointers must be 16-byte aligned");
-    if (send_cap_elems < cr.packed_base + cr.packed_elems)
+    if (cr.packed_elems > 0 && send_cap_elems < cr.packed_base + cr.packed_elems)  // nothing sent: nothing written
         return fail(COVAP_EINVAL, "covap_compress: send buffer too small for this step");
     const int32_t dt = plan->opts.dtype;
     const int64_t abytes = plan->total_elems * grad_esz(dt), sbytes = send_cap_elems * payload_esz(dt);
@@ -992,7 +995,7 @@ covap_status_t covap_compress_aliased(const covap_plan_t *plan, uint64_t step, i
     if (!accum || !send) return fail(COVAP_EINVAL, "covap_compress_aliased: null device pointer");
     if (!aligned16(accum) || !aligned16(send))
         return fail(COVAP_EINVAL, "covap_compress_aliased: device pointers must be 16-byte aligned");
-    if (send_cap_elems < cr.packed_base + cr.packed_elems)
+    if (cr.packed_elems > 0 && send_cap_elems < cr.packed_base + cr.packed_elems)  // nothing sent: nothing written
         return fail(COVAP_EINVAL, "covap_compress_aliased: send buffer too small for this step");
     const int64_t esz = plan->opts.dtype == COVAP_F32 ? 4 : 2;
     if (overlap(accum, plan->total_elems * esz, send, send_cap_elems * esz))
@@ -1025,7 +1028,7 @@ covap_status_t covap_decompress(const covap_plan_t *plan, uint64_t step, int32_t
     if (!aligned16(recv) || !aligned16(dense_out))
         return fail(COVAP_EINVAL, "covap_decompress: device pointers must be 16-byte aligned");
     if (n_workers < 1) return fail(COVAP_EINVAL, "covap_decompress: n_workers < 1");
-    if (stride_elems < cr.packed_base + cr.packed_elems)
+    if (cr.packed_elems > 0 && stride_elems < cr.packed_base + cr.packed_elems)
         return fail(COVAP_EINVAL, "covap_decompress: row stride smaller than the packed payload");
     if (n_workers > 1 && stride_elems % plan->elems_per_vec != 0)
         return fail(COVAP_EINVAL, "covap_decompress: row stride must be a multiple of 16 bytes");

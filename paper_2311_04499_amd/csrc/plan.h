@@ -25,6 +25,7 @@ struct covap_plan_s {
     covap_plan_opts_t opts;
     int32_t K;
     int32_t elems_per_vec;                // 4 for fp32, 8 for bf16 (16-byte vectors)
+    int32_t align_elems;                  // alignment unit of shard starts, in the arena and in the packed layout
     int64_t total_elems;                  // arena size D
     std::vector<int64_t> tensor_off;
     std::vector<covap_shard_rec> shards;

@@ -119,7 +119,7 @@ def test_half_payload_on_median_shards_and_buckets(B):
     K, N = 4, 4
     plan = B.covap_plan(layers, 0, K, dtype=B.COVAP_F32_PAY16, bucket_cap_bytes=80_000,
                         mode=B.COVAP_SHARD_MEDIAN)
-    tab = oracle.plan_median(layers, 20_000, K, 0, 8)
+    tab = oracle.plan_median(layers, 20_000, K, 0, 512)         # 1 KiB of half payload
     D = tab.D
     assert plan.total_elems == D and plan.num_buckets == tab.n_buckets
     R = torch.zeros(D, device=DEV)

@@ -67,7 +67,7 @@ def make_median_plans(B, numel, K, dtype=torch.float32, cap_bytes=25 << 20, ref=
     esz = 4 if dtype == torch.float32 else 2
     plan = B.covap_plan(numel, 0, K, dtype=code, bucket_cap_bytes=cap_bytes,
                         mode=B.COVAP_SHARD_MEDIAN, ref_elems=ref)
-    tab = oracle.plan_median(numel, max(1, cap_bytes // esz), K, ref, 16 // esz)
+    tab = oracle.plan_median(numel, max(1, cap_bytes // esz), K, ref, 1024 // esz)   # 1 KiB alignment unit
     assert plan.total_elems == tab.D and plan.num_shards == tab.n_shards
     assert plan.num_buckets == tab.n_buckets
     return plan, tab
@@ -418,7 +418,7 @@ def test_mixed_precision_on_median_shards(B):
     K = 4
     plan = B.covap_plan(layers, 0, K, dtype=B.COVAP_BF16_RES32, bucket_cap_bytes=40_000,
                         mode=B.COVAP_SHARD_MEDIAN)
-    tab = oracle.plan_median(layers, 20_000, K, 0, 8)
+    tab = oracle.plan_median(layers, 20_000, K, 0, 512)         # 1 KiB of bf16
     D = tab.D
     assert plan.total_elems == D
     R = torch.zeros(D, device=DEV)

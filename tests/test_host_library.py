@@ -99,11 +99,11 @@ def test_median_planner_tables_match_oracle(B, layers, K, cap, ref):
     if layers is None:
         layers = workloads.config(3).numel
     # (element type, bytes per gradient element, alignment unit in elements)
-    for dtype, esz, align in ((B.COVAP_F32, 4, 4), (B.COVAP_BF16, 2, 8), (B.COVAP_F32_PAY16, 4, 8)):
+    for dtype, esz, align in ((B.COVAP_F32, 4, 256), (B.COVAP_BF16, 2, 512), (B.COVAP_F32_PAY16, 4, 512)):
         plan = B.covap_plan(layers, 0, K, dtype=dtype, bucket_cap_bytes=cap,
                             mode=B.COVAP_SHARD_MEDIAN, ref_elems=ref)
         tab = oracle.plan_median(layers, max(1, cap // esz), K, ref, align)
-        assert plan.total_elems == tab.D
+        assert plan.total_elems == tab.D and plan.align_elems == align
         assert plan.num_shards == tab.n_shards and plan.num_buckets == tab.n_buckets
         for i in range(len(layers)):
             assert plan.tensor_offset(i) == int(tab.tensor_offsets[i])
