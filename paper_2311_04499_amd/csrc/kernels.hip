@@ -30,7 +30,7 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kProbeThreads = 256;
+constexpr int kProbeThreads = 64;
 
 template <bool NT>
 __device__ __forceinline__ u32x4 ld16(const u32x4 *p)
@@ -713,24 +713,14 @@ __global__ __launch_bounds__(kThreads) void k_decompress_pay16(const u32x4 *__re
 
 // ---- probes ------------------------------------------------------------------------
 
+// Both probes use the launch shape that the sweeps found best for the hot path:
+// one-wave workgroups, one 16-byte vector per thread.
 template <bool NT>
 __global__ __launch_bounds__(kProbeThreads) void k_copy(u32x4 *__restrict__ dst,
                                                    const u32x4 *__restrict__ src, int64_t nvec)
 {
-    constexpr int U = 4;
-    const int64_t base = (int64_t)blockIdx.x * (kProbeThreads * U) + threadIdx.x;
-    if (base + (U - 1) * kProbeThreads < nvec) {
-        u32x4 v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = ld16<NT>(src + base + u * kProbeThreads);
-#pragma unroll
-        for (int u = 0; u < U; ++u) st16<NT>(dst + base + u * kProbeThreads, v[u]);
-    } else {
-        for (int u = 0; u < U; ++u) {
-            const int64_t i = base + u * kProbeThreads;
-            if (i < nvec) st16<NT>(dst + i, ld16<NT>(src + i));
-        }
-    }
+    const int64_t i = (int64_t)blockIdx.x * kProbeThreads + threadIdx.x;
+    if (i < nvec) st16<NT>(dst + i, ld16<NT>(src + i));
 }
 
 template <bool NT>
@@ -739,12 +729,8 @@ __global__ __launch_bounds__(kProbeThreads) void k_triad(u32x4 *__restrict__ a,
                                                     const u32x4 *__restrict__ c, float s,
                                                     int64_t nvec)
 {
-    constexpr int U = 4;
-    const int64_t base = (int64_t)blockIdx.x * (kProbeThreads * U) + threadIdx.x;
-    for (int u = 0; u < U; ++u) {
-        const int64_t i = base + u * kProbeThreads;
-        if (i < nvec) st16<NT>(a + i, ops_f32::ef(ld16<NT>(b + i), ld16<NT>(c + i), s));
-    }
+    const int64_t i = (int64_t)blockIdx.x * kProbeThreads + threadIdx.x;
+    if (i < nvec) st16<NT>(a + i, ops_f32::ef(ld16<NT>(b + i), ld16<NT>(c + i), s));
 }
 
 // ---- host-side launch helpers ----------------------------------------------------------
@@ -1058,7 +1044,7 @@ covap_status_t covap_probe_copy(void *dst, const void *src, size_t bytes, void *
         return fail(COVAP_EINVAL, "covap_probe_copy: pointers and size must be 16-byte multiples");
     if (bytes == 0) return COVAP_OK;
     const int64_t nvec = (int64_t)(bytes / 16);
-    const int64_t per = kProbeThreads * 4;
+    const int64_t per = kProbeThreads;
     const uint32_t grid = (uint32_t)((nvec + per - 1) / per);
     if (covap::tune().nontemporal)
         k_copy<true><<<grid, kProbeThreads, 0, (hipStream_t)stream>>>((u32x4 *)dst, (const u32x4 *)src, nvec);
@@ -1075,7 +1061,7 @@ covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float
         return fail(COVAP_EINVAL, "covap_probe_triad: pointers 16-byte aligned, n a multiple of 4");
     if (n == 0) return COVAP_OK;
     const int64_t nvec = n / 4;
-    const int64_t per = kProbeThreads * 4;
+    const int64_t per = kProbeThreads;
     const uint32_t grid = (uint32_t)((nvec + per - 1) / per);
     if (covap::tune().nontemporal)
         k_triad<true><<<grid, kProbeThreads, 0, (hipStream_t)stream>>>((u32x4 *)a, (const u32x4 *)b,
