@@ -280,11 +280,14 @@ def main():
             if "topk" in out and "k" in out["topk"]:
                 kk = out["topk"]["k"]
                 sv = torch.randn(N, kk, device=dev)
-                si = torch.stack([torch.sort(torch.randperm(D, device=dev)[:kk]).values.to(torch.int32)
-                                  for _ in range(min(N, 4))])
-                si = si.repeat((N + si.shape[0] - 1) // si.shape[0], 1)[:N].contiguous()
-                us = timed_us(lambda t: B.sparse_decompress(sv, si, dense, stream=stream), reps=5)
+                # N different ascending index rows: one coordinate per cell of D/kk elements
+                cell = D // kk
+                si = (torch.arange(kk, device=dev, dtype=torch.int64)[None, :] * cell +
+                      torch.randint(0, cell, (N, kk), generator=g, device=dev)).to(torch.int32).contiguous()
+                us = timed_us(lambda t: B.sparse_decompress_sorted(sv, si, dense, stream=stream), reps=5)
+                us_pw = timed_us(lambda t: B.sparse_decompress(sv, si, dense, stream=stream), reps=3)
                 out["topk"]["decompress_us_per_iter"] = round(us, 1)
+                out["topk"]["decompress_per_worker_launches_us"] = round(us_pw, 1)
                 out["topk"]["compress_plus_decompress_vs_covap"] = round(
                     (out["topk"]["us_per_iter"] + us) / (ms_step * 1e3), 2)
                 del sv, si

@@ -265,6 +265,16 @@ covap_status_t sparse_decompress(const void *vals, const uint32_t *idx, int32_t 
                                  int64_t k, int64_t stride_elems, int64_t n, void *dense_out,
                                  void *stream);
 
+/* The same mean for payloads whose indices ascend inside every row (what
+ * topk_compress writes; Random-k payloads qualify if the caller drew or sorted
+ * its coordinates in ascending order): one pass over dense_out instead of one
+ * launch per worker.  Same arguments, same result bits.  Rows that are not
+ * ascending give an unspecified result (but no access outside the buffers).
+ * More than 64 workers are handed to sparse_decompress. */
+covap_status_t sparse_decompress_sorted(const void *vals, const uint32_t *idx, int32_t n_workers,
+                                        int64_t k, int64_t stride_elems, int64_t n, void *dense_out,
+                                        void *stream);
+
 /* ---- measurement helpers ------------------------------------------------ */
 
 /* Plain streaming kernels used to measure the achievable HBM rate next to the

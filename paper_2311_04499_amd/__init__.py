@@ -9,7 +9,7 @@ a built library raises.
 
 _BINDING_NAMES = (
     "covap_plan", "covap_compress", "covap_compress_aliased", "covap_decompress", "topk_compress", "topk_workspace_bytes",
-    "randk_compress", "fp16_compress", "fp16_decompress", "sparse_decompress",
+    "randk_compress", "fp16_compress", "fp16_decompress", "sparse_decompress", "sparse_decompress_sorted",
     "covap_ratio_from_ccr", "covap_ratio_from_times", "covap_ef_coeff",
     "Plan", "CovapError", "lib", "build",
 )

@@ -121,6 +121,8 @@ def lib():
     L.fp16_decompress.argtypes = [_vp, C.c_int32, C.c_int64, C.c_int64, _vp, _vp]
     L.sparse_decompress.restype = C.c_int
     L.sparse_decompress.argtypes = [_vp, _vp, C.c_int32, C.c_int64, C.c_int64, C.c_int64, _vp, _vp]
+    L.sparse_decompress_sorted.restype = C.c_int
+    L.sparse_decompress_sorted.argtypes = [_vp, _vp, C.c_int32, C.c_int64, C.c_int64, C.c_int64, _vp, _vp]
     L.covap_probe_copy.restype = C.c_int
     L.covap_probe_copy.argtypes = [_vp, _vp, C.c_size_t, _vp]
     L.covap_probe_triad.restype = C.c_int
@@ -297,6 +299,17 @@ def sparse_decompress(vals, idx, dense_out, k: Optional[int] = None, n: Optional
     n = dense_out.numel() if n is None else n
     _check(lib().sparse_decompress(_ptr(vals), _ptr(idx), n_workers, k, stride_elems, n,
                                    _ptr(dense_out), _stream(stream)))
+
+
+def sparse_decompress_sorted(vals, idx, dense_out, k: Optional[int] = None, n: Optional[int] = None,
+                             n_workers: Optional[int] = None, stride_elems: Optional[int] = None,
+                             stream=None) -> None:
+    n_workers = vals.shape[0] if n_workers is None else n_workers
+    stride_elems = vals.stride(0) if stride_elems is None else stride_elems
+    k = vals.shape[1] if k is None else k
+    n = dense_out.numel() if n is None else n
+    _check(lib().sparse_decompress_sorted(_ptr(vals), _ptr(idx), n_workers, k, stride_elems, n,
+                                          _ptr(dense_out), _stream(stream)))
 
 
 def covap_ratio_from_ccr(ccr: float) -> int:

@@ -171,6 +171,162 @@ __global__ __launch_bounds__(kThreads) void k_scale(float *out, int64_t n, float
     }
 }
 
+// Mean of N <= 64 sparse payloads whose indices ascend inside every row (what
+// topk_compress writes), in one pass over the dense result: a one-wave workgroup
+// walks a run of consecutive 4096-element tiles, builds each tile in LDS and writes
+// it out once.  Lane w keeps a cursor into row w (found by a binary search at the
+// first tile and carried forward).  Per tile one load instruction fetches the 16
+// entries after the cursor of four rows at a time (lane = 16 * row-in-group + entry);
+// those that fall into the tile are added with LDS float adds, one instruction per
+// row and the rows in ascending order, which is the worker order the definition asks
+// for: LDS operations of one wave are carried out in program order, entries of one
+// row are distinct (no two lanes of an instruction meet), and the LDS adder rounds to
+// nearest even with subnormals like the vector unit (the parity tests cover both).
+// The common case is straight-line code -- every load of a tile is unconditional
+// (clamped addresses, masked results) and in flight before the first is used; a tile
+// in which some row has 16 or more entries takes a plain loop instead.  Unsorted rows
+// give an unspecified result but no access outside the buffers.  ROWS = lanes that
+// carry a row (the smallest of 8, 16, 32, 64 that holds N).
+constexpr int kSpTile = 4096;
+constexpr int kSpRows = 64;
+
+__device__ __forceinline__ void lds_add(float *p, float v)
+{
+    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);  // ds_add_f32
+}
+
+template <int ROWS, bool FULL>  // FULL: N == ROWS, which removes every test of a row number against N
+__global__ __launch_bounds__(64) void k_sparse_mean_sorted(const float *__restrict__ vals,
+                                                           const uint32_t *__restrict__ idx, int32_t N,
+                                                           uint32_t k, int64_t stride, int64_t n,
+                                                           float *__restrict__ out, int64_t tiles_per_wg,
+                                                           float n_f, float inv_n, int pow2)
+{
+    constexpr int GROUPS = ROWS / 4;
+    __shared__ float tile[kSpTile];
+    const int lane = threadIdx.x;
+    const int q = lane >> 4, e = lane & 15;  // row inside a group of four, entry inside the window
+    const int64_t ntiles = (n + kSpTile - 1) / kSpTile;
+    const int64_t tile_lo = (int64_t)blockIdx.x * tiles_per_wg;
+    int64_t tile_hi = tile_lo + tiles_per_wg;
+    if (tile_hi > ntiles) tile_hi = ntiles;
+    if (tile_lo >= tile_hi) return;  // k >= 1 from here on (the host handles empty payloads)
+
+    // Cursor of row `lane`: first entry whose index is >= the start of the first tile.
+    uint32_t start = 0u;
+    if (lane < N) {
+        const uint32_t *my_idx = idx + (int64_t)lane * stride;
+        const uint32_t first = (uint32_t)(tile_lo * kSpTile);
+        uint32_t lo = 0u, hi = k;
+        while (lo < hi) {
+            const uint32_t mid = lo + ((hi - lo) >> 1);
+            if (my_idx[mid] < first)
+                lo = mid + 1u;
+            else
+                hi = mid;
+        }
+        start = lo;
+    }
+    // From here on every lane carries, for each group g, the cursor and the row base of
+    // the row it loads for: row 4g + q.  The 16 lanes of a row hold the same cursor.
+    uint32_t cur[GROUPS];
+    const uint32_t *row_idx[GROUPS];
+    const float *row_val[GROUPS];
+    bool row_live[GROUPS];
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g) {
+        const int w = 4 * g + q;
+        cur[g] = (uint32_t)__shfl((int)start, w, 64);
+        row_live[g] = FULL || w < N;
+        row_idx[g] = idx + (int64_t)(row_live[g] ? w : 0) * stride;
+        row_val[g] = vals + (int64_t)(row_live[g] ? w : 0) * stride;
+    }
+    const uint32_t k_last = k - 1u;
+
+    for (int64_t t = tile_lo; t < tile_hi; ++t) {
+        const int64_t T0 = t * kSpTile;
+        const int64_t left = n - T0;
+        const uint32_t len = (uint32_t)(left < kSpTile ? left : kSpTile);
+        const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int v = 0; v < kSpTile / 4 / 64; ++v) ((f32x4 *)tile)[v * 64 + lane] = zero;
+
+        // window [cursor, cursor + 16) of every row: index relative to the tile start
+        // (anything outside the tile, past the row's end or in an unused row reads as
+        // "not in the tile") and value
+        uint32_t rel[GROUPS];
+        float val[GROUPS];
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g) {
+            const uint32_t j = cur[g] + (uint32_t)e;  // no wrap: cursor <= k <= n < 2^32 - 16 (checked on the host)
+            const uint32_t at = j < k ? j : k_last;
+            rel[g] = row_idx[g][at];
+            val[g] = row_val[g][at];
+        }
+        bool full_window = false;  // a row whose 16th entry is in the tile may have more there
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g) {
+            const uint32_t j = cur[g] + (uint32_t)e;
+            const uint32_t r = rel[g] - (uint32_t)T0;  // wraps to a huge value below T0
+            rel[g] = (row_live[g] && j < k) ? r : 0xffffffffu;
+            full_window |= e == 15 && rel[g] < len;
+        }
+        if (__ballot(full_window) == 0ull) {
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) {
+                const bool in = rel[g] < len;
+                const uint64_t m = __ballot(in);
+                cur[g] += (uint32_t)__popcll((m >> (16 * q)) & 0xffffull);  // in-tile entries of this lane's row
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {  // one add instruction per row, rows in order
+                    if (q == r && in) lds_add(&tile[rel[g]], val[g]);
+                }
+            }
+        } else {
+            // plain loop: row after row, 64 entries at a time, until the row leaves the tile
+            for (int w = 0; w < N; ++w) {
+                const uint32_t base = (uint32_t)__shfl((int)cur[w >> 2], (w & 3) * 16, 64);
+                uint32_t total = 0u, cnt = 64u;
+                while (cnt == 64u) {
+                    const int64_t j = (int64_t)base + total + lane;
+                    uint32_t r = 0xffffffffu;
+                    if (j < (int64_t)k) r = idx[(int64_t)w * stride + j] - (uint32_t)T0;
+                    const bool in = r < len;
+                    cnt = (uint32_t)__popcll(__ballot(in));
+                    if (in) lds_add(&tile[r], vals[(int64_t)w * stride + j]);
+                    total += cnt;
+                }
+#pragma unroll
+                for (int g = 0; g < GROUPS; ++g)
+                    if (4 * g + q == w) cur[g] += total;
+            }
+        }
+
+        // mean and write-out (the wave's own LDS operations above are complete, in order,
+        // before its reads below)
+        float *o = out + T0;
+        if (len == (uint32_t)kSpTile) {
+#pragma unroll
+            for (int v = 0; v < kSpTile / 4 / 64; ++v) {
+                f32x4 x = ((const f32x4 *)tile)[v * 64 + lane];
+                if (N > 1) {
+                    x.x = pow2 ? x.x * inv_n : __fdiv_rn(x.x, n_f);
+                    x.y = pow2 ? x.y * inv_n : __fdiv_rn(x.y, n_f);
+                    x.z = pow2 ? x.z * inv_n : __fdiv_rn(x.z, n_f);
+                    x.w = pow2 ? x.w * inv_n : __fdiv_rn(x.w, n_f);
+                }
+                __builtin_nontemporal_store(x, (f32x4 *)o + v * 64 + lane);
+            }
+        } else {  // the arena's last, short tile
+            for (uint32_t i = lane; i < len; i += 64) {
+                float x = tile[i];
+                if (N > 1) x = pow2 ? x * inv_n : __fdiv_rn(x, n_f);
+                o[i] = x;
+            }
+        }
+    }
+}
+
 covap_status_t check(const char *what)
 {
     const hipError_t e = hipGetLastError();
@@ -266,5 +422,44 @@ covap_status_t sparse_decompress(const void *vals, const uint32_t *idx, int32_t 
     }
     return check("sparse_decompress");
 }
+
+covap_status_t sparse_decompress_sorted(const void *vals, const uint32_t *idx, int32_t n_workers,
+                                        int64_t k, int64_t stride_elems, int64_t n, void *dense_out,
+                                        void *stream)
+{
+    if (n_workers > kSpRows || k == 0)  // the one-pass kernel keeps one cursor per lane and wants k >= 1
+        return sparse_decompress(vals, idx, n_workers, k, stride_elems, n, dense_out, stream);
+    covap::clear_error();
+    if (n < 0 || k < 0 || k > n || n_workers < 1 || stride_elems < k || n >= ((int64_t)1 << 32) - 16)
+        return fail(COVAP_EINVAL,
+                    "sparse_decompress_sorted: need 0 <= k <= n < 2^32 - 16, n_workers >= 1, stride >= k");
+    if (n == 0) return COVAP_OK;
+    if (!dense_out || !al16(dense_out) || (k > 0 && (!vals || !idx)))
+        return fail(COVAP_EINVAL, "sparse_decompress_sorted: null or misaligned device pointer");
+    if (((uintptr_t)vals & 3u) || ((uintptr_t)idx & 3u))
+        return fail(COVAP_EINVAL, "sparse_decompress_sorted: misaligned device pointer");
+    const int64_t ntiles = (n + kSpTile - 1) / kSpTile;
+    // Five workgroups per CU, all resident at once, each with one long run of tiles: the
+    // binary search at the start of a run costs about four tiles' worth of time, and a
+    // second, partly filled round of workgroups costs more than lower occupancy does
+    // (measured at 86 k tiles: 408 us this way, 495..525 us with 2..16 tiles per run).
+    int64_t tiles_per_wg = (ntiles + 1279) / 1280;
+    if (tiles_per_wg < 1) tiles_per_wg = 1;
+    const uint32_t grid = (uint32_t)((ntiles + tiles_per_wg - 1) / tiles_per_wg);
+    const int pow2 = (n_workers & (n_workers - 1)) == 0;
+    const float n_f = (float)n_workers;
+    const auto kern = n_workers == 64   ? k_sparse_mean_sorted<64, true>
+                      : n_workers > 32  ? k_sparse_mean_sorted<64, false>
+                      : n_workers == 32 ? k_sparse_mean_sorted<32, true>
+                      : n_workers > 16  ? k_sparse_mean_sorted<32, false>
+                      : n_workers == 16 ? k_sparse_mean_sorted<16, true>
+                      : n_workers > 8   ? k_sparse_mean_sorted<16, false>
+                      : n_workers == 8  ? k_sparse_mean_sorted<8, true>
+                                        : k_sparse_mean_sorted<8, false>;
+    kern<<<grid, 64, 0, (hipStream_t)stream>>>((const float *)vals, idx, n_workers, (uint32_t)k, stride_elems, n,
+                                               (float *)dense_out, tiles_per_wg, n_f, 1.0f / n_f, pow2);
+    return check("sparse_decompress_sorted");
+}
+
 
 }  // extern "C"

@@ -104,6 +104,10 @@ def test_randk_and_sparse_mean(B, n):
                                   idx_all[:workers].cpu().numpy().view(np.uint32).copy(), k, n)
         torch.cuda.synchronize()
         same(out.cpu().numpy(), want, f"sparse mean N={workers}")
+        out2 = torch.full((n,), float("nan"), device=DEV)         # rows ascend: the one-pass form applies
+        B.sparse_decompress_sorted(vals_all, idx_all, out2, n_workers=workers)
+        torch.cuda.synchronize()
+        same(out2.cpu().numpy(), want, f"sorted sparse mean N={workers}")
 
 
 def test_topk_payloads_round_trip_through_sparse_mean(B):
@@ -124,6 +128,44 @@ def test_topk_payloads_round_trip_through_sparse_mean(B):
     B.sparse_decompress(vals, idx, out)
     torch.cuda.synchronize()
     same(idx.cpu().numpy().view(np.uint32), ic, "idx")
+    same(out.cpu().numpy(), oracle.sparse_mean(vc, ic, k, n), "dense mean")
+    out.fill_(float("nan"))
+    B.sparse_decompress_sorted(vals, idx, out)
+    torch.cuda.synchronize()
+    same(out.cpu().numpy(), oracle.sparse_mean(vc, ic, k, n), "dense mean, one pass")
+
+
+@pytest.mark.parametrize("n,k,N,kind", [
+    (100_003, 3_000, 64, "uniform"),        # every lane has a row; N = 2^6 takes the scaling path
+    (100_003, 3_000, 65, "uniform"),        # more rows than lanes: handed to the per-worker form
+    (70_001, 5_000, 5, "clustered"),        # hundreds of entries of one row in one tile
+    (8_192 * 3, 8_192 * 3, 3, "uniform"),   # k = n: every element of every row
+    (20_000, 0, 4, "uniform"),              # empty payloads
+    (5, 2, 7, "uniform"),
+    (300_007, 2_000, 32, "subnormal"),      # sums that are subnormal or cancel to zero
+    (300_007, 2_000, 16, "same_support"),   # every row hits the same elements: the order of the adds matters
+])
+def test_sorted_sparse_mean_shapes(B, n, k, N, kind):
+    rng = np.random.default_rng(n + k + N)
+    ic = np.zeros((N, max(k, 1)), np.uint32)
+    for w in range(N):
+        if kind == "clustered":                                  # all of the row inside two short ranges
+            pool = np.concatenate([np.arange(9_000, 12_000), np.arange(60_000, 63_000)])
+            ic[w, :k] = np.sort(rng.choice(pool, k, replace=False))
+        elif kind == "same_support" and w > 0:
+            ic[w] = ic[0]
+        elif k:
+            ic[w, :k] = np.sort(rng.choice(n if kind != "subnormal" else 4_000, k, replace=False))
+    vc = rng.standard_normal((N, max(k, 1))).astype(np.float32)
+    if kind == "subnormal":
+        vc = (vc * np.float32(1e-38)).astype(np.float32)         # partial sums cross the subnormal range
+    if kind == "same_support":
+        vc = (vc * (10.0 ** rng.integers(-3, 4, vc.shape))).astype(np.float32)   # rounding depends on the order
+    vals = torch.from_numpy(vc).to(DEV)
+    idx = torch.from_numpy(ic.view(np.int32)).to(DEV)
+    out = torch.full((n,), float("nan"), device=DEV)
+    B.sparse_decompress_sorted(vals, idx, out, k=k, n_workers=N)
+    torch.cuda.synchronize()
     same(out.cpu().numpy(), oracle.sparse_mean(vc, ic, k, n), "dense mean")
 
 
