@@ -270,7 +270,7 @@ covap_status_t sparse_decompress(const void *vals, const uint32_t *idx, int32_t 
  * its coordinates in ascending order): one pass over dense_out instead of one
  * launch per worker.  Same arguments, same result bits.  Rows that are not
  * ascending give an unspecified result (but no access outside the buffers).
- * More than 64 workers are handed to sparse_decompress. */
+ * More than 64 workers are handed to sparse_decompress.  n < 2^32 - 16. */
 covap_status_t sparse_decompress_sorted(const void *vals, const uint32_t *idx, int32_t n_workers,
                                         int64_t k, int64_t stride_elems, int64_t n, void *dense_out,
                                         void *stream);
