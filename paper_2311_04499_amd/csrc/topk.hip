@@ -3,10 +3,10 @@
 // nearly all of Top-k's compression time).  Exact and deterministic: a sample only
 // decides how much work the exact selection has to do, never what it returns.
 //
-//   sample   A = fma(c, R, G) on 4096 evenly spread 256-element chunks; histogram of
+//   sample   A = fma(c, R, G) on 1024 evenly spread 256-element chunks; histogram of
 //            key bits 30..20 -> a bin b_lo that very probably lies at or below the bin
 //            of the k-th largest key, with only a fraction of a percent of the keys
-//            at or above it                                          (reads 8 MB)
+//            at or above it                                          (reads 2 MB)
 //   pass 1   A = fma(c, R, G); R <- A; every element whose bin is >= b_lo is copied,
 //            in index order, into a 32-entry slot array of its 1024-element tile
 //                                                                (reads 2D, writes D)
@@ -72,7 +72,7 @@ constexpr int kAtomicRows = 3;    // general tail levels 1, 2, 3: one row each, 
 constexpr int kSlotGrid = 64;     // slot passes and the sample: one slice per workgroup, plain stores
 constexpr int kSlotThreads = 1024;
 constexpr int kHistRows = kAtomicRows + 3 * kSlotGrid;  // rows of 2048 counters in the workspace
-constexpr int kSampleChunks = 4096;  // the sample: this many chunks of 64 vectors (256 elements)
+constexpr int kSampleChunks = 1024;  // the sample: this many chunks of 64 vectors (256 elements)
 constexpr int kSampleThreads = 256;
 enum { kAlways = 0, kSlotTail = 1, kGeneralTail = 2 };
 
@@ -661,10 +661,14 @@ __global__ __launch_bounds__(kSlotThreads) void k_topk_slots_hist(const topk_sta
     constexpr int BINS = LEVEL == 3 ? kBins3 : kBins12;
     constexpr int SHIFT = LEVEL == 1 ? 20 : (LEVEL == 2 ? 9 : 0);
     constexpr int HI_SHIFT = LEVEL == 1 ? 31 : (LEVEL == 2 ? 20 : 9);
-    __shared__ uint32_t lds[BINS];
+    // Level 1 sees every entry and nearly all of them fall into a handful of bins just
+    // above b_lo: four copies of the histogram, picked by lane, spread those LDS atomics.
+    constexpr int COPIES = LEVEL == 1 ? 4 : 1;
+    __shared__ uint32_t lds[COPIES * BINS];
     const int tid = threadIdx.x;
-    for (int i = tid; i < BINS; i += kSlotThreads) lds[i] = 0u;
+    for (int i = tid; i < COPIES * BINS; i += kSlotThreads) lds[i] = 0u;
     __syncthreads();
+    uint32_t *mine = lds + (tid & (COPIES - 1)) * BINS;
     const uint32_t want = LEVEL == 1 ? 0u : st->prefix >> HI_SHIFT;  // keys have bit 31 clear
     const int64_t nvs = ntiles * (kSlots / 4);
     const int64_t stride = (int64_t)gridDim.x * kSlotThreads;
@@ -689,12 +693,17 @@ __global__ __launch_bounds__(kSlotThreads) void k_topk_slots_hist(const topk_sta
             for (int j = 0; j < 4; ++j) {
                 const uint32_t key = v[i][j] & kAbs;
                 if (q4 + j < cnt[i] && (key >> HI_SHIFT) == want)
-                    atomicAdd(&lds[(key >> SHIFT) & (BINS - 1)], 1u);
+                    atomicAdd(&mine[(key >> SHIFT) & (BINS - 1)], 1u);
             }
         }
     }
     __syncthreads();
-    for (int i = tid; i < BINS; i += kSlotThreads) hist[blockIdx.x * 2048 + i] = lds[i];
+    for (int i = tid; i < BINS; i += kSlotThreads) {
+        uint32_t sum = 0u;
+#pragma unroll
+        for (int c = 0; c < COPIES; ++c) sum += lds[c * BINS + i];
+        hist[blockIdx.x * 2048 + i] = sum;
+    }
 }
 
 // Per-tile numbers of slot entries above and at the threshold.

@@ -194,11 +194,12 @@ def test_both_tails_are_exercised_and_agree_with_the_oracle(B, kind, want):
 
 
 def test_a_misleading_sample_falls_back_to_the_general_tail(B):
-    """White box: the sample that proposes the lower bound b_lo takes 4096 evenly spread
-    256-element chunks; at n = 4 * 4096 * 256 that is the first quarter of every 1024
-    elements.  Large values only there make the sample overestimate their share four
-    times, the bins >= b_lo then hold fewer than k keys, and the exact general tail must
-    take over (flag bit 1) with the same bits as the oracle."""
+    """White box: the sample that proposes the lower bound b_lo takes 1024 evenly spread
+    256-element chunks; at n = 4 * 4096 * 256 that is the first 256 of every 4096
+    elements.  Large values only in the first quarter of every 1024 elements make the
+    sample overestimate their share four times, the bins >= b_lo then hold fewer than k
+    keys, and the exact general tail must take over (flag bit 1) with the same bits as
+    the oracle."""
     n = 4 * 4096 * 256
     k = n // 100
     rng = np.random.default_rng(5)
