@@ -619,3 +619,31 @@ def test_two_streams_run_independent_plans(B):
             oracle.compress(s_["tab"], s_["K"], t, to_np(G), s_["Rc"], sc)
             assert_same(to_np(send), sc, f"send t={t}")
             assert_same(to_np(s_["R"]), s_["Rc"], f"residual t={t}")
+
+
+# ------------------------------------------------------------------ seeded random shapes
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_layouts_intervals_and_worker_counts(B, seed):
+    """Seeded random cases: tensor lists, shard sizes, intervals, worker counts, element
+    types, both sharding modes and per-bucket calls, a few iterations each, every output
+    against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    n_t = int(rng.integers(1, 7))
+    numel = [int(x) for x in rng.integers(1, 60_000, n_t)]
+    dtype = (torch.float32, torch.bfloat16)[int(rng.integers(0, 2))]
+    epv = 4 if dtype == torch.float32 else 8
+    K = int(rng.integers(1, 9))
+    N = int(rng.integers(1, 6))
+    c = float(rng.choice([1.0, 0.5, 0.3]))
+    per_bucket = bool(rng.integers(0, 2))
+    if rng.integers(0, 2):
+        S = int(rng.choice([1, 2, 8, 31, 256, 1000])) * epv
+        cap = int(rng.choice([S * epv, 40_000, 25 << 20]))
+        wl = workloads.scaled_down(workloads.config(2), numel, S)
+        run_iterations(B, wl, numel, S, K, N, K + 2, dtype=dtype, c=c, per_bucket=per_bucket, cap_bytes=cap)
+    else:
+        cap = int(rng.choice([4, 20_000, 200_000]))
+        wl = workloads.scaled_down(workloads.config(3), numel, 4096)
+        plans = make_median_plans(B, numel, K, dtype=dtype, cap_bytes=cap)
+        run_iterations(B, wl, numel, 0, K, N, K + 2, dtype=dtype, c=c, per_bucket=per_bucket, plans=plans)
