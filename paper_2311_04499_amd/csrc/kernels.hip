@@ -114,7 +114,15 @@ struct ops_bf16 {
         if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
         return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
     }
-    static __device__ __forceinline__ uint32_t pack(float a, float b) { return rne(a) | (rne(b) << 16); }
+    // two values at once with gfx950's own conversion (v_cvt_pk_bf16_f32: round to nearest
+    // even, subnormals kept; the parity tests sweep the fp32 pattern space against rne())
+    static __device__ __forceinline__ uint32_t pack(float a, float b)
+    {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        const f32x2 v = {a, b};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    }
 
     static __device__ __forceinline__ u32x4 ef(u32x4 g, u32x4 r, float c)
     {

@@ -647,3 +647,33 @@ def test_random_layouts_intervals_and_worker_counts(B, seed):
         wl = workloads.scaled_down(workloads.config(3), numel, 4096)
         plans = make_median_plans(B, numel, K, dtype=dtype, cap_bytes=cap)
         run_iterations(B, wl, numel, 0, K, N, K + 2, dtype=dtype, c=c, per_bucket=per_bucket, plans=plans)
+
+
+def test_bf16_rounding_over_the_float32_pattern_space(B):
+    """Every upper half (sign, exponent, top mantissa bits: 65,536 values) crossed with 64
+    lower halves (ties, their neighbours, extremes, random): 4.2 M fp32 patterns, incl.
+    subnormals, Inf and NaN, pushed through the kernel's fp32 -> bf16 rounding (the
+    fp32-residual mode with G = 0, c = 1 sends bf16(R)) and compared with the oracle."""
+    rng = np.random.default_rng(9)
+    lows = np.unique(np.r_[[0x0000, 0x0001, 0x7fff, 0x8000, 0x8001, 0xffff, 0x4000, 0xc000],
+                           rng.integers(0, 1 << 16, 56)]).astype(np.uint32)
+    pats = ((np.arange(1 << 16, dtype=np.uint32)[:, None] << 16) | lows[None, :]).ravel()
+    n = pats.size // 8 * 8
+    pats = pats[:n]
+    Rn = pats.view(np.float32).copy()
+    S = 1 << 16
+    plan = B.covap_plan([n], S, 1, dtype=B.COVAP_BF16_RES32)
+    tab = oracle.plan_fixed([n], S, 1 << 40)
+    G = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    R = torch.from_numpy(Rn).to(DEV)
+    send = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    B.covap_compress(plan, 0, G, R, send)
+    torch.cuda.synchronize()
+    Rc = Rn.copy()
+    sc = np.zeros(n, np.uint16)
+    oracle.compress(tab, 1, 0, np.zeros(n, np.uint16), Rc, sc)
+    got = to_np(send)
+    nan = np.isnan(Rn)
+    assert np.array_equal(got[~nan], sc[~nan])                       # every finite and infinite pattern, bit for bit
+    assert np.all((got[nan] & 0x7f80) == 0x7f80) and np.all((got[nan] & 0x007f) != 0)   # NaN stays NaN
+    assert_same(to_np(R)[~nan], Rc[~nan], "residual")
