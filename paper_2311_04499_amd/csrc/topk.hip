@@ -15,9 +15,14 @@
 //   ties to keep; per-tile counts; 3-phase exclusive scan; ordered write of
 //   (value, index), R <- +0 there.
 //
+// A tile with more than 32 such elements (clustered data: a layer with a larger
+// gradient scale, a few hot embedding rows) gets no slots: it is put on a list, and
+// every kernel of the slot tail then also walks that list and reads those tiles
+// from R, one wave per tile.
+//
 // If the bins >= b_lo turn out to hold fewer than k keys (the sample misled), or if
-// any tile has more than 32 such elements (heavily clustered or tied data, large
-// k), a flag is raised on the device and the general path runs instead: three full
+// the list grows beyond 1/32 of the tiles (data full of ties, a very large k), a
+// flag is raised on the device and the general path runs instead: three full
 // histogram passes, a counting pass and a compaction pass over R (5 more reads of
 // D).  The host launches both tails; every kernel of the tail that is not taken
 // returns at once, so no host round trip is needed.  Both tails give the same bits.
@@ -54,14 +59,15 @@ struct topk_state {
     uint32_t k_rem;      // how many are still to be taken from the current bin
     uint32_t threshold;  // T, valid after level 3
     uint32_t ties;       // number of keys == T to keep, valid after level 3
-    uint32_t overflow;   // != 0: the general tail runs (bit 0: a tile did not fit its slots,
-                         // bit 1: the bins >= b_lo hold fewer than k keys)
+    uint32_t overflow;   // != 0: the general tail runs (bit 0: too many tiles did not fit their
+                         // slots, bit 1: the bins >= b_lo hold fewer than k keys)
     uint32_t b_lo;       // pass 1 looks only at keys whose level-1 bin is >= b_lo
     uint32_t k;          // the k of this call
-    uint32_t pad;
+    uint32_t n_crowded;  // tiles that did not fit their slots; the slot tail reads those from R
 };
 
 constexpr int kSlots = 32;  // slot entries per 1024-element tile
+constexpr uint32_t kCrowded = 0xffffffffu;  // slot count of a tile that did not fit and is listed instead
 // A histogram is either one row that workgroups add their non-empty LDS bins to,
 // or several partial copies ("slices"), one per workgroup, that the pick kernel
 // adds up.  Global atomics run at about 1.5 G/s on this chip whatever the address
@@ -94,6 +100,7 @@ struct topk_ws {
     uint32_t *cnt_eq;     // [ntiles]
     uint32_t *chunk_gt;   // [nchunks] -> exclusive prefix
     uint32_t *chunk_eq;   // [nchunks]
+    uint32_t *crowded;    // [ntiles]  list of the tiles that did not fit their slots (any order)
 };
 
 __host__ __device__ inline int64_t div_up(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -117,6 +124,7 @@ size_t ws_layout(int64_t n, void *base, topk_ws *out)
     const size_t o_eq = take((size_t)ntiles * 4);
     const size_t o_cgt = take((size_t)nchunks * 4);
     const size_t o_ceq = take((size_t)nchunks * 4);
+    const size_t o_crowded = take((size_t)ntiles * 4);
     if (out) {
         char *b = (char *)base;
         out->state = (topk_state *)(b + o_state);
@@ -128,6 +136,7 @@ size_t ws_layout(int64_t n, void *base, topk_ws *out)
         out->cnt_eq = (uint32_t *)(b + o_eq);
         out->chunk_gt = (uint32_t *)(b + o_cgt);
         out->chunk_eq = (uint32_t *)(b + o_ceq);
+        out->crowded = (uint32_t *)(b + o_crowded);
     }
     return off;
 }
@@ -176,6 +185,7 @@ __global__ __launch_bounds__(kSampleThreads) void k_topk_sample(const float *__r
         st->overflow = 0u;
         st->b_lo = 0u;
         st->k = k;
+        st->n_crowded = 0u;
     }
     for (int i = tid; i < kBins12; i += kSampleThreads) lds[i] = 0u;
     __syncthreads();
@@ -227,13 +237,16 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 // bin is >= b_lo into the slots of its tile.  One workgroup of WAVES waves per
 // 1024-element tile, in four rounds of 64 lanes x 4 elements (ascending index
 // order); a wave takes 4 / WAVES consecutive rounds.  Ranks inside a round come from
-// the lane masks of the four components, ranks across waves through LDS.
+// the lane masks of the four components, ranks across waves through LDS.  A tile
+// with more than 32 such elements (clustered data: a layer with a larger gradient
+// scale, a few hot embedding rows) is put on a list instead.
 template <int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void k_topk_pass1(const float *__restrict__ G, float *R,
                                                            int64_t n, float c, topk_state *st,
                                                            uint32_t *__restrict__ slot_cnt,
                                                            uint32_t *__restrict__ slot_idx,
-                                                           uint32_t *__restrict__ slot_bits)
+                                                           uint32_t *__restrict__ slot_bits,
+                                                           uint32_t *__restrict__ crowded)
 {
     constexpr int ROUNDS = 4 / WAVES;
     __shared__ uint32_t wave_total[WAVES];
@@ -306,9 +319,12 @@ __global__ __launch_bounds__(64 * WAVES) void k_topk_pass1(const float *__restri
         }
     }
     if (threadIdx.x == 0) {
-        slot_cnt[tile] = total < (uint32_t)kSlots ? total : (uint32_t)kSlots;
-        if (total > (uint32_t)kSlots && (*(volatile uint32_t *)&st->overflow & 1u) == 0u)
-            atomicOr(&st->overflow, 1u);
+        if (total > (uint32_t)kSlots) {  // the tile goes on the list; the tail reads it from R instead
+            crowded[atomicAdd(&st->n_crowded, 1u)] = (uint32_t)tile;  // at most once per tile: never past ntiles
+            slot_cnt[tile] = kCrowded;
+        } else {
+            slot_cnt[tile] = total;
+        }
     }
 }
 
@@ -362,8 +378,9 @@ __global__ __launch_bounds__(kHistThreads) void k_topk_hist(const float *__restr
 //   LEVEL 0     on the sample: wanted = `target`; the digit becomes b_lo (0 if the
 //               sample is too small to tell)
 //   LEVEL 1     wanted = k; the digit opens the prefix.  On the slots (GATE kSlotTail)
-//               a total below k means that b_lo was too high: the general tail is
-//               switched on.
+//               a total below k means that b_lo was too high, and a crowded list
+//               longer than `target` that too many tiles missed their slots: either
+//               switches the general tail on.
 //   LEVEL 2, 3  wanted = k_rem; the digit extends the prefix; level 3 fixes T.
 constexpr int kPickThreads = 1024;  // all of them add up the slices; the first 256 then scan
 
@@ -416,7 +433,10 @@ __global__ __launch_bounds__(kPickThreads) void k_topk_pick(topk_state *st,
     }
     if (!scanner) return;  // no barrier follows
     const uint32_t incl = part[tid], excl = incl - mine;
-    if (LEVEL == 1 && GATE == kSlotTail && tid == 255 && incl < k_rem) atomicOr(&st->overflow, 2u);
+    if (LEVEL == 1 && GATE == kSlotTail && tid == 255) {
+        if (incl < k_rem) atomicOr(&st->overflow, 2u);
+        if (st->n_crowded > target) atomicOr(&st->overflow, 1u);  // target: the longest list the slot tail takes
+    }
     if (k_rem > 0u && excl < k_rem && k_rem <= incl) {  // at most one thread
         uint32_t above = excl;
 #pragma unroll
@@ -462,6 +482,33 @@ __device__ __forceinline__ u32x4 load_keys(const float *R, int64_t n, int64_t e,
     return k;
 }
 
+// Numbers of keys above and at the threshold in one 1024-element tile of R (one wave).
+__device__ __forceinline__ void count_tile(const float *__restrict__ R, int64_t n, int64_t tile, uint32_t T,
+                                           int lane, uint32_t *__restrict__ cnt_gt,
+                                           uint32_t *__restrict__ cnt_eq)
+{
+    const int64_t base = tile * kTile;
+    uint32_t gt = 0u, eq = 0u;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
+        uint32_t valid;
+        const u32x4 k = load_keys(R, n, e, &valid);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool ok = (valid >> j) & 1u;
+            gt += (ok && k[j] > T) ? 1u : 0u;
+            eq += (ok && k[j] == T) ? 1u : 0u;
+        }
+    }
+    gt = wave_sum(gt);
+    eq = wave_sum(eq);
+    if (lane == 0) {
+        cnt_gt[tile] = gt;
+        cnt_eq[tile] = eq;
+    }
+}
+
 __global__ __launch_bounds__(64) void k_topk_count(const float *__restrict__ R, int64_t n, int64_t ntiles,
                                                    const topk_state *__restrict__ st,
                                                    uint32_t *__restrict__ cnt_gt,
@@ -469,29 +516,8 @@ __global__ __launch_bounds__(64) void k_topk_count(const float *__restrict__ R, 
 {
     if (skip_tail(st, kGeneralTail)) return;
     const uint32_t T = st->threshold;
-    const int lane = threadIdx.x;
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t base = tile * kTile;
-        uint32_t gt = 0u, eq = 0u;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
-            uint32_t valid;
-            const u32x4 k = load_keys(R, n, e, &valid);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const bool ok = (valid >> j) & 1u;
-                gt += (ok && k[j] > T) ? 1u : 0u;
-                eq += (ok && k[j] == T) ? 1u : 0u;
-            }
-        }
-        gt = wave_sum(gt);
-        eq = wave_sum(eq);
-        if (lane == 0) {
-            cnt_gt[tile] = gt;
-            cnt_eq[tile] = eq;
-        }
-    }
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x)
+        count_tile(R, n, tile, T, threadIdx.x, cnt_gt, cnt_eq);
 }
 
 // Phase A: each workgroup turns kScanChunk tile counts into chunk-local
@@ -576,8 +602,66 @@ __global__ __launch_bounds__(256) void k_topk_scan_b(uint32_t *chunk_gt, uint32_
     }
 }
 
-// Pass 5: one wave per tile.  Element order inside a tile is (round u, lane,
-// component), which is ascending index; ranks come from wavefront prefix sums.
+// Ordered write of one tile's kept elements, read from R (one wave).  Element order
+// inside a tile is (round u, lane, component), which is ascending index; ranks come
+// from wavefront prefix sums.
+__device__ __forceinline__ void write_tile(float *R, int64_t n, int64_t tile, uint32_t T, uint32_t ties,
+                                           int lane, const uint32_t *__restrict__ cnt_gt,
+                                           const uint32_t *__restrict__ cnt_eq,
+                                           const uint32_t *__restrict__ chunk_gt,
+                                           const uint32_t *__restrict__ chunk_eq,
+                                           float *__restrict__ vals, uint32_t *__restrict__ idx,
+                                           uint32_t kmax)
+{
+    const int64_t chunk = tile / kScanChunk;
+    const uint32_t gt_before = chunk_gt[chunk] + cnt_gt[tile];
+    uint32_t eq_before = chunk_eq[chunk] + cnt_eq[tile];
+    uint32_t out_pos = gt_before + (eq_before < ties ? eq_before : ties);
+    const int64_t base = tile * kTile;
+#pragma unroll 1
+    for (int u = 0; u < 4; ++u) {
+        const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
+        uint32_t valid;
+        const u32x4 k = load_keys(R, n, e, &valid);
+        uint32_t gtm = 0u, eqm = 0u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool ok = (valid >> j) & 1u;
+            gtm |= (ok && k[j] > T) ? (1u << j) : 0u;
+            eqm |= (ok && k[j] == T) ? (1u << j) : 0u;
+        }
+        if (__ballot((gtm | eqm) != 0u) == 0ull) continue;  // nothing to keep in this round
+        const uint32_t eq_cnt = __popc(eqm);
+        const uint32_t eq_incl = wave_incl_scan(eq_cnt);
+        const uint32_t eq_total = __shfl(eq_incl, 63, 64);
+        uint32_t eq_rank = eq_before + eq_incl - eq_cnt;  // rank of this lane's first tie
+        uint32_t selm = gtm;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if ((eqm >> j) & 1u) {
+                if (eq_rank < ties) selm |= 1u << j;
+                ++eq_rank;
+            }
+        }
+        const uint32_t sel_cnt = __popc(selm);
+        const uint32_t sel_incl = wave_incl_scan(sel_cnt);
+        const uint32_t sel_total = __shfl(sel_incl, 63, 64);
+        uint32_t pos = out_pos + sel_incl - sel_cnt;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (((selm >> j) & 1u) && pos < kmax) {  // pos < kmax always holds; the test keeps a corrupted workspace harmless
+                const int64_t i = e + j;
+                vals[pos] = R[i];
+                idx[pos] = (uint32_t)i;
+                R[i] = 0.0f;
+                ++pos;
+            }
+        }
+        eq_before += eq_total;
+        out_pos += sel_total;
+    }
+}
+
 __global__ __launch_bounds__(64) void k_topk_write(float *R, int64_t n,
                                                    const topk_state *__restrict__ st,
                                                    const uint32_t *__restrict__ cnt_gt,
@@ -589,63 +673,23 @@ __global__ __launch_bounds__(64) void k_topk_write(float *R, int64_t n,
 {
     if (skip_tail(st, kGeneralTail)) return;
     const uint32_t T = st->threshold, ties = st->ties;
-    const int lane = threadIdx.x;
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t chunk = tile / kScanChunk;
-        const uint32_t gt_before = chunk_gt[chunk] + cnt_gt[tile];
-        uint32_t eq_before = chunk_eq[chunk] + cnt_eq[tile];
-        uint32_t out_pos = gt_before + (eq_before < ties ? eq_before : ties);
-        const int64_t base = tile * kTile;
-#pragma unroll 1
-        for (int u = 0; u < 4; ++u) {
-            const int64_t e = base + (int64_t)(u * 64 + lane) * 4;
-            uint32_t valid;
-            const u32x4 k = load_keys(R, n, e, &valid);
-            uint32_t gtm = 0u, eqm = 0u;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const bool ok = (valid >> j) & 1u;
-                gtm |= (ok && k[j] > T) ? (1u << j) : 0u;
-                eqm |= (ok && k[j] == T) ? (1u << j) : 0u;
-            }
-            if (__ballot((gtm | eqm) != 0u) == 0ull) continue;  // nothing to keep in this round
-            const uint32_t eq_cnt = __popc(eqm);
-            const uint32_t eq_incl = wave_incl_scan(eq_cnt);
-            const uint32_t eq_total = __shfl(eq_incl, 63, 64);
-            uint32_t eq_rank = eq_before + eq_incl - eq_cnt;  // rank of this lane's first tie
-            uint32_t selm = gtm;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if ((eqm >> j) & 1u) {
-                    if (eq_rank < ties) selm |= 1u << j;
-                    ++eq_rank;
-                }
-            }
-            const uint32_t sel_cnt = __popc(selm);
-            const uint32_t sel_incl = wave_incl_scan(sel_cnt);
-            const uint32_t sel_total = __shfl(sel_incl, 63, 64);
-            uint32_t pos = out_pos + sel_incl - sel_cnt;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (((selm >> j) & 1u) && pos < kmax) {  // pos < kmax always holds (see above)
-                    const int64_t i = e + j;
-                    vals[pos] = R[i];
-                    idx[pos] = (uint32_t)i;
-                    R[i] = 0.0f;
-                    ++pos;
-                }
-            }
-            eq_before += eq_total;
-            out_pos += sel_total;
-        }
-    }
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x)
+        write_tile(R, n, tile, T, ties, threadIdx.x, cnt_gt, cnt_eq, chunk_gt, chunk_eq, vals, idx, kmax);
 }
 
 // ---- slot tail -------------------------------------------------------------------------
 
 // A tile's 32 slot entries are eight 16-byte vectors.  The slot-tail kernels give one
 // thread to each such vector, so that a wave reads 1 KB of slots at a time, and look
-// only at the entries below the tile's count.
+// only at the entries below the tile's count.  The tiles on the crowded list have no
+// slots: every slot-tail kernel then walks the list, one wave per tile, and reads those
+// tiles from R.  When the list grows beyond a small share of the tiles (data full of
+// ties, a very large k) the general tail takes over instead.
+__host__ __device__ inline uint32_t crowded_limit(int64_t ntiles)
+{
+    const int64_t share = ntiles / 32;
+    return (uint32_t)(share > 1024 ? share : 1024);
+}
 
 // Histogram of one digit over the slot entries (level 1: all of them; levels 2, 3:
 // those that match the prefix): a few large workgroups, each with an LDS histogram
@@ -655,6 +699,8 @@ __global__ __launch_bounds__(kSlotThreads) void k_topk_slots_hist(const topk_sta
                                                                   const uint32_t *__restrict__ slot_cnt,
                                                                   const uint32_t *__restrict__ slot_bits,
                                                                   int64_t ntiles,
+                                                                  const uint32_t *__restrict__ crowded,
+                                                                  const float *__restrict__ R, int64_t n,
                                                                   uint32_t *__restrict__ hist)
 {
     if (skip_tail(st, kSlotTail)) return;
@@ -689,11 +735,34 @@ __global__ __launch_bounds__(kSlotThreads) void k_topk_slots_hist(const topk_sta
 #pragma unroll
         for (int i = 0; i < U; ++i) {
             const uint32_t q4 = (uint32_t)((w0 + i * stride) & 7) * 4u;
+            const uint32_t c = cnt[i] == kCrowded ? 0u : cnt[i];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const uint32_t key = v[i][j] & kAbs;
-                if (q4 + j < cnt[i] && (key >> HI_SHIFT) == want)
+                if (q4 + j < c && (key >> HI_SHIFT) == want)
                     atomicAdd(&mine[(key >> SHIFT) & (BINS - 1)], 1u);
+            }
+        }
+    }
+    // the crowded tiles, from R: one wave per tile.  Level 1 counts, like the slots do,
+    // only the keys at or above b_lo.
+    const uint32_t n_crowded = st->n_crowded;
+    if (n_crowded <= crowded_limit(ntiles)) {
+        const uint32_t b_lo = st->b_lo;
+        const int lane = tid & 63;
+        constexpr int kWaves = kSlotThreads / 64;
+        for (uint32_t i = blockIdx.x * kWaves + (tid >> 6); i < n_crowded; i += gridDim.x * kWaves) {
+            const int64_t base = (int64_t)crowded[i] * kTile;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                uint32_t valid;
+                const u32x4 key = load_keys(R, n, base + (int64_t)(u * 64 + lane) * 4, &valid);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool ok = ((valid >> j) & 1u) && (key[j] >> HI_SHIFT) == want &&
+                                    (LEVEL != 1 || (key[j] >> 20) >= b_lo);
+                    if (ok) atomicAdd(&mine[(key[j] >> SHIFT) & (BINS - 1)], 1u);
+                }
             }
         }
     }
@@ -710,7 +779,10 @@ __global__ __launch_bounds__(kSlotThreads) void k_topk_slots_hist(const topk_sta
 __global__ __launch_bounds__(256) void k_topk_slots_count(const topk_state *__restrict__ st,
                                                           const uint32_t *__restrict__ slot_cnt,
                                                           const uint32_t *__restrict__ slot_bits,
-                                                          int64_t ntiles, uint32_t *__restrict__ cnt_gt,
+                                                          int64_t ntiles,
+                                                          const uint32_t *__restrict__ crowded,
+                                                          const float *__restrict__ R, int64_t n,
+                                                          uint32_t *__restrict__ cnt_gt,
                                                           uint32_t *__restrict__ cnt_eq)
 {
     if (skip_tail(st, kSlotTail)) return;
@@ -718,9 +790,11 @@ __global__ __launch_bounds__(256) void k_topk_slots_count(const topk_state *__re
     const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const uint32_t T = st->threshold;
     uint32_t gt = 0u, eq = 0u;
+    bool listed = false;
     if (w < nvs) {
         const uint32_t cnt = slot_cnt[w >> 3], q4 = (uint32_t)(w & 7) * 4u;
-        if (q4 < cnt) {
+        listed = cnt == kCrowded;
+        if (!listed && q4 < cnt) {
             const u32x4 v = ((const u32x4 *)slot_bits)[w];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -735,10 +809,15 @@ __global__ __launch_bounds__(256) void k_topk_slots_count(const topk_state *__re
         gt += __shfl_xor(gt, d, 64);
         eq += __shfl_xor(eq, d, 64);
     }
-    if (w < nvs && (w & 7) == 0) {
+    if (w < nvs && (w & 7) == 0 && !listed) {
         cnt_gt[w >> 3] = gt;
         cnt_eq[w >> 3] = eq;
     }
+    // the crowded tiles, from R: one wave per tile (this kernel's waves walk the list)
+    const uint32_t n_crowded = st->n_crowded;
+    const uint32_t wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = gridDim.x * 4;
+    for (uint32_t i = wave; i < n_crowded; i += n_waves)
+        count_tile(R, n, crowded[i], T, threadIdx.x & 63, cnt_gt, cnt_eq);
 }
 
 // Exclusive prefix sum over each group of eight neighbouring lanes.
@@ -756,10 +835,12 @@ __device__ __forceinline__ uint32_t group8_excl_scan(uint32_t x)
 
 // Ordered write of the kept slot entries; entries of a tile are in ascending index
 // order across its eight lanes.
-__global__ __launch_bounds__(256) void k_topk_slots_write(float *R, const topk_state *__restrict__ st,
+__global__ __launch_bounds__(256) void k_topk_slots_write(float *R, int64_t n,
+                                                          const topk_state *__restrict__ st,
                                                           const uint32_t *__restrict__ slot_cnt,
                                                           const uint32_t *__restrict__ slot_idx,
                                                           const uint32_t *__restrict__ slot_bits,
+                                                          const uint32_t *__restrict__ crowded,
                                                           const uint32_t *__restrict__ cnt_gt,
                                                           const uint32_t *__restrict__ cnt_eq,
                                                           const uint32_t *__restrict__ chunk_gt,
@@ -776,7 +857,7 @@ __global__ __launch_bounds__(256) void k_topk_slots_write(float *R, const topk_s
     if (w < nvs) {
         const int64_t tile = w >> 3;
         const uint32_t cnt = slot_cnt[tile], q4 = (uint32_t)(w & 7) * 4u;
-        if (q4 < cnt) {
+        if (cnt != kCrowded && q4 < cnt) {
             v = ((const u32x4 *)slot_bits)[w];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -800,17 +881,25 @@ __global__ __launch_bounds__(256) void k_topk_slots_write(float *R, const topk_s
         }
     }
     uint32_t pos = tile_pos + group8_excl_scan(__popc(selm));
-    if (selm == 0u) return;  // no shuffle follows
-    const u32x4 at = ((const u32x4 *)slot_idx)[w];
+    if (selm != 0u) {
+        const u32x4 at = ((const u32x4 *)slot_idx)[w];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        if (((selm >> j) & 1u) && pos < kmax) {  // pos < kmax always holds; the test keeps a corrupted workspace harmless
-            vals[pos] = __uint_as_float(v[j]);
-            idx[pos] = at[j];
-            R[at[j]] = 0.0f;
-            ++pos;
+        for (int j = 0; j < 4; ++j) {
+            if (((selm >> j) & 1u) && pos < kmax) {  // pos < kmax always holds; the test keeps a corrupted workspace harmless
+                vals[pos] = __uint_as_float(v[j]);
+                idx[pos] = at[j];
+                R[at[j]] = 0.0f;
+                ++pos;
+            }
         }
     }
+    // the crowded tiles, from R: one wave per tile (this kernel's waves walk the list;
+    // whole waves arrive here together, the branch above has closed)
+    const uint32_t n_crowded = st->n_crowded;
+    const uint32_t wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = gridDim.x * 4;
+    for (uint32_t i = wave; i < n_crowded; i += n_waves)
+        write_tile(R, n, crowded[i], T, ties, threadIdx.x & 63, cnt_gt, cnt_eq, chunk_gt, chunk_eq, vals, idx,
+                   kmax);
 }
 
 covap_status_t check(const char *what)
@@ -880,16 +969,20 @@ covap_status_t topk_compress(const void *grad, void *residual, int64_t n, int64_
     const covap::tuning &tn = covap::tune();
     const auto pass1 = tn.topk_pass1_waves == 4 ? k_topk_pass1<4> : (tn.topk_pass1_waves == 2 ? k_topk_pass1<2> : k_topk_pass1<1>);
     pass1<<<(uint32_t)ntiles, 64 * tn.topk_pass1_waves, (size_t)tn.topk_pass1_lds_pad, st>>>(
-        G, R, n, ef_coeff, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits);
+        G, R, n, ef_coeff, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.crowded);
     if (k > 0) {
         // slot tail (every kernel returns at once when the general tail is switched on)
-        k_topk_slots_hist<1><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, h1s);
-        k_topk_pick<1, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h1s, kSlotGrid, 0u);
-        k_topk_slots_hist<2><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, h2s);
+        k_topk_slots_hist<1><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles,
+                                                                 ws.crowded, R, n, h1s);
+        k_topk_pick<1, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h1s, kSlotGrid, crowded_limit(ntiles));
+        k_topk_slots_hist<2><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles,
+                                                                 ws.crowded, R, n, h2s);
         k_topk_pick<2, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h2s, kSlotGrid, 0u);
-        k_topk_slots_hist<3><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, h3s);
+        k_topk_slots_hist<3><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles,
+                                                                 ws.crowded, R, n, h3s);
         k_topk_pick<3, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h3s, kSlotGrid, 0u);
-        k_topk_slots_count<<<slot_vec_grid, 256, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.cnt_gt, ws.cnt_eq);
+        k_topk_slots_count<<<slot_vec_grid, 256, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.crowded, R, n,
+                                                          ws.cnt_gt, ws.cnt_eq);
         // general tail (returns at once otherwise)
         k_topk_hist<1><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(R, n, ws.state, h1g);
         k_topk_pick<1, kGeneralTail><<<1, kPickThreads, 0, st>>>(ws.state, h1g, 1, 0u);
@@ -901,9 +994,9 @@ covap_status_t topk_compress(const void *grad, void *residual, int64_t n, int64_
         // common: exclusive scan of the per-tile counts, then the ordered write
         k_topk_scan_a<<<(uint32_t)nchunks, 256, 0, st>>>(ws.cnt_gt, ws.cnt_eq, ntiles, ws.chunk_gt, ws.chunk_eq);
         k_topk_scan_b<<<1, 256, 0, st>>>(ws.chunk_gt, ws.chunk_eq, nchunks);
-        k_topk_slots_write<<<slot_vec_grid, 256, 0, st>>>(R, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.cnt_gt,
-                                                          ws.cnt_eq, ws.chunk_gt, ws.chunk_eq, ntiles,
-                                                          (float *)out_vals, out_idx, (uint32_t)k);
+        k_topk_slots_write<<<slot_vec_grid, 256, 0, st>>>(R, n, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits,
+                                                          ws.crowded, ws.cnt_gt, ws.cnt_eq, ws.chunk_gt, ws.chunk_eq,
+                                                          ntiles, (float *)out_vals, out_idx, (uint32_t)k);
         k_topk_write<<<tail_grid, 64, 0, st>>>(R, n, ws.state, ws.cnt_gt, ws.cnt_eq, ws.chunk_gt,
                                                      ws.chunk_eq, ntiles, (float *)out_vals, out_idx, (uint32_t)k);
     }

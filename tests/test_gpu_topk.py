@@ -159,8 +159,8 @@ def tail_taken(ws):
     return "general" if int(ws.view(torch.int32)[4].item()) != 0 else "slots"
 
 
-@pytest.mark.parametrize("kind,want", [("normal", "slots"), ("student_t", "slots"), ("clustered", "general"),
-                                       ("ties", "general"), ("k_large", "general")])
+@pytest.mark.parametrize("kind,want", [("normal", "slots"), ("student_t", "slots"), ("clustered", "slots+list"),
+                                       ("layer_scales", "slots+list"), ("ties", "general"), ("k_large", "general")])
 def test_both_tails_are_exercised_and_agree_with_the_oracle(B, kind, want):
     n = 1_200_003
     k = n // 1000
@@ -172,6 +172,10 @@ def test_both_tails_are_exercised_and_agree_with_the_oracle(B, kind, want):
     elif kind == "clustered":                              # all the large values sit in a few tiles
         Gn = (rng.standard_normal(n) * 1e-3).astype(np.float32)
         Gn[5000:9000] *= 100.0
+    elif kind == "layer_scales":                           # layers of very different gradient scale
+        Gn = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+        for lo, hi, sc in ((0, 300_000, 0.05), (300_000, 300_700, 30.0), (700_001, 703_333, 8.0), (900_000, n, 0.3)):
+            Gn[lo:hi] *= sc
     elif kind == "ties":
         Gn = rng.integers(-3, 4, n).astype(np.float32)
     else:
@@ -185,7 +189,9 @@ def test_both_tails_are_exercised_and_agree_with_the_oracle(B, kind, want):
     idx = torch.empty(k, dtype=torch.int32, device=DEV)
     B.topk_compress(G, R, k, vals, idx, ws)
     torch.cuda.synchronize()
-    assert tail_taken(ws) == want
+    crowded_tiles = int(ws.view(torch.int32)[7].item())    # word 7: tiles that missed their slots and are read from R
+    assert tail_taken(ws) == want.split("+")[0]
+    assert (crowded_tiles > 0) == (want != "slots")
     Rc = Rn.copy()
     ov, oi = oracle.topk(Gn, Rc, k)
     assert np.array_equal(idx.cpu().numpy().view(np.uint32), oi)
