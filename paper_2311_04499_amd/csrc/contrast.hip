@@ -230,16 +230,14 @@ __global__ __launch_bounds__(64) void k_sparse_mean_sorted(const float *__restri
     // From here on every lane carries, for each group g, the cursor and the row base of
     // the row it loads for: row 4g + q.  The 16 lanes of a row hold the same cursor.
     uint32_t cur[GROUPS];
-    const uint32_t *row_idx[GROUPS];
-    const float *row_val[GROUPS];
+    uint32_t row_off[GROUPS];  // first entry of the row in idx / vals (the host checks that it fits 32 bits)
     bool row_live[GROUPS];
 #pragma unroll
     for (int g = 0; g < GROUPS; ++g) {
         const int w = 4 * g + q;
         cur[g] = (uint32_t)__shfl((int)start, w, 64);
         row_live[g] = FULL || w < N;
-        row_idx[g] = idx + (int64_t)(row_live[g] ? w : 0) * stride;
-        row_val[g] = vals + (int64_t)(row_live[g] ? w : 0) * stride;
+        row_off[g] = (uint32_t)(row_live[g] ? w : 0) * (uint32_t)stride;
     }
     const uint32_t k_last = k - 1u;
 
@@ -259,9 +257,9 @@ __global__ __launch_bounds__(64) void k_sparse_mean_sorted(const float *__restri
 #pragma unroll
         for (int g = 0; g < GROUPS; ++g) {
             const uint32_t j = cur[g] + (uint32_t)e;  // no wrap: cursor <= k <= n < 2^32 - 16 (checked on the host)
-            const uint32_t at = j < k ? j : k_last;
-            rel[g] = row_idx[g][at];
-            val[g] = row_val[g][at];
+            const uint64_t at = (uint64_t)row_off[g] + (j < k ? j : k_last);
+            rel[g] = idx[at];
+            val[g] = vals[at];
         }
         bool full_window = false;  // a row whose 16th entry is in the tile may have more there
 #pragma unroll
@@ -283,22 +281,61 @@ __global__ __launch_bounds__(64) void k_sparse_mean_sorted(const float *__restri
                 }
             }
         } else {
-            // plain loop: row after row, 64 entries at a time, until the row leaves the tile
-            for (int w = 0; w < N; ++w) {
-                const uint32_t base = (uint32_t)__shfl((int)cur[w >> 2], (w & 3) * 16, 64);
-                uint32_t total = 0u, cnt = 64u;
-                while (cnt == 64u) {
-                    const int64_t j = (int64_t)base + total + lane;
-                    uint32_t r = 0xffffffffu;
-                    if (j < (int64_t)k) r = idx[(int64_t)w * stride + j] - (uint32_t)T0;
-                    const bool in = r < len;
-                    cnt = (uint32_t)__popcll(__ballot(in));
-                    if (in) lds_add(&tile[r], vals[(int64_t)w * stride + j]);
-                    total += cnt;
+            // crowded tile: four rows at a time, the next 256 entries of each (four loads of
+            // 64), all sixteen index and value loads in flight together; a row that still has
+            // entries in the tile after that goes on alone, 64 at a time
+            for (int w0 = 0; w0 < N; w0 += 4) {
+                const int g0 = w0 >> 2;
+                uint32_t cg = 0u;
+#pragma unroll
+                for (int g = 0; g < GROUPS; ++g) cg = g == g0 ? cur[g] : cg;
+                uint32_t base[4], rr[4][4];
+                float vv[4][4];
+                bool lv[4][4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int w = w0 + r;
+                    const bool live = w < N;
+                    base[r] = (uint32_t)__shfl((int)cg, r * 16, 64);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int64_t j = (int64_t)base[r] + 64 * u + lane;
+                        const int64_t at = (int64_t)(live ? w : 0) * stride + (j < (int64_t)k ? j : (int64_t)k - 1);
+                        rr[r][u] = idx[at];
+                        vv[r][u] = vals[at];
+                        lv[r][u] = live && j < (int64_t)k;
+                    }
                 }
+                __builtin_amdgcn_sched_barrier(0);  // all thirty-two loads first
+                uint32_t tot[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {  // rows in order
+                    tot[r] = 0u;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const uint32_t rel_u = lv[r][u] ? rr[r][u] - (uint32_t)T0 : 0xffffffffu;
+                        const bool in = rel_u < len;
+                        tot[r] += (uint32_t)__popcll(__ballot(in));
+                        if (in) lds_add(&tile[rel_u], vv[r][u]);
+                    }
+                    if (tot[r] == 256u) {
+                        const int w = w0 + r;
+                        uint32_t cnt = 64u;
+                        while (cnt == 64u) {
+                            const int64_t j = (int64_t)base[r] + tot[r] + lane;
+                            uint32_t rel_j = 0xffffffffu;
+                            if (j < (int64_t)k) rel_j = idx[(int64_t)w * stride + j] - (uint32_t)T0;
+                            const bool in = rel_j < len;
+                            cnt = (uint32_t)__popcll(__ballot(in));
+                            if (in) lds_add(&tile[rel_j], vals[(int64_t)w * stride + j]);
+                            tot[r] += cnt;
+                        }
+                    }
+                }
+                const uint32_t add = q == 0 ? tot[0] : (q == 1 ? tot[1] : (q == 2 ? tot[2] : tot[3]));
 #pragma unroll
                 for (int g = 0; g < GROUPS; ++g)
-                    if (4 * g + q == w) cur[g] += total;
+                    if (g == g0) cur[g] += add;
             }
         }
 
@@ -427,7 +464,8 @@ covap_status_t sparse_decompress_sorted(const void *vals, const uint32_t *idx, i
                                         int64_t k, int64_t stride_elems, int64_t n, void *dense_out,
                                         void *stream)
 {
-    if (n_workers > kSpRows || k == 0)  // the one-pass kernel keeps one cursor per lane and wants k >= 1
+    // the one-pass kernel keeps one cursor per lane, wants k >= 1 and 32-bit offsets into the payloads
+    if (n_workers > kSpRows || k == 0 || (int64_t)n_workers * stride_elems >= ((int64_t)1 << 32))
         return sparse_decompress(vals, idx, n_workers, k, stride_elems, n, dense_out, stream);
     covap::clear_error();
     if (n < 0 || k < 0 || k > n || n_workers < 1 || stride_elems < k || n >= ((int64_t)1 << 32) - 16)
