@@ -3,18 +3,21 @@
 //
 // Both kernels are pure HBM streaming (at most one FMA per 12 bytes moved), so
 // the design is about memory access only:
-//   * every thread moves 16-byte vectors; a 256-thread workgroup owns one
-//     "tile" of 256 * UNROLL consecutive vectors of ONE shard, so the filter's
+//   * every thread moves 16-byte vectors; a workgroup of THREADS threads owns one
+//     "tile" of THREADS * UNROLL consecutive vectors of ONE shard, so the filter's
 //     decision (sent / kept) is uniform over the workgroup and costs a few
-//     scalar integer operations per tile -- never per element;
-//   * all loads of a tile are issued before the first use, so each wave keeps
-//     UNROLL (compress: 2*UNROLL) 16-byte loads in flight;
+//     scalar integer operations per tile -- never per element.  The measured best
+//     on MI355X is the smallest shape: one wave, one vector per thread;
+//   * all loads of a tile are issued before the first use; decompress walks the N
+//     payload rows with one row in flight per wave (more was slower);
 //   * data that is not read again in the same iteration (everything here) is
 //     moved with streaming (non-temporal) hints;
 //   * shard starts and packed offsets are multiples of the vector size, so the
 //     vector path is always aligned; a shard's ragged tail (< one vector) goes
-//     through a scalar path in the same launch.
-// No LDS and no MFMA: there is no data reuse and no contraction.
+//     through a scalar path in the same launch.  Alignment to 1 KiB, one wave's
+//     access, is faster still, which the planner provides for variable-length shards.
+// No LDS (beyond an unused reservation that caps occupancy) and no MFMA: there is no
+// data reuse and no contraction.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
