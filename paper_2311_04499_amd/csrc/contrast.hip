@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kThreads) void k_ef_accumulate(const float *__restr
         a.y = __builtin_fmaf(c, r.y, g.y);
         a.z = __builtin_fmaf(c, r.z, g.z);
         a.w = __builtin_fmaf(c, r.w, g.w);
-        ((f32x4 *)R)[v] = a;  // the gather that follows reads a few of these again
+        __builtin_nontemporal_store(a, (f32x4 *)R + v);  // streaming: the gather that follows touches 1 % of it
     }
     if (blockIdx.x == 0 && (int64_t)threadIdx.x < n - nvec * 4) {
         const int64_t i = nvec * 4 + threadIdx.x;
