@@ -677,3 +677,24 @@ def test_bf16_rounding_over_the_float32_pattern_space(B):
     assert np.array_equal(got[~nan], sc[~nan])                       # every finite and infinite pattern, bit for bit
     assert np.all((got[nan] & 0x7f80) == 0x7f80) and np.all((got[nan] & 0x007f) != 0)   # NaN stays NaN
     assert_same(to_np(R)[~nan], Rc[~nan], "residual")
+
+
+def test_empty_arena_is_a_no_op(B):
+    """No elements: every hot-path call succeeds, launches nothing and leaves the buffers alone."""
+    for mode in (B.COVAP_SHARD_FIXED, B.COVAP_SHARD_MEDIAN):
+        plan = B.covap_plan([0, 0], 8, 2, mode=mode)
+        G = torch.full((16,), 3.0, device=DEV)
+        R = torch.full((16,), 4.0, device=DEV)
+        send = torch.full((16,), 5.0, device=DEV)
+        recv = torch.full((2, 16), 6.0, device=DEV)
+        out = torch.full((16,), 7.0, device=DEV)
+        for t in range(3):
+            B.covap_compress(plan, t, G, R, send)
+            B.covap_compress_aliased(plan, t, R, send)
+            B.covap_decompress(plan, t, recv, out)
+        torch.cuda.synchronize()
+        assert bool((R == 4.0).all()) and bool((send == 5.0).all()) and bool((out == 7.0).all())
+    ws = torch.empty(max(B.topk_workspace_bytes(0), 256), dtype=torch.uint8, device=DEV)
+    B.topk_compress(G, R, 0, send, recv.view(torch.int32)[0], ws, n=0)       # n = 0: nothing to do
+    torch.cuda.synchronize()
+    assert bool((R == 4.0).all())

@@ -192,3 +192,20 @@ def test_hot_path_rejects_bad_arguments_before_touching_the_gpu(B):
         B.covap_tune_set("compress_unroll", 3)
     assert B.covap_tune_get("compress_unroll") in (1, 2, 4)
     assert B.covap_tune_get("compress_threads") in (64, 256)
+
+
+@pytest.mark.parametrize("numel", [[0], [0, 0, 0], [5, 0, 7], [0, 16, 0]])
+def test_empty_tensors_and_empty_arenas(B, numel):
+    """Tensors without elements take no room; an arena without elements has no shards,
+    no buckets and an empty payload at every step, in both sharding modes."""
+    for mode, tab in ((B.COVAP_SHARD_FIXED, oracle.plan_fixed(numel, 8, 1 << 20)),
+                      (B.COVAP_SHARD_MEDIAN, oracle.plan_median(numel, 1 << 20, 2, 0, 256))):
+        plan = B.covap_plan(numel, 8, 2, mode=mode)
+        assert plan.total_elems == tab.D == sum(numel)
+        assert plan.num_shards == tab.n_shards and plan.num_buckets == tab.n_buckets
+        assert [plan.tensor_offset(i) for i in range(len(numel))] == [sum(numel[:i]) for i in range(len(numel))]
+        for t in range(4):
+            assert plan.packed_elems(t) == oracle.packed_elems(tab, 2, t)
+            assert plan.selected(t) == [s for s in range(tab.n_shards) if oracle.selected(s, t, 2)]
+        if sum(numel) == 0:
+            assert plan.num_shards == 0 and plan.packed_elems_max == 0
