@@ -213,7 +213,8 @@ covap_status_t covap_decompress(const covap_plan_t *plan, uint64_t step, int32_t
 
 /* ---- fine-grained top-k sparsifier (contrast point; Sec. I, Table II) --- */
 
-/* Bytes of device workspace topk_compress needs for n elements. */
+/* Bytes of device workspace topk_compress needs for n elements of `dtype`
+ * (0 for n < 0 or an element type topk_compress does not take). */
 size_t topk_workspace_bytes(int64_t n, int32_t dtype);
 
 /* A = fma(c, residual, grad) over n fp32 elements; keep the k entries of

@@ -916,7 +916,7 @@ extern "C" {
 
 size_t topk_workspace_bytes(int64_t n, int32_t dtype)
 {
-    if (n < 0) return 0;
+    if (n < 0 || dtype != COVAP_F32) return 0;  // fp32 only, as topk_compress
     return ws_layout(n, nullptr, nullptr);
 }
 
