@@ -267,3 +267,34 @@ def test_first_pass_launch_shapes_give_the_same_bits(B, waves):
         check_against_oracle(B, Gn, Rn, k, c=0.5)
     finally:
         B.covap_tune_set("topk_pass1_waves", old)
+
+
+@pytest.mark.parametrize("k", [1500, 2600, 3999, 4900])
+def test_threshold_ties_spread_over_listed_and_slotted_tiles(B, k):
+    """A hot region made of three repeated magnitudes (its tiles miss their slots and are
+    read from the residual) plus single elements of the same magnitudes scattered over the
+    rest (which sit in slots): the threshold falls on a repeated magnitude, so the tie rule
+    -- lowest indices first -- has to hold across both kinds of tiles."""
+    n = 1_000_003
+    rng = np.random.default_rng(k)
+    Gn = (rng.standard_normal(n) * 1e-4).astype(np.float32)
+    hot = np.arange(400_000, 404_000)
+    Gn[hot] = (rng.integers(1, 4, hot.size) * np.float32(0.01) * rng.choice([-1, 1], hot.size)).astype(np.float32)
+    lone = np.arange(123, n, 997)
+    Gn[lone] = (rng.integers(1, 4, lone.size) * np.float32(0.01)).astype(np.float32)
+    Rn = np.zeros(n, np.float32)
+    G = torch.from_numpy(Gn).to(DEV)
+    R = torch.from_numpy(Rn).to(DEV)
+    ws = torch.empty(B.topk_workspace_bytes(n), dtype=torch.uint8, device=DEV)
+    vals = torch.empty(k, device=DEV)
+    idx = torch.empty(k, dtype=torch.int32, device=DEV)
+    B.topk_compress(G, R, k, vals, idx, ws)
+    torch.cuda.synchronize()
+    st = ws.view(torch.int32)[:8].cpu().numpy()
+    assert st[4] == 0 and st[7] > 0                                  # slot tail, with listed tiles
+    ov, oi = oracle.topk(Gn, Rn, k)
+    assert np.array_equal(idx.cpu().numpy().view(np.uint32), oi)
+    assert np.array_equal(vals.cpu().numpy().view(np.uint32), ov.view(np.uint32))
+    assert np.array_equal(R.cpu().numpy().view(np.uint32), Rn.view(np.uint32))
+    kept_mag = np.abs(ov)
+    assert (kept_mag == kept_mag.min()).sum() > 1                    # the threshold really is tied
