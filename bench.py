@@ -341,6 +341,17 @@ def main():
         sres = {"buckets": nb, "launches_per_step": 2 * nb,
                 "eager_us_per_step": round(eager_wall_us, 1),
                 "whole_arena_us_per_step": round(ms_step * 1e3, 1)}
+
+        # what a bucket hook would do: compress bucket by bucket as the gradients become
+        # ready, average everything in one call once the exchange is over
+        def hook_like(t):
+            for b in range(nb):
+                B.covap_compress(plan, t, ring[0], residual, recv[0], bucket=b)
+            B.covap_decompress(plan, t, recv, dense, n_workers=N, stride_elems=stride)
+
+        hook_like(0)
+        _, hook_wall_us = timed(hook_like, reps)
+        sres["per_bucket_compress_one_decompress_us_per_step"] = round(hook_wall_us, 1)
         try:
             graphs = []
             side = torch.cuda.Stream()
