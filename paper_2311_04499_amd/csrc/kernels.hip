@@ -23,7 +23,6 @@
 #include <cstdint>
 #include <algorithm>
 #include <type_traits>
-#include <vector>
 
 #include "half_util.h"
 #include "plan.h"
@@ -814,58 +813,64 @@ void for_each_launch(const covap_plan_s *plan, const covap::call_range &cr, int 
     // the short zero-fill tiles at this coarse grain avoids that (measured: 18 %
     // on the VGG-19-shaped set).  Finer alternation is harmful: neighbouring
     // workgroups would then write streams a power of two apart.
-    struct seg {
-        int64_t off, poff;
-        uint32_t len;
-        bool sent;
-    };
+    //
+    // The segments are produced on the fly by two cursors, one walking the sent
+    // shards of the call and one the others; nothing is allocated.
     const int32_t K = plan->K;
     const int64_t seg_elems = (int64_t)kSegTiles * tile_elems;
-    std::vector<seg> sent, unsent;
-    for (int32_t s = cr.sh_lo; s < cr.sh_hi; ++s) {
-        const covap_shard_rec &sh = plan->shards[(size_t)s];
-        const bool is_sent = s % K == cr.first_sel;
-        if (sent_only && !is_sent) continue;
-        for (int64_t in = 0; in < sh.len; in += seg_elems) {
-            seg g;
-            g.off = sh.off + in;
-            g.poff = sh.packed_off + in;
-            g.len = (uint32_t)std::min<int64_t>(seg_elems, sh.len - in);
-            g.sent = is_sent;
-            (is_sent ? sent : unsent).push_back(g);
-        }
-    }
-    std::vector<seg> order;
-    order.reserve(sent.size() + unsent.size());
-    const size_t total = sent.size() + unsent.size();
-    size_t hs = 0, ls = 0;
-    for (size_t i = 0; i < total; ++i) {
-        const size_t want = ((i + 1) * sent.size() + total - 1) / total;  // sent segments due by now
-        if (hs < sent.size() && (hs < want || ls == unsent.size()))
-            order.push_back(sent[hs++]);
-        else
-            order.push_back(unsent[ls++]);
-    }
-    for (size_t lo = 0; lo < order.size(); lo += kMaxUnits) {
-        const size_t hi = lo + kMaxUnits < order.size() ? lo + kMaxUnits : order.size();
-        table_geom g;
-        g.n_units = (uint32_t)(hi - lo);
-        uint32_t tiles = 0;
-        for (size_t u = 0; u < (size_t)kMaxUnits; ++u) {
-            g.first[u] = tiles;
-            if (lo + u < hi) {
-                const seg &sg = order[lo + u];
-                g.off[u] = sg.off;
-                g.poff[u] = sg.poff;
-                g.len[u] = sg.len | (sg.sent ? 0x80000000u : 0u);
-                tiles += (uint32_t)((sg.len + tile_elems - 1) / tile_elems);
-            } else {
-                g.off[u] = 0;
-                g.poff[u] = 0;
-                g.len[u] = 0u;
+    struct cursor {
+        const covap_plan_s *plan;
+        int32_t s, hi, K, first_sel;
+        int64_t in;  // elements of shard s already handed out
+        bool want_sent;
+        bool kind(int32_t sh) const { return (sh % K == first_sel) == want_sent; }
+        void settle()
+        {  // move to the next shard of this cursor's kind that has elements left
+            while (s < hi && (!kind(s) || in >= plan->shards[(size_t)s].len)) {
+                ++s;
+                in = 0;
             }
         }
+    };
+    cursor cs{plan, cr.sh_lo, cr.sh_hi, K, cr.first_sel, 0, true};
+    cursor cu{plan, cr.sh_lo, cr.sh_hi, K, cr.first_sel, 0, false};
+    size_t n_sent = 0, n_unsent = 0;
+    for (int32_t s = cr.sh_lo; s < cr.sh_hi; ++s) {
+        const size_t segs = (size_t)((plan->shards[(size_t)s].len + seg_elems - 1) / seg_elems);
+        if (s % K == cr.first_sel)
+            n_sent += segs;
+        else if (!sent_only)
+            n_unsent += segs;
+    }
+    const size_t total = n_sent + n_unsent;
+    size_t done_sent = 0, done_unsent = 0, i = 0;
+    while (i < total) {
+        table_geom g;
+        uint32_t tiles = 0, units = 0;
+        for (; units < (uint32_t)kMaxUnits; ++units) {
+            g.first[units] = tiles;
+            if (i >= total) {
+                g.off[units] = 0;
+                g.poff[units] = 0;
+                g.len[units] = 0u;
+                continue;
+            }
+            const size_t want = ((i + 1) * n_sent + total - 1) / total;  // sent segments due by now
+            const bool take_sent = done_sent < n_sent && (done_sent < want || done_unsent == n_unsent);
+            cursor &c = take_sent ? cs : cu;
+            c.settle();
+            const covap_shard_rec &sh = plan->shards[(size_t)c.s];
+            const int64_t len = std::min<int64_t>(seg_elems, sh.len - c.in);
+            g.off[units] = sh.off + c.in;
+            g.poff[units] = sh.packed_off + c.in;
+            g.len[units] = (uint32_t)len | (take_sent ? 0x80000000u : 0u);
+            tiles += (uint32_t)((len + tile_elems - 1) / tile_elems);
+            c.in += len;
+            (take_sent ? done_sent : done_unsent) += 1;
+            ++i;
+        }
         g.first[kMaxUnits] = tiles;
+        g.n_units = units;
         if (tiles) f(g, dim3(tiles));
     }
 }
