@@ -698,3 +698,41 @@ def test_empty_arena_is_a_no_op(B):
     B.topk_compress(G, R, 0, send, recv.view(torch.int32)[0], ws, n=0)       # n = 0: nothing to do
     torch.cuda.synchronize()
     assert bool((R == 4.0).all())
+
+
+def test_long_run_conserves_every_gradient_on_the_device(B):
+    """100 iterations on integer-valued gradients (sums stay exact in fp32), c = 1: at the
+    end, everything that was ever sent plus the residual equals the sum of all gradients,
+    element by element and exactly -- the telescoped form of Algorithm 1's invariant, checked
+    on the GPU path over a run as long as the benchmark configurations ask for.  The oracle
+    runs the same 100 iterations on its own residual; payload and residual are compared with
+    it every tenth iteration and at the end."""
+    numel, S, K, T = [300_007, 65_536, 11], 8192, 5, 100
+    plan, tab = make_plans(B, numel, S, K)
+    D = tab.D
+    stride = (plan.packed_elems_max + 3) // 4 * 4
+    R = torch.zeros(D, device=DEV)
+    Rc = np.zeros(D, np.float32)
+    total_grad = torch.zeros(D, dtype=torch.float64, device=DEV)
+    total_sent = torch.zeros(D, dtype=torch.float64, device=DEV)
+    send = torch.zeros(stride, device=DEV)
+    for t in range(T):
+        G = workloads.integer_valued(D, seed=900 + t, lo=-500, hi=500, device=DEV)
+        total_grad += G
+        send.fill_(float("nan"))
+        B.covap_compress(plan, t, G, R, send)
+        sc = np.full(stride, np.nan, np.float32)
+        oracle.compress(tab, K, t, G.cpu().numpy(), Rc, sc)
+        p = 0
+        for s in plan.selected(t):                       # independent unpack from the plan's shard list
+            off, ln, _ = plan.shard(s)
+            total_sent[off:off + ln] += send[p:p + ln]
+            p += ln
+        assert p == plan.packed_elems(t)
+        if t % 10 == 0 or t == T - 1:
+            torch.cuda.synchronize()
+            assert_same(to_np(send), sc, f"send t={t}")
+            assert_same(to_np(R), Rc, f"residual t={t}")
+    torch.cuda.synchronize()
+    assert torch.equal(total_sent + R.double(), total_grad)
+    assert int((R != 0).sum()) > 0
