@@ -70,7 +70,9 @@ def test_half_payload_iterations(B, numel, S, K, N, c):
             same_bits(R.cpu().numpy(), Rc, f"residual t={t}")
             if N > 1:
                 recv[1:] = workloads.payload_rows(wl, N - 1, stride, t, DEV, torch.float16)
+            own_row = recv_c[0].copy()                   # the oracle averages its own payload, not the GPU's
             recv_c = half_bits(recv)
+            recv_c[0] = own_row
             out = torch.full((D,), float("nan"), device=DEV)
             out_c = np.empty(D, np.float32)
             B.covap_decompress(plan, t, recv, out)
