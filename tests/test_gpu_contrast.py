@@ -56,7 +56,9 @@ def test_fp16_compress_and_mean(B, n):
         recv[1:] = (workloads.payload_rows(wl, N - 1, stride, t, DEV)).to(torch.float16)
         out = torch.full((n,), float("nan"), device=DEV)
         B.fp16_decompress(recv, out, n=n)
-        want = oracle.fp16_mean(recv.cpu().view(torch.int16).numpy().view(np.uint16), n)
+        recv_c = recv.cpu().view(torch.int16).numpy().view(np.uint16).copy()
+        recv_c[0, :n] = hc                                   # the oracle averages its own payload, not the GPU's
+        want = oracle.fp16_mean(recv_c, n)
         torch.cuda.synchronize()
         same(out.cpu().numpy(), want, f"mean t={t}")
 
