@@ -8,6 +8,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstdio>
 
 #include "half_util.h"
 #include "plan.h"
@@ -367,8 +368,11 @@ __global__ __launch_bounds__(64) void k_sparse_mean_sorted(const float *__restri
 covap_status_t check(const char *what)
 {
     const hipError_t e = hipGetLastError();
-    if (e != hipSuccess)
-        return covap::fail(COVAP_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+    if (e != hipSuccess) {
+        char msg[200];
+        std::snprintf(msg, sizeof msg, "%s: %s", what, hipGetErrorString(e));
+        return covap::fail(COVAP_EHIP, msg);
+    }
     return COVAP_OK;
 }
 

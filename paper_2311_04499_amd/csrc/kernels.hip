@@ -21,6 +21,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstdio>
 #include <algorithm>
 #include <type_traits>
 
@@ -781,8 +782,11 @@ fixed_geom make_geom(const covap_plan_s *p, const covap::call_range &cr, int til
 covap_status_t check_launch(const char *what)
 {
     const hipError_t e = hipGetLastError();
-    if (e != hipSuccess)
-        return covap::fail(COVAP_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+    if (e != hipSuccess) {
+        char msg[200];
+        std::snprintf(msg, sizeof msg, "%s: %s", what, hipGetErrorString(e));
+        return covap::fail(COVAP_EHIP, msg);
+    }
     return COVAP_OK;
 }
 

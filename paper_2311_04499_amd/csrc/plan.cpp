@@ -5,20 +5,25 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <new>
 
 namespace covap {
 
-static thread_local std::string g_last_error;
+// The calling thread's last error text lives in a fixed buffer, so that reporting an
+// error never allocates (and so can neither fail nor throw across the C boundary).
+static thread_local char g_last_error[256] = "";
 
-covap_status_t fail(covap_status_t st, const std::string &msg)
+covap_status_t fail(covap_status_t st, const char *msg)
 {
-    g_last_error = msg;
+    std::snprintf(g_last_error, sizeof g_last_error, "%s", msg ? msg : "");
     return st;
 }
 
-void clear_error() { g_last_error.clear(); }
+covap_status_t fail(covap_status_t st, const std::string &msg) { return fail(st, msg.c_str()); }
+
+void clear_error() { g_last_error[0] = '\0'; }
 
 tuning &tune()
 {
@@ -420,7 +425,7 @@ int32_t covap_tune_get(const char *key)
     return -1;
 }
 
-const char *covap_last_error(void) { return g_last_error.c_str(); }
+const char *covap_last_error(void) { return g_last_error; }
 const char *covap_version(void) { return "0.1.0"; }
 
 }  // extern "C"

@@ -38,6 +38,7 @@ struct covap_plan_s {
 namespace covap {
 
 // Records msg as the calling thread's last error and returns st.
+covap_status_t fail(covap_status_t st, const char *msg);  // no allocation: hot-path calls use this form
 covap_status_t fail(covap_status_t st, const std::string &msg);
 void clear_error();
 

@@ -37,6 +37,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstdio>
 
 #include "plan.h"
 
@@ -905,8 +906,11 @@ __global__ __launch_bounds__(256) void k_topk_slots_write(float *R, int64_t n,
 covap_status_t check(const char *what)
 {
     const hipError_t e = hipGetLastError();
-    if (e != hipSuccess)
-        return covap::fail(COVAP_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+    if (e != hipSuccess) {
+        char msg[200];
+        std::snprintf(msg, sizeof msg, "%s: %s", what, hipGetErrorString(e));
+        return covap::fail(COVAP_EHIP, msg);
+    }
     return COVAP_OK;
 }
 
