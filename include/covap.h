@@ -230,6 +230,27 @@ covap_status_t topk_compress(const void *grad, void *residual, int64_t n, int64_
                              uint32_t *out_idx, void *workspace, size_t ws_bytes,
                              void *stream);
 
+/* topk_compress for callers that cannot allocate device memory or carry a
+ * workspace around: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments (without the workspace), same kernels and
+ * the same result bits as topk_compress; the workspace is a fixed array inside the
+ * library's code object (about 6.1 MB on every GPU the library runs on, held until
+ * the process ends), whose device address is looked up once per device on the first
+ * call made with that device current.  The call allocates nothing and frees nothing.
+ *   n at most topk_static_max_elems() = 2^24 elements; EINVAL beyond that (use
+ *   topk_compress with a caller-owned workspace for larger inputs)
+ *   the device that owns `stream` and the buffers must be the current device
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one
+ * GPU (different streams, different threads) race and give unspecified results (but
+ * touch nothing outside the array and the caller's buffers); calls on one stream are
+ * ordered and need nothing else.  The array keeps the previous call's contents; the
+ * first kernel of every call resets the parts that are accumulated into, so no
+ * clearing is needed between calls. */
+int64_t topk_static_max_elems(void);
+covap_status_t topk_compress_static(const void *grad, void *residual, int64_t n, int64_t k,
+                                    int32_t dtype, float ef_coeff, void *out_vals,
+                                    uint32_t *out_idx, void *stream);
+
 /* ---- further contrast points without data dependencies (Sec. II-C, Table III) --- */
 
 /* Random-k sparsifier with error feedback.  The k coordinates are the caller's

@@ -113,6 +113,10 @@ def lib():
     L.topk_compress.restype = C.c_int
     L.topk_compress.argtypes = [_vp, _vp, C.c_int64, C.c_int64, C.c_int32, C.c_float, _vp, _vp, _vp,
                                 C.c_size_t, _vp]
+    L.topk_static_max_elems.restype = C.c_int64
+    L.topk_static_max_elems.argtypes = []
+    L.topk_compress_static.restype = C.c_int
+    L.topk_compress_static.argtypes = [_vp, _vp, C.c_int64, C.c_int64, C.c_int32, C.c_float, _vp, _vp, _vp]
     L.randk_compress.restype = C.c_int
     L.randk_compress.argtypes = [_vp, _vp, C.c_int64, _vp, C.c_int64, C.c_float, _vp, _vp]
     L.fp16_compress.restype = C.c_int
@@ -266,6 +270,19 @@ def topk_compress(grad, residual, k: int, out_vals, out_idx, workspace, ef_coeff
         ws_bytes = workspace.numel() * workspace.element_size()
     _check(lib().topk_compress(_ptr(grad), _ptr(residual), n, k, dtype, ef_coeff, _ptr(out_vals),
                                _ptr(out_idx), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def topk_static_max_elems() -> int:
+    return lib().topk_static_max_elems()
+
+
+def topk_compress_static(grad, residual, k: int, out_vals, out_idx, ef_coeff: float = 1.0,
+                         n: Optional[int] = None, dtype: int = COVAP_F32, stream=None) -> None:
+    """topk_compress on the library's built-in workspace (no allocation anywhere)."""
+    if n is None:
+        n = grad.numel()
+    _check(lib().topk_compress_static(_ptr(grad), _ptr(residual), n, k, dtype, ef_coeff,
+                                      _ptr(out_vals), _ptr(out_idx), _stream(stream)))
 
 
 def randk_compress(grad, residual, idx, out_vals, ef_coeff: float = 1.0, n: Optional[int] = None,

@@ -36,6 +36,7 @@
 // caller's workspace; nothing is allocated.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <cstdio>
 
@@ -104,42 +105,52 @@ struct topk_ws {
     uint32_t *crowded;    // [ntiles]  list of the tiles that did not fit their slots (any order)
 };
 
-__host__ __device__ inline int64_t div_up(int64_t a, int64_t b) { return (a + b - 1) / b; }
+__host__ __device__ constexpr int64_t div_up(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Byte offsets of the workspace's parts for n elements, each on a 256-byte boundary.
+struct ws_offsets {
+    size_t state, hist, slot_cnt, slot_idx, slot_bits, cnt_gt, cnt_eq, chunk_gt, chunk_eq, crowded, total;
+};
+
+constexpr size_t round256(size_t bytes) { return (bytes + 255) / 256 * 256; }
+
+constexpr ws_offsets ws_offsets_for(int64_t n)
+{
+    const size_t ntiles = (size_t)div_up(n > 0 ? n : 1, kTile);
+    const size_t nchunks = (size_t)div_up((int64_t)ntiles, kScanChunk);
+    ws_offsets o{};
+    size_t off = 0;
+    o.state = off;     off += round256(sizeof(topk_state));
+    o.hist = off;      off += round256((size_t)kHistRows * 2048 * sizeof(uint32_t));
+    o.slot_cnt = off;  off += round256(ntiles * 4);
+    o.slot_idx = off;  off += round256(ntiles * kSlots * 4);
+    o.slot_bits = off; off += round256(ntiles * kSlots * 4);
+    o.cnt_gt = off;    off += round256(ntiles * 4);
+    o.cnt_eq = off;    off += round256(ntiles * 4);
+    o.chunk_gt = off;  off += round256(nchunks * 4);
+    o.chunk_eq = off;  off += round256(nchunks * 4);
+    o.crowded = off;   off += round256(ntiles * 4);
+    o.total = off;
+    return o;
+}
 
 size_t ws_layout(int64_t n, void *base, topk_ws *out)
 {
-    const int64_t ntiles = div_up(n > 0 ? n : 1, kTile);
-    const int64_t nchunks = div_up(ntiles, kScanChunk);
-    size_t off = 0;
-    auto take = [&](size_t bytes) {
-        const size_t at = off;
-        off += (bytes + 255) / 256 * 256;
-        return at;
-    };
-    const size_t o_state = take(sizeof(topk_state));
-    const size_t o_hist = take((size_t)kHistRows * 2048 * sizeof(uint32_t));
-    const size_t o_scnt = take((size_t)ntiles * 4);
-    const size_t o_sidx = take((size_t)ntiles * kSlots * 4);
-    const size_t o_sbits = take((size_t)ntiles * kSlots * 4);
-    const size_t o_gt = take((size_t)ntiles * 4);
-    const size_t o_eq = take((size_t)ntiles * 4);
-    const size_t o_cgt = take((size_t)nchunks * 4);
-    const size_t o_ceq = take((size_t)nchunks * 4);
-    const size_t o_crowded = take((size_t)ntiles * 4);
+    const ws_offsets o = ws_offsets_for(n);
     if (out) {
         char *b = (char *)base;
-        out->state = (topk_state *)(b + o_state);
-        out->hist = (uint32_t *)(b + o_hist);
-        out->slot_cnt = (uint32_t *)(b + o_scnt);
-        out->slot_idx = (uint32_t *)(b + o_sidx);
-        out->slot_bits = (uint32_t *)(b + o_sbits);
-        out->cnt_gt = (uint32_t *)(b + o_gt);
-        out->cnt_eq = (uint32_t *)(b + o_eq);
-        out->chunk_gt = (uint32_t *)(b + o_cgt);
-        out->chunk_eq = (uint32_t *)(b + o_ceq);
-        out->crowded = (uint32_t *)(b + o_crowded);
+        out->state = (topk_state *)(b + o.state);
+        out->hist = (uint32_t *)(b + o.hist);
+        out->slot_cnt = (uint32_t *)(b + o.slot_cnt);
+        out->slot_idx = (uint32_t *)(b + o.slot_idx);
+        out->slot_bits = (uint32_t *)(b + o.slot_bits);
+        out->cnt_gt = (uint32_t *)(b + o.cnt_gt);
+        out->cnt_eq = (uint32_t *)(b + o.cnt_eq);
+        out->chunk_gt = (uint32_t *)(b + o.chunk_gt);
+        out->chunk_eq = (uint32_t *)(b + o.chunk_eq);
+        out->crowded = (uint32_t *)(b + o.crowded);
     }
-    return off;
+    return o.total;
 }
 
 // ---- wavefront helpers (64 lanes) ---------------------------------------------
@@ -914,36 +925,45 @@ covap_status_t check(const char *what)
     return COVAP_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-size_t topk_workspace_bytes(int64_t n, int32_t dtype)
+// Argument checks shared by the entry points; `what` names the caller in the message.
+covap_status_t check_topk_args(const char *what, const void *grad, const void *residual, int64_t n, int64_t k,
+                               int32_t dtype, const void *out_vals, const uint32_t *out_idx)
 {
-    if (n < 0 || dtype != COVAP_F32) return 0;  // fp32 only, as topk_compress
-    return ws_layout(n, nullptr, nullptr);
+    char msg[160];
+    if (dtype != COVAP_F32) {
+        std::snprintf(msg, sizeof msg, "%s: fp32 only", what);
+        return covap::fail(COVAP_EUNSUPPORTED, msg);
+    }
+    if (n < 0 || k < 0 || k > n) {
+        std::snprintf(msg, sizeof msg, "%s: need 0 <= k <= n", what);
+        return covap::fail(COVAP_EINVAL, msg);
+    }
+    if (n >= ((int64_t)1 << 32)) {
+        std::snprintf(msg, sizeof msg, "%s: n >= 2^32", what);
+        return covap::fail(COVAP_EINVAL, msg);
+    }
+    if (n == 0) return COVAP_OK;
+    if (!grad || !residual || (k > 0 && (!out_vals || !out_idx))) {
+        std::snprintf(msg, sizeof msg, "%s: null device pointer", what);
+        return covap::fail(COVAP_EINVAL, msg);
+    }
+    if (((uintptr_t)grad & 15u) || ((uintptr_t)residual & 15u) || ((uintptr_t)out_vals & 3u) ||
+        ((uintptr_t)out_idx & 3u)) {
+        std::snprintf(msg, sizeof msg, "%s: misaligned device pointer", what);
+        return covap::fail(COVAP_EINVAL, msg);
+    }
+    return COVAP_OK;
 }
 
-covap_status_t topk_compress(const void *grad, void *residual, int64_t n, int64_t k, int32_t dtype,
-                             float ef_coeff, void *out_vals, uint32_t *out_idx, void *workspace,
-                             size_t ws_bytes, void *stream)
+// Enqueues the whole selection on `st`.  Arguments are already validated;
+// `workspace` holds at least ws_layout(n) bytes on a 256-byte boundary.  The first
+// kernel resets every part of the workspace that a later one adds to, so stale
+// contents are harmless.
+void run_topk(const void *grad, void *residual, int64_t n, int64_t k, float ef_coeff, void *out_vals,
+              uint32_t *out_idx, void *workspace, hipStream_t st)
 {
-    covap::clear_error();
-    if (dtype != COVAP_F32) return covap::fail(COVAP_EUNSUPPORTED, "topk_compress: fp32 only");
-    if (n < 0 || k < 0 || k > n) return covap::fail(COVAP_EINVAL, "topk_compress: need 0 <= k <= n");
-    if (n >= ((int64_t)1 << 32)) return covap::fail(COVAP_EINVAL, "topk_compress: n >= 2^32");
-    if (n == 0) return COVAP_OK;
-    if (!grad || !residual || !workspace || (k > 0 && (!out_vals || !out_idx)))
-        return covap::fail(COVAP_EINVAL, "topk_compress: null device pointer");
-    if (((uintptr_t)grad & 15u) || ((uintptr_t)residual & 15u) || ((uintptr_t)workspace & 255u) ||
-        ((uintptr_t)out_vals & 3u) || ((uintptr_t)out_idx & 3u))
-        return covap::fail(COVAP_EINVAL, "topk_compress: misaligned device pointer");
-    if (ws_bytes < ws_layout(n, nullptr, nullptr))
-        return covap::fail(COVAP_EINVAL, "topk_compress: workspace too small");
-
     topk_ws ws;
     ws_layout(n, workspace, &ws);
-    hipStream_t st = (hipStream_t)stream;
     const float *G = (const float *)grad;
     float *R = (float *)residual;
     const int64_t nvec = n / 4;
@@ -1004,7 +1024,97 @@ covap_status_t topk_compress(const void *grad, void *residual, int64_t n, int64_
         k_topk_write<<<tail_grid, 64, 0, st>>>(R, n, ws.state, ws.cnt_gt, ws.cnt_eq, ws.chunk_gt,
                                                      ws.chunk_eq, ntiles, (float *)out_vals, out_idx, (uint32_t)k);
     }
+}
+
+// ---- the workspace of topk_compress_static ----------------------------------------------
+//
+// Callers that may not allocate (HIP graph capture, serving loops) get the workspace
+// from a fixed array in the code object.  Every GPU the library runs on holds its own
+// copy at its own address until the process ends; host code must not use the array's
+// name as an address, only what hipGetSymbolAddress returns for the current device.
+constexpr int64_t kStaticMaxN = (int64_t)1 << 24;  // 16 Mi elements: about 6.1 MB of workspace
+constexpr size_t kStaticBytes = ws_offsets_for(kStaticMaxN).total;
+constexpr int kMaxDevices = 64;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+
+std::atomic<void *> g_scratch_ptr[kMaxDevices];  // device address of `scratch`, by device ordinal
+
+// Device address of the current device's copy of `scratch`; looked up once per device.
+// Two threads that race here both get the same address.
+covap_status_t static_workspace(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        char msg[200];
+        std::snprintf(msg, sizeof msg, "topk_compress_static: hipGetDevice: %s", hipGetErrorString(e));
+        return covap::fail(COVAP_EHIP, msg);
+    }
+    if (dev < 0 || dev >= kMaxDevices)
+        return covap::fail(COVAP_EUNSUPPORTED, "topk_compress_static: device ordinal beyond 63");
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            char msg[200];
+            std::snprintf(msg, sizeof msg, "topk_compress_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+            return covap::fail(COVAP_EHIP, msg);
+        }
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return COVAP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t topk_workspace_bytes(int64_t n, int32_t dtype)
+{
+    if (n < 0 || dtype != COVAP_F32) return 0;  // fp32 only, as topk_compress
+    return ws_layout(n, nullptr, nullptr);
+}
+
+covap_status_t topk_compress(const void *grad, void *residual, int64_t n, int64_t k, int32_t dtype,
+                             float ef_coeff, void *out_vals, uint32_t *out_idx, void *workspace,
+                             size_t ws_bytes, void *stream)
+{
+    covap::clear_error();
+    const covap_status_t rs = check_topk_args("topk_compress", grad, residual, n, k, dtype, out_vals, out_idx);
+    if (rs != COVAP_OK || n == 0) return rs;
+    if (!workspace) return covap::fail(COVAP_EINVAL, "topk_compress: null device pointer");
+    if ((uintptr_t)workspace & 255u) return covap::fail(COVAP_EINVAL, "topk_compress: misaligned device pointer");
+    if (ws_bytes < ws_layout(n, nullptr, nullptr))
+        return covap::fail(COVAP_EINVAL, "topk_compress: workspace too small");
+    run_topk(grad, residual, n, k, ef_coeff, out_vals, out_idx, workspace, (hipStream_t)stream);
     return check("topk_compress");
+}
+
+int64_t topk_static_max_elems(void) { return kStaticMaxN; }
+
+covap_status_t topk_compress_static(const void *grad, void *residual, int64_t n, int64_t k, int32_t dtype,
+                                    float ef_coeff, void *out_vals, uint32_t *out_idx, void *stream)
+{
+    covap::clear_error();
+    const covap_status_t rs =
+        check_topk_args("topk_compress_static", grad, residual, n, k, dtype, out_vals, out_idx);
+    if (rs != COVAP_OK || n == 0) return rs;
+    if (n > kStaticMaxN)
+        return covap::fail(COVAP_EINVAL,
+                           "topk_compress_static: n exceeds topk_static_max_elems() (2^24); use topk_compress "
+                           "with a caller-owned workspace");
+    static_assert(ws_offsets_for(kStaticMaxN).total <= kStaticBytes, "scratch holds the largest layout");
+    void *workspace = nullptr;
+    const covap_status_t ws = static_workspace(&workspace);
+    if (ws != COVAP_OK) return ws;
+    run_topk(grad, residual, n, k, ef_coeff, out_vals, out_idx, workspace, (hipStream_t)stream);
+    return check("topk_compress_static");
 }
 
 }  // extern "C"
