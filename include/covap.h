@@ -111,7 +111,7 @@ typedef struct {
  * covap_plan_tensor_offset.
  * On success *out receives a plan to be released with covap_plan_free.
  * EINVAL: null argument, n_tensors < 1, a negative count, K < 1, bad shard
- * size or cap, total elements >= 2^38. */
+ * size or cap, more than 2^33 elements in all (alignment padding included). */
 covap_status_t covap_plan(const int64_t *tensor_numel, int32_t n_tensors,
                           const covap_plan_opts_t *opts, covap_plan_t **out);
 void covap_plan_free(covap_plan_t *plan);
@@ -151,6 +151,24 @@ int64_t covap_plan_packed_base(const covap_plan_t *plan, uint64_t step, int32_t 
 /* Largest covap_plan_packed_elems(step, -1) over all steps: the size to give
  * send buffers and the row stride of receive buffers. */
 int64_t covap_plan_packed_elems_max(const covap_plan_t *plan);
+
+/* Replays, on the host, the launches that a hot-path call would make -- the same
+ * index arithmetic the kernels run on their workgroup index, compiled for the host
+ * -- and lists the tiles they resolve to, in launch and workgroup order: tile i
+ * covers n[i] elements from arena offset off[i]; sel[i] is 1 if its shard is sent at
+ * `step`, and then poff[i] is where the tile starts in the packed layout.  For
+ * checking the launch geometry without a GPU; no hot-path call uses it.
+ *   tile_elems  elements per workgroup: a power of two, 256..8192
+ *   sent_only   0: every shard of the call, as covap_compress and covap_decompress
+ *               launch; 1: only the sent shards, as covap_compress_aliased launches
+ *   cap         capacity of the four arrays [host], any of which may be null; tiles
+ *               beyond cap are counted but not stored
+ *   n_launches, n_workgroups  [host, may be null] kernel launches of the call and
+ *               workgroups in all (some return at once without a tile)
+ * Returns the number of tiles, or -1 on a bad argument. */
+int64_t covap_plan_trace(const covap_plan_t *plan, uint64_t step, int32_t bucket, int32_t tile_elems,
+                         int32_t sent_only, int64_t cap, int64_t *off, int64_t *poff, int32_t *n,
+                         uint8_t *sel, int32_t *n_launches, int64_t *n_workgroups);
 
 /* ---- ratio policy and error-feedback scheduler (host) ------------------- */
 
@@ -319,8 +337,11 @@ covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float
  *   "topk_pass1_waves"   waves that share a 1024-element tile in the first pass of
  *                        topk_compress: 1, 2, 4
  *   "topk_pass1_lds_pad" as decompress_lds_pad, for that pass: 0, 6144, 8192, 24576
- * No knob changes any result bit.  EINVAL for an unknown key or value.  Global
- * to the process and not thread-safe against running calls. */
+ * No knob changes any result bit.  EINVAL for an unknown key or value.  For
+ * tuning sweeps and tests only: the knobs are global to the process (every plan and
+ * every later call sees a change).  Stores and loads are atomic and a hot-path call
+ * reads the knobs once, so a change made while another thread is inside a call
+ * takes effect for that thread's next call, never in the middle of one. */
 covap_status_t covap_tune_set(const char *key, int32_t value);
 int32_t covap_tune_get(const char *key);
 

@@ -110,6 +110,32 @@ def _p(a: np.ndarray, ptr):
     return a.ctypes.data_as(ptr)
 
 
+def _ranges(tab: "ShardTable", lo: int, hi: int, threads: int):
+    """[lo, hi) cut into runs of whole shards of about equal element counts, a few per thread."""
+    if threads <= 1 or hi - lo <= 1:
+        return [(lo, hi)]
+    want = max(1, int(tab.len[lo:hi].sum()) // (4 * threads))
+    cuts, acc = [lo], 0
+    for s in range(lo, hi):
+        acc += int(tab.len[s])
+        if acc >= want and s + 1 < hi:
+            cuts.append(s + 1)
+            acc = 0
+    cuts.append(hi)
+    return list(zip(cuts[:-1], cuts[1:]))
+
+
+def _run(calls, threads: int):
+    """Run the C calls one after the other, or -- threads > 1 -- on a thread pool (ctypes
+    releases the interpreter lock).  Every call covers its own run of whole shards and works
+    out its own packed position, so the element-wise results do not depend on the split."""
+    if threads <= 1 or len(calls) <= 1:
+        return [f() for f in calls]
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        return list(ex.map(lambda f: f(), calls))
+
+
 def _chk(a: np.ndarray, dtype) -> np.ndarray:
     if a.dtype != dtype or not a.flags.c_contiguous:
         raise TypeError(f"expected C-contiguous {dtype}, got {a.dtype}")
@@ -242,27 +268,27 @@ def _kind(a: np.ndarray):
 
 
 def compress(tab: ShardTable, interval: int, t: int, G, R, send, c: float = 1.0,
-             bucket: int = -1) -> int:
+             bucket: int = -1, threads: int = 1) -> int:
     """In place: R becomes the new residual, send receives the packed shards.
     G/send uint16 (bf16 patterns) with R float32 selects the mixed-precision form;
-    G/R float32 with send uint16 (fp16 patterns) the half-payload form."""
+    G/R float32 with send uint16 (fp16 patterns) the half-payload form.
+    threads > 1: the same C routine is called on runs of whole shards from a thread pool."""
     lo, hi = tab.bucket_range(bucket)
     if G.dtype == np.float32 and send.dtype == np.uint16:
         _chk(G, np.float32), _chk(R, np.float32), _chk(send, np.uint16)
-        return int(lib().orc_compress_f32_pay16(
-            _p(G, _f32p), _p(R, _f32p), _p(send, _u16p), _p(tab.off, _i64p), _p(tab.len, _i64p),
-            lo, hi, interval, t, c, tab.align))
-    if G.dtype == np.uint16 and R.dtype == np.float32:
+        f, args = lib().orc_compress_f32_pay16, (_p(G, _f32p), _p(R, _f32p), _p(send, _u16p))
+    elif G.dtype == np.uint16 and R.dtype == np.float32:
         _chk(G, np.uint16), _chk(send, np.uint16), _chk(R, np.float32)
-        return int(lib().orc_compress_bf16_res32(
-            _p(G, _u16p), _p(R, _f32p), _p(send, _u16p), _p(tab.off, _i64p), _p(tab.len, _i64p),
-            lo, hi, interval, t, c, tab.align))
-    name, ptr = _kind(G)
-    for a in (G, R, send):
-        _chk(a, G.dtype)
-    f = getattr(lib(), "orc_compress_" + name)
-    return int(f(_p(G, ptr), _p(R, ptr), _p(send, ptr), _p(tab.off, _i64p), _p(tab.len, _i64p),
-                 lo, hi, interval, t, c, tab.align))
+        f, args = lib().orc_compress_bf16_res32, (_p(G, _u16p), _p(R, _f32p), _p(send, _u16p))
+    else:
+        name, ptr = _kind(G)
+        for a in (G, R, send):
+            _chk(a, G.dtype)
+        f, args = getattr(lib(), "orc_compress_" + name), (_p(G, ptr), _p(R, ptr), _p(send, ptr))
+    off, ln = _p(tab.off, _i64p), _p(tab.len, _i64p)
+    calls = [lambda a=a, b=b: f(*args, off, ln, a, b, interval, t, c, tab.align)
+             for a, b in _ranges(tab, lo, hi, threads)]
+    return int(sum(_run(calls, threads)))
 
 
 def compress_aliased(tab: ShardTable, interval: int, t: int, accum, send, bucket: int = -1) -> int:
@@ -274,24 +300,26 @@ def compress_aliased(tab: ShardTable, interval: int, t: int, accum, send, bucket
                                           tab.align))
 
 
-def decompress(tab: ShardTable, interval: int, t: int, recv, out, bucket: int = -1) -> None:
+def decompress(tab: ShardTable, interval: int, t: int, recv, out, bucket: int = -1,
+               threads: int = 1) -> None:
     """recv: [N, stride] packed payload rows; out: dense arena, fully written.
-    recv uint16 with out float32 selects the half-payload form."""
-    if recv.dtype == np.uint16 and out.dtype == np.float32:
-        _chk(recv, np.uint16), _chk(out, np.float32)
-        assert recv.ndim == 2
-        lo, hi = tab.bucket_range(bucket)
-        lib().orc_decompress_pay16(_p(recv, _u16p), recv.shape[0], recv.shape[1], _p(out, _f32p),
-                                   _p(tab.off, _i64p), _p(tab.len, _i64p), lo, hi, interval, t, tab.align)
-        return
-    name, ptr = _kind(recv)
-    _chk(recv, recv.dtype)
-    _chk(out, recv.dtype)
+    recv uint16 with out float32 selects the half-payload form.
+    threads > 1: the same C routine is called on runs of whole shards from a thread pool."""
     assert recv.ndim == 2
     lo, hi = tab.bucket_range(bucket)
-    f = getattr(lib(), "orc_decompress_" + name)
-    f(_p(recv, ptr), recv.shape[0], recv.shape[1], _p(out, ptr), _p(tab.off, _i64p),
-      _p(tab.len, _i64p), lo, hi, interval, t, tab.align)
+    if recv.dtype == np.uint16 and out.dtype == np.float32:
+        _chk(recv, np.uint16), _chk(out, np.float32)
+        f, args = lib().orc_decompress_pay16, (_p(recv, _u16p), recv.shape[0], recv.shape[1], _p(out, _f32p))
+    else:
+        name, ptr = _kind(recv)
+        _chk(recv, recv.dtype)
+        _chk(out, recv.dtype)
+        f = getattr(lib(), "orc_decompress_" + name)
+        args = (_p(recv, ptr), recv.shape[0], recv.shape[1], _p(out, ptr))
+    off, ln = _p(tab.off, _i64p), _p(tab.len, _i64p)
+    calls = [lambda a=a, b=b: f(*args, off, ln, a, b, interval, t, tab.align)
+             for a, b in _ranges(tab, lo, hi, threads)]
+    _run(calls, threads)
 
 
 def topk(G, R, k: int, c: float = 1.0):

@@ -96,6 +96,9 @@ def lib():
     L.covap_plan_packed_elems.argtypes = [_vp, C.c_uint64, C.c_int32]
     L.covap_plan_packed_base.restype = C.c_int64
     L.covap_plan_packed_base.argtypes = [_vp, C.c_uint64, C.c_int32]
+    L.covap_plan_trace.restype = C.c_int64
+    L.covap_plan_trace.argtypes = [_vp, C.c_uint64, C.c_int32, C.c_int32, C.c_int32, C.c_int64, _vp, _vp, _vp, _vp,
+                                   _i32p, _i64p]
     L.covap_ratio_from_ccr.restype = C.c_int
     L.covap_ratio_from_ccr.argtypes = [C.c_double, _i32p]
     L.covap_ratio_from_times.restype = C.c_int
@@ -161,6 +164,27 @@ def _ptr(t) -> int:
     return t.ctypes.data
 
 
+def _need(t, what: str, elems: int, esz: Optional[int] = None) -> None:
+    """The kernels trust the sizes they are given, and a read or write past an allocation
+    is a GPU memory fault: refuse a tensor (or array) that is too small or of the wrong
+    element width before its address is taken.  Raw integer addresses are the caller's
+    responsibility."""
+    if t is None or isinstance(t, int):
+        return
+    n = t.numel() if hasattr(t, "numel") else t.size
+    if n < elems:
+        raise ValueError(f"{what}: {n} elements, the call needs at least {elems}")
+    if esz is not None:
+        w = t.element_size() if hasattr(t, "element_size") else t.itemsize
+        if w != esz:
+            raise ValueError(f"{what}: {w}-byte elements, the plan's element type has {esz}")
+
+
+_GRAD_ESZ = {COVAP_F32: 4, COVAP_BF16: 2, COVAP_BF16_RES32: 2, COVAP_F32_PAY16: 4}
+_RESIDUAL_ESZ = {COVAP_F32: 4, COVAP_BF16: 2, COVAP_BF16_RES32: 4, COVAP_F32_PAY16: 4}
+_PAYLOAD_ESZ = {COVAP_F32: 4, COVAP_BF16: 2, COVAP_BF16_RES32: 2, COVAP_F32_PAY16: 2}
+
+
 def _stream(stream) -> int:
     if stream is None:
         import torch
@@ -222,6 +246,21 @@ class Plan:
     def packed_base(self, step: int, bucket: int = -1) -> int:
         return lib().covap_plan_packed_base(self._h, step, bucket)
 
+    def trace(self, step: int, bucket: int = -1, tile_elems: int = 256, sent_only: bool = False):
+        """Host replay of the call's launches: numpy arrays (off, poff, n, sel) of the
+        tiles in launch order, plus (launches, workgroups)."""
+        import numpy as np
+        nl, nw = C.c_int32(), C.c_int64()
+        cnt = lib().covap_plan_trace(self._h, step, bucket, tile_elems, int(sent_only), 0, None, None, None,
+                                     None, C.byref(nl), C.byref(nw))
+        if cnt < 0:
+            raise CovapError(1, lib().covap_last_error().decode())
+        off, poff = np.empty(cnt, np.int64), np.empty(cnt, np.int64)
+        n, sel = np.empty(cnt, np.int32), np.empty(cnt, np.uint8)
+        lib().covap_plan_trace(self._h, step, bucket, tile_elems, int(sent_only), cnt, off.ctypes.data,
+                               poff.ctypes.data, n.ctypes.data, sel.ctypes.data, None, None)
+        return off, poff, n, sel, nl.value, nw.value
+
 
 def covap_plan(tensor_numel: Sequence[int], shard_elems: int, K: int, dtype: int = COVAP_F32,
                bucket_cap_bytes: int = 25 << 20, mode: int = COVAP_SHARD_FIXED,
@@ -236,6 +275,10 @@ def covap_plan(tensor_numel: Sequence[int], shard_elems: int, K: int, dtype: int
 def covap_compress(plan: Plan, step: int, grad, residual, send, ef_coeff: float = 1.0,
                    bucket: int = -1, stream=None, send_cap_elems: Optional[int] = None) -> None:
     cap = send.numel() if send_cap_elems is None else send_cap_elems
+    D = plan.total_elems                      # with median sharding this includes alignment padding
+    _need(grad, "grad", D, _GRAD_ESZ[plan.dtype])
+    _need(residual, "residual", D, _RESIDUAL_ESZ[plan.dtype])
+    _need(send, "send", cap, _PAYLOAD_ESZ[plan.dtype])
     _check(lib().covap_compress(plan.handle, step, bucket, _ptr(grad), _ptr(residual), _ptr(send),
                                 cap, ef_coeff, _stream(stream)))
 
@@ -243,6 +286,8 @@ def covap_compress(plan: Plan, step: int, grad, residual, send, ef_coeff: float 
 def covap_compress_aliased(plan: Plan, step: int, accum, send, bucket: int = -1, stream=None,
                            send_cap_elems: Optional[int] = None) -> None:
     cap = send.numel() if send_cap_elems is None else send_cap_elems
+    _need(accum, "accum", plan.total_elems, _GRAD_ESZ[plan.dtype])
+    _need(send, "send", cap, _PAYLOAD_ESZ[plan.dtype])
     _check(lib().covap_compress_aliased(plan.handle, step, bucket, _ptr(accum), _ptr(send), cap,
                                         _stream(stream)))
 
@@ -253,6 +298,11 @@ def covap_decompress(plan: Plan, step: int, recv, dense_out, n_workers: Optional
         n_workers = recv.shape[0]
     if stride_elems is None:
         stride_elems = recv.stride(0) if recv.dim() == 2 else recv.numel()
+    used = plan.packed_elems(step, bucket)
+    if used > 0 and n_workers >= 1:
+        _need(recv, "recv", (n_workers - 1) * stride_elems + plan.packed_base(step, bucket) + used,
+              _PAYLOAD_ESZ[plan.dtype])
+    _need(dense_out, "dense_out", plan.total_elems, _GRAD_ESZ[plan.dtype])
     _check(lib().covap_decompress(plan.handle, step, bucket, _ptr(recv), n_workers, stride_elems,
                                   _ptr(dense_out), _stream(stream)))
 
@@ -268,6 +318,10 @@ def topk_compress(grad, residual, k: int, out_vals, out_idx, workspace, ef_coeff
         n = grad.numel()
     if ws_bytes is None:
         ws_bytes = workspace.numel() * workspace.element_size()
+    _need(grad, "grad", n, 4), _need(residual, "residual", n, 4)
+    _need(out_vals, "out_vals", k, 4), _need(out_idx, "out_idx", k, 4)
+    if not isinstance(workspace, int) and workspace is not None:
+        _need(workspace, "workspace", -(-ws_bytes // workspace.element_size()))
     _check(lib().topk_compress(_ptr(grad), _ptr(residual), n, k, dtype, ef_coeff, _ptr(out_vals),
                                _ptr(out_idx), _ptr(workspace), ws_bytes, _stream(stream)))
 
@@ -281,6 +335,8 @@ def topk_compress_static(grad, residual, k: int, out_vals, out_idx, ef_coeff: fl
     """topk_compress on the library's built-in workspace (no allocation anywhere)."""
     if n is None:
         n = grad.numel()
+    _need(grad, "grad", n, 4), _need(residual, "residual", n, 4)
+    _need(out_vals, "out_vals", k, 4), _need(out_idx, "out_idx", k, 4)
     _check(lib().topk_compress_static(_ptr(grad), _ptr(residual), n, k, dtype, ef_coeff,
                                       _ptr(out_vals), _ptr(out_idx), _stream(stream)))
 
@@ -289,6 +345,8 @@ def randk_compress(grad, residual, idx, out_vals, ef_coeff: float = 1.0, n: Opti
                    k: Optional[int] = None, stream=None) -> None:
     n = grad.numel() if n is None else n
     k = idx.numel() if k is None else k
+    _need(grad, "grad", n, 4), _need(residual, "residual", n, 4)
+    _need(idx, "idx", k, 4), _need(out_vals, "out_vals", k, 4)
     _check(lib().randk_compress(_ptr(grad), _ptr(residual), n, _ptr(idx), k, ef_coeff,
                                 _ptr(out_vals), _stream(stream)))
 
@@ -296,6 +354,7 @@ def randk_compress(grad, residual, idx, out_vals, ef_coeff: float = 1.0, n: Opti
 def fp16_compress(grad, residual, out_half, ef_coeff: float = 1.0, n: Optional[int] = None,
                   stream=None) -> None:
     n = grad.numel() if n is None else n
+    _need(grad, "grad", n, 4), _need(residual, "residual", n, 4), _need(out_half, "out_half", n, 2)
     _check(lib().fp16_compress(_ptr(grad), _ptr(residual), n, ef_coeff, _ptr(out_half), _stream(stream)))
 
 
@@ -304,6 +363,9 @@ def fp16_decompress(recv, dense_out, n: Optional[int] = None, n_workers: Optiona
     n_workers = recv.shape[0] if n_workers is None else n_workers
     stride_elems = recv.stride(0) if stride_elems is None else stride_elems
     n = dense_out.numel() if n is None else n
+    if n_workers >= 1:
+        _need(recv, "recv", (n_workers - 1) * stride_elems + n, 2)
+    _need(dense_out, "dense_out", n, 4)
     _check(lib().fp16_decompress(_ptr(recv), n_workers, stride_elems, n, _ptr(dense_out), _stream(stream)))
 
 
@@ -314,6 +376,10 @@ def sparse_decompress(vals, idx, dense_out, k: Optional[int] = None, n: Optional
     stride_elems = vals.stride(0) if stride_elems is None else stride_elems
     k = vals.shape[1] if k is None else k
     n = dense_out.numel() if n is None else n
+    if n_workers >= 1 and k > 0:
+        _need(vals, "vals", (n_workers - 1) * stride_elems + k, 4)
+        _need(idx, "idx", (n_workers - 1) * stride_elems + k, 4)
+    _need(dense_out, "dense_out", n, 4)
     _check(lib().sparse_decompress(_ptr(vals), _ptr(idx), n_workers, k, stride_elems, n,
                                    _ptr(dense_out), _stream(stream)))
 
@@ -325,6 +391,10 @@ def sparse_decompress_sorted(vals, idx, dense_out, k: Optional[int] = None, n: O
     stride_elems = vals.stride(0) if stride_elems is None else stride_elems
     k = vals.shape[1] if k is None else k
     n = dense_out.numel() if n is None else n
+    if n_workers >= 1 and k > 0:
+        _need(vals, "vals", (n_workers - 1) * stride_elems + k, 4)
+        _need(idx, "idx", (n_workers - 1) * stride_elems + k, 4)
+    _need(dense_out, "dense_out", n, 4)
     _check(lib().sparse_decompress_sorted(_ptr(vals), _ptr(idx), n_workers, k, stride_elems, n,
                                           _ptr(dense_out), _stream(stream)))
 

@@ -11,6 +11,7 @@
 #include <cstdio>
 
 #include "half_util.h"
+#include "launch.h"
 #include "plan.h"
 
 namespace {
@@ -365,17 +366,6 @@ __global__ __launch_bounds__(64) void k_sparse_mean_sorted(const float *__restri
     }
 }
 
-covap_status_t check(const char *what)
-{
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) {
-        char msg[200];
-        std::snprintf(msg, sizeof msg, "%s: %s", what, hipGetErrorString(e));
-        return covap::fail(COVAP_EHIP, msg);
-    }
-    return COVAP_OK;
-}
-
 bool al16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 uint32_t blocks(int64_t items, int per) { return (uint32_t)((items + per - 1) / per); }
 
@@ -397,11 +387,12 @@ covap_status_t randk_compress(const void *grad, void *residual, int64_t n, const
     if (!al16(grad) || !al16(residual) || ((uintptr_t)idx & 3u) || ((uintptr_t)out_vals & 3u))
         return fail(COVAP_EINVAL, "randk_compress: misaligned device pointer");
     hipStream_t st = (hipStream_t)stream;
-    k_ef_accumulate<<<blocks(n / 4 > 0 ? n / 4 : 1, kThreads), kThreads, 0, st>>>(
-        (const float *)grad, (float *)residual, n, ef_coeff);
+    covap::launch_status ls;
+    ls += covap::launch(k_ef_accumulate, dim3(blocks(n / 4 > 0 ? n / 4 : 1, kThreads)), dim3(kThreads), 0, st,  (const float *)grad, (float *)residual, n, ef_coeff);
     if (k > 0)
-        k_gather_clear<<<blocks(k, 256), 256, 0, st>>>((float *)residual, idx, k, (float *)out_vals);
-    return check("randk_compress");
+        ls += covap::launch(k_gather_clear, dim3(blocks(k, 256)), dim3(256), 0, st, (float *)residual, idx, k,
+                            (float *)out_vals);
+    return ls.report("randk_compress");
 }
 
 covap_status_t fp16_compress(const void *grad, void *residual, int64_t n, float ef_coeff,
@@ -413,9 +404,9 @@ covap_status_t fp16_compress(const void *grad, void *residual, int64_t n, float 
     if (!grad || !residual || !out_half) return fail(COVAP_EINVAL, "fp16_compress: null device pointer");
     if (!al16(grad) || !al16(residual) || !al16(out_half))
         return fail(COVAP_EINVAL, "fp16_compress: device pointers must be 16-byte aligned");
-    k_fp16_compress<<<blocks(n / 4 > 0 ? n / 4 : 1, kThreads), kThreads, 0, (hipStream_t)stream>>>(
-        (const float *)grad, (float *)residual, n, ef_coeff, (uint16_t *)out_half);
-    return check("fp16_compress");
+    covap::launch_status ls;
+    ls += covap::launch(k_fp16_compress, dim3(blocks(n / 4 > 0 ? n / 4 : 1, kThreads)), dim3(kThreads), 0, (hipStream_t)stream,  (const float *)grad, (float *)residual, n, ef_coeff, (uint16_t *)out_half);
+    return ls.report("fp16_compress");
 }
 
 covap_status_t fp16_decompress(const void *recv, int32_t n_workers, int64_t stride_elems, int64_t n,
@@ -431,9 +422,9 @@ covap_status_t fp16_decompress(const void *recv, int32_t n_workers, int64_t stri
         return fail(COVAP_EINVAL, "fp16_decompress: null or misaligned device pointer");
     const int pow2 = (n_workers & (n_workers - 1)) == 0;
     const float n_f = (float)n_workers;
-    k_fp16_decompress<<<blocks(n / 8 > 0 ? n / 8 : 1, kThreads), kThreads, 0, (hipStream_t)stream>>>(
-        (const uint16_t *)recv, n_workers, stride_elems, n, (float *)dense_out, n_f, 1.0f / n_f, pow2);
-    return check("fp16_decompress");
+    covap::launch_status ls;
+    ls += covap::launch(k_fp16_decompress, dim3(blocks(n / 8 > 0 ? n / 8 : 1, kThreads)), dim3(kThreads), 0, (hipStream_t)stream,  (const uint16_t *)recv, n_workers, stride_elems, n, (float *)dense_out, n_f, 1.0f / n_f, pow2);
+    return ls.report("fp16_decompress");
 }
 
 covap_status_t sparse_decompress(const void *vals, const uint32_t *idx, int32_t n_workers, int64_t k,
@@ -450,18 +441,19 @@ covap_status_t sparse_decompress(const void *vals, const uint32_t *idx, int32_t 
     hipStream_t st = (hipStream_t)stream;
     float *out = (float *)dense_out;
     const uint32_t dense_grid = blocks(n / 4 > 0 ? n / 4 : 1, kThreads);
-    k_zero<<<dense_grid, kThreads, 0, st>>>(out, n);
+    covap::launch_status ls;
+    ls += covap::launch(k_zero, dim3(dense_grid), dim3(kThreads), 0, st, out, n);
     if (k > 0) {
         for (int32_t w = 0; w < n_workers; ++w)
-            k_scatter_add<<<blocks(k, 256), 256, 0, st>>>(out, idx + (int64_t)w * stride_elems,
-                                                          (const float *)vals + (int64_t)w * stride_elems, k);
+            ls += covap::launch(k_scatter_add, dim3(blocks(k, 256)), dim3(256), 0, st, out,
+                                idx + (int64_t)w * stride_elems, (const float *)vals + (int64_t)w * stride_elems, k);
         if (n_workers > 1) {
             const int pow2 = (n_workers & (n_workers - 1)) == 0;
             const float n_f = (float)n_workers;
-            k_scale<<<dense_grid, kThreads, 0, st>>>(out, n, n_f, 1.0f / n_f, pow2);
+            ls += covap::launch(k_scale, dim3(dense_grid), dim3(kThreads), 0, st, out, n, n_f, 1.0f / n_f, pow2);
         }
     }
-    return check("sparse_decompress");
+    return ls.report("sparse_decompress");
 }
 
 covap_status_t sparse_decompress_sorted(const void *vals, const uint32_t *idx, int32_t n_workers,
@@ -498,9 +490,9 @@ covap_status_t sparse_decompress_sorted(const void *vals, const uint32_t *idx, i
                       : n_workers > 8   ? k_sparse_mean_sorted<16, false>
                       : n_workers == 8  ? k_sparse_mean_sorted<8, true>
                                         : k_sparse_mean_sorted<8, false>;
-    kern<<<grid, 64, 0, (hipStream_t)stream>>>((const float *)vals, idx, n_workers, (uint32_t)k, stride_elems, n,
-                                               (float *)dense_out, tiles_per_wg, n_f, 1.0f / n_f, pow2);
-    return check("sparse_decompress_sorted");
+    covap::launch_status ls;
+    ls += covap::launch(kern, dim3(grid), dim3(64), 0, (hipStream_t)stream, (const float *)vals, idx, n_workers, (uint32_t)k, stride_elems, n, (float *)dense_out, tiles_per_wg, n_f, 1.0f / n_f, pow2);
+    return ls.report("sparse_decompress_sorted");
 }
 
 

@@ -22,13 +22,17 @@
 
 #include <cstdint>
 #include <cstdio>
-#include <algorithm>
 #include <type_traits>
 
 #include "half_util.h"
+#include "launch.h"
 #include "plan.h"
 
 namespace {
+
+using covap::fixed_geom;
+using covap::table_geom;
+using covap::tile_ref;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -182,101 +186,6 @@ struct ops_bf16_res32 : ops_bf16 {
 struct ops_f32_pay16 : ops_f32 {
     static constexpr bool PAY16 = true;
 };
-
-// ---- tile geometry -----------------------------------------------------------
-
-// Fixed-size shards: shard s covers [s*S, min((s+1)*S, D)); every shard is cut
-// into tiles_per_shard = ceil(S / TILE) tiles.  Shard s is sent at this step
-// iff s mod K == first_sel (Definition 1 rewritten for a fixed step).  The
-// shards of one residue class all have S elements except possibly the last of
-// the arena, so the packed offset of shard s is (s / K) * S.
-//
-// All per-tile decisions are taken in 32-bit scalar arithmetic (S < 2^31); only
-// the two final offsets are 64-bit products.  64-bit compare-and-select chains
-// are avoided here on purpose: hipcc 7.2 turned `left < TILE ? left : TILE` on
-// int64 into an s_cselect that read a stale SCC, so every ragged tile ran as a
-// full one.
-struct fixed_geom {
-    int64_t S;
-    uint32_t shard_len;  // S
-    uint32_t last_len;   // elements of the last shard of the arena, 1..S
-    uint32_t n_shards;
-    int32_t K;
-    int32_t first_sel;
-    uint32_t tiles_per_shard;
-    uint32_t sh_lo;        // first shard this launch covers (per-bucket calls start mid-arena)
-    uint32_t sh_step;      // 1: every shard from sh_lo on; K: only the sent ones
-};
-
-struct tile_ref {
-    int64_t off;   // arena element offset
-    int64_t poff;  // packed element offset
-    int32_t n;     // elements in the tile, 1..TILE
-    bool sel;
-};
-
-template <int TILE>
-__device__ __forceinline__ bool resolve_tile(const fixed_geom &g, tile_ref &t)
-{
-    const uint32_t tile = blockIdx.x;
-    const uint32_t q = tile / g.tiles_per_shard;
-    const uint32_t j = tile - q * g.tiles_per_shard;
-    const uint32_t s = g.sh_lo + q * g.sh_step;
-    const uint32_t sh_len = (s + 1u == g.n_shards) ? g.last_len : g.shard_len;
-    const uint32_t in = j * (uint32_t)TILE;
-    if (in >= sh_len) return false;
-    const uint32_t left = sh_len - in;
-    t.n = (int32_t)(left < (uint32_t)TILE ? left : (uint32_t)TILE);
-    t.off = (int64_t)s * g.S + (int64_t)in;
-    t.sel = (int32_t)(s % (uint32_t)g.K) == g.first_sel;
-    t.poff = (int64_t)(s / (uint32_t)g.K) * g.S + (int64_t)in;
-    return true;
-}
-
-// Variable-length shards (median sharding): the host cuts the shards of the call
-// into segments and passes the records of up to kMaxUnits segments in the kernel
-// arguments, so no device table is ever allocated.  The grid is one-dimensional
-// and holds exactly the tiles of these segments; a workgroup finds its segment
-// by a two-level scalar search over the tile prefix.
-constexpr int kMaxUnits = 128;
-constexpr int kSegTiles = 4096;  // longest run of tiles of one kind (sent / not sent) in a launch
-
-struct table_geom {
-    int64_t off[kMaxUnits];         // arena offset of each segment (vector aligned)
-    int64_t poff[kMaxUnits];        // packed offset of each segment (vector aligned)
-    uint32_t len[kMaxUnits];        // elements; bit 31 set = its shard is sent at this step
-    uint32_t first[kMaxUnits + 1];  // first tile of each segment in this launch; [n_units] = grid size
-    uint32_t n_units;
-};
-
-template <int TILE>
-__device__ __forceinline__ bool resolve_tile(const table_geom &g, tile_ref &t)
-{
-    const uint32_t tile = blockIdx.x;
-    // Two-level scalar search, three dependent kernel-argument reads in all (a plain
-    // binary search needs eight, and a zero-fill workgroup lives hardly longer than
-    // that): eight pivots at fixed positions, then the 16 entries of one block.
-    // Unused entries hold the grid size, which no tile index reaches.
-    static_assert(kMaxUnits % 16 == 0, "blocks of 16 units");
-    uint32_t blk = 0;
-#pragma unroll
-    for (int i = 1; i < kMaxUnits / 16; ++i) blk += g.first[16 * i] <= tile ? 1u : 0u;
-    const uint32_t *f = g.first + 16 * blk;
-    uint32_t lo = 16 * blk;
-#pragma unroll
-    for (int j = 1; j < 16; ++j) lo += f[j] <= tile ? 1u : 0u;
-    const uint32_t u = lo;
-    const uint32_t word = g.len[u];
-    const uint32_t sh_len = word & 0x7fffffffu;
-    const uint32_t in = (tile - g.first[u]) * (uint32_t)TILE;
-    if (in >= sh_len) return false;
-    const uint32_t left = sh_len - in;
-    t.n = (int32_t)(left < (uint32_t)TILE ? left : (uint32_t)TILE);
-    t.off = g.off[u] + (int64_t)in;
-    t.sel = (word >> 31) != 0u;
-    t.poff = g.poff[u] + (int64_t)in;
-    return true;
-}
 
 // ---- compress: error feedback + filter + pack + residual -----------------------
 
@@ -488,7 +397,7 @@ __global__ __launch_bounds__(kThreads) void k_compress(const u32x4 *__restrict__
 {
     constexpr int TILE = kThreads * OPS::EPV * UNROLL;
     tile_ref t;
-    if (!resolve_tile<TILE>(g, t)) return;
+    if (!covap::resolve_tile(g, blockIdx.x, (uint32_t)TILE, t)) return;
     if constexpr (OPS::MIXED)
         compress_tile_mixed<kThreads, UNROLL, NT>((const uint16_t *)G, (float *)R, (uint16_t *)send, t, c);
     else if constexpr (OPS::PAY16)
@@ -511,7 +420,7 @@ __global__ __launch_bounds__(64) void k_take(u32x4 *acc, u32x4 *__restrict__ sen
     constexpr int EPV = 16 / ESZ;
     constexpr int TILE = 64 * EPV;
     tile_ref t;
-    if (!resolve_tile<TILE>(g, t)) return;
+    if (!covap::resolve_tile(g, blockIdx.x, (uint32_t)TILE, t)) return;
     const int tid = threadIdx.x;
     u32x4 *ap = acc + t.off / EPV;
     u32x4 *sp = send + t.poff / EPV;
@@ -638,7 +547,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const u32x4 *__restrict
 {
     constexpr int TILE = kThreads * OPS::EPV * UNROLL;
     tile_ref t;
-    if (!resolve_tile<TILE>(g, t)) return;
+    if (!covap::resolve_tile(g, blockIdx.x, (uint32_t)TILE, t)) return;
     decompress_tile<OPS, kThreads, UNROLL, WU, NT>(recv, out, t, N, stride_elems, n_f, inv_n, pow2);
 }
 
@@ -655,7 +564,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress_pay16(const u32x4 *__re
     using covap_dev::half_lo;
     constexpr int TILE = kThreads * 8;
     tile_ref t;
-    if (!resolve_tile<TILE>(g, t)) return;
+    if (!covap::resolve_tile(g, blockIdx.x, (uint32_t)TILE, t)) return;
     const int tid = threadIdx.x;
     float *o = out + t.off;
     if (!t.sel) {  // nothing was sent for this shard: the dense result is +0
@@ -754,42 +663,6 @@ bool overlap(const void *a, int64_t abytes, const void *b, int64_t bbytes)
     return a0 < b0 + (uintptr_t)bbytes && b0 < a0 + (uintptr_t)abytes;
 }
 
-fixed_geom make_geom(const covap_plan_s *p, const covap::call_range &cr, int tile_elems,
-                     bool sent_only, uint32_t *grid)
-{
-    fixed_geom g;
-    g.S = p->opts.shard_elems;
-    g.shard_len = (uint32_t)g.S;
-    g.n_shards = (uint32_t)p->shards.size();
-    g.last_len = p->shards.empty() ? 0u : (uint32_t)p->shards.back().len;
-    g.K = p->K;
-    g.first_sel = cr.first_sel;
-    g.tiles_per_shard = (uint32_t)((g.S + tile_elems - 1) / tile_elems);
-    const uint32_t K = (uint32_t)g.K, lo = (uint32_t)cr.sh_lo, n = (uint32_t)(cr.sh_hi - cr.sh_lo);
-    if (sent_only) {
-        const uint32_t phase = ((uint32_t)cr.first_sel + K - lo % K) % K;  // offset of the first sent shard
-        g.sh_lo = lo + phase;
-        g.sh_step = K;
-        *grid = (phase < n ? (n - phase + K - 1) / K : 0u) * g.tiles_per_shard;
-    } else {
-        g.sh_lo = lo;
-        g.sh_step = 1u;
-        *grid = n * g.tiles_per_shard;
-    }
-    return g;
-}
-
-covap_status_t check_launch(const char *what)
-{
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) {
-        char msg[200];
-        std::snprintf(msg, sizeof msg, "%s: %s", what, hipGetErrorString(e));
-        return covap::fail(COVAP_EHIP, msg);
-    }
-    return COVAP_OK;
-}
-
 // Calls f(std::integral_constant<int, V>) for the V in Vs... that equals v.
 template <int... Vs, typename F>
 bool pick(int v, F &&f)
@@ -798,98 +671,39 @@ bool pick(int v, F &&f)
 }
 
 // Runs f(geom, grid) once per launch the call needs: one launch for fixed-size
-// shards, one per kMaxUnits segments otherwise.  sent_only: cover only the shards
-// sent at this step.
+// shards, one per kMaxUnits list entries otherwise (the geometry is copied from the
+// plan's tables; nothing is allocated).  sent_only: cover only the shards sent at
+// this step.
 template <typename F>
 void for_each_launch(const covap_plan_s *plan, const covap::call_range &cr, int tile_elems,
                      bool sent_only, F &&f)
 {
     if (plan->uniform) {
         uint32_t grid = 0;
-        const fixed_geom g = make_geom(plan, cr, tile_elems, sent_only, &grid);
+        const fixed_geom g = covap::fixed_launch(plan, cr, (uint32_t)tile_elems, sent_only, &grid);
         if (grid) f(g, dim3(grid));
         return;
     }
-    // Cut every shard into segments of at most kSegTiles tiles and order the
-    // segments so that sent and unsent ones alternate in proportion.  A long run
-    // of sent tiles makes decompress run in lock-step "generations" of long-lived
-    // waves whose last, partly filled generation is pure loss; alternating with
-    // the short zero-fill tiles at this coarse grain avoids that (measured: 18 %
-    // on the VGG-19-shaped set).  Finer alternation is harmful: neighbouring
-    // workgroups would then write streams a power of two apart.
-    //
-    // The segments are produced on the fly by two cursors, one walking the sent
-    // shards of the call and one the others; nothing is allocated.
-    const int32_t K = plan->K;
-    const int64_t seg_elems = (int64_t)kSegTiles * tile_elems;
-    struct cursor {
-        const covap_plan_s *plan;
-        int32_t s, hi, K, first_sel;
-        int64_t in;  // elements of shard s already handed out
-        bool want_sent;
-        bool kind(int32_t sh) const { return (sh % K == first_sel) == want_sent; }
-        void settle()
-        {  // move to the next shard of this cursor's kind that has elements left
-            while (s < hi && (!kind(s) || in >= plan->shards[(size_t)s].len)) {
-                ++s;
-                in = 0;
-            }
-        }
-    };
-    cursor cs{plan, cr.sh_lo, cr.sh_hi, K, cr.first_sel, 0, true};
-    cursor cu{plan, cr.sh_lo, cr.sh_hi, K, cr.first_sel, 0, false};
-    size_t n_sent = 0, n_unsent = 0;
-    for (int32_t s = cr.sh_lo; s < cr.sh_hi; ++s) {
-        const size_t segs = (size_t)((plan->shards[(size_t)s].len + seg_elems - 1) / seg_elems);
-        if (s % K == cr.first_sel)
-            n_sent += segs;
-        else if (!sent_only)
-            n_unsent += segs;
-    }
-    const size_t total = n_sent + n_unsent;
-    size_t done_sent = 0, done_unsent = 0, i = 0;
-    while (i < total) {
+    const int32_t n = covap::table_launches(plan, cr, sent_only);
+    for (int32_t i = 0; i < n; ++i) {
         table_geom g;
-        uint32_t tiles = 0, units = 0;
-        for (; units < (uint32_t)kMaxUnits; ++units) {
-            g.first[units] = tiles;
-            if (i >= total) {
-                g.off[units] = 0;
-                g.poff[units] = 0;
-                g.len[units] = 0u;
-                continue;
-            }
-            const size_t want = ((i + 1) * n_sent + total - 1) / total;  // sent segments due by now
-            const bool take_sent = done_sent < n_sent && (done_sent < want || done_unsent == n_unsent);
-            cursor &c = take_sent ? cs : cu;
-            c.settle();
-            const covap_shard_rec &sh = plan->shards[(size_t)c.s];
-            const int64_t len = std::min<int64_t>(seg_elems, sh.len - c.in);
-            g.off[units] = sh.off + c.in;
-            g.poff[units] = sh.packed_off + c.in;
-            g.len[units] = (uint32_t)len | (take_sent ? 0x80000000u : 0u);
-            tiles += (uint32_t)((len + tile_elems - 1) / tile_elems);
-            c.in += len;
-            (take_sent ? done_sent : done_unsent) += 1;
-            ++i;
-        }
-        g.first[kMaxUnits] = tiles;
-        g.n_units = units;
-        if (tiles) f(g, dim3(tiles));
+        covap::table_launch(plan, cr, (uint32_t)tile_elems, sent_only, i, &g);
+        const uint32_t grid = covap::grid_of(g);
+        if (grid) f(g, dim3(grid));
     }
 }
 
 template <typename OPS>
 bool launch_compress(const covap::tuning &tn, const covap_plan_s *plan, const covap::call_range &cr,
-                     hipStream_t st, const void *G, void *R, void *send, float c)
+                     hipStream_t st, const void *G, void *R, void *send, float c, covap::launch_status &ls)
 {
     return pick<64, 256>(tn.compress_threads, [&](auto T) {
         pick<1, 2, 4>(tn.compress_unroll, [&](auto U) {
             pick<0, 1>(tn.nontemporal, [&](auto NT) {
                 for_each_launch(plan, cr, T() * OPS::EPV * U(), false, [&](const auto &g, dim3 grid) {
                     typedef std::decay_t<decltype(g)> GEOM;
-                    k_compress<OPS, GEOM, T(), U(), NT() != 0><<<grid, T(), 0, st>>>(
-                        (const u32x4 *)G, (u32x4 *)R, (u32x4 *)send, g, c);
+                    ls += covap::launch(k_compress<OPS, GEOM, T(), U(), NT() != 0>, grid, dim3(T()), 0, st,
+                                        (const u32x4 *)G, (u32x4 *)R, (u32x4 *)send, g, c);
                 });
             });
         });
@@ -899,7 +713,7 @@ bool launch_compress(const covap::tuning &tn, const covap_plan_s *plan, const co
 template <typename OPS>
 bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
                        const covap::call_range &cr, hipStream_t st, const void *recv, void *out,
-                       int32_t N, int64_t stride)
+                       int32_t N, int64_t stride, covap::launch_status &ls)
 {
     const int pow2 = (N & (N - 1)) == 0;
     const float n_f = (float)N, inv_n = 1.0f / n_f;
@@ -910,8 +724,9 @@ bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
                     for_each_launch(plan, cr, T() * OPS::EPV * U(), false, [&](const auto &g, dim3 grid) {
                         typedef std::decay_t<decltype(g)> GEOM;
                         // the LDS reservation is never touched: it only caps occupancy
-                        k_decompress<OPS, GEOM, T(), U(), WU(), NT() != 0><<<grid, T(), (size_t)tn.decompress_lds_pad, st>>>(
-                            (const u32x4 *)recv, (u32x4 *)out, g, N, stride, n_f, inv_n, pow2);
+                        ls += covap::launch(k_decompress<OPS, GEOM, T(), U(), WU(), NT() != 0>, grid, dim3(T()),
+                                            (size_t)tn.decompress_lds_pad, st, (const u32x4 *)recv, (u32x4 *)out, g,
+                                            N, stride, n_f, inv_n, pow2);
                     });
                 });
             });
@@ -923,7 +738,7 @@ bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
 // 16-byte payload vector per thread).
 bool launch_decompress_pay16(const covap::tuning &tn, const covap_plan_s *plan,
                              const covap::call_range &cr, hipStream_t st, const void *recv, void *out,
-                             int32_t N, int64_t stride)
+                             int32_t N, int64_t stride, covap::launch_status &ls)
 {
     const int pow2 = (N & (N - 1)) == 0;
     const float n_f = (float)N, inv_n = 1.0f / n_f;
@@ -932,8 +747,9 @@ bool launch_decompress_pay16(const covap::tuning &tn, const covap_plan_s *plan,
             pick<0, 1>(tn.nontemporal, [&](auto NT) {
                 for_each_launch(plan, cr, T() * 8, false, [&](const auto &g, dim3 grid) {
                     typedef std::decay_t<decltype(g)> GEOM;
-                    k_decompress_pay16<GEOM, T(), WU(), NT() != 0><<<grid, T(), (size_t)tn.decompress_lds_pad, st>>>(
-                        (const u32x4 *)recv, (float *)out, g, N, stride, n_f, inv_n, pow2);
+                    ls += covap::launch(k_decompress_pay16<GEOM, T(), WU(), NT() != 0>, grid, dim3(T()),
+                                        (size_t)tn.decompress_lds_pad, st, (const u32x4 *)recv, (float *)out, g, N,
+                                        stride, n_f, inv_n, pow2);
                 });
             });
         });
@@ -972,19 +788,20 @@ covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t b
         return fail(COVAP_EINVAL, "covap_compress: grad, residual and send must not overlap");
     if (cr.sh_hi == cr.sh_lo) return COVAP_OK;
 
-    const covap::tuning &tn = covap::tune();
+    const covap::tuning tn = covap::tune();
     hipStream_t st = (hipStream_t)stream;
+    covap::launch_status ls;
     bool ok;
     if (plan->opts.dtype == COVAP_F32)
-        ok = launch_compress<ops_f32>(tn, plan, cr, st, grad, residual, send, ef_coeff);
+        ok = launch_compress<ops_f32>(tn, plan, cr, st, grad, residual, send, ef_coeff, ls);
     else if (plan->opts.dtype == COVAP_BF16)
-        ok = launch_compress<ops_bf16>(tn, plan, cr, st, grad, residual, send, ef_coeff);
+        ok = launch_compress<ops_bf16>(tn, plan, cr, st, grad, residual, send, ef_coeff, ls);
     else if (plan->opts.dtype == COVAP_BF16_RES32)
-        ok = launch_compress<ops_bf16_res32>(tn, plan, cr, st, grad, residual, send, ef_coeff);
+        ok = launch_compress<ops_bf16_res32>(tn, plan, cr, st, grad, residual, send, ef_coeff, ls);
     else
-        ok = launch_compress<ops_f32_pay16>(tn, plan, cr, st, grad, residual, send, ef_coeff);
+        ok = launch_compress<ops_f32_pay16>(tn, plan, cr, st, grad, residual, send, ef_coeff, ls);
     if (!ok) return fail(COVAP_EINVAL, "covap_compress: launch knobs select no kernel");
-    return check_launch("covap_compress");
+    return ls.report("covap_compress");
 }
 
 covap_status_t covap_compress_aliased(const covap_plan_t *plan, uint64_t step, int32_t bucket,
@@ -1009,17 +826,15 @@ covap_status_t covap_compress_aliased(const covap_plan_t *plan, uint64_t step, i
     if (cr.sh_hi == cr.sh_lo) return COVAP_OK;
     hipStream_t st = (hipStream_t)stream;
     const bool nt = covap::tune().nontemporal != 0;
+    covap::launch_status ls;
     for_each_launch(plan, cr, 64 * plan->elems_per_vec, true, [&](const auto &g, dim3 grid) {
         typedef std::decay_t<decltype(g)> GEOM;
-        if (esz == 4) {
-            if (nt) k_take<GEOM, 4, true><<<grid, 64, 0, st>>>((u32x4 *)accum, (u32x4 *)send, g);
-            else k_take<GEOM, 4, false><<<grid, 64, 0, st>>>((u32x4 *)accum, (u32x4 *)send, g);
-        } else {
-            if (nt) k_take<GEOM, 2, true><<<grid, 64, 0, st>>>((u32x4 *)accum, (u32x4 *)send, g);
-            else k_take<GEOM, 2, false><<<grid, 64, 0, st>>>((u32x4 *)accum, (u32x4 *)send, g);
-        }
+        void (*kernel)(u32x4 *, u32x4 *, GEOM) =
+            esz == 4 ? (nt ? k_take<GEOM, 4, true> : k_take<GEOM, 4, false>)
+                     : (nt ? k_take<GEOM, 2, true> : k_take<GEOM, 2, false>);
+        ls += covap::launch(kernel, grid, dim3(64), 0, st, (u32x4 *)accum, (u32x4 *)send, g);
     });
-    return check_launch("covap_compress_aliased");
+    return ls.report("covap_compress_aliased");
 }
 
 covap_status_t covap_decompress(const covap_plan_t *plan, uint64_t step, int32_t bucket,
@@ -1044,17 +859,18 @@ covap_status_t covap_decompress(const covap_plan_t *plan, uint64_t step, int32_t
         return fail(COVAP_EINVAL, "covap_decompress: recv and dense_out must not overlap");
     if (cr.sh_hi == cr.sh_lo) return COVAP_OK;
 
-    const covap::tuning &tn = covap::tune();
+    const covap::tuning tn = covap::tune();
     hipStream_t st = (hipStream_t)stream;
+    covap::launch_status ls;
     bool ok;
     if (dt == COVAP_F32)
-        ok = launch_decompress<ops_f32>(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems);
+        ok = launch_decompress<ops_f32>(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems, ls);
     else if (dt == COVAP_F32_PAY16)
-        ok = launch_decompress_pay16(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems);
+        ok = launch_decompress_pay16(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems, ls);
     else
-        ok = launch_decompress<ops_bf16>(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems);
+        ok = launch_decompress<ops_bf16>(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems, ls);
     if (!ok) return fail(COVAP_EINVAL, "covap_decompress: launch knobs select no kernel");
-    return check_launch("covap_decompress");
+    return ls.report("covap_decompress");
 }
 
 covap_status_t covap_probe_copy(void *dst, const void *src, size_t bytes, void *stream)
@@ -1066,11 +882,10 @@ covap_status_t covap_probe_copy(void *dst, const void *src, size_t bytes, void *
     const int64_t nvec = (int64_t)(bytes / 16);
     const int64_t per = kProbeThreads;
     const uint32_t grid = (uint32_t)((nvec + per - 1) / per);
-    if (covap::tune().nontemporal)
-        k_copy<true><<<grid, kProbeThreads, 0, (hipStream_t)stream>>>((u32x4 *)dst, (const u32x4 *)src, nvec);
-    else
-        k_copy<false><<<grid, kProbeThreads, 0, (hipStream_t)stream>>>((u32x4 *)dst, (const u32x4 *)src, nvec);
-    return check_launch("covap_probe_copy");
+    covap::launch_status ls;
+    ls += covap::launch(covap::tune().nontemporal ? k_copy<true> : k_copy<false>, dim3(grid), dim3(kProbeThreads), 0,
+                        (hipStream_t)stream, (u32x4 *)dst, (const u32x4 *)src, nvec);
+    return ls.report("covap_probe_copy");
 }
 
 covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float s, int64_t n,
@@ -1083,13 +898,10 @@ covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float
     const int64_t nvec = n / 4;
     const int64_t per = kProbeThreads;
     const uint32_t grid = (uint32_t)((nvec + per - 1) / per);
-    if (covap::tune().nontemporal)
-        k_triad<true><<<grid, kProbeThreads, 0, (hipStream_t)stream>>>((u32x4 *)a, (const u32x4 *)b,
-                                                                  (const u32x4 *)c, s, nvec);
-    else
-        k_triad<false><<<grid, kProbeThreads, 0, (hipStream_t)stream>>>((u32x4 *)a, (const u32x4 *)b,
-                                                                   (const u32x4 *)c, s, nvec);
-    return check_launch("covap_probe_triad");
+    covap::launch_status ls;
+    ls += covap::launch(covap::tune().nontemporal ? k_triad<true> : k_triad<false>, dim3(grid), dim3(kProbeThreads),
+                        0, (hipStream_t)stream, (u32x4 *)a, (const u32x4 *)b, (const u32x4 *)c, s, nvec);
+    return ls.report("covap_probe_triad");
 }
 
 }  // extern "C"

@@ -4,6 +4,7 @@
 #include "plan.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -21,34 +22,51 @@ covap_status_t fail(covap_status_t st, const char *msg)
     return st;
 }
 
-covap_status_t fail(covap_status_t st, const std::string &msg) { return fail(st, msg.c_str()); }
-
 void clear_error() { g_last_error[0] = '\0'; }
 
-tuning &tune()
+static int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// Number of shard indices s < x with s mod K < c (0 <= c <= K).
+static int64_t below_class(int64_t x, int64_t c, int64_t K) { return (x / K) * c + std::min(c, x % K); }
+
+// The shards of class c inside [lo, hi): first and last index, or first >= hi if none.
+static void class_span(int32_t lo, int32_t hi, int32_t c, int32_t K, int64_t *first, int64_t *last)
 {
-    static tuning t;
-    return t;
+    const int64_t f = (int64_t)lo + (((int64_t)c - lo % K) % K + K) % K;
+    *first = f;
+    *last = f < hi ? f + ((int64_t)hi - 1 - f) / K * K : f;
 }
 
+// Packed layout: at any step the selected shards (one residue class mod K) are
+// stored in ascending shard order, each starting at the next multiple of the
+// plan's alignment unit.  A shard's packed offset therefore depends only on the
+// earlier shards of its own class -- the same number at every step that sends
+// it -- and the packed range of a bucket (or of the arena) at a step follows from
+// the first and the last shard of the step's class inside it; no table by step or
+// by class is kept.  With fixed-size shards no padding ever appears (only the
+// arena's last shard can be ragged).
 covap_status_t resolve(const covap_plan_s *plan, uint64_t step, int32_t bucket, call_range *out)
 {
     if (!plan) return fail(COVAP_EINVAL, "plan is null");
     const int32_t nb = (int32_t)plan->buckets.size();
     if (bucket < -1 || bucket >= nb) return fail(COVAP_ERANGE, "bucket out of range");
-    const int32_t r = (int32_t)(step % (uint64_t)plan->K);
-    out->first_sel = first_selected(step, plan->K);
-    if (bucket < 0) {
-        out->sh_lo = 0;
-        out->sh_hi = (int32_t)plan->shards.size();
-        out->packed_base = 0;
-        out->packed_elems = plan->packed_total[r];
-    } else {
-        const covap_bucket_rec &b = plan->buckets[bucket];
-        out->sh_lo = b.sh_lo;
-        out->sh_hi = b.sh_hi;
-        out->packed_base = b.packed_base[r];
-        out->packed_elems = b.packed_elems[r];
+    const int32_t K = plan->K, c = first_selected(step, K);
+    out->first_sel = c;
+    out->bucket = bucket;
+    out->sh_lo = bucket < 0 ? 0 : plan->buckets[(size_t)bucket].sh_lo;
+    out->sh_hi = bucket < 0 ? (int32_t)plan->shards.size() : plan->buckets[(size_t)bucket].sh_hi;
+    int64_t first, last;
+    class_span(out->sh_lo, out->sh_hi, c, K, &first, &last);
+    if (first < out->sh_hi) {
+        const covap_shard_rec &f = plan->shards[(size_t)first], &l = plan->shards[(size_t)last];
+        out->packed_base = f.packed_off;
+        out->packed_elems = l.packed_off + l.len - f.packed_off;
+    } else {  // nothing of this class here: the base is where the class would continue
+        const int64_t prev = first - K;
+        out->packed_base = prev >= 0 ? round_up(plan->shards[(size_t)prev].packed_off + plan->shards[(size_t)prev].len,
+                                                plan->align_elems)
+                                     : 0;
+        out->packed_elems = 0;
     }
     return COVAP_OK;
 }
@@ -70,48 +88,138 @@ static void assign_buckets(covap_plan_s *p, int64_t cap_elems)
     }
 }
 
-static int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+// Class-by-class list of the shards [lo, hi), appended to `list`.
+static void append_units(const covap_plan_s *p, int32_t lo, int32_t hi, covap_unit_list *list)
+{
+    const int32_t K = p->K;
+    std::vector<int32_t> order;
+    order.reserve((size_t)(hi - lo));
+    for (int32_t s = lo; s < hi; ++s) order.push_back(s);
+    std::sort(order.begin(), order.end(), [K](int32_t a, int32_t b) {
+        return a % K != b % K ? a % K < b % K : a < b;
+    });
+    for (int32_t s : order) {
+        const covap_shard_rec &sh = p->shards[(size_t)s];
+        list->off.push_back(sh.off);
+        list->poff.push_back(sh.packed_off);
+        list->len.push_back((uint32_t)sh.len);
+        for (int j = 0; j <= kTileLog2Max - kTileLog2Min; ++j) {
+            const int64_t tile = (int64_t)1 << (kTileLog2Min + j);
+            list->tiles[j].push_back(list->tiles[j].back() + (uint32_t)((sh.len + tile - 1) / tile));
+        }
+    }
+}
 
-// Packed layout: at any step the selected shards (one residue class mod K) are
-// stored in ascending shard order, each starting at the next multiple of the
-// plan's alignment unit.  A shard's packed offset therefore depends only on the
-// earlier shards of its own class -- the same number at every step that sends
-// it.  With fixed-size shards no padding ever appears (only the arena's last
-// shard can be ragged).  Also fills the per-bucket and whole-arena packed
-// extents by residue.
+// Packed offsets, bucket ranges, the largest payload, and (variable-length shards)
+// the unit lists the launches copy from.
 static void finish_tables(covap_plan_s *p)
 {
     const int32_t K = p->K;
     const int64_t al = p->align_elems;
-    const int32_t nb = p->shards.empty() ? 0 : p->shards.back().bucket + 1;
-    p->buckets.assign((size_t)nb, covap_bucket_rec());
-    for (auto &b : p->buckets) {
-        b.sh_lo = -1;
-        b.sh_hi = -1;
-        b.packed_base.assign((size_t)K, 0);
-        b.packed_elems.assign((size_t)K, 0);
-    }
-    std::vector<int64_t> end((size_t)K, 0);  // running end of each class's packed layout
-    for (size_t s = 0; s < p->shards.size(); ++s) {
+    const size_t n = p->shards.size();
+    const int32_t nb = n ? p->shards.back().bucket + 1 : 0;
+    p->buckets.assign((size_t)nb, covap_bucket_rec{-1, -1});
+    p->packed_max = 0;
+    for (size_t s = 0; s < n; ++s) {
         covap_shard_rec &sh = p->shards[s];
         covap_bucket_rec &b = p->buckets[(size_t)sh.bucket];
-        if (b.sh_lo < 0) {  // first shard of its bucket: where would each class continue?
-            b.sh_lo = (int32_t)s;
-            for (int32_t r = 0; r < K; ++r)  // r = step mod K sends class (K - r) mod K
-                b.packed_base[(size_t)r] = round_up(end[(size_t)((K - r) % K)], al);
-        }
+        if (b.sh_lo < 0) b.sh_lo = (int32_t)s;
         b.sh_hi = (int32_t)s + 1;
-        const size_t cls = s % (size_t)K;
-        sh.packed_off = round_up(end[cls], al);
-        end[cls] = sh.packed_off + sh.len;
-        const size_t r = (size_t)((K - (int32_t)cls) % K);
-        b.packed_elems[r] = end[cls] - b.packed_base[r];
+        // the previous shard of the same class, if any, ends where this one may start
+        sh.packed_off = s >= (size_t)K ? round_up(p->shards[s - (size_t)K].packed_off + p->shards[s - (size_t)K].len, al) : 0;
+        p->packed_max = std::max(p->packed_max, sh.packed_off + sh.len);
     }
-    p->packed_total.assign((size_t)K, 0);
-    p->packed_max = 0;
-    for (int32_t r = 0; r < K; ++r) {
-        p->packed_total[(size_t)r] = end[(size_t)((K - r) % K)];
-        p->packed_max = std::max(p->packed_max, p->packed_total[(size_t)r]);
+    if (p->uniform) return;
+    for (covap_unit_list *list : {&p->by_arena, &p->by_bucket})
+        for (auto &t : list->tiles) t.assign(1, 0u);
+    append_units(p, 0, (int32_t)n, &p->by_arena);
+    for (const covap_bucket_rec &b : p->buckets) append_units(p, b.sh_lo, b.sh_hi, &p->by_bucket);
+}
+
+// ---- launch geometry ---------------------------------------------------------------
+
+fixed_geom fixed_launch(const covap_plan_s *p, const call_range &cr, uint32_t tile_elems, bool sent_only,
+                        uint32_t *grid)
+{
+    fixed_geom g;
+    g.S = p->opts.shard_elems;
+    g.shard_len = (uint32_t)g.S;
+    g.n_shards = (uint32_t)p->shards.size();
+    g.last_len = p->shards.empty() ? 0u : (uint32_t)p->shards.back().len;
+    g.K = p->K;
+    g.first_sel = cr.first_sel;
+    g.tiles_per_shard = (uint32_t)((g.S + tile_elems - 1) / tile_elems);
+    const uint32_t K = (uint32_t)g.K, lo = (uint32_t)cr.sh_lo, n = (uint32_t)(cr.sh_hi - cr.sh_lo);
+    if (sent_only) {
+        const uint32_t phase = ((uint32_t)cr.first_sel + K - lo % K) % K;  // offset of the first sent shard
+        g.sh_lo = lo + phase;
+        g.sh_step = K;
+        *grid = (phase < n ? (n - phase + K - 1) / K : 0u) * g.tiles_per_shard;
+    } else {
+        g.sh_lo = lo;
+        g.sh_step = 1u;
+        *grid = n * g.tiles_per_shard;
+    }
+    return g;
+}
+
+// Positions [*ua, *ub) of the call's units in its list, and [*sa, *sb) of those of
+// the class sent at this step.
+static const covap_unit_list &call_units(const covap_plan_s *p, const call_range &cr, bool sent_only,
+                                         int64_t *ua, int64_t *ub, int64_t *sa, int64_t *sb)
+{
+    const int64_t K = p->K, c = cr.first_sel;
+    const int64_t base = cr.bucket < 0 ? 0 : cr.sh_lo;
+    *sa = base + below_class(cr.sh_hi, c, K) - below_class(cr.sh_lo, c, K);
+    *sb = base + below_class(cr.sh_hi, c + 1, K) - below_class(cr.sh_lo, c + 1, K);
+    *ua = sent_only ? *sa : base;
+    *ub = sent_only ? *sb : base + (cr.sh_hi - cr.sh_lo);
+    return cr.bucket < 0 ? p->by_arena : p->by_bucket;
+}
+
+int32_t table_launches(const covap_plan_s *p, const call_range &cr, bool sent_only)
+{
+    int64_t ua, ub, sa, sb;
+    call_units(p, cr, sent_only, &ua, &ub, &sa, &sb);
+    return (int32_t)((ub - ua + kMaxUnits - 1) / kMaxUnits);
+}
+
+void table_launch(const covap_plan_s *p, const call_range &cr, uint32_t tile_elems, bool sent_only, int32_t i,
+                  table_geom *g)
+{
+    int64_t ua, ub, sa, sb;
+    const covap_unit_list &list = call_units(p, cr, sent_only, &ua, &ub, &sa, &sb);
+    int lg = 0;
+    while (((uint32_t)1 << lg) < tile_elems) ++lg;
+    const uint32_t *tiles = list.tiles[lg - kTileLog2Min].data();
+    const int64_t pa = ua + (int64_t)i * kMaxUnits, pb = std::min<int64_t>(pa + kMaxUnits, ub);
+    const size_t cnt = (size_t)(pb - pa);
+    std::memcpy(g->off, list.off.data() + pa, cnt * sizeof(int64_t));
+    std::memcpy(g->poff, list.poff.data() + pa, cnt * sizeof(int64_t));
+    std::memcpy(g->len, list.len.data() + pa, cnt * sizeof(uint32_t));
+    for (size_t u = 0; u < cnt; ++u) g->first[u] = tiles[pa + (int64_t)u] - tiles[pa];
+    for (size_t u = cnt; u < (size_t)kMaxUnits; ++u) {  // never looked up: no tile index reaches kNoTile
+        g->off[u] = 0;
+        g->poff[u] = 0;
+        g->len[u] = 0u;
+        g->first[u] = kNoTile;
+    }
+    g->first[kMaxUnits] = kNoTile;
+    const uint32_t total = tiles[pb] - tiles[pa];
+    const int64_t ca = std::min(std::max(sa, pa), pb), cb = std::min(std::max(sb, pa), pb);  // sent units of this launch
+    g->sent_lo = tiles[ca] - tiles[pa];
+    g->n_sent = tiles[cb] - tiles[ca];
+    g->n_unsent = total - g->n_sent;
+    // deal sent and unsent tiles out in alternating blocks when there are enough of both
+    const uint32_t fewer = std::min(g->n_sent, g->n_unsent);
+    g->mixed = fewer > 0u ? 1u : 0u;
+    g->g_shift = 12;
+    while (g->g_shift > 6 && fewer < (4u << g->g_shift)) --g->g_shift;
+    g->rho = 0u;
+    if (g->mixed) {
+        const uint64_t G = (uint64_t)1 << g->g_shift;
+        const uint64_t bs = (g->n_sent + G - 1) >> g->g_shift, bu = (g->n_unsent + G - 1) >> g->g_shift;
+        g->rho = (uint32_t)(((bs << 32) + (bs + bu) - 1) / (bs + bu));  // ceil(bs * 2^32 / (bs + bu)) < 2^32 as bu >= 1
     }
 }
 
@@ -203,6 +311,49 @@ static void build_median(covap_plan_s *p, const int64_t *numel, int32_t n, int64
 
 using namespace covap;
 
+// Largest arena: the size up to which the kernels' grids and 64-bit offsets have been
+// run on the hardware (2^33 elements: 32 GiB of fp32 per buffer).
+static constexpr int64_t kMaxTotalElems = (int64_t)1 << 33;
+
+namespace {
+struct knob {
+    const char *key;
+    int covap::tuning::*field;
+    int initial;
+    int allowed[4];  // -1 ends the list
+};
+const knob kKnobs[] = {
+    {"compress_threads", &covap::tuning::compress_threads, 64, {64, 256, -1, -1}},
+    {"compress_unroll", &covap::tuning::compress_unroll, 1, {1, 2, 4, -1}},
+    {"decompress_threads", &covap::tuning::decompress_threads, 64, {64, 256, -1, -1}},
+    {"decompress_tile", &covap::tuning::decompress_tile, 1, {1, 2, 4, -1}},
+    {"decompress_unroll", &covap::tuning::decompress_unroll, 1, {1, 2, 4, -1}},
+    {"nontemporal", &covap::tuning::nontemporal, 1, {0, 1, -1, -1}},
+    {"decompress_lds_pad", &covap::tuning::decompress_lds_pad, 6144, {0, 6144, 8192, -1}},
+    {"topk_pass1_waves", &covap::tuning::topk_pass1_waves, 4, {1, 2, 4, -1}},
+    {"topk_pass1_lds_pad", &covap::tuning::topk_pass1_lds_pad, 0, {0, 6144, 8192, 24576}},
+};
+constexpr int kNumKnobs = (int)(sizeof kKnobs / sizeof kKnobs[0]);
+
+// The knobs' current values; -1 = never set (the knob's initial value applies).
+std::atomic<int> g_knob[kNumKnobs] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
+
+int knob_value(int i)
+{
+    const int v = g_knob[i].load(std::memory_order_relaxed);
+    return v < 0 ? kKnobs[i].initial : v;
+}
+}  // namespace
+
+namespace covap {
+tuning tune()
+{
+    tuning t;
+    for (int i = 0; i < kNumKnobs; ++i) t.*(kKnobs[i].field) = knob_value(i);
+    return t;
+}
+}  // namespace covap
+
 extern "C" {
 
 covap_status_t covap_plan(const int64_t *tensor_numel, int32_t n_tensors,
@@ -225,8 +376,7 @@ covap_status_t covap_plan(const int64_t *tensor_numel, int32_t n_tensors,
     for (int32_t i = 0; i < n_tensors; ++i) {
         if (tensor_numel[i] < 0) return fail(COVAP_EINVAL, "covap_plan: negative element count");
         total += tensor_numel[i];
-        if (total >= ((int64_t)1 << 38))  // keeps every grid below 2^31 workgroups
-            return fail(COVAP_EINVAL, "covap_plan: total elements >= 2^38");
+        if (total > kMaxTotalElems) return fail(COVAP_EINVAL, "covap_plan: more than 2^33 elements in all");
     }
     if (opts->mode != COVAP_SHARD_FIXED && opts->mode != COVAP_SHARD_MEDIAN)
         return fail(COVAP_EINVAL, "covap_plan: unknown mode");
@@ -265,8 +415,12 @@ covap_status_t covap_plan(const int64_t *tensor_numel, int32_t n_tensors,
                 delete p;
                 return fail(COVAP_EINVAL, "covap_plan: a shard exceeds 2^31 - 1 elements");
             }
+        if (p->total_elems > kMaxTotalElems) {  // alignment padding of variable-length shards counts
+            delete p;
+            return fail(COVAP_EINVAL, "covap_plan: more than 2^33 elements in all");
+        }
         finish_tables(p);
-    } catch (const std::bad_alloc &) {
+    } catch (...) {  // bad_alloc, or length_error from a vector: nothing may cross the C boundary
         delete p;
         return fail(COVAP_ENOMEM, "covap_plan: out of host memory");
     }
@@ -382,37 +536,20 @@ covap_status_t covap_ef_coeff(float init_value, uint64_t num_steps, uint64_t asc
     return COVAP_OK;
 }
 
-namespace {
-struct knob {
-    const char *key;
-    int covap::tuning::*field;
-    int allowed[5];  // 0-terminated unless the knob allows 0 (then -1-terminated)
-};
-const knob kKnobs[] = {
-    {"compress_threads", &covap::tuning::compress_threads, {64, 256, -1, -1, -1}},
-    {"compress_unroll", &covap::tuning::compress_unroll, {1, 2, 4, -1, -1}},
-    {"decompress_threads", &covap::tuning::decompress_threads, {64, 256, -1, -1, -1}},
-    {"decompress_tile", &covap::tuning::decompress_tile, {1, 2, 4, -1, -1}},
-    {"decompress_unroll", &covap::tuning::decompress_unroll, {1, 2, 4, -1, -1}},
-    {"nontemporal", &covap::tuning::nontemporal, {0, 1, -1, -1, -1}},
-    {"decompress_lds_pad", &covap::tuning::decompress_lds_pad, {0, 6144, 8192, -1, -1}},
-    {"topk_pass1_waves", &covap::tuning::topk_pass1_waves, {1, 2, 4, -1, -1}},
-    {"topk_pass1_lds_pad", &covap::tuning::topk_pass1_lds_pad, {0, 6144, 8192, 24576, -1}},
-};
-}  // namespace
-
 covap_status_t covap_tune_set(const char *key, int32_t value)
 {
     clear_error();
     if (!key) return fail(COVAP_EINVAL, "covap_tune_set: null key");
-    for (const knob &k : kKnobs) {
-        if (std::strcmp(key, k.key)) continue;
-        for (int a : k.allowed)
+    for (int i = 0; i < kNumKnobs; ++i) {
+        if (std::strcmp(key, kKnobs[i].key)) continue;
+        for (int a : kKnobs[i].allowed)
             if (a >= 0 && a == value) {
-                tune().*(k.field) = value;
+                g_knob[i].store(value, std::memory_order_relaxed);
                 return COVAP_OK;
             }
-        return fail(COVAP_EINVAL, std::string("covap_tune_set: value not allowed for ") + key);
+        char msg[160];
+        std::snprintf(msg, sizeof msg, "covap_tune_set: value %d not allowed for %s", (int)value, kKnobs[i].key);
+        return fail(COVAP_EINVAL, msg);
     }
     return fail(COVAP_EINVAL, "covap_tune_set: unknown key");
 }
@@ -420,9 +557,57 @@ covap_status_t covap_tune_set(const char *key, int32_t value)
 int32_t covap_tune_get(const char *key)
 {
     if (!key) return -1;
-    for (const knob &k : kKnobs)
-        if (!std::strcmp(key, k.key)) return tune().*(k.field);
+    for (int i = 0; i < kNumKnobs; ++i)
+        if (!std::strcmp(key, kKnobs[i].key)) return knob_value(i);
     return -1;
+}
+
+int64_t covap_plan_trace(const covap_plan_t *plan, uint64_t step, int32_t bucket, int32_t tile_elems,
+                         int32_t sent_only, int64_t cap, int64_t *off, int64_t *poff, int32_t *n,
+                         uint8_t *sel, int32_t *n_launches, int64_t *n_workgroups)
+{
+    clear_error();
+    call_range cr;
+    if (resolve(plan, step, bucket, &cr) != COVAP_OK) return -1;
+    if (tile_elems < (1 << kTileLog2Min) || tile_elems > (1 << kTileLog2Max) || (tile_elems & (tile_elems - 1))) {
+        fail(COVAP_EINVAL, "covap_plan_trace: tile_elems must be a power of two in 256..8192");
+        return -1;
+    }
+    int64_t count = 0, groups = 0;
+    int32_t launches = 0;
+    auto replay = [&](const auto &g, uint32_t grid) {
+        if (grid == 0u) return;
+        ++launches;
+        groups += grid;
+        for (uint32_t b = 0; b < grid; ++b) {
+            tile_ref t;
+            if (!resolve_tile(g, b, (uint32_t)tile_elems, t)) continue;
+            if (count < cap) {
+                if (off) off[count] = t.off;
+                if (poff) poff[count] = t.poff;
+                if (n) n[count] = t.n;
+                if (sel) sel[count] = t.sel ? 1 : 0;
+            }
+            ++count;
+        }
+    };
+    if (cr.sh_hi > cr.sh_lo) {
+        if (plan->uniform) {
+            uint32_t grid = 0;
+            const fixed_geom g = fixed_launch(plan, cr, (uint32_t)tile_elems, sent_only != 0, &grid);
+            replay(g, grid);
+        } else {
+            const int32_t nl = table_launches(plan, cr, sent_only != 0);
+            for (int32_t i = 0; i < nl; ++i) {
+                table_geom g;
+                table_launch(plan, cr, (uint32_t)tile_elems, sent_only != 0, i, &g);
+                replay(g, grid_of(g));
+            }
+        }
+    }
+    if (n_launches) *n_launches = launches;
+    if (n_workgroups) *n_workgroups = groups;
+    return count;
 }
 
 const char *covap_last_error(void) { return g_last_error; }

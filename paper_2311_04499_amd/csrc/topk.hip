@@ -40,6 +40,7 @@
 #include <cstdint>
 #include <cstdio>
 
+#include "launch.h"
 #include "plan.h"
 
 namespace {
@@ -914,17 +915,6 @@ __global__ __launch_bounds__(256) void k_topk_slots_write(float *R, int64_t n,
                    kmax);
 }
 
-covap_status_t check(const char *what)
-{
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) {
-        char msg[200];
-        std::snprintf(msg, sizeof msg, "%s: %s", what, hipGetErrorString(e));
-        return covap::fail(COVAP_EHIP, msg);
-    }
-    return COVAP_OK;
-}
-
 // Argument checks shared by the entry points; `what` names the caller in the message.
 covap_status_t check_topk_args(const char *what, const void *grad, const void *residual, int64_t n, int64_t k,
                                int32_t dtype, const void *out_vals, const uint32_t *out_idx)
@@ -959,9 +949,10 @@ covap_status_t check_topk_args(const char *what, const void *grad, const void *r
 // `workspace` holds at least ws_layout(n) bytes on a 256-byte boundary.  The first
 // kernel resets every part of the workspace that a later one adds to, so stale
 // contents are harmless.
-void run_topk(const void *grad, void *residual, int64_t n, int64_t k, float ef_coeff, void *out_vals,
-              uint32_t *out_idx, void *workspace, hipStream_t st)
+covap::launch_status run_topk(const void *grad, void *residual, int64_t n, int64_t k, float ef_coeff,
+                              void *out_vals, uint32_t *out_idx, void *workspace, hipStream_t st)
 {
+    covap::launch_status ls;
     topk_ws ws;
     ws_layout(n, workspace, &ws);
     const float *G = (const float *)grad;
@@ -987,43 +978,35 @@ void run_topk(const void *grad, void *residual, int64_t n, int64_t k, float ef_c
     // the general tail's tile kernels walk the tiles with a bounded grid, so that
     // they cost next to nothing when they are not taken
     const uint32_t tail_grid = (uint32_t)(ntiles < 16384 ? ntiles : 16384);
-    k_topk_sample<<<kSlotGrid, kSampleThreads, 0, st>>>(G, R, ef_coeff, nchunks_s, n_s, ws.state, ws.hist, hs,
-                                                        (uint32_t)k);
-    k_topk_pick<0, kAlways><<<1, kPickThreads, 0, st>>>(ws.state, hs, kSlotGrid, target);
-    const covap::tuning &tn = covap::tune();
+    ls += covap::launch(k_topk_sample, dim3(kSlotGrid), dim3(kSampleThreads), 0, st, G, R, ef_coeff, nchunks_s, n_s, ws.state, ws.hist, hs, (uint32_t)k);
+    ls += covap::launch(k_topk_pick<0, kAlways>, dim3(1), dim3(kPickThreads), 0, st, ws.state, hs, kSlotGrid, target);
+    const covap::tuning tn = covap::tune();
     const auto pass1 = tn.topk_pass1_waves == 4 ? k_topk_pass1<4> : (tn.topk_pass1_waves == 2 ? k_topk_pass1<2> : k_topk_pass1<1>);
-    pass1<<<(uint32_t)ntiles, 64 * tn.topk_pass1_waves, (size_t)tn.topk_pass1_lds_pad, st>>>(
-        G, R, n, ef_coeff, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.crowded);
+    ls += covap::launch(pass1, dim3((uint32_t)ntiles), dim3(64 * tn.topk_pass1_waves), (size_t)tn.topk_pass1_lds_pad, st,  G, R, n, ef_coeff, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.crowded);
     if (k > 0) {
         // slot tail (every kernel returns at once when the general tail is switched on)
-        k_topk_slots_hist<1><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles,
-                                                                 ws.crowded, R, n, h1s);
-        k_topk_pick<1, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h1s, kSlotGrid, crowded_limit(ntiles));
-        k_topk_slots_hist<2><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles,
-                                                                 ws.crowded, R, n, h2s);
-        k_topk_pick<2, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h2s, kSlotGrid, 0u);
-        k_topk_slots_hist<3><<<kSlotGrid, kSlotThreads, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles,
-                                                                 ws.crowded, R, n, h3s);
-        k_topk_pick<3, kSlotTail><<<1, kPickThreads, 0, st>>>(ws.state, h3s, kSlotGrid, 0u);
-        k_topk_slots_count<<<slot_vec_grid, 256, 0, st>>>(ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.crowded, R, n,
-                                                          ws.cnt_gt, ws.cnt_eq);
+        ls += covap::launch(k_topk_slots_hist<1>, dim3(kSlotGrid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.crowded, R, n, h1s);
+        ls += covap::launch(k_topk_pick<1, kSlotTail>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h1s, kSlotGrid, crowded_limit(ntiles));
+        ls += covap::launch(k_topk_slots_hist<2>, dim3(kSlotGrid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.crowded, R, n, h2s);
+        ls += covap::launch(k_topk_pick<2, kSlotTail>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h2s, kSlotGrid, 0u);
+        ls += covap::launch(k_topk_slots_hist<3>, dim3(kSlotGrid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.crowded, R, n, h3s);
+        ls += covap::launch(k_topk_pick<3, kSlotTail>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h3s, kSlotGrid, 0u);
+        ls += covap::launch(k_topk_slots_count, dim3(slot_vec_grid), dim3(256), 0, st, ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.crowded, R, n, ws.cnt_gt, ws.cnt_eq);
         // general tail (returns at once otherwise)
-        k_topk_hist<1><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(R, n, ws.state, h1g);
-        k_topk_pick<1, kGeneralTail><<<1, kPickThreads, 0, st>>>(ws.state, h1g, 1, 0u);
-        k_topk_hist<2><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(R, n, ws.state, h2g);
-        k_topk_pick<2, kGeneralTail><<<1, kPickThreads, 0, st>>>(ws.state, h2g, 1, 0u);
-        k_topk_hist<3><<<(uint32_t)hist_grid, kHistThreads, 0, st>>>(R, n, ws.state, h3g);
-        k_topk_pick<3, kGeneralTail><<<1, kPickThreads, 0, st>>>(ws.state, h3g, 1, 0u);
-        k_topk_count<<<tail_grid, 64, 0, st>>>(R, n, ntiles, ws.state, ws.cnt_gt, ws.cnt_eq);
+        ls += covap::launch(k_topk_hist<1>, dim3((uint32_t)hist_grid), dim3(kHistThreads), 0, st, R, n, ws.state, h1g);
+        ls += covap::launch(k_topk_pick<1, kGeneralTail>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h1g, 1, 0u);
+        ls += covap::launch(k_topk_hist<2>, dim3((uint32_t)hist_grid), dim3(kHistThreads), 0, st, R, n, ws.state, h2g);
+        ls += covap::launch(k_topk_pick<2, kGeneralTail>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h2g, 1, 0u);
+        ls += covap::launch(k_topk_hist<3>, dim3((uint32_t)hist_grid), dim3(kHistThreads), 0, st, R, n, ws.state, h3g);
+        ls += covap::launch(k_topk_pick<3, kGeneralTail>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h3g, 1, 0u);
+        ls += covap::launch(k_topk_count, dim3(tail_grid), dim3(64), 0, st, R, n, ntiles, ws.state, ws.cnt_gt, ws.cnt_eq);
         // common: exclusive scan of the per-tile counts, then the ordered write
-        k_topk_scan_a<<<(uint32_t)nchunks, 256, 0, st>>>(ws.cnt_gt, ws.cnt_eq, ntiles, ws.chunk_gt, ws.chunk_eq);
-        k_topk_scan_b<<<1, 256, 0, st>>>(ws.chunk_gt, ws.chunk_eq, nchunks);
-        k_topk_slots_write<<<slot_vec_grid, 256, 0, st>>>(R, n, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits,
-                                                          ws.crowded, ws.cnt_gt, ws.cnt_eq, ws.chunk_gt, ws.chunk_eq,
-                                                          ntiles, (float *)out_vals, out_idx, (uint32_t)k);
-        k_topk_write<<<tail_grid, 64, 0, st>>>(R, n, ws.state, ws.cnt_gt, ws.cnt_eq, ws.chunk_gt,
-                                                     ws.chunk_eq, ntiles, (float *)out_vals, out_idx, (uint32_t)k);
+        ls += covap::launch(k_topk_scan_a, dim3((uint32_t)nchunks), dim3(256), 0, st, ws.cnt_gt, ws.cnt_eq, ntiles, ws.chunk_gt, ws.chunk_eq);
+        ls += covap::launch(k_topk_scan_b, dim3(1), dim3(256), 0, st, ws.chunk_gt, ws.chunk_eq, nchunks);
+        ls += covap::launch(k_topk_slots_write, dim3(slot_vec_grid), dim3(256), 0, st, R, n, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.crowded, ws.cnt_gt, ws.cnt_eq, ws.chunk_gt, ws.chunk_eq, ntiles, (float *)out_vals, out_idx, (uint32_t)k);
+        ls += covap::launch(k_topk_write, dim3(tail_grid), dim3(64), 0, st, R, n, ws.state, ws.cnt_gt, ws.cnt_eq, ws.chunk_gt, ws.chunk_eq, ntiles, (float *)out_vals, out_idx, (uint32_t)k);
     }
+    return ls;
 }
 
 // ---- the workspace of topk_compress_static ----------------------------------------------
@@ -1092,8 +1075,8 @@ covap_status_t topk_compress(const void *grad, void *residual, int64_t n, int64_
     if ((uintptr_t)workspace & 255u) return covap::fail(COVAP_EINVAL, "topk_compress: misaligned device pointer");
     if (ws_bytes < ws_layout(n, nullptr, nullptr))
         return covap::fail(COVAP_EINVAL, "topk_compress: workspace too small");
-    run_topk(grad, residual, n, k, ef_coeff, out_vals, out_idx, workspace, (hipStream_t)stream);
-    return check("topk_compress");
+    return run_topk(grad, residual, n, k, ef_coeff, out_vals, out_idx, workspace, (hipStream_t)stream)
+        .report("topk_compress");
 }
 
 int64_t topk_static_max_elems(void) { return kStaticMaxN; }
@@ -1113,8 +1096,8 @@ covap_status_t topk_compress_static(const void *grad, void *residual, int64_t n,
     void *workspace = nullptr;
     const covap_status_t ws = static_workspace(&workspace);
     if (ws != COVAP_OK) return ws;
-    run_topk(grad, residual, n, k, ef_coeff, out_vals, out_idx, workspace, (hipStream_t)stream);
-    return check("topk_compress_static");
+    return run_topk(grad, residual, n, k, ef_coeff, out_vals, out_idx, workspace, (hipStream_t)stream)
+        .report("topk_compress_static");
 }
 
 }  // extern "C"

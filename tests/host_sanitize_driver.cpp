@@ -56,6 +56,51 @@ static int exercise(const std::vector<int64_t> &numel, int32_t mode, int32_t dty
         }
         CHECK(prev <= covap_plan_packed_elems(p, t, -1));
     }
+    // replay of the launch geometry: the tiles of a call add up to the elements of its shards,
+    // stay inside the arena, and the sent ones stay inside the step's payload
+    const bool small = covap_plan_total_elems(p) < (1 << 20);
+    for (uint64_t t = 0; t < (uint64_t)(small ? K + 1 : 2) && t < 5; ++t) {
+        for (int32_t b = -1; b < (small ? nb : 0); ++b) {
+            for (int32_t tile : {256, 8192}) {
+                for (int32_t sent_only = 0; sent_only < 2; ++sent_only) {
+                    int32_t launches = 0;
+                    int64_t groups = 0;
+                    const int64_t cnt = covap_plan_trace(p, t, b, tile, sent_only, 0, nullptr, nullptr, nullptr,
+                                                         nullptr, &launches, &groups);
+                    CHECK(cnt >= 0 && groups >= cnt);
+                    std::vector<int64_t> off((size_t)cnt + 1), poff((size_t)cnt + 1);
+                    std::vector<int32_t> n((size_t)cnt + 1);
+                    std::vector<uint8_t> sel((size_t)cnt + 1);
+                    CHECK(covap_plan_trace(p, t, b, tile, sent_only, cnt, off.data(), poff.data(), n.data(),
+                                           sel.data(), nullptr, nullptr) == cnt);
+                    int64_t elems = 0, sent = 0;
+                    for (int64_t i = 0; i < cnt; ++i) {
+                        CHECK(n[(size_t)i] >= 1 && n[(size_t)i] <= tile && off[(size_t)i] >= 0);
+                        CHECK(off[(size_t)i] + n[(size_t)i] <= covap_plan_total_elems(p));
+                        elems += n[(size_t)i];
+                        if (sel[(size_t)i]) {
+                            sent += n[(size_t)i];
+                            CHECK(poff[(size_t)i] >= covap_plan_packed_base(p, t, b));
+                            CHECK(poff[(size_t)i] + n[(size_t)i] <=
+                                  covap_plan_packed_base(p, t, b) + covap_plan_packed_elems(p, t, b));
+                        }
+                    }
+                    int64_t want = 0, want_sent = 0;
+                    int32_t lo = 0, hi = ns;
+                    if (b >= 0) CHECK(covap_plan_bucket(p, b, &lo, &hi) == COVAP_OK);
+                    for (int32_t s = lo; s < hi; ++s) {
+                        int64_t len;
+                        CHECK(covap_plan_shard(p, s, nullptr, &len, nullptr) == COVAP_OK);
+                        const bool is_sent = covap_plan_is_selected(p, t, s) == 1;
+                        if (is_sent) want_sent += len;
+                        if (is_sent || !sent_only) want += len;
+                    }
+                    CHECK(elems == want && sent == want_sent);
+                }
+            }
+        }
+    }
+    CHECK(covap_plan_trace(p, 0, -1, 100, 0, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr) == -1);
     CHECK(covap_plan_shard(p, ns, nullptr, nullptr, nullptr) == COVAP_ERANGE);
     CHECK(covap_plan_packed_elems(p, 0, nb) == -1);
     CHECK(covap_plan_tensor_offset(p, (int32_t)numel.size()) == -1);

@@ -178,11 +178,13 @@ def test_argument_errors(B):
     idx = torch.zeros(10, dtype=torch.int32, device=DEV)
     v = torch.zeros(10, device=DEV)
     with pytest.raises(B.CovapError):
-        B.randk_compress(G, R, idx, v, k=101)
+        B.randk_compress(G, R, torch.zeros(101, dtype=torch.int32, device=DEV), torch.zeros(101, device=DEV), k=101)
+    with pytest.raises(ValueError):                                  # the binding refuses short buffers itself
+        B.randk_compress(G, R, idx, v, k=11)
     with pytest.raises(B.CovapError):
         B.fp16_compress(G[1:], R, h)
     with pytest.raises(B.CovapError):
-        B.fp16_decompress(h.view(1, 104), G, n=100, n_workers=2, stride_elems=50)
+        B.fp16_decompress(torch.zeros(208, dtype=torch.float16, device=DEV), G, n=100, n_workers=2, stride_elems=50)
     with pytest.raises(B.CovapError):
         B.sparse_decompress(v.view(1, 10), idx.view(1, 10), G, n_workers=0)
     torch.cuda.synchronize()

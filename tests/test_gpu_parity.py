@@ -248,7 +248,23 @@ def test_argument_errors(B):
         B.covap_compress(plan, 0, G, R, send, send_cap_elems=10)
     assert e.value.status == 1
     with pytest.raises(B.CovapError):
-        B.covap_compress(plan, 0, G[1:], R, send)               # misaligned
+        B.covap_compress(plan, 0, torch.zeros(10_001, device=DEV)[1:], R, send)   # misaligned
+    # the binding refuses buffers that are too small or of the wrong element width before any address is taken
+    with pytest.raises(ValueError):
+        B.covap_compress(plan, 0, G[:9_999], R, send)
+    with pytest.raises(ValueError):
+        B.covap_compress(plan, 0, G, R.to(torch.bfloat16), send)
+    with pytest.raises(ValueError):
+        B.covap_compress(plan, 0, G, R, send, send_cap_elems=send.numel() + 1)
+    with pytest.raises(ValueError):
+        B.covap_decompress(plan, 0, send, G[:9_000], n_workers=1, stride_elems=send.numel())
+    with pytest.raises(ValueError):
+        B.covap_decompress(plan, 0, send, G, n_workers=2, stride_elems=send.numel())     # second row missing
+    mplan = B.covap_plan([1000, 1000], 0, 2, bucket_cap_bytes=4, mode=B.COVAP_SHARD_MEDIAN)
+    assert mplan.total_elems == 2024                            # 1 KiB padding after the first tensor
+    with pytest.raises(ValueError):
+        B.covap_compress(mplan, 0, torch.zeros(2000, device=DEV), torch.zeros(2024, device=DEV),
+                         torch.zeros(1024, device=DEV))
     with pytest.raises(B.CovapError):
         B.covap_compress(plan, 0, G, G, send)                   # overlap
     with pytest.raises(B.CovapError) as e:
@@ -257,37 +273,9 @@ def test_argument_errors(B):
     with pytest.raises(B.CovapError):
         B.covap_decompress(plan, 0, send, G, n_workers=0, stride_elems=send.numel())
     with pytest.raises(B.CovapError):
-        B.covap_decompress(plan, 0, send, G, n_workers=2, stride_elems=send.numel() // 2 - 1)
+        B.covap_decompress(plan, 0, torch.zeros(2 * send.numel(), device=DEV), G, n_workers=2,
+                           stride_elems=send.numel() // 2 - 1)       # rows shorter than the payload
     torch.cuda.synchronize()
-
-
-def test_full_size_gpt2_medium_in_bench_configuration(B):
-    """The benchmark's own workload, shapes and launch configuration (payload
-    mode, default knobs), every element compared with the oracle: step 14 sends
-    the short last shard, step 3 does not; the residual carries over."""
-    wl = workloads.config(5)
-    plan, tab = make_plans(B, wl.numel, wl.shard_elems, wl.K)
-    D, N, K = wl.D, wl.n_workers, wl.K
-    stride = (plan.packed_elems_max + 3) // 4 * 4
-    recv = torch.empty(N, stride, device=DEV)
-    recv[1:] = workloads.payload_rows(wl, N - 1, stride, 0, DEV)
-    R = workloads.gradient(wl, 1, 0, DEV)                 # a non-trivial starting residual
-    Rc = to_np(R)
-    out = torch.empty(D, device=DEV)
-    for t in (14, 3):
-        G = workloads.gradient(wl, 0, t, DEV)
-        B.covap_compress(plan, t, G, R, recv[0])
-        B.covap_decompress(plan, t, recv, out, n_workers=N, stride_elems=stride)
-        torch.cuda.synchronize()
-        recv_c = to_np(recv)
-        recv_c[0, :] = np.nan
-        oracle.compress(tab, K, t, to_np(G), Rc, recv_c[0])
-        P = plan.packed_elems(t)
-        assert_same(to_np(recv[0])[:P], recv_c[0, :P], f"send t={t}")
-        assert_same(to_np(R), Rc, f"residual t={t}")
-        out_c = np.empty(D, np.float32)
-        oracle.decompress(tab, K, t, recv_c, out_c)           # row 0 is the oracle's own payload
-        assert_same(to_np(out), out_c, f"dense t={t}")
 
 
 # ------------------------------------------------------------------ median sharding (Sec. III-C)
@@ -299,6 +287,9 @@ MEDIAN_CASES = [
     ([1_003, 2_001, 30_007, 5, 4_099, 17, 90_001, 3], 3, 20_000, 0),           # ragged everywhere
     ([257] * 300, 5, 4, 0),                                                    # more shards than one launch carries
     ([100_000, 7], 16, 1 << 20, 1_000),                                        # capped at K pieces
+    ([3_000_000, 5], 2, 25 << 20, 0),                                          # a shard of ~12 k tiles beside a tiny one
+    ([2_500_000, 7], 2, 4, 0),                                                 # the same, one layer per tensor
+    ([9_000_000, 300, 2_000_000, 11], 3, 4, 1_000_000),                        # pieces of ~3 M elements
 ]
 
 
@@ -326,6 +317,28 @@ def test_median_sharded_bf16_and_knobs(B):
             B.covap_tune_set(k, v)
     plans = make_median_plans(B, layers, 4, dtype=torch.bfloat16, cap_bytes=40_000)
     run_iterations(B, wl, layers, 0, 4, 3, 9, dtype=torch.bfloat16, plans=plans, c=0.25)
+
+
+def test_median_sharded_long_shards_bf16_and_largest_launch_shapes(B):
+    """Shards of millions of elements with the largest tiles (8192 elements) and in bf16, whole-arena and
+    bucket by bucket: sent and unsent tiles are dealt out in alternating blocks inside one launch."""
+    layers = [2_500_000, 7, 1_300_001]
+    wl = workloads.scaled_down(workloads.config(3), layers, 4096)
+    old = {k: B.covap_tune_get(k) for k in KNOBS}
+    try:
+        for k in KNOBS:
+            B.covap_tune_set(k, KNOBS[k][-1])
+        for dtype in (torch.float32, torch.bfloat16):
+            plans = make_median_plans(B, layers, 2, dtype=dtype, cap_bytes=4)
+            run_iterations(B, wl, layers, 0, 2, 3, 3, dtype=dtype, plans=plans)
+            plans = make_median_plans(B, layers, 2, dtype=dtype, cap_bytes=4)
+            run_iterations(B, wl, layers, 0, 2, 2, 3, dtype=dtype, plans=plans, per_bucket=True, c=0.5)
+    finally:
+        for k, v in old.items():
+            B.covap_tune_set(k, v)
+    for dtype in (torch.float32, torch.bfloat16):
+        plans = make_median_plans(B, layers, 3, dtype=dtype, cap_bytes=25 << 20, ref=400_000)
+        run_iterations(B, wl, layers, 0, 3, 2, 7, dtype=dtype, plans=plans)
 
 
 # ------------------------------------------------------------------ HIP graph capture
@@ -520,45 +533,6 @@ def test_aliased_rejects_mixed_precision(B):
     with pytest.raises(B.CovapError) as e:
         B.covap_compress_aliased(plan, 0, a, s)
     assert e.value.status == 5
-
-
-# ------------------------------------------------------------------ the other configurations at full size
-
-@pytest.mark.parametrize("cfg,dtype", [(2, torch.float32), (3, torch.float32), (4, torch.float32),
-                                       (4, torch.bfloat16)])
-def test_full_size_configurations(B, cfg, dtype):
-    """ResNet-50-, VGG-19- and BERT-base-shaped sets at their real sizes, shard
-    sizes, worker counts and intervals (BERT's from CCR = 6), payload mode, two
-    steps with the residual carried over; every element against the oracle."""
-    wl = workloads.config(cfg)
-    K = B.covap_ratio_from_ccr(6.0) if cfg == 4 else wl.K
-    assert K == wl.K
-    plan, tab = make_plans(B, wl.numel, wl.shard_elems, K, dtype)
-    D, N = wl.D, wl.n_workers
-    epv = 4 if dtype == torch.float32 else 8
-    stride = (plan.packed_elems_max + epv - 1) // epv * epv
-    recv = torch.empty(N, stride, dtype=dtype, device=DEV)
-    recv[1:] = workloads.payload_rows(wl, N - 1, stride, 0, DEV, dtype)
-    R = torch.zeros(D, dtype=dtype, device=DEV)
-    Rc = to_np(R)
-    out = torch.empty(D, dtype=dtype, device=DEV)
-    last = tab.n_shards - 1
-    t_last = (K - last % K) % K                              # the step that sends the short last shard
-    for t in (t_last + K - 1, t_last + K):                   # one step before it, then that step
-        G = workloads.gradient(wl, 0, t, DEV, dtype)
-        B.covap_compress(plan, t, G, R, recv[0])
-        B.covap_decompress(plan, t, recv, out, n_workers=N, stride_elems=stride)
-        torch.cuda.synchronize()
-        P = plan.packed_elems(t)
-        recv_c = to_np(recv)
-        sent_gpu = recv_c[0, :P].copy()
-        oracle.compress(tab, K, t, to_np(G), Rc, recv_c[0])
-        assert_same(sent_gpu, recv_c[0, :P], f"send t={t}")
-        assert_same(to_np(R), Rc, f"residual t={t}")
-        out_c = np.empty(D, recv_c.dtype)
-        oracle.decompress(tab, K, t, recv_c, out_c)
-        assert_same(to_np(out), out_c, f"dense t={t}")
-    assert plan.is_selected(t, last) == 1
 
 
 # ------------------------------------------------------------------ more corners

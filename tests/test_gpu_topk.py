@@ -142,7 +142,9 @@ def test_argument_errors(B):
     vals = torch.empty(10, device=DEV)
     idx = torch.empty(10, dtype=torch.int32, device=DEV)
     with pytest.raises(B.CovapError):
-        B.topk_compress(G, R, 1001, vals, idx, ws)
+        B.topk_compress(G, R, 1001, torch.empty(1001, device=DEV), torch.empty(1001, dtype=torch.int32, device=DEV), ws)
+    with pytest.raises(ValueError):                                  # the binding refuses short buffers itself
+        B.topk_compress(G, R, 11, vals, idx, ws)
     with pytest.raises(B.CovapError):
         B.topk_compress(G, R, -1, vals, idx, ws)
     with pytest.raises(B.CovapError):

@@ -71,8 +71,8 @@ def test_static_workspace_limit_and_errors(B):
     n = B.topk_static_max_elems() + 1
     G = torch.zeros(n, device=DEV)
     R = torch.zeros(n, device=DEV)
-    vals = torch.zeros(8, device=DEV)
-    idx = torch.zeros(8, dtype=torch.int32, device=DEV)
+    vals = torch.zeros(16, device=DEV)
+    idx = torch.zeros(16, dtype=torch.int32, device=DEV)
     with pytest.raises(B.CovapError) as e:
         B.topk_compress_static(G, R, 8, vals, idx)
     assert e.value.status == 1 and "topk_static_max_elems" in str(e.value)
