@@ -201,6 +201,18 @@ covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t b
                               const void *grad, void *residual, void *send,
                               int64_t send_cap_elems, float ef_coeff, void *stream);
 
+/* covap_compress on a grid of at most `max_workgroups` workgroups (>= 1) that walk
+ * the call's tiles with a grid stride.  Same arguments otherwise, same result bits.
+ * For running under a compute-bound kernel of another stream, the way the method
+ * hides compression behind backward propagation (Sec. II-B): a few resident waves
+ * per compute unit move the data while the other kernel keeps the rest of the unit.
+ * On an idle GPU it is slower than covap_compress unless max_workgroups is in the
+ * tens of thousands. */
+covap_status_t covap_compress_bounded(const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                                      const void *grad, void *residual, void *send,
+                                      int64_t send_cap_elems, float ef_coeff,
+                                      int32_t max_workgroups, void *stream);
+
 /* Aliased-residual form of steps 1-4, for callers whose gradient-accumulation
  * buffer doubles as the residual: the producer adds every new gradient into
  * `accum` (that addition IS Algorithm 1 line 2 with c = 1), and this call only
@@ -324,6 +336,13 @@ covap_status_t sparse_decompress_sorted(const void *vals, const uint32_t *idx, i
 covap_status_t covap_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
 covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float s, int64_t n,
                                  void *stream);
+
+/* A compute-only kernel for overlap measurements: `workgroups` workgroups of 256
+ * threads, each wave issuing 4 * iters matrix-core instructions on registers, with
+ * `lds_bytes` of (unused) LDS reserved per workgroup to set its occupancy; one store
+ * per thread at the end into out [device, workgroups * 256 floats]. */
+covap_status_t covap_probe_mfma(float *out, int32_t workgroups, int32_t iters, int32_t lds_bytes,
+                                void *stream);
 
 /* Launch-shape knobs for tuning sweeps (the defaults are the measured best on
  * MI355X).  Keys and allowed values:

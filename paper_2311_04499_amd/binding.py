@@ -107,6 +107,9 @@ def lib():
     L.covap_ef_coeff.argtypes = [C.c_float, C.c_uint64, C.c_uint64, C.c_float, C.POINTER(C.c_float)]
     L.covap_compress.restype = C.c_int
     L.covap_compress.argtypes = [_vp, C.c_uint64, C.c_int32, _vp, _vp, _vp, C.c_int64, C.c_float, _vp]
+    L.covap_compress_bounded.restype = C.c_int
+    L.covap_compress_bounded.argtypes = [_vp, C.c_uint64, C.c_int32, _vp, _vp, _vp, C.c_int64, C.c_float, C.c_int32,
+                                         _vp]
     L.covap_compress_aliased.restype = C.c_int
     L.covap_compress_aliased.argtypes = [_vp, C.c_uint64, C.c_int32, _vp, _vp, C.c_int64, _vp]
     L.covap_decompress.restype = C.c_int
@@ -134,6 +137,8 @@ def lib():
     L.covap_probe_copy.argtypes = [_vp, _vp, C.c_size_t, _vp]
     L.covap_probe_triad.restype = C.c_int
     L.covap_probe_triad.argtypes = [_vp, _vp, _vp, C.c_float, C.c_int64, _vp]
+    L.covap_probe_mfma.restype = C.c_int
+    L.covap_probe_mfma.argtypes = [_vp, C.c_int32, C.c_int32, C.c_int32, _vp]
     L.covap_tune_set.restype = C.c_int
     L.covap_tune_set.argtypes = [C.c_char_p, C.c_int32]
     L.covap_tune_get.restype = C.c_int32
@@ -273,14 +278,20 @@ def covap_plan(tensor_numel: Sequence[int], shard_elems: int, K: int, dtype: int
 
 
 def covap_compress(plan: Plan, step: int, grad, residual, send, ef_coeff: float = 1.0,
-                   bucket: int = -1, stream=None, send_cap_elems: Optional[int] = None) -> None:
+                   bucket: int = -1, stream=None, send_cap_elems: Optional[int] = None,
+                   max_workgroups: Optional[int] = None) -> None:
+    """covap_compress, or covap_compress_bounded when max_workgroups is given."""
     cap = send.numel() if send_cap_elems is None else send_cap_elems
     D = plan.total_elems                      # with median sharding this includes alignment padding
     _need(grad, "grad", D, _GRAD_ESZ[plan.dtype])
     _need(residual, "residual", D, _RESIDUAL_ESZ[plan.dtype])
     _need(send, "send", cap, _PAYLOAD_ESZ[plan.dtype])
-    _check(lib().covap_compress(plan.handle, step, bucket, _ptr(grad), _ptr(residual), _ptr(send),
-                                cap, ef_coeff, _stream(stream)))
+    if max_workgroups is None:
+        _check(lib().covap_compress(plan.handle, step, bucket, _ptr(grad), _ptr(residual), _ptr(send),
+                                    cap, ef_coeff, _stream(stream)))
+    else:
+        _check(lib().covap_compress_bounded(plan.handle, step, bucket, _ptr(grad), _ptr(residual),
+                                            _ptr(send), cap, ef_coeff, max_workgroups, _stream(stream)))
 
 
 def covap_compress_aliased(plan: Plan, step: int, accum, send, bucket: int = -1, stream=None,
@@ -423,6 +434,11 @@ def covap_probe_copy(dst, src, nbytes: int, stream=None) -> None:
 
 def covap_probe_triad(a, b, c, s: float, n: int, stream=None) -> None:
     _check(lib().covap_probe_triad(_ptr(a), _ptr(b), _ptr(c), s, n, _stream(stream)))
+
+
+def covap_probe_mfma(out, workgroups: int, iters: int, lds_bytes: int = 0, stream=None) -> None:
+    _need(out, "out", workgroups * 256, 4)
+    _check(lib().covap_probe_mfma(_ptr(out), workgroups, iters, lds_bytes, _stream(stream)))
 
 
 def covap_tune_set(key: str, value: int) -> None:

@@ -391,19 +391,31 @@ __device__ __forceinline__ void compress_tile_pay16(const float *__restrict__ G,
     }
 }
 
-template <typename OPS, typename GEOM, int kThreads, int UNROLL, bool NT>
+// PERSIST = false: one tile per workgroup, the grid holds exactly the tiles (the fastest
+// shape when the kernel has the chip to itself).  PERSIST = true: a grid of a size the
+// caller chose walks the n_tiles tiles with a grid stride; few resident waves leave the
+// rest of every compute unit to a kernel of another stream (covap_compress_bounded).
+template <typename OPS, typename GEOM, int kThreads, int UNROLL, bool NT, bool PERSIST>
 __global__ __launch_bounds__(kThreads) void k_compress(const u32x4 *__restrict__ G, u32x4 *R,
-                                                       u32x4 *__restrict__ send, GEOM g, float c)
+                                                       u32x4 *__restrict__ send, GEOM g, float c,
+                                                       uint32_t n_tiles)
 {
     constexpr int TILE = kThreads * OPS::EPV * UNROLL;
-    tile_ref t;
-    if (!covap::resolve_tile(g, blockIdx.x, (uint32_t)TILE, t)) return;
-    if constexpr (OPS::MIXED)
-        compress_tile_mixed<kThreads, UNROLL, NT>((const uint16_t *)G, (float *)R, (uint16_t *)send, t, c);
-    else if constexpr (OPS::PAY16)
-        compress_tile_pay16<kThreads, UNROLL, NT>((const float *)G, (float *)R, (uint16_t *)send, t, c);
-    else
-        compress_tile<OPS, kThreads, UNROLL, NT>(G, R, send, t, c);
+    auto one = [&](uint32_t b) {
+        tile_ref t;
+        if (!covap::resolve_tile(g, b, (uint32_t)TILE, t)) return;
+        if constexpr (OPS::MIXED)
+            compress_tile_mixed<kThreads, UNROLL, NT>((const uint16_t *)G, (float *)R, (uint16_t *)send, t, c);
+        else if constexpr (OPS::PAY16)
+            compress_tile_pay16<kThreads, UNROLL, NT>((const float *)G, (float *)R, (uint16_t *)send, t, c);
+        else
+            compress_tile<OPS, kThreads, UNROLL, NT>(G, R, send, t, c);
+    };
+    if constexpr (PERSIST) {
+        for (uint32_t b = blockIdx.x; b < n_tiles; b += gridDim.x) one(b);
+    } else {
+        one(blockIdx.x);
+    }
 }
 
 // ---- take: aliased-residual form of compress ------------------------------------------
@@ -653,6 +665,32 @@ __global__ __launch_bounds__(kProbeThreads) void k_triad(u32x4 *__restrict__ a,
     if (i < nvec) st16<NT>(a + i, ops_f32::ef(ld16<NT>(b + i), ld16<NT>(c + i), s));
 }
 
+// Matrix-core work on registers only: every wave issues 4 * iters MFMA instructions
+// (32x32x8 bf16, four independent accumulators) and touches memory once, at the end.
+// A stand-in for a purely compute-bound kernel of another stream: what the hot path
+// costs next to it is contention for the compute units alone, not for the memory
+// system.
+typedef short bf16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(256) void k_mfma_spin(float *__restrict__ out, int32_t iters)
+{
+    const int tid = threadIdx.x;
+    const bf16x4_t a = {(short)(0x3f80 + (tid & 7)), (short)0x3f80, (short)0x3c00, (short)0x3f00};
+    const bf16x4_t b = {(short)0x3f80, (short)(0x3c00 + (tid & 3)), (short)0x3f80, (short)0x3e00};
+    f32x16_t acc0 = {}, acc1 = {}, acc2 = {}, acc3 = {};
+    for (int32_t i = 0; i < iters; ++i) {
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a, b, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(b, a, acc1, 0, 0, 0);
+        acc2 = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a, a, acc2, 0, 0, 0);
+        acc3 = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(b, b, acc3, 0, 0, 0);
+    }
+    float sum = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) sum += (acc0[j] + acc1[j]) + (acc2[j] + acc3[j]);
+    out[(int64_t)blockIdx.x * 256 + tid] = sum;
+}
+
 // ---- host-side launch helpers ----------------------------------------------------------
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
@@ -693,17 +731,24 @@ void for_each_launch(const covap_plan_s *plan, const covap::call_range &cr, int 
     }
 }
 
+// max_groups = 0: one workgroup per tile; > 0: at most that many workgroups, persistent.
 template <typename OPS>
 bool launch_compress(const covap::tuning &tn, const covap_plan_s *plan, const covap::call_range &cr,
-                     hipStream_t st, const void *G, void *R, void *send, float c, covap::launch_status &ls)
+                     hipStream_t st, const void *G, void *R, void *send, float c, uint32_t max_groups,
+                     covap::launch_status &ls)
 {
     return pick<64, 256>(tn.compress_threads, [&](auto T) {
         pick<1, 2, 4>(tn.compress_unroll, [&](auto U) {
             pick<0, 1>(tn.nontemporal, [&](auto NT) {
                 for_each_launch(plan, cr, T() * OPS::EPV * U(), false, [&](const auto &g, dim3 grid) {
                     typedef std::decay_t<decltype(g)> GEOM;
-                    ls += covap::launch(k_compress<OPS, GEOM, T(), U(), NT() != 0>, grid, dim3(T()), 0, st,
-                                        (const u32x4 *)G, (u32x4 *)R, (u32x4 *)send, g, c);
+                    if (max_groups == 0u)
+                        ls += covap::launch(k_compress<OPS, GEOM, T(), U(), NT() != 0, false>, grid, dim3(T()), 0,
+                                            st, (const u32x4 *)G, (u32x4 *)R, (u32x4 *)send, g, c, grid.x);
+                    else
+                        ls += covap::launch(k_compress<OPS, GEOM, T(), U(), NT() != 0, true>,
+                                            dim3(grid.x < max_groups ? grid.x : max_groups), dim3(T()), 0, st,
+                                            (const u32x4 *)G, (u32x4 *)R, (u32x4 *)send, g, c, grid.x);
                 });
             });
         });
@@ -765,27 +810,28 @@ int64_t payload_esz(int32_t dtype) { return dtype == COVAP_F32 ? 4 : 2; }
 
 using covap::fail;
 
-extern "C" {
+namespace {
 
-covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t bucket,
-                              const void *grad, void *residual, void *send,
-                              int64_t send_cap_elems, float ef_coeff, void *stream)
+// covap_compress and covap_compress_bounded: argument checks and launches.
+covap_status_t compress_call(const char *who, const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                                    const void *grad, void *residual, void *send, int64_t send_cap_elems,
+                                    float ef_coeff, uint32_t max_groups, void *stream)
 {
     covap::clear_error();
     covap::call_range cr;
     const covap_status_t rs = covap::resolve(plan, step, bucket, &cr);
     if (rs != COVAP_OK) return rs;
-    if (!grad || !residual || !send) return fail(COVAP_EINVAL, "covap_compress: null device pointer");
+    if (!grad || !residual || !send) return fail(COVAP_EINVAL, who, "null device pointer");
     if (!aligned16(grad) || !aligned16(residual) || !aligned16(send))
-        return fail(COVAP_EINVAL, "covap_compress: device pointers must be 16-byte aligned");
+        return fail(COVAP_EINVAL, who, "device pointers must be 16-byte aligned");
     if (cr.packed_elems > 0 && send_cap_elems < cr.packed_base + cr.packed_elems)  // nothing sent: nothing written
-        return fail(COVAP_EINVAL, "covap_compress: send buffer too small for this step");
+        return fail(COVAP_EINVAL, who, "send buffer too small for this step");
     const int32_t dt = plan->opts.dtype;
     const int64_t abytes = plan->total_elems * grad_esz(dt), sbytes = send_cap_elems * payload_esz(dt);
     const int64_t rbytes = plan->total_elems * residual_esz(dt);
     if (overlap(grad, abytes, residual, rbytes) || overlap(grad, abytes, send, sbytes) ||
         overlap(residual, rbytes, send, sbytes))
-        return fail(COVAP_EINVAL, "covap_compress: grad, residual and send must not overlap");
+        return fail(COVAP_EINVAL, who, "grad, residual and send must not overlap");
     if (cr.sh_hi == cr.sh_lo) return COVAP_OK;
 
     const covap::tuning tn = covap::tune();
@@ -793,15 +839,41 @@ covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t b
     covap::launch_status ls;
     bool ok;
     if (plan->opts.dtype == COVAP_F32)
-        ok = launch_compress<ops_f32>(tn, plan, cr, st, grad, residual, send, ef_coeff, ls);
+        ok = launch_compress<ops_f32>(tn, plan, cr, st, grad, residual, send, ef_coeff, max_groups, ls);
     else if (plan->opts.dtype == COVAP_BF16)
-        ok = launch_compress<ops_bf16>(tn, plan, cr, st, grad, residual, send, ef_coeff, ls);
+        ok = launch_compress<ops_bf16>(tn, plan, cr, st, grad, residual, send, ef_coeff, max_groups, ls);
     else if (plan->opts.dtype == COVAP_BF16_RES32)
-        ok = launch_compress<ops_bf16_res32>(tn, plan, cr, st, grad, residual, send, ef_coeff, ls);
+        ok = launch_compress<ops_bf16_res32>(tn, plan, cr, st, grad, residual, send, ef_coeff, max_groups, ls);
     else
-        ok = launch_compress<ops_f32_pay16>(tn, plan, cr, st, grad, residual, send, ef_coeff, ls);
-    if (!ok) return fail(COVAP_EINVAL, "covap_compress: launch knobs select no kernel");
-    return ls.report("covap_compress");
+        ok = launch_compress<ops_f32_pay16>(tn, plan, cr, st, grad, residual, send, ef_coeff, max_groups, ls);
+    if (!ok) return fail(COVAP_EINVAL, who, "launch knobs select no kernel");
+    return ls.report(who);
+}
+
+
+}  // namespace
+
+extern "C" {
+
+covap_status_t covap_compress(const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                              const void *grad, void *residual, void *send,
+                              int64_t send_cap_elems, float ef_coeff, void *stream)
+{
+    return compress_call("covap_compress", plan, step, bucket, grad, residual, send, send_cap_elems, ef_coeff, 0u,
+                         stream);
+}
+
+covap_status_t covap_compress_bounded(const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                                      const void *grad, void *residual, void *send,
+                                      int64_t send_cap_elems, float ef_coeff, int32_t max_workgroups,
+                                      void *stream)
+{
+    if (max_workgroups < 1) {
+        covap::clear_error();
+        return fail(COVAP_EINVAL, "covap_compress_bounded", "max_workgroups < 1");
+    }
+    return compress_call("covap_compress_bounded", plan, step, bucket, grad, residual, send, send_cap_elems,
+                         ef_coeff, (uint32_t)max_workgroups, stream);
 }
 
 covap_status_t covap_compress_aliased(const covap_plan_t *plan, uint64_t step, int32_t bucket,
@@ -902,6 +974,17 @@ covap_status_t covap_probe_triad(float *a, const float *b, const float *c, float
     ls += covap::launch(covap::tune().nontemporal ? k_triad<true> : k_triad<false>, dim3(grid), dim3(kProbeThreads),
                         0, (hipStream_t)stream, (u32x4 *)a, (const u32x4 *)b, (const u32x4 *)c, s, nvec);
     return ls.report("covap_probe_triad");
+}
+
+covap_status_t covap_probe_mfma(float *out, int32_t workgroups, int32_t iters, int32_t lds_bytes, void *stream)
+{
+    covap::clear_error();
+    if (!out || workgroups < 1 || workgroups > (1 << 20) || iters < 0 || lds_bytes < 0 || lds_bytes > 160 * 1024)
+        return fail(COVAP_EINVAL, "covap_probe_mfma", "need out, 1 <= workgroups <= 2^20, iters >= 0, 0 <= lds_bytes <= 160 KiB");
+    covap::launch_status ls;
+    ls += covap::launch(k_mfma_spin, dim3((uint32_t)workgroups), dim3(256), (size_t)lds_bytes, (hipStream_t)stream, out,
+                        iters);
+    return ls.report("covap_probe_mfma");
 }
 
 }  // extern "C"

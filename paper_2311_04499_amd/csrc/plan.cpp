@@ -22,6 +22,12 @@ covap_status_t fail(covap_status_t st, const char *msg)
     return st;
 }
 
+covap_status_t fail(covap_status_t st, const char *who, const char *msg)
+{
+    std::snprintf(g_last_error, sizeof g_last_error, "%s: %s", who ? who : "", msg ? msg : "");
+    return st;
+}
+
 void clear_error() { g_last_error[0] = '\0'; }
 
 static int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }

@@ -52,6 +52,7 @@ constexpr int kTileLog2Min = 8, kTileLog2Max = 13;  // 64 threads x 4 elements .
 
 // Records msg as the calling thread's last error and returns st.  Never allocates.
 covap_status_t fail(covap_status_t st, const char *msg);
+covap_status_t fail(covap_status_t st, const char *who, const char *msg);  // "who: msg"
 void clear_error();
 
 // Residue class sent at `step`: shards with s mod K == first_selected(step).

@@ -74,7 +74,7 @@ def make_median_plans(B, numel, K, dtype=torch.float32, cap_bytes=25 << 20, ref=
 
 
 def run_iterations(B, wl, numel, S, K, N, iters, dtype=torch.float32, c=1.0, per_bucket=False,
-                   cap_bytes=25 << 20, slack=0, plans=None):
+                   cap_bytes=25 << 20, slack=0, plans=None, max_workgroups=None):
     """Full-fidelity loop: every one of the N workers compresses its own gradient
     each iteration; their send buffers are the rows handed to decompress.  Both
     sides run the same loop on the same inputs and are compared after every call."""
@@ -98,7 +98,8 @@ def run_iterations(B, wl, numel, S, K, N, iters, dtype=torch.float32, c=1.0, per
             G = G[:D].contiguous()
             Gn = to_np(G)
             for b in buckets:
-                B.covap_compress(plan, t, G, R_gpu[w], recv_gpu[w], ef_coeff=c, bucket=b)
+                B.covap_compress(plan, t, G, R_gpu[w], recv_gpu[w], ef_coeff=c, bucket=b,
+                                 max_workgroups=max_workgroups)
                 oracle.compress(tab, K, t, Gn, R_cpu[w], recv_cpu[w], c, bucket=b)
             torch.cuda.synchronize()
             assert_same(to_np(recv_gpu[w]), recv_cpu[w], f"send t={t} w={w}")
@@ -156,6 +157,31 @@ def test_per_bucket_calls(B):
     numel = [300_000, 12_345]
     wl = workloads.scaled_down(workloads.config(2), numel, 8192)
     run_iterations(B, wl, numel, 8192, 3, 2, 4, per_bucket=True, cap_bytes=100_000, c=0.5)
+
+
+@pytest.mark.parametrize("groups", [1, 7, 300, 1_000_000])
+def test_bounded_grid_compress(B, groups):
+    """covap_compress_bounded: a grid of at most `groups` workgroups walks the tiles; same bits as the
+    oracle whatever the bound (one workgroup doing everything, a bound that does not divide the tile
+    count, a bound above it), on both shard layouts and element types, whole-arena and per bucket."""
+    wl = workloads.scaled_down(workloads.config(1), [100_003], 4096)
+    run_iterations(B, wl, [100_003], 4096, 3, 2, 4, max_workgroups=groups, c=0.5)
+    run_iterations(B, wl, [9_001, 12_345], 1000, 5, 2, 6, per_bucket=True, cap_bytes=9000, max_workgroups=groups)
+    run_iterations(B, wl, [8 * 4096 + 9], 8192, 4, 2, 5, dtype=torch.bfloat16, max_workgroups=groups)
+    layers = [1_003, 2_001, 30_007, 5, 4_099, 17, 90_001, 3]
+    wl = workloads.scaled_down(workloads.config(3), layers, 4096)
+    for dtype in (torch.float32, torch.bfloat16):
+        plans = make_median_plans(B, layers, 4, dtype=dtype, cap_bytes=40_000)
+        run_iterations(B, wl, layers, 0, 4, 2, 5, dtype=dtype, plans=plans, max_workgroups=groups)
+    if groups == 300:
+        layers = [2_500_000, 7]                                  # thousands of tiles per workgroup's walk
+        wl = workloads.scaled_down(workloads.config(3), layers, 4096)
+        plans = make_median_plans(B, layers, 2, cap_bytes=4)
+        run_iterations(B, wl, layers, 0, 2, 2, 3, plans=plans, max_workgroups=groups, per_bucket=True)
+        with pytest.raises(B.CovapError):
+            plan, _ = make_plans(B, [1000], 64, 2)
+            z = torch.zeros(1000, device=DEV)
+            B.covap_compress(plan, 0, z, torch.zeros_like(z), torch.zeros_like(z), max_workgroups=0)
 
 
 KNOBS = {"compress_threads": [64, 256], "compress_unroll": [1, 2, 4],
