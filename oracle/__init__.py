@@ -51,6 +51,9 @@ def lib():
         L.orc_plan_buckets.argtypes = [_i64p, C.c_int64, C.c_int64, _i32p]
         L.orc_plan_median_parts.restype = C.c_int64
         L.orc_plan_median_parts.argtypes = [_i64p, C.c_int32, C.c_int64, C.c_int32, _i32p]
+        L.orc_plan_median_layout.restype = C.c_int64
+        L.orc_plan_median_layout.argtypes = [_i64p, C.c_int32, C.c_int64, C.c_int32, C.c_int64, C.c_int64,
+                                             _i64p, _i64p, _i64p, _i32p, _i64p]
         L.orc_plan_even_slices.restype = C.c_int32
         L.orc_plan_even_slices.argtypes = [C.c_int64, C.c_int32, C.c_int64, _i64p]
         L.orc_selected.restype = C.c_int32
@@ -192,33 +195,21 @@ def plan_median(tensor_numel, bucket_cap_elems: int, interval: int, ref: int = 0
     median-based even slicing capped at the interval.  Every communication
     tensor starts at a multiple of `align` elements in the arena (each is a
     buffer of its own in the framework the paper builds on), layers inside it
-    are tight; slices are multiples of `align` except the last of a tensor."""
+    are tight; slices are multiples of `align` except the last of a tensor.
+    The layout is worked out by orc_plan_median_layout; this only marshals."""
     numel = np.ascontiguousarray(tensor_numel, dtype=np.int64)
     n = len(numel)
-    group_of = np.zeros(max(n, 1), dtype=np.int32)
-    n_groups = lib().orc_plan_group_layers(_p(numel, _i64p), n, bucket_cap_elems, _p(group_of, _i32p))
-    group_numel = np.zeros(n_groups, dtype=np.int64)
-    for i in range(n):
-        group_numel[group_of[i]] += numel[i]
-    parts, _ = median_parts(group_numel, ref, interval)
-    offs = np.zeros(n, dtype=np.int64)
-    off, ln, bucket = [], [], []
-    pos = 0
-    i = 0
-    for g in range(n_groups):
-        pos = (pos + align - 1) // align * align
-        start = pos
-        while i < n and group_of[i] == g:
-            offs[i] = pos
-            pos += int(numel[i])
-            i += 1
-        o = start
-        for l in even_slices(int(group_numel[g]), int(parts[g]), align):
-            off.append(o)
-            ln.append(int(l))
-            bucket.append(g)
-            o += int(l)
-    return ShardTable(off, ln, bucket, pos, offs, align)
+    offs = np.zeros(max(n, 1), dtype=np.int64)
+    arena = C.c_int64(0)
+    count = lib().orc_plan_median_layout(_p(numel, _i64p), n, bucket_cap_elems, interval, ref, align,
+                                         _p(offs, _i64p), None, None, None, C.byref(arena))
+    off = np.zeros(max(count, 1), dtype=np.int64)
+    ln = np.zeros(max(count, 1), dtype=np.int64)
+    bucket = np.zeros(max(count, 1), dtype=np.int32)
+    lib().orc_plan_median_layout(_p(numel, _i64p), n, bucket_cap_elems, interval, ref, align,
+                                 _p(offs, _i64p), _p(off, _i64p), _p(ln, _i64p), _p(bucket, _i32p),
+                                 C.byref(arena))
+    return ShardTable(off[:count], ln[:count], bucket[:count], arena.value, offs[:n], align)
 
 
 def median_parts(numel, ref: int, interval: int):

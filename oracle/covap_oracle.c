@@ -158,6 +158,60 @@ int32_t orc_plan_even_slices(int64_t numel, int32_t parts, int64_t align,
     return n;
 }
 
+/* Sec. III-C end to end: the arena of a model under the paper's sharding rule.
+ * Layers are merged into communication tensors (orc_plan_group_layers); the
+ * median rule decides into how many pieces each is cut (orc_plan_median_parts)
+ * and the even slicing how long the pieces are (orc_plan_even_slices).  Every
+ * communication tensor starts at a multiple of `align` elements of the arena
+ * (each is a buffer of its own in the framework the paper builds on), layers
+ * inside it lie end to end; every piece is one shard for the filter, numbered
+ * in arena order.  Fills tensor_off[n] (arena offset of each layer) and, when
+ * sh_off is not NULL, the shards' offsets, lengths and communication-tensor
+ * ids; returns the number of shards and writes the arena size to *arena. */
+int64_t orc_plan_median_layout(const int64_t *numel, int32_t n, int64_t cap_elems, int32_t I,
+                               int64_t ref, int64_t align, int64_t *tensor_off,
+                               int64_t *sh_off, int64_t *sh_len, int32_t *sh_tensor,
+                               int64_t *arena)
+{
+    *arena = 0;
+    if (n <= 0) return 0;
+    int32_t *group_of = (int32_t *)malloc(sizeof(int32_t) * (size_t)n);
+    int32_t n_groups = orc_plan_group_layers(numel, n, cap_elems, group_of);
+    int64_t *group_numel = (int64_t *)calloc((size_t)n_groups, sizeof(int64_t));
+    for (int32_t i = 0; i < n; ++i) group_numel[group_of[i]] += numel[i];
+    int32_t *parts = (int32_t *)malloc(sizeof(int32_t) * (size_t)n_groups);
+    orc_plan_median_parts(group_numel, n_groups, ref, I, parts);
+    int64_t *piece = (int64_t *)malloc(sizeof(int64_t) * (size_t)(I > 0 ? I : 1));
+    int64_t n_shards = 0, end = 0;
+    int32_t layer = 0;
+    for (int32_t g = 0; g < n_groups; ++g) {
+        int64_t begin = (end + align - 1) / align * align; /* the tensor's own buffer */
+        int64_t at = begin;
+        for (; layer < n && group_of[layer] == g; ++layer) { /* its layers, end to end */
+            if (tensor_off) tensor_off[layer] = at;
+            at += numel[layer];
+        }
+        end = at;
+        int32_t m = orc_plan_even_slices(group_numel[g], parts[g], align, piece);
+        int64_t o = begin;
+        for (int32_t j = 0; j < m; ++j) {
+            if (sh_off) {
+                sh_off[n_shards] = o;
+                sh_len[n_shards] = piece[j];
+                sh_tensor[n_shards] = g;
+            }
+            o += piece[j];
+            ++n_shards;
+        }
+    }
+    *arena = end;
+    free(piece);
+    free(parts);
+    free(group_numel);
+    free(group_of);
+    return n_shards;
+}
+
 /* ------------------------------------------------------------------ */
 /* Coarse-grained filter (Sec. III-A; Definition 1)                    */
 /* ------------------------------------------------------------------ */
