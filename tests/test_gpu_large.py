@@ -1,5 +1,5 @@
-"""More than 2^32 elements in one arena, shards of the largest size the planner allows
-(2^30 elements), packed offsets beyond 2^31: every element of send, residual and dense
+"""The largest arena the planner accepts (just under 2^33 elements, 34 GB per fp32 buffer), shards of
+the largest size it allows (2^30 elements), packed offsets beyond 2^32: every element of send, residual and dense
 result is checked on the device, shard by shard, against values that are exact by
 construction (small integers, c = 1, N = 2), with the layout taken from the oracle's
 planner and filter.  The oracle's element loops are not run at this size (17 GB per
@@ -36,15 +36,17 @@ def fill(t: torch.Tensor, mult: int):
         t[lo:hi] = pattern(lo, hi, mult)
 
 
-def test_arena_beyond_2_to_32_elements(B):
+def test_arena_at_the_planner_s_size_limit(B):
     free, _ = torch.cuda.mem_get_info()
-    if free < 90 << 30:
-        pytest.skip("needs about 80 GB of device memory")
+    if free < 170 << 30:
+        pytest.skip("needs about 150 GB of device memory")
     S, K, N = 1 << 30, 2, 2
-    D = 4 * S + (1 << 20) + 12
+    D = (1 << 33) - (1 << 20) + 12                        # eight shards, the last one short
+    with pytest.raises(B.CovapError):
+        B.covap_plan([1 << 33, 1], S, K)                   # one element past the limit
     plan = B.covap_plan([D], S, K)
     tab = oracle.plan_fixed([D], S, 1 << 40)
-    assert plan.total_elems == D > 1 << 32 and plan.num_shards == tab.n_shards == 5
+    assert plan.total_elems == D > 1 << 32 and plan.num_shards == tab.n_shards == 8
     G = torch.empty(D, device=DEV)
     R = torch.empty(D, device=DEV)
     out = torch.empty(D, device=DEV)

@@ -209,3 +209,16 @@ def test_empty_tensors_and_empty_arenas(B, numel):
             assert plan.selected(t) == [s for s in range(tab.n_shards) if oracle.selected(s, t, 2)]
         if sum(numel) == 0:
             assert plan.num_shards == 0 and plan.packed_elems_max == 0
+
+
+def test_size_limit_of_the_planner(B):
+    """2^33 elements in all is the most a plan takes (what the kernels have been run at); padding counts."""
+    assert B.covap_plan([1 << 33], 1 << 30, 2).total_elems == 1 << 33
+    with pytest.raises(B.CovapError) as e:
+        B.covap_plan([1 << 33, 1], 1 << 30, 2)
+    assert e.value.status == 1
+    med = dict(mode=B.COVAP_SHARD_MEDIAN, bucket_cap_bytes=4, ref_elems=1 << 28)     # 16 pieces of about 2^29 elements
+    with pytest.raises(B.CovapError) as e:
+        B.covap_plan([(1 << 33) - 100, 50], 0, 16, **med)            # 1 KiB padding pushes it over
+    assert "2^33" in str(e.value)
+    assert B.covap_plan([(1 << 33) - 1024, 50], 0, 16, **med).total_elems == (1 << 33) - 974
