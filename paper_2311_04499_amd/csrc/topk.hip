@@ -36,6 +36,7 @@
 // caller's workspace; nothing is allocated.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cstdint>
 #include <cstdio>
@@ -51,7 +52,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kBins12 = 2048;  // digits of levels 1 and 2: key bits 30..20 and 19..9
 constexpr int kBins3 = 512;    // digit of level 3: key bits 8..0
 constexpr int kHistThreads = 256;
-constexpr int kHistWaves = kHistThreads / 64;
 constexpr int kTile = 1024;        // elements per compaction tile: 64 lanes x 4 vectors x 4 elements
 constexpr int kScanChunk = 1024;   // tile counts scanned per workgroup in phase A
 constexpr uint32_t kAbs = 0x7fffffffu;
@@ -347,25 +347,25 @@ __global__ __launch_bounds__(64 * WAVES) void k_topk_pass1(const float *__restri
 // the keys that match the prefix found so far.  Persistent workgroups: each walks
 // tiles of kHistThreads vectors with a grid stride and keeps one LDS histogram per
 // wave.
-template <int LEVEL>
-__global__ __launch_bounds__(kHistThreads) void k_topk_hist(const float *__restrict__ R, int64_t n,
-                                                            const topk_state *__restrict__ st,
-                                                            uint32_t *__restrict__ hist)
+// NT threads per workgroup; `lds` holds 4 * BINS counters (one histogram per wave
+// modulo four); the first `groups` workgroups of the grid take part.
+template <int LEVEL, int NT>
+__device__ __forceinline__ void general_hist(const float *__restrict__ R, int64_t n,
+                                             const topk_state *__restrict__ st,
+                                             uint32_t *__restrict__ hist, uint32_t *lds, uint32_t groups)
 {
     constexpr int BINS = LEVEL == 3 ? kBins3 : kBins12;
     constexpr int SHIFT = LEVEL == 1 ? 20 : (LEVEL == 2 ? 9 : 0);
     constexpr int HI_SHIFT = LEVEL == 1 ? 31 : (LEVEL == 2 ? 20 : 9);  // bits above this digit
-    __shared__ uint32_t lds[kHistWaves][BINS];
     const int tid = threadIdx.x;
-    if (skip_tail(st, kGeneralTail)) return;  // same answer for every thread of the grid
     const uint32_t want = LEVEL == 1 ? 0u : st->prefix >> HI_SHIFT;  // keys have bit 31 clear
-    uint32_t *mine = lds[tid >> 6];
-    for (int i = tid; i < kHistWaves * BINS; i += kHistThreads) (&lds[0][0])[i] = 0u;
+    uint32_t *mine = lds + ((tid >> 6) & 3) * BINS;
+    for (int i = tid; i < 4 * BINS; i += NT) lds[i] = 0u;
     __syncthreads();
 
     const int64_t nvec = n / 4;
-    const int64_t stride = (int64_t)gridDim.x * kHistThreads;
-    for (int64_t v = (int64_t)blockIdx.x * kHistThreads + tid; v < nvec; v += stride) {
+    const int64_t stride = (int64_t)groups * NT;
+    for (int64_t v = (int64_t)blockIdx.x * NT + tid; v < nvec; v += stride) {
         const u32x4 key = __builtin_nontemporal_load((const u32x4 *)R + v) & kAbs;
         if ((key.x >> HI_SHIFT) == want) atomicAdd(&mine[(key.x >> SHIFT) & (BINS - 1)], 1u);
         if ((key.y >> HI_SHIFT) == want) atomicAdd(&mine[(key.y >> SHIFT) & (BINS - 1)], 1u);
@@ -378,10 +378,8 @@ __global__ __launch_bounds__(kHistThreads) void k_topk_hist(const float *__restr
         if ((key >> HI_SHIFT) == want) atomicAdd(&mine[(key >> SHIFT) & (BINS - 1)], 1u);
     }
     __syncthreads();
-    for (int b = tid; b < BINS; b += kHistThreads) {
-        uint32_t s = 0u;
-#pragma unroll
-        for (int w = 0; w < kHistWaves; ++w) s += lds[w][b];
+    for (int b = tid; b < BINS; b += NT) {
+        const uint32_t s = (lds[b] + lds[BINS + b]) + (lds[2 * BINS + b] + lds[3 * BINS + b]);
         if (s) atomicAdd(&hist[b], s);
     }
 }
@@ -395,23 +393,24 @@ __global__ __launch_bounds__(kHistThreads) void k_topk_hist(const float *__restr
 //               longer than `target` that too many tiles missed their slots: either
 //               switches the general tail on.
 //   LEVEL 2, 3  wanted = k_rem; the digit extends the prefix; level 3 fixes T.
-constexpr int kPickThreads = 1024;  // all of them add up the slices; the first 256 then scan
+// One workgroup of NT >= 256 threads runs it: all of them add up the slices, the first
+// 256 then scan.  `lds` holds 256 + BINS words.  Barriers inside: every thread of the
+// workgroup must call it, and nothing that needs a barrier may follow.
+constexpr int kPickThreads = 1024;
+constexpr int kPickLds = 256 + kBins12;
 
-template <int LEVEL, int GATE>
-__global__ __launch_bounds__(kPickThreads) void k_topk_pick(topk_state *st,
-                                                           const uint32_t *__restrict__ hist,
-                                                           int nslices, uint32_t target)
+template <int LEVEL, int GATE, int NT>
+__device__ __forceinline__ void pick(topk_state *st, const uint32_t *hist, int nslices, uint32_t target,
+                                     uint32_t *lds)
 {
-    if (skip_tail(st, GATE)) return;
     constexpr int BINS = LEVEL == 3 ? kBins3 : kBins12;
     constexpr int PER = BINS / 256;
     constexpr int SHIFT = LEVEL <= 1 ? 20 : (LEVEL == 2 ? 9 : 0);
-    __shared__ uint32_t part[256];
-    __shared__ uint32_t total[BINS];
+    uint32_t *part = lds, *total = lds + 256;
     const int tid = threadIdx.x;
     const uint32_t k_rem = LEVEL == 0 ? target : (LEVEL == 1 ? st->k : st->k_rem);
     const uint32_t base_prefix = LEVEL <= 1 ? 0u : st->prefix;
-    for (int bin = tid; bin < BINS; bin += kPickThreads) {  // neighbouring threads read neighbouring counters
+    for (int bin = tid; bin < BINS; bin += NT) {  // neighbouring threads read neighbouring counters
         uint32_t c[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
         int sl = 0;
         for (; sl + 8 <= nslices; sl += 8) {  // eight independent loads in flight
@@ -675,21 +674,6 @@ __device__ __forceinline__ void write_tile(float *R, int64_t n, int64_t tile, ui
     }
 }
 
-__global__ __launch_bounds__(64) void k_topk_write(float *R, int64_t n,
-                                                   const topk_state *__restrict__ st,
-                                                   const uint32_t *__restrict__ cnt_gt,
-                                                   const uint32_t *__restrict__ cnt_eq,
-                                                   const uint32_t *__restrict__ chunk_gt,
-                                                   const uint32_t *__restrict__ chunk_eq,
-                                                   int64_t ntiles, float *__restrict__ vals,
-                                                   uint32_t *__restrict__ idx, uint32_t kmax)
-{
-    if (skip_tail(st, kGeneralTail)) return;
-    const uint32_t T = st->threshold, ties = st->ties;
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x)
-        write_tile(R, n, tile, T, ties, threadIdx.x, cnt_gt, cnt_eq, chunk_gt, chunk_eq, vals, idx, kmax);
-}
-
 // ---- slot tail -------------------------------------------------------------------------
 
 // A tile's 32 slot entries are eight 16-byte vectors.  The slot-tail kernels give one
@@ -707,30 +691,29 @@ __host__ __device__ inline uint32_t crowded_limit(int64_t ntiles)
 // Histogram of one digit over the slot entries (level 1: all of them; levels 2, 3:
 // those that match the prefix): a few large workgroups, each with an LDS histogram
 // that it stores as its own slice.
+// The first kSlotGrid workgroups of the grid take part (kSlotThreads threads each);
+// `lds` holds 4 * BINS counters.
 template <int LEVEL>
-__global__ __launch_bounds__(kSlotThreads) void k_topk_slots_hist(const topk_state *__restrict__ st,
-                                                                  const uint32_t *__restrict__ slot_cnt,
-                                                                  const uint32_t *__restrict__ slot_bits,
-                                                                  int64_t ntiles,
-                                                                  const uint32_t *__restrict__ crowded,
-                                                                  const float *__restrict__ R, int64_t n,
-                                                                  uint32_t *__restrict__ hist)
+__device__ __forceinline__ void slots_hist(const topk_state *__restrict__ st,
+                                           const uint32_t *__restrict__ slot_cnt,
+                                           const uint32_t *__restrict__ slot_bits, int64_t ntiles,
+                                           const uint32_t *__restrict__ crowded,
+                                           const float *__restrict__ R, int64_t n,
+                                           uint32_t *__restrict__ hist, uint32_t *lds)
 {
-    if (skip_tail(st, kSlotTail)) return;
     constexpr int BINS = LEVEL == 3 ? kBins3 : kBins12;
     constexpr int SHIFT = LEVEL == 1 ? 20 : (LEVEL == 2 ? 9 : 0);
     constexpr int HI_SHIFT = LEVEL == 1 ? 31 : (LEVEL == 2 ? 20 : 9);
     // Level 1 sees every entry and nearly all of them fall into a handful of bins just
     // above b_lo: four copies of the histogram, picked by lane, spread those LDS atomics.
     constexpr int COPIES = LEVEL == 1 ? 4 : 1;
-    __shared__ uint32_t lds[COPIES * BINS];
     const int tid = threadIdx.x;
     for (int i = tid; i < COPIES * BINS; i += kSlotThreads) lds[i] = 0u;
     __syncthreads();
     uint32_t *mine = lds + (tid & (COPIES - 1)) * BINS;
     const uint32_t want = LEVEL == 1 ? 0u : st->prefix >> HI_SHIFT;  // keys have bit 31 clear
     const int64_t nvs = ntiles * (kSlots / 4);
-    const int64_t stride = (int64_t)gridDim.x * kSlotThreads;
+    const int64_t stride = (int64_t)kSlotGrid * kSlotThreads;
     constexpr int U = 8;  // vectors in flight per thread; the counts are loaded alongside, not before
     for (int64_t w0 = (int64_t)blockIdx.x * kSlotThreads + tid; w0 < nvs; w0 += U * stride) {
         uint32_t cnt[U];
@@ -764,7 +747,7 @@ __global__ __launch_bounds__(kSlotThreads) void k_topk_slots_hist(const topk_sta
         const uint32_t b_lo = st->b_lo;
         const int lane = tid & 63;
         constexpr int kWaves = kSlotThreads / 64;
-        for (uint32_t i = blockIdx.x * kWaves + (tid >> 6); i < n_crowded; i += gridDim.x * kWaves) {
+        for (uint32_t i = blockIdx.x * kWaves + (tid >> 6); i < n_crowded; i += kSlotGrid * kWaves) {
             const int64_t base = (int64_t)crowded[i] * kTile;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -789,16 +772,15 @@ __global__ __launch_bounds__(kSlotThreads) void k_topk_slots_hist(const topk_sta
 }
 
 // Per-tile numbers of slot entries above and at the threshold.
-__global__ __launch_bounds__(256) void k_topk_slots_count(const topk_state *__restrict__ st,
-                                                          const uint32_t *__restrict__ slot_cnt,
-                                                          const uint32_t *__restrict__ slot_bits,
-                                                          int64_t ntiles,
-                                                          const uint32_t *__restrict__ crowded,
-                                                          const float *__restrict__ R, int64_t n,
-                                                          uint32_t *__restrict__ cnt_gt,
-                                                          uint32_t *__restrict__ cnt_eq)
+// The first `groups` workgroups of the grid take part (256 threads each).
+__device__ __forceinline__ void slots_count(const topk_state *__restrict__ st,
+                                            const uint32_t *__restrict__ slot_cnt,
+                                            const uint32_t *__restrict__ slot_bits, int64_t ntiles,
+                                            const uint32_t *__restrict__ crowded,
+                                            const float *__restrict__ R, int64_t n,
+                                            uint32_t *__restrict__ cnt_gt, uint32_t *__restrict__ cnt_eq,
+                                            uint32_t groups)
 {
-    if (skip_tail(st, kSlotTail)) return;
     const int64_t nvs = ntiles * (kSlots / 4);
     const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const uint32_t T = st->threshold;
@@ -828,7 +810,7 @@ __global__ __launch_bounds__(256) void k_topk_slots_count(const topk_state *__re
     }
     // the crowded tiles, from R: one wave per tile (this kernel's waves walk the list)
     const uint32_t n_crowded = st->n_crowded;
-    const uint32_t wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = gridDim.x * 4;
+    const uint32_t wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = groups * 4;
     for (uint32_t i = wave; i < n_crowded; i += n_waves)
         count_tile(R, n, crowded[i], T, threadIdx.x & 63, cnt_gt, cnt_eq);
 }
@@ -848,20 +830,19 @@ __device__ __forceinline__ uint32_t group8_excl_scan(uint32_t x)
 
 // Ordered write of the kept slot entries; entries of a tile are in ascending index
 // order across its eight lanes.
-__global__ __launch_bounds__(256) void k_topk_slots_write(float *R, int64_t n,
-                                                          const topk_state *__restrict__ st,
-                                                          const uint32_t *__restrict__ slot_cnt,
-                                                          const uint32_t *__restrict__ slot_idx,
-                                                          const uint32_t *__restrict__ slot_bits,
-                                                          const uint32_t *__restrict__ crowded,
-                                                          const uint32_t *__restrict__ cnt_gt,
-                                                          const uint32_t *__restrict__ cnt_eq,
-                                                          const uint32_t *__restrict__ chunk_gt,
-                                                          const uint32_t *__restrict__ chunk_eq,
-                                                          int64_t ntiles, float *__restrict__ vals,
-                                                          uint32_t *__restrict__ idx, uint32_t kmax)
+// The first `groups` workgroups of the grid take part (256 threads each).
+__device__ __forceinline__ void slots_write(float *R, int64_t n, const topk_state *__restrict__ st,
+                                            const uint32_t *__restrict__ slot_cnt,
+                                            const uint32_t *__restrict__ slot_idx,
+                                            const uint32_t *__restrict__ slot_bits,
+                                            const uint32_t *__restrict__ crowded,
+                                            const uint32_t *__restrict__ cnt_gt,
+                                            const uint32_t *__restrict__ cnt_eq,
+                                            const uint32_t *__restrict__ chunk_gt,
+                                            const uint32_t *__restrict__ chunk_eq, int64_t ntiles,
+                                            float *__restrict__ vals, uint32_t *__restrict__ idx,
+                                            uint32_t kmax, uint32_t groups)
 {
-    if (skip_tail(st, kSlotTail)) return;
     const int64_t nvs = ntiles * (kSlots / 4);
     const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const uint32_t T = st->threshold, ties = st->ties;
@@ -909,10 +890,142 @@ __global__ __launch_bounds__(256) void k_topk_slots_write(float *R, int64_t n,
     // the crowded tiles, from R: one wave per tile (this kernel's waves walk the list;
     // whole waves arrive here together, the branch above has closed)
     const uint32_t n_crowded = st->n_crowded;
-    const uint32_t wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = gridDim.x * 4;
+    const uint32_t wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = groups * 4;
     for (uint32_t i = wave; i < n_crowded; i += n_waves)
         write_tile(R, n, crowded[i], T, ties, threadIdx.x & 63, cnt_gt, cnt_eq, chunk_gt, chunk_eq, vals, idx,
                    kmax);
+}
+
+// ---- the kernels of the tail --------------------------------------------------------------
+//
+// The slot tail and the general tail exclude each other (a device flag, set by the pick
+// that follows the first histogram below, says which runs), so each step of the two is
+// one kernel that branches on the flag: a grid large enough for either, the surplus
+// workgroups returning at once.  The digit picks stay kernels of their own.  Letting the
+// workgroup that finishes its part of a histogram last do the pick (a ticket counter) was
+// tried and is slower on this chip: the device-scope release that must precede the ticket
+// writes back the L2 of the workgroup's XCD, which costs 10-12 us per kernel even when
+// issued by one thread per workgroup (40 us when every thread fences) -- more than the
+// 4-5 us of the launch it saves; the same holds for folding the second scan phase into
+// the first.
+
+constexpr int kGenGrid = 512;  // general-tail histogram passes: workgroups of kSlotThreads threads
+
+__global__ __launch_bounds__(kPickThreads) void k_topk_pick_sample(topk_state *st, const uint32_t *hist,
+                                                                   uint32_t target)
+{
+    __shared__ uint32_t lds[kPickLds];
+    pick<0, kAlways, kPickThreads>(st, hist, kSlotGrid, target, lds);
+}
+
+// Level-1 histogram of the slots (the pick that follows decides which tail runs).
+__global__ __launch_bounds__(kSlotThreads) void k_topk_digit1(const topk_state *__restrict__ st,
+                                                              const uint32_t *__restrict__ slot_cnt,
+                                                              const uint32_t *__restrict__ slot_bits,
+                                                              int64_t ntiles,
+                                                              const uint32_t *__restrict__ crowded,
+                                                              const float *__restrict__ R, int64_t n,
+                                                              uint32_t *__restrict__ slices)
+{
+    __shared__ uint32_t lds[4 * kBins12];
+    slots_hist<1>(st, slot_cnt, slot_bits, ntiles, crowded, R, n, slices, lds);
+}
+
+__global__ __launch_bounds__(kPickThreads) void k_topk_pick1(topk_state *st, const uint32_t *slices,
+                                                             uint32_t crowded_max)
+{
+    __shared__ uint32_t lds[kPickLds];
+    pick<1, kSlotTail, kPickThreads>(st, slices, kSlotGrid, crowded_max, lds);
+}
+
+// Slot tail: histogram of digit LEVEL (2 or 3) over the slots.  General tail: of digit
+// LEVEL - 1 over the whole residual.
+template <int LEVEL>
+__global__ __launch_bounds__(kSlotThreads) void k_topk_digit(const topk_state *__restrict__ st,
+                                                             const uint32_t *__restrict__ slot_cnt,
+                                                             const uint32_t *__restrict__ slot_bits,
+                                                             int64_t ntiles,
+                                                             const uint32_t *__restrict__ crowded,
+                                                             const float *__restrict__ R, int64_t n,
+                                                             uint32_t *__restrict__ slices,
+                                                             uint32_t *__restrict__ row, uint32_t gen_groups)
+{
+    __shared__ uint32_t lds[4 * kBins12];
+    if (st->overflow == 0u) {  // the same answer in every workgroup: it was fixed by an earlier kernel
+        if (blockIdx.x >= (uint32_t)kSlotGrid) return;
+        slots_hist<LEVEL>(st, slot_cnt, slot_bits, ntiles, crowded, R, n, slices, lds);
+    } else {
+        if (blockIdx.x >= gen_groups) return;
+        general_hist<LEVEL - 1, kSlotThreads>(R, n, st, row, lds, gen_groups);
+    }
+}
+
+// The pick after k_topk_digit<LEVEL>.
+template <int LEVEL>
+__global__ __launch_bounds__(kPickThreads) void k_topk_pick_digit(topk_state *st, const uint32_t *slices,
+                                                                  const uint32_t *row)
+{
+    __shared__ uint32_t lds[kPickLds];
+    if (st->overflow == 0u)
+        pick<LEVEL, kSlotTail, kPickThreads>(st, slices, kSlotGrid, 0u, lds);
+    else
+        pick<LEVEL - 1, kGeneralTail, kPickThreads>(st, row, 1, 0u, lds);
+}
+
+// Slot tail: per-tile counts against the threshold.  General tail: histogram of the third digit.
+__global__ __launch_bounds__(256) void k_topk_count_or_digit3(const topk_state *__restrict__ st,
+                                                              const uint32_t *__restrict__ slot_cnt,
+                                                              const uint32_t *__restrict__ slot_bits,
+                                                              int64_t ntiles,
+                                                              const uint32_t *__restrict__ crowded,
+                                                              const float *__restrict__ R, int64_t n,
+                                                              uint32_t *__restrict__ cnt_gt,
+                                                              uint32_t *__restrict__ cnt_eq,
+                                                              uint32_t *__restrict__ row, uint32_t slot_groups,
+                                                              uint32_t gen_groups)
+{
+    __shared__ uint32_t lds[4 * kBins3];
+    if (st->overflow == 0u) {
+        if (blockIdx.x >= slot_groups) return;
+        slots_count(st, slot_cnt, slot_bits, ntiles, crowded, R, n, cnt_gt, cnt_eq, slot_groups);
+    } else {
+        if (blockIdx.x >= gen_groups) return;
+        general_hist<3, 256>(R, n, st, row, lds, gen_groups);
+    }
+}
+
+// General tail only: the third digit's pick (returns at once otherwise).
+__global__ __launch_bounds__(kPickThreads) void k_topk_pick3_general(topk_state *st, const uint32_t *row)
+{
+    __shared__ uint32_t lds[kPickLds];
+    if (st->overflow == 0u) return;
+    pick<3, kGeneralTail, kPickThreads>(st, row, 1, 0u, lds);
+}
+
+// The ordered write of (value, index), and +0 into the residual there: from the slots, or
+// (general tail) from the residual, one wave per tile.
+__global__ __launch_bounds__(256) void k_topk_emit(float *R, int64_t n, const topk_state *__restrict__ st,
+                                                   const uint32_t *__restrict__ slot_cnt,
+                                                   const uint32_t *__restrict__ slot_idx,
+                                                   const uint32_t *__restrict__ slot_bits,
+                                                   const uint32_t *__restrict__ crowded,
+                                                   const uint32_t *__restrict__ cnt_gt,
+                                                   const uint32_t *__restrict__ cnt_eq,
+                                                   const uint32_t *__restrict__ chunk_gt,
+                                                   const uint32_t *__restrict__ chunk_eq, int64_t ntiles,
+                                                   float *__restrict__ vals, uint32_t *__restrict__ idx,
+                                                   uint32_t kmax, uint32_t slot_groups)
+{
+    if (st->overflow == 0u) {
+        if (blockIdx.x >= slot_groups) return;
+        slots_write(R, n, st, slot_cnt, slot_idx, slot_bits, crowded, cnt_gt, cnt_eq, chunk_gt, chunk_eq, ntiles,
+                    vals, idx, kmax, slot_groups);
+    } else {
+        const uint32_t T = st->threshold, ties = st->ties;
+        const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = (int64_t)gridDim.x * 4;
+        for (int64_t tile = wave; tile < ntiles; tile += n_waves)
+            write_tile(R, n, tile, T, ties, threadIdx.x & 63, cnt_gt, cnt_eq, chunk_gt, chunk_eq, vals, idx, kmax);
+    }
 }
 
 // Argument checks shared by the entry points; `what` names the caller in the message.
@@ -978,33 +1091,42 @@ covap::launch_status run_topk(const void *grad, void *residual, int64_t n, int64
     // the general tail's tile kernels walk the tiles with a bounded grid, so that
     // they cost next to nothing when they are not taken
     const uint32_t tail_grid = (uint32_t)(ntiles < 16384 ? ntiles : 16384);
-    ls += covap::launch(k_topk_sample, dim3(kSlotGrid), dim3(kSampleThreads), 0, st, G, R, ef_coeff, nchunks_s, n_s, ws.state, ws.hist, hs, (uint32_t)k);
-    ls += covap::launch(k_topk_pick<0, kAlways>, dim3(1), dim3(kPickThreads), 0, st, ws.state, hs, kSlotGrid, target);
+    ls += covap::launch(k_topk_sample, dim3(kSlotGrid), dim3(kSampleThreads), 0, st, G, R, ef_coeff, nchunks_s, n_s,
+                        ws.state, ws.hist, hs, (uint32_t)k);
+    ls += covap::launch(k_topk_pick_sample, dim3(1), dim3(kPickThreads), 0, st, ws.state, hs, target);
     const covap::tuning tn = covap::tune();
     const auto pass1 = tn.topk_pass1_waves == 4 ? k_topk_pass1<4> : (tn.topk_pass1_waves == 2 ? k_topk_pass1<2> : k_topk_pass1<1>);
-    ls += covap::launch(pass1, dim3((uint32_t)ntiles), dim3(64 * tn.topk_pass1_waves), (size_t)tn.topk_pass1_lds_pad, st,  G, R, n, ef_coeff, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.crowded);
+    ls += covap::launch(pass1, dim3((uint32_t)ntiles), dim3(64 * tn.topk_pass1_waves), (size_t)tn.topk_pass1_lds_pad,
+                        st, G, R, n, ef_coeff, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.crowded);
     if (k > 0) {
-        // slot tail (every kernel returns at once when the general tail is switched on)
-        ls += covap::launch(k_topk_slots_hist<1>, dim3(kSlotGrid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.crowded, R, n, h1s);
-        ls += covap::launch(k_topk_pick<1, kSlotTail>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h1s, kSlotGrid, crowded_limit(ntiles));
-        ls += covap::launch(k_topk_slots_hist<2>, dim3(kSlotGrid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.crowded, R, n, h2s);
-        ls += covap::launch(k_topk_pick<2, kSlotTail>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h2s, kSlotGrid, 0u);
-        ls += covap::launch(k_topk_slots_hist<3>, dim3(kSlotGrid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.crowded, R, n, h3s);
-        ls += covap::launch(k_topk_pick<3, kSlotTail>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h3s, kSlotGrid, 0u);
-        ls += covap::launch(k_topk_slots_count, dim3(slot_vec_grid), dim3(256), 0, st, ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.crowded, R, n, ws.cnt_gt, ws.cnt_eq);
-        // general tail (returns at once otherwise)
-        ls += covap::launch(k_topk_hist<1>, dim3((uint32_t)hist_grid), dim3(kHistThreads), 0, st, R, n, ws.state, h1g);
-        ls += covap::launch(k_topk_pick<1, kGeneralTail>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h1g, 1, 0u);
-        ls += covap::launch(k_topk_hist<2>, dim3((uint32_t)hist_grid), dim3(kHistThreads), 0, st, R, n, ws.state, h2g);
-        ls += covap::launch(k_topk_pick<2, kGeneralTail>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h2g, 1, 0u);
-        ls += covap::launch(k_topk_hist<3>, dim3((uint32_t)hist_grid), dim3(kHistThreads), 0, st, R, n, ws.state, h3g);
-        ls += covap::launch(k_topk_pick<3, kGeneralTail>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h3g, 1, 0u);
-        ls += covap::launch(k_topk_count, dim3(tail_grid), dim3(64), 0, st, R, n, ntiles, ws.state, ws.cnt_gt, ws.cnt_eq);
-        // common: exclusive scan of the per-tile counts, then the ordered write
-        ls += covap::launch(k_topk_scan_a, dim3((uint32_t)nchunks), dim3(256), 0, st, ws.cnt_gt, ws.cnt_eq, ntiles, ws.chunk_gt, ws.chunk_eq);
+        // every kernel from here on serves whichever tail the first one switches on
+        const uint32_t gen1024 = (uint32_t)std::min<int64_t>(kGenGrid, div_up(nvec > 0 ? nvec : 1, kSlotThreads));
+        const uint32_t gen256 = (uint32_t)hist_grid;
+        const uint32_t digit_grid = gen1024 > (uint32_t)kSlotGrid ? gen1024 : (uint32_t)kSlotGrid;
+        ls += covap::launch(k_topk_digit1, dim3(kSlotGrid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt,
+                            ws.slot_bits, ntiles, ws.crowded, R, n, h1s);
+        ls += covap::launch(k_topk_pick1, dim3(1), dim3(kPickThreads), 0, st, ws.state, h1s, crowded_limit(ntiles));
+        ls += covap::launch(k_topk_digit<2>, dim3(digit_grid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt,
+                            ws.slot_bits, ntiles, ws.crowded, R, n, h2s, h1g, gen1024);
+        ls += covap::launch(k_topk_pick_digit<2>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h2s, h1g);
+        ls += covap::launch(k_topk_digit<3>, dim3(digit_grid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt,
+                            ws.slot_bits, ntiles, ws.crowded, R, n, h3s, h2g, gen1024);
+        ls += covap::launch(k_topk_pick_digit<3>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h3s, h2g);
+        ls += covap::launch(k_topk_count_or_digit3, dim3(slot_vec_grid > gen256 ? slot_vec_grid : gen256), dim3(256), 0,
+                            st, ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.crowded, R, n, ws.cnt_gt, ws.cnt_eq,
+                            h3g, slot_vec_grid, gen256);
+        // general tail only (both return at once otherwise): its last pick, per-tile counts over the residual
+        ls += covap::launch(k_topk_pick3_general, dim3(1), dim3(kPickThreads), 0, st, ws.state, h3g);
+        ls += covap::launch(k_topk_count, dim3(tail_grid), dim3(64), 0, st, R, n, ntiles, ws.state, ws.cnt_gt,
+                            ws.cnt_eq);
+        // exclusive scan of the per-tile counts, then the ordered write
+        ls += covap::launch(k_topk_scan_a, dim3((uint32_t)nchunks), dim3(256), 0, st, ws.cnt_gt, ws.cnt_eq, ntiles,
+                            ws.chunk_gt, ws.chunk_eq);
         ls += covap::launch(k_topk_scan_b, dim3(1), dim3(256), 0, st, ws.chunk_gt, ws.chunk_eq, nchunks);
-        ls += covap::launch(k_topk_slots_write, dim3(slot_vec_grid), dim3(256), 0, st, R, n, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.crowded, ws.cnt_gt, ws.cnt_eq, ws.chunk_gt, ws.chunk_eq, ntiles, (float *)out_vals, out_idx, (uint32_t)k);
-        ls += covap::launch(k_topk_write, dim3(tail_grid), dim3(64), 0, st, R, n, ws.state, ws.cnt_gt, ws.cnt_eq, ws.chunk_gt, ws.chunk_eq, ntiles, (float *)out_vals, out_idx, (uint32_t)k);
+        const uint32_t emit_waves = tail_grid / 4 + 1;
+        ls += covap::launch(k_topk_emit, dim3(slot_vec_grid > emit_waves ? slot_vec_grid : emit_waves), dim3(256), 0, st,
+                            R, n, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.crowded, ws.cnt_gt, ws.cnt_eq,
+                            ws.chunk_gt, ws.chunk_eq, ntiles, (float *)out_vals, out_idx, (uint32_t)k, slot_vec_grid);
     }
     return ls;
 }
