@@ -44,6 +44,8 @@ def parse_args():
     ap.add_argument("--shard-mode", choices=["fixed", "median"], default="fixed",
                     help="fixed-size shards (default) or the median sharding of Sec. III-C")
     ap.add_argument("--tune", action="append", default=[], help="key=value launch knob")
+    ap.add_argument("--row-align", type=int, default=1024,
+                    help="receive rows start on multiples of this many elements (default 1024)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-topk", action="store_true")
     ap.add_argument("--no-probes", action="store_true")
@@ -88,7 +90,7 @@ DTYPES = {  # name -> (gradient/dense, residual, payload) torch dtype names and 
 class Run:
     """One workload resident in HBM: plan, gradient ring, residual, receive rows, dense result."""
 
-    def __init__(self, torch, B, workloads, cfg, dtype, shard_mode, dev="cuda:0", ring=3):
+    def __init__(self, torch, B, workloads, cfg, dtype, shard_mode, dev="cuda:0", ring=3, row_align=1024):
         self.torch, self.B = torch, B
         self.wl = wl = workloads.config(cfg)
         t, r, p, code = DTYPES[dtype]
@@ -98,7 +100,7 @@ class Run:
         self.plan = B.covap_plan(wl.numel, wl.shard_elems, wl.K, dtype=getattr(B, code),
                                  mode=B.COVAP_SHARD_FIXED if shard_mode == "fixed" else B.COVAP_SHARD_MEDIAN)
         self.D, self.N, self.K = self.plan.total_elems, wl.n_workers, wl.K
-        self.stride = (self.plan.packed_elems_max + 1023) // 1024 * 1024      # rows start on 2 KiB boundaries at least
+        self.stride = (self.plan.packed_elems_max + row_align - 1) // row_align * row_align   # default: 2 KiB boundaries at least
         self.ring = [workloads.gradient(wl, 0, i, dev, self.tdtype) for i in range(ring)]
         if self.D > wl.D:    # median sharding pads every communication tensor to a 1 KiB boundary of the arena
             self.ring = [torch.cat([g, g.new_zeros(self.D - wl.D)]) for g in self.ring]
@@ -204,7 +206,7 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    run = Run(torch, B, workloads, args.config, args.dtype, args.shard_mode, dev)
+    run = Run(torch, B, workloads, args.config, args.dtype, args.shard_mode, dev, row_align=args.row_align)
     wl, plan, D, N, K = run.wl, run.plan, run.D, run.N, run.K
     esz, stride, ring, residual, recv, dense = run.esz, run.stride, run.ring, run.residual, run.recv, run.dense
     stream = torch.cuda.current_stream()

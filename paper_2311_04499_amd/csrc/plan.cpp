@@ -485,8 +485,8 @@ int32_t covap_plan_selected(const covap_plan_t *p, uint64_t step, int32_t *ids, 
     if (!p) return -1;
     int32_t n = 0;
     const int32_t ns = (int32_t)p->shards.size();
-    for (int32_t s = first_selected(step, p->K); s < ns; s += p->K) {
-        if (ids && n < cap) ids[n] = s;
+    for (int64_t s = first_selected(step, p->K); s < ns; s += p->K) {  // 64-bit: s + K passes 2^31 for large K
+        if (ids && n < cap) ids[n] = (int32_t)s;
         ++n;
     }
     return n;

@@ -24,8 +24,9 @@
 // the list grows beyond 1/32 of the tiles (data full of ties, a very large k), a
 // flag is raised on the device and the general path runs instead: three full
 // histogram passes, a counting pass and a compaction pass over R (5 more reads of
-// D).  The host launches both tails; every kernel of the tail that is not taken
-// returns at once, so no host round trip is needed.  Both tails give the same bits.
+// D).  The two tails exclude each other, so the host launches one sequence of kernels
+// whose steps branch on the flag (surplus workgroups of the larger grid return at
+// once); no host round trip is needed.  Both tails give the same bits.
 //
 // key = bit pattern of |A| as an unsigned integer: a total order on magnitudes
 // (NaN above Inf).  Among keys equal to T the lowest indices are kept, which

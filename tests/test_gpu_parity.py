@@ -565,6 +565,7 @@ def test_aliased_rejects_mixed_precision(B):
 
 @pytest.mark.parametrize("numel,S,K,N", [
     ([50_001], 4096, 1000, 2),          # interval far larger than the shard count
+    ([50_001], 4096, (1 << 31) - 1, 2), # the largest interval the ratio policy hands out
     ([50_001], 4096, 13, 130),          # many workers, not a power of two
     ([4096 * 40], 4096, 40, 1),         # exactly one shard per step, single worker
     ([123_457], 4, 3, 2),               # smallest legal shard: tens of thousands of shards

@@ -222,3 +222,27 @@ def test_size_limit_of_the_planner(B):
         B.covap_plan([(1 << 33) - 100, 50], 0, 16, **med)            # 1 KiB padding pushes it over
     assert "2^33" in str(e.value)
     assert B.covap_plan([(1 << 33) - 1024, 50], 0, 16, **med).total_elems == (1 << 33) - 974
+
+
+def test_the_largest_interval_costs_no_memory(B):
+    """K = 2^31 - 1 (the largest the ratio policy hands out): plans and their queries keep no table by
+    step or by class, so this is instant and matches the oracle on the steps that send anything."""
+    K = (1 << 31) - 1
+    assert B.covap_ratio_from_ccr(2147483646.5) == K
+    for mode, kw in ((B.COVAP_SHARD_FIXED, dict(shard_elems=4096)), (B.COVAP_SHARD_MEDIAN, dict(shard_elems=0, bucket_cap_bytes=4000))):
+        numel = [10_000, 3, 70_001] * 50
+        plan = B.covap_plan(numel, kw.pop("shard_elems"), K, mode=mode, **kw)
+        ns = plan.num_shards
+        assert plan.packed_elems_max == max(plan.shard(s)[1] for s in range(ns))   # one shard at a time
+        for t in (0, 1, K - 1, K, K - 5, 2 ** 63):
+            sel = plan.selected(t)
+            assert sel == [s for s in range(ns) if oracle.selected(s, t, K)] and len(sel) <= 1
+            assert plan.packed_elems(t) == (plan.shard(sel[0])[1] if sel else 0)
+            for b in (0, plan.num_buckets - 1):
+                lo, hi = plan.bucket(b)
+                inside = [s for s in sel if lo <= s < hi]
+                assert plan.packed_elems(t, b) == (plan.shard(inside[0])[1] if inside else 0)
+                if inside:
+                    assert plan.packed_base(t, b) == 0
+            off, poff, n, sel_flag, launches, groups = plan.trace(t, -1, 256, True)
+            assert int(n.sum()) == plan.packed_elems(t)
