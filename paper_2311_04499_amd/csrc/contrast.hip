@@ -388,7 +388,8 @@ covap_status_t randk_compress(const void *grad, void *residual, int64_t n, const
         return fail(COVAP_EINVAL, "randk_compress: misaligned device pointer");
     hipStream_t st = (hipStream_t)stream;
     covap::launch_status ls;
-    ls += covap::launch(k_ef_accumulate, dim3(blocks(n / 4 > 0 ? n / 4 : 1, kThreads)), dim3(kThreads), 0, st,  (const float *)grad, (float *)residual, n, ef_coeff);
+    ls += covap::launch(k_ef_accumulate, dim3(blocks(n / 4 > 0 ? n / 4 : 1, kThreads)), dim3(kThreads), 0, st,
+                        (const float *)grad, (float *)residual, n, ef_coeff);
     if (k > 0)
         ls += covap::launch(k_gather_clear, dim3(blocks(k, 256)), dim3(256), 0, st, (float *)residual, idx, k,
                             (float *)out_vals);
@@ -405,7 +406,9 @@ covap_status_t fp16_compress(const void *grad, void *residual, int64_t n, float 
     if (!al16(grad) || !al16(residual) || !al16(out_half))
         return fail(COVAP_EINVAL, "fp16_compress: device pointers must be 16-byte aligned");
     covap::launch_status ls;
-    ls += covap::launch(k_fp16_compress, dim3(blocks(n / 4 > 0 ? n / 4 : 1, kThreads)), dim3(kThreads), 0, (hipStream_t)stream,  (const float *)grad, (float *)residual, n, ef_coeff, (uint16_t *)out_half);
+    ls += covap::launch(k_fp16_compress, dim3(blocks(n / 4 > 0 ? n / 4 : 1, kThreads)), dim3(kThreads), 0,
+                        (hipStream_t)stream, (const float *)grad, (float *)residual, n, ef_coeff,
+                        (uint16_t *)out_half);
     return ls.report("fp16_compress");
 }
 
@@ -423,7 +426,9 @@ covap_status_t fp16_decompress(const void *recv, int32_t n_workers, int64_t stri
     const int pow2 = (n_workers & (n_workers - 1)) == 0;
     const float n_f = (float)n_workers;
     covap::launch_status ls;
-    ls += covap::launch(k_fp16_decompress, dim3(blocks(n / 8 > 0 ? n / 8 : 1, kThreads)), dim3(kThreads), 0, (hipStream_t)stream,  (const uint16_t *)recv, n_workers, stride_elems, n, (float *)dense_out, n_f, 1.0f / n_f, pow2);
+    ls += covap::launch(k_fp16_decompress, dim3(blocks(n / 8 > 0 ? n / 8 : 1, kThreads)), dim3(kThreads), 0,
+                        (hipStream_t)stream, (const uint16_t *)recv, n_workers, stride_elems, n, (float *)dense_out,
+                        n_f, 1.0f / n_f, pow2);
     return ls.report("fp16_decompress");
 }
 
@@ -491,7 +496,8 @@ covap_status_t sparse_decompress_sorted(const void *vals, const uint32_t *idx, i
                       : n_workers == 8  ? k_sparse_mean_sorted<8, true>
                                         : k_sparse_mean_sorted<8, false>;
     covap::launch_status ls;
-    ls += covap::launch(kern, dim3(grid), dim3(64), 0, (hipStream_t)stream, (const float *)vals, idx, n_workers, (uint32_t)k, stride_elems, n, (float *)dense_out, tiles_per_wg, n_f, 1.0f / n_f, pow2);
+    ls += covap::launch(kern, dim3(grid), dim3(64), 0, (hipStream_t)stream, (const float *)vals, idx, n_workers,
+                        (uint32_t)k, stride_elems, n, (float *)dense_out, tiles_per_wg, n_f, 1.0f / n_f, pow2);
     return ls.report("sparse_decompress_sorted");
 }
 

@@ -980,7 +980,8 @@ covap_status_t covap_probe_mfma(float *out, int32_t workgroups, int32_t iters, i
 {
     covap::clear_error();
     if (!out || workgroups < 1 || workgroups > (1 << 20) || iters < 0 || lds_bytes < 0 || lds_bytes > 160 * 1024)
-        return fail(COVAP_EINVAL, "covap_probe_mfma", "need out, 1 <= workgroups <= 2^20, iters >= 0, 0 <= lds_bytes <= 160 KiB");
+        return fail(COVAP_EINVAL, "covap_probe_mfma",
+                    "need out, 1 <= workgroups <= 2^20, iters >= 0, 0 <= lds_bytes <= 160 KiB");
     covap::launch_status ls;
     ls += covap::launch(k_mfma_spin, dim3((uint32_t)workgroups), dim3(256), (size_t)lds_bytes, (hipStream_t)stream, out,
                         iters);

@@ -132,7 +132,11 @@ static void finish_tables(covap_plan_s *p)
         if (b.sh_lo < 0) b.sh_lo = (int32_t)s;
         b.sh_hi = (int32_t)s + 1;
         // the previous shard of the same class, if any, ends where this one may start
-        sh.packed_off = s >= (size_t)K ? round_up(p->shards[s - (size_t)K].packed_off + p->shards[s - (size_t)K].len, al) : 0;
+        sh.packed_off = 0;
+        if (s >= (size_t)K) {
+            const covap_shard_rec &before = p->shards[s - (size_t)K];
+            sh.packed_off = round_up(before.packed_off + before.len, al);
+        }
         p->packed_max = std::max(p->packed_max, sh.packed_off + sh.len);
     }
     if (p->uniform) return;

@@ -70,7 +70,13 @@ struct topk_state {
     uint32_t n_crowded;  // tiles that did not fit their slots; the slot tail reads those from R
 };
 
-constexpr int kSlots = 32;  // slot entries per 1024-element tile
+// Slot entries per 1024-element tile.  The bins >= b_lo hold 2..10 times the keys needed (a bin is an eighth
+// of an octave), i.e. a handful per tile: with 16 slots so many tiles went on the crowded list that the call
+// took 0.95 ms instead of 0.81.
+constexpr int kSlots = 32;
+constexpr int kSlotVecs = kSlots / 4;  // 16-byte vectors of slot entries per tile: one lane each in the slot tail
+constexpr int kSlotVecShift = kSlotVecs == 8 ? 3 : 2;
+static_assert(kSlotVecs == 1 << kSlotVecShift, "4 or 8 slot vectors per tile");
 constexpr uint32_t kCrowded = 0xffffffffu;  // slot count of a tile that did not fit and is listed instead
 // A histogram is either one row that workgroups add their non-empty LDS bins to,
 // or several partial copies ("slices"), one per workgroup, that the pick kernel
@@ -677,7 +683,7 @@ __device__ __forceinline__ void write_tile(float *R, int64_t n, int64_t tile, ui
 
 // ---- slot tail -------------------------------------------------------------------------
 
-// A tile's 32 slot entries are eight 16-byte vectors.  The slot-tail kernels give one
+// A tile's kSlots slot entries are kSlotVecs 16-byte vectors.  The slot-tail kernels give one
 // thread to each such vector, so that a wave reads 1 KB of slots at a time, and look
 // only at the entries below the tile's count.  The tiles on the crowded list have no
 // slots: every slot-tail kernel then walks the list, one wave per tile, and reads those
@@ -713,7 +719,7 @@ __device__ __forceinline__ void slots_hist(const topk_state *__restrict__ st,
     __syncthreads();
     uint32_t *mine = lds + (tid & (COPIES - 1)) * BINS;
     const uint32_t want = LEVEL == 1 ? 0u : st->prefix >> HI_SHIFT;  // keys have bit 31 clear
-    const int64_t nvs = ntiles * (kSlots / 4);
+    const int64_t nvs = ntiles * kSlotVecs;
     const int64_t stride = (int64_t)kSlotGrid * kSlotThreads;
     constexpr int U = 8;  // vectors in flight per thread; the counts are loaded alongside, not before
     for (int64_t w0 = (int64_t)blockIdx.x * kSlotThreads + tid; w0 < nvs; w0 += U * stride) {
@@ -725,13 +731,13 @@ __device__ __forceinline__ void slots_hist(const topk_state *__restrict__ st,
             cnt[i] = 0u;
             v[i] = u32x4{0u, 0u, 0u, 0u};
             if (w < nvs) {
-                cnt[i] = slot_cnt[w >> 3];
+                cnt[i] = slot_cnt[w >> kSlotVecShift];
                 v[i] = ((const u32x4 *)slot_bits)[w];  // entries at or above the count are stale, and skipped below
             }
         }
 #pragma unroll
         for (int i = 0; i < U; ++i) {
-            const uint32_t q4 = (uint32_t)((w0 + i * stride) & 7) * 4u;
+            const uint32_t q4 = (uint32_t)((w0 + i * stride) & (kSlotVecs - 1)) * 4u;
             const uint32_t c = cnt[i] == kCrowded ? 0u : cnt[i];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -782,13 +788,13 @@ __device__ __forceinline__ void slots_count(const topk_state *__restrict__ st,
                                             uint32_t *__restrict__ cnt_gt, uint32_t *__restrict__ cnt_eq,
                                             uint32_t groups)
 {
-    const int64_t nvs = ntiles * (kSlots / 4);
+    const int64_t nvs = ntiles * kSlotVecs;
     const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const uint32_t T = st->threshold;
     uint32_t gt = 0u, eq = 0u;
     bool listed = false;
     if (w < nvs) {
-        const uint32_t cnt = slot_cnt[w >> 3], q4 = (uint32_t)(w & 7) * 4u;
+        const uint32_t cnt = slot_cnt[w >> kSlotVecShift], q4 = (uint32_t)(w & (kSlotVecs - 1)) * 4u;
         listed = cnt == kCrowded;
         if (!listed && q4 < cnt) {
             const u32x4 v = ((const u32x4 *)slot_bits)[w];
@@ -801,13 +807,13 @@ __device__ __forceinline__ void slots_count(const topk_state *__restrict__ st,
         }
     }
 #pragma unroll
-    for (int d = 1; d < 8; d <<= 1) {  // the eight lanes of a tile; every lane of the wave takes part
+    for (int d = 1; d < kSlotVecs; d <<= 1) {  // the lanes of a tile; every lane of the wave takes part
         gt += __shfl_xor(gt, d, 64);
         eq += __shfl_xor(eq, d, 64);
     }
-    if (w < nvs && (w & 7) == 0 && !listed) {
-        cnt_gt[w >> 3] = gt;
-        cnt_eq[w >> 3] = eq;
+    if (w < nvs && (w & (kSlotVecs - 1)) == 0 && !listed) {
+        cnt_gt[w >> kSlotVecShift] = gt;
+        cnt_eq[w >> kSlotVecShift] = eq;
     }
     // the crowded tiles, from R: one wave per tile (this kernel's waves walk the list)
     const uint32_t n_crowded = st->n_crowded;
@@ -816,13 +822,13 @@ __device__ __forceinline__ void slots_count(const topk_state *__restrict__ st,
         count_tile(R, n, crowded[i], T, threadIdx.x & 63, cnt_gt, cnt_eq);
 }
 
-// Exclusive prefix sum over each group of eight neighbouring lanes.
-__device__ __forceinline__ uint32_t group8_excl_scan(uint32_t x)
+// Exclusive prefix sum over each group of kSlotVecs neighbouring lanes (the lanes of one tile).
+__device__ __forceinline__ uint32_t tile_lanes_excl_scan(uint32_t x)
 {
-    const int l = threadIdx.x & 7;
+    const int l = threadIdx.x & (kSlotVecs - 1);
     uint32_t incl = x;
 #pragma unroll
-    for (int d = 1; d < 8; d <<= 1) {
+    for (int d = 1; d < kSlotVecs; d <<= 1) {
         const uint32_t y = __shfl_up(incl, d, 64);
         if (l >= d) incl += y;
     }
@@ -830,7 +836,7 @@ __device__ __forceinline__ uint32_t group8_excl_scan(uint32_t x)
 }
 
 // Ordered write of the kept slot entries; entries of a tile are in ascending index
-// order across its eight lanes.
+// order across its kSlotVecs lanes.
 // The first `groups` workgroups of the grid take part (256 threads each).
 __device__ __forceinline__ void slots_write(float *R, int64_t n, const topk_state *__restrict__ st,
                                             const uint32_t *__restrict__ slot_cnt,
@@ -844,14 +850,14 @@ __device__ __forceinline__ void slots_write(float *R, int64_t n, const topk_stat
                                             float *__restrict__ vals, uint32_t *__restrict__ idx,
                                             uint32_t kmax, uint32_t groups)
 {
-    const int64_t nvs = ntiles * (kSlots / 4);
+    const int64_t nvs = ntiles * kSlotVecs;
     const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const uint32_t T = st->threshold, ties = st->ties;
     u32x4 v = {0u, 0u, 0u, 0u};
     uint32_t gtm = 0u, eqm = 0u, eq_before = 0u, tile_pos = 0u;
     if (w < nvs) {
-        const int64_t tile = w >> 3;
-        const uint32_t cnt = slot_cnt[tile], q4 = (uint32_t)(w & 7) * 4u;
+        const int64_t tile = w >> kSlotVecShift;
+        const uint32_t cnt = slot_cnt[tile], q4 = (uint32_t)(w & (kSlotVecs - 1)) * 4u;
         if (cnt != kCrowded && q4 < cnt) {
             v = ((const u32x4 *)slot_bits)[w];
 #pragma unroll
@@ -866,7 +872,7 @@ __device__ __forceinline__ void slots_write(float *R, int64_t n, const topk_stat
         }
     }
     // every lane of the wave takes part in the two scans
-    uint32_t eq_rank = eq_before + group8_excl_scan(__popc(eqm));
+    uint32_t eq_rank = eq_before + tile_lanes_excl_scan(__popc(eqm));
     uint32_t selm = gtm;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -875,7 +881,7 @@ __device__ __forceinline__ void slots_write(float *R, int64_t n, const topk_stat
             ++eq_rank;
         }
     }
-    uint32_t pos = tile_pos + group8_excl_scan(__popc(selm));
+    uint32_t pos = tile_pos + tile_lanes_excl_scan(__popc(selm));
     if (selm != 0u) {
         const u32x4 at = ((const u32x4 *)slot_idx)[w];
 #pragma unroll
@@ -1088,7 +1094,7 @@ covap::launch_status run_topk(const void *grad, void *residual, int64_t n, int64
     const int64_t m = (int64_t)n_s * 256;
     const int64_t want = 2 * div_up(k * m, n) + 32;
     const uint32_t target = (uint32_t)(want < ((int64_t)1 << 31) ? want : ((int64_t)1 << 31));
-    const uint32_t slot_vec_grid = (uint32_t)div_up(ntiles * (kSlots / 4), 256);
+    const uint32_t slot_vec_grid = (uint32_t)div_up(ntiles * kSlotVecs, 256);
     // the general tail's tile kernels walk the tiles with a bounded grid, so that
     // they cost next to nothing when they are not taken
     const uint32_t tail_grid = (uint32_t)(ntiles < 16384 ? ntiles : 16384);
