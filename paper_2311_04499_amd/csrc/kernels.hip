@@ -1,5 +1,6 @@
-// COVAP hot-path kernels for gfx950 (MI355X): covap_compress and
-// covap_decompress, plus two plain streaming probes.
+// COVAP hot-path kernels for gfx950 (MI355X): covap_compress (also on a bounded,
+// persistent grid), its aliased form and covap_decompress, plus the measurement
+// probes (two plain streaming kernels and one that only keeps the matrix cores busy).
 //
 // Both kernels are pure HBM streaming (at most one FMA per 12 bytes moved), so
 // the design is about memory access only:
@@ -16,8 +17,10 @@
 //     vector path is always aligned; a shard's ragged tail (< one vector) goes
 //     through a scalar path in the same launch.  Alignment to 1 KiB, one wave's
 //     access, is faster still, which the planner provides for variable-length shards.
-// No LDS (beyond an unused reservation that caps occupancy) and no MFMA: there is no
-// data reuse and no contraction.
+// How a workgroup index becomes a tile is in geom.h (shared with the host, which
+// builds the launch geometry in plan.cpp and can replay it).  The hot path uses no LDS
+// (beyond an unused reservation that caps occupancy) and no MFMA: there is no data
+// reuse and no contraction.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>

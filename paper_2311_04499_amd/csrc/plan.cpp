@@ -1,6 +1,7 @@
-// Host side of libcovap: planner (arena layout, shards, buckets, interval),
-// ratio policy and error-feedback scheduler.  Pure host code: nothing here
-// touches the GPU, so plans can be built and queried on a machine without one.
+// Host side of libcovap: planner (arena layout, shards, buckets, interval), the
+// launch geometry of a hot-path call and its replay (covap_plan_trace), ratio policy,
+// error-feedback scheduler and the launch knobs.  Pure host code: nothing here
+// touches the GPU, so plans can be built, queried and traced on a machine without one.
 #include "plan.h"
 
 #include <algorithm>
