@@ -15,8 +15,9 @@ HIP-event duration, against the 8 TB/s peak), `kernels` (both), `configs` (the o
 benchmark configurations, briefly), `median_sharding` (the same workload under the
 paper's own sharding rule), `host_us_per_call`, the contrast kernels, the streamed
 (per-bucket / overlapped) measurements and `cpu_baseline` (the CPU oracle on one full
-iteration, one thread and all cores).  `--gpus N` with N > 1 is refused: this build
-is a single-GPU path with no collectives.
+iteration, one thread and all cores).  The line is a digest (about 2.5 KB); every
+measurement in full goes to the file named by --details.  `--gpus N` with N > 1 is
+refused: this build is a single-GPU path with no collectives.
 """
 import argparse
 import json
@@ -51,6 +52,8 @@ def parse_args():
     ap.add_argument("--no-probes", action="store_true")
     ap.add_argument("--no-streamed", action="store_true",
                     help="skip the per-bucket / HIP-graph / overlap measurements")
+    ap.add_argument("--details", default=os.path.join(ROOT, "gpurun_out", "bench_details.json"),
+                    help="file that receives every measurement in full (the stdout line is a digest)")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the other configurations, the median-sharding run and the host-cost figures")
     return ap.parse_args()
@@ -378,7 +381,68 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, run, args)
 
-    print(json.dumps(out), flush=True)
+    # The one line on stdout stays short (a record keeper may keep only the end of a run's output); everything
+    # measured goes, in full, to a file beside it.
+    details = args.details
+    try:
+        os.makedirs(os.path.dirname(details) or ".", exist_ok=True)
+        with open(details, "w") as f:
+            json.dump(out, f, indent=1)
+    except OSError:
+        details = None
+    print(json.dumps(compact(out, details), separators=(",", ":")), flush=True)
+
+
+def compact(out, details):
+    """The contract's fields in full, the rest boiled down to the figures that matter."""
+    line = {k: out[k] for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step",
+                                "higher_is_better", "scaling", "vs_baseline", "dtype", "data")}
+    c = out["config"]
+    line["config"] = {k: c[k] for k in ("workload", "elements", "shard_elems", "n_workers", "K", "mode", "sharding")}
+    r = out["roofline"]
+    line["roofline"] = {k: r[k] for k in ("bound", "kernel", "achieved", "peak", "unit", "frac", "traffic",
+                                          "traffic_source", "avg_launch_us")}
+    line["hbm_frac"] = out["hbm_frac"]
+    line["target_hbm_frac_0.70_met"] = out["target_hbm_frac_0.70_met"]
+    line["kernels"] = {k[6:]: {"avg_us": v["avg_us"], "frac": v["frac"]} for k, v in out["kernels"].items()}
+    if "cpu_baseline" in out:
+        b = out["cpu_baseline"]
+        line["cpu_baseline"] = {k: b[k] for k in ("value", "unit", "cores", "kind", "sample")}
+        if "all_cores" in b:
+            a = b["all_cores"]
+            line["cpu_baseline"]["all_cores"] = {"value": a["value"], "cores": a["cores"],
+                                                 "bit_identical": a["bit_identical_to_single_thread"]}
+    if "topk" in out and "us_per_iter" in out["topk"]:
+        t = out["topk"]
+        line["topk"] = {k: t[k] for k in ("us_per_iter", "vs_covap_compress", "target_10x_below_topk_met",
+                                          "decompress_us_per_iter") if k in t}
+    if "aliased_compress" in out:
+        a = out["aliased_compress"]
+        line["aliased_compress"] = {k: a[k] for k in ("us_per_iter", "topk_over_aliased") if k in a}
+    if "streamed" in out:
+        st = out["streamed"]
+        line["streamed"] = {"buckets": st["buckets"], "eager_us_per_step": st["eager_us_per_step"],
+                            "graph_us_per_step": st.get("graph_us_per_step")}
+        brief_ov = lambda v: {k: v[k] for k in ("hidden_frac", "exposed_us", "sync_only_us", "compress_us", "backward_us")}
+        if "overlap" in st:
+            line["streamed"]["overlap"] = dict(brief_ov(st["overlap"]), variant=st["overlap"]["variant"])
+            for name in ("mfma_only_handover_every_8", "gemm_aliased_handover_every_8"):
+                if name in st["overlap_variants"]:
+                    line["streamed"][name] = brief_ov(st["overlap_variants"][name])
+        elif "overlap_error" in st:
+            line["streamed"]["overlap_error"] = st["overlap_error"][:80]
+    if "configs" in out:
+        line["configs"] = [{"workload": c["workload"], "dtype": c["dtype"], "ms_per_step": c["ms_per_step"],
+                            "compress_frac": c["compress"]["frac"], "decompress_frac": c["decompress"]["frac"]}
+                           for c in out["configs"]]
+    if "median_sharding" in out:
+        m = out["median_sharding"]
+        line["median_sharding"] = {"ms_per_step": m["ms_per_step"], "compress_frac": m["compress"]["frac"],
+                                   "decompress_frac": m["decompress"]["frac"], "launches_per_call": m["launches_per_call"]}
+    if "host_us_per_call" in out:
+        line["host_us_per_call"] = out["host_us_per_call"]
+    line["details"] = os.path.relpath(details, ROOT) if details else None
+    return line
 
 
 def streamed(torch, B, run, ms_step, args):
