@@ -243,6 +243,22 @@ __global__ __launch_bounds__(64) void k_sparse_mean_sorted(const float *__restri
     }
     const uint32_t k_last = k - 1u;
 
+    // Window [cursor, cursor + 16) of every row: raw index and value.  The loads are
+    // unconditional (addresses clamped to the row) so that all of them are in flight
+    // together; what lies outside the row or the tile is masked out afterwards.
+    uint32_t raw[GROUPS];
+    float val[GROUPS];
+    auto load_windows = [&]() {
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g) {
+            const uint32_t j = cur[g] + (uint32_t)e;  // no wrap: cursor <= k <= n < 2^32 - 16 (checked on the host)
+            const uint64_t at = (uint64_t)row_off[g] + (j < k ? j : k_last);
+            raw[g] = idx[at];
+            val[g] = vals[at];
+        }
+    };
+    load_windows();
+
     for (int64_t t = tile_lo; t < tile_hi; ++t) {
         const int64_t T0 = t * kSpTile;
         const int64_t left = n - T0;
@@ -251,17 +267,16 @@ __global__ __launch_bounds__(64) void k_sparse_mean_sorted(const float *__restri
 #pragma unroll
         for (int v = 0; v < kSpTile / 4 / 64; ++v) ((f32x4 *)tile)[v * 64 + lane] = zero;
 
-        // window [cursor, cursor + 16) of every row: index relative to the tile start
-        // (anything outside the tile, past the row's end or in an unused row reads as
-        // "not in the tile") and value
+        // the windows were loaded while the previous tile was being added up and written
+        // out (the cursors they start from are known as soon as that tile's entries have
+        // been counted); index relative to the tile start, anything outside the tile, past
+        // the row's end or in an unused row reads as "not in the tile"
         uint32_t rel[GROUPS];
-        float val[GROUPS];
+        float now[GROUPS];
 #pragma unroll
         for (int g = 0; g < GROUPS; ++g) {
-            const uint32_t j = cur[g] + (uint32_t)e;  // no wrap: cursor <= k <= n < 2^32 - 16 (checked on the host)
-            const uint64_t at = (uint64_t)row_off[g] + (j < k ? j : k_last);
-            rel[g] = idx[at];
-            val[g] = vals[at];
+            rel[g] = raw[g];
+            now[g] = val[g];
         }
         bool full_window = false;  // a row whose 16th entry is in the tile may have more there
 #pragma unroll
@@ -274,12 +289,16 @@ __global__ __launch_bounds__(64) void k_sparse_mean_sorted(const float *__restri
         if (__ballot(full_window) == 0ull) {
 #pragma unroll
             for (int g = 0; g < GROUPS; ++g) {
-                const bool in = rel[g] < len;
-                const uint64_t m = __ballot(in);
+                const uint64_t m = __ballot(rel[g] < len);
                 cur[g] += (uint32_t)__popcll((m >> (16 * q)) & 0xffffull);  // in-tile entries of this lane's row
+            }
+            load_windows();  // the next tile's, in flight during the adds and the write-out below
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) {
+                const bool in = rel[g] < len;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {  // one add instruction per row, rows in order
-                    if (q == r && in) lds_add(&tile[rel[g]], val[g]);
+                    if (q == r && in) lds_add(&tile[rel[g]], now[g]);
                 }
             }
         } else {
@@ -339,6 +358,7 @@ __global__ __launch_bounds__(64) void k_sparse_mean_sorted(const float *__restri
                 for (int g = 0; g < GROUPS; ++g)
                     if (g == g0) cur[g] += add;
             }
+            load_windows();
         }
 
         // mean and write-out (the wave's own LDS operations above are complete, in order,
