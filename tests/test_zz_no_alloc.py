@@ -90,3 +90,36 @@ def test_static_workspace_limit_and_errors(B):
     R0 = torch.randn(n, generator=g, device=DEV)
     ref, got = both(B, G, R0, n // 1000, 1.0)
     same(got, ref, "largest n")
+
+
+def test_static_workspace_under_hip_graph_replay(B):
+    """What the entry point is for: captured once in a HIP graph (capture forbids allocation; the call
+    records kernels only, no memset node) and replayed with the program's own eager work and
+    synchronisations in between; every replay must give the bits the oracle gives for that step's inputs."""
+    import oracle
+    n, k = 300_017, 301
+    wl = workloads.scaled_down(workloads.config(5), [n], 4096)
+    G = torch.empty(n, device=DEV)
+    R = torch.zeros(n, device=DEV)
+    vals = torch.empty(k, device=DEV)
+    idx = torch.empty(k, dtype=torch.int32, device=DEV)
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    G.copy_(workloads.gradient(wl, 0, 0, DEV))
+    B.topk_compress_static(G, R, k, vals, idx, ef_coeff=0.5)      # first use outside capture: the address look-up
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=side):
+        B.topk_compress_static(G, R, k, vals, idx, ef_coeff=0.5)
+    R.zero_()
+    Rc = np.zeros(n, np.float32)
+    for t in range(4):
+        G.copy_(workloads.gradient(wl, 0, t, DEV))
+        torch.cuda.synchronize()
+        g.replay()
+        other = torch.randn(1000, device=DEV).sum().item()        # eager work between replays
+        torch.cuda.synchronize()
+        ov, oi = oracle.topk(G.cpu().numpy(), Rc, k, 0.5)
+        assert np.array_equal(idx.cpu().numpy().view(np.uint32), oi), f"indices t={t}"
+        assert np.array_equal(vals.cpu().numpy().view(np.uint32), ov.view(np.uint32)), f"values t={t}"
+        assert np.array_equal(R.cpu().numpy().view(np.uint32), Rc.view(np.uint32)), f"residual t={t}"
+        assert other == other
