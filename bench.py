@@ -184,8 +184,8 @@ def brief(run, steps, warmup):
             "elements": run.D, "shards": run.plan.num_shards, "n_workers": run.N, "K": run.K, "steps": steps,
             "ms_per_step": round(wall * 1e3 / steps, 4),
             "grad_GB/s": round(run.esz * run.D / (wall / steps) / 1e9, 1),
-            "compress": {k: kc[k] for k in ("avg_us", "GB/s", "frac")},
-            "decompress": {k: kd[k] for k in ("avg_us", "GB/s", "frac")}}
+            "compress": {k: kc[k] for k in ("avg_us", "p10_us", "median_us", "p90_us", "GB/s", "frac")},
+            "decompress": {k: kd[k] for k in ("avg_us", "p10_us", "median_us", "p90_us", "GB/s", "frac")}}
 
 
 def main():
