@@ -57,26 +57,38 @@ def same_bits(gpu, cpu, what):
                          f"got bits {int(got[i])} want {int(want[i])}")
 
 
-def run_payload_mode(B, wl, plan, tab, steps, dtype=torch.float32, per_bucket=lambda t: False, c=1.0):
+KINDS = {  # element type of (gradient and dense result, residual, payload) and the plan's code
+    "f32": (torch.float32, torch.float32, torch.float32, "COVAP_F32"),
+    "bf16": (torch.bfloat16, torch.bfloat16, torch.bfloat16, "COVAP_BF16"),
+    "bf16_res32": (torch.bfloat16, torch.float32, torch.bfloat16, "COVAP_BF16_RES32"),
+    "f32_pay16": (torch.float32, torch.float32, torch.float16, "COVAP_F32_PAY16"),
+}
+
+
+def np_of(dtype):
+    return np.float32 if dtype == torch.float32 else np.uint16
+
+
+def run_payload_mode(B, wl, plan, tab, steps, kind="f32", per_bucket=lambda t: False, c=1.0):
     """Worker 0 runs the real compress every step (its residual carries over); rows 1..N-1 of
     the receive buffer are synthetic payloads at packed shape, uploaded once; gradients cycle
     through a ring of three generated sets."""
+    gdt, rdt, pdt, _ = KINDS[kind]
     K, N, D = wl.K, wl.n_workers, tab.D
-    np_dt = np.float32 if dtype == torch.float32 else np.uint16
     stride = (plan.packed_elems_max + 1023) // 1024 * 1024       # the benchmark's row stride
-    recv = torch.empty(N, stride, dtype=dtype, device=DEV)
-    recv[1:] = workloads.payload_rows(wl, N - 1, stride, 0, DEV, dtype)
+    recv = torch.empty(N, stride, dtype=pdt, device=DEV)
+    recv[1:] = workloads.payload_rows(wl, N - 1, stride, 0, DEV, pdt)
     recv_c = to_np(recv)
     ring, ring_c = [], []
     for i in range(3):
-        G = workloads.gradient(wl, 0, i, DEV, dtype)
+        G = workloads.gradient(wl, 0, i, DEV, gdt)
         if G.numel() < D:                                        # alignment padding of variable-length shards
-            G = torch.cat([G, torch.ones(D - G.numel(), dtype=dtype, device=DEV)])
+            G = torch.cat([G, torch.ones(D - G.numel(), dtype=gdt, device=DEV)])
         ring.append(G)
         ring_c.append(to_np(G))
-    R = torch.zeros(D, dtype=dtype, device=DEV)
-    Rc = np.zeros(D, np_dt)
-    out = torch.full((D,), float("nan"), dtype=dtype, device=DEV)
+    R = torch.zeros(D, dtype=rdt, device=DEV)
+    Rc = np.zeros(D, np_of(rdt))
+    out = torch.full((D,), float("nan"), dtype=gdt, device=DEV)
     out_c = to_np(out)
     nb = tab.n_buckets
     for t in steps:
@@ -97,19 +109,19 @@ def run_payload_mode(B, wl, plan, tab, steps, dtype=torch.float32, per_bucket=la
     return R
 
 
-def fixed_plans(B, wl, dtype):
-    code = B.COVAP_F32 if dtype == torch.float32 else B.COVAP_BF16
-    esz = 4 if dtype == torch.float32 else 2
-    plan = B.covap_plan(wl.numel, wl.shard_elems, wl.K, dtype=code)
+def fixed_plans(B, wl, kind):
+    gdt, _, _, code = KINDS[kind]
+    esz = 4 if gdt == torch.float32 else 2
+    plan = B.covap_plan(wl.numel, wl.shard_elems, wl.K, dtype=getattr(B, code))
     tab = oracle.plan_fixed(wl.numel, wl.shard_elems, (25 << 20) // esz)
     assert plan.total_elems == tab.D == wl.D and plan.num_shards == tab.n_shards
     return plan, tab
 
 
-def median_plans(B, wl, dtype):
-    code = B.COVAP_F32 if dtype == torch.float32 else B.COVAP_BF16
-    esz = 4 if dtype == torch.float32 else 2
-    plan = B.covap_plan(wl.numel, 0, wl.K, dtype=code, mode=B.COVAP_SHARD_MEDIAN)
+def median_plans(B, wl, kind):
+    gdt, _, _, code = KINDS[kind]
+    esz = 4 if gdt == torch.float32 else 2
+    plan = B.covap_plan(wl.numel, 0, wl.K, dtype=getattr(B, code), mode=B.COVAP_SHARD_MEDIAN)
     tab = oracle.plan_median(wl.numel, (25 << 20) // esz, wl.K, 0, 1024 // esz)
     assert plan.total_elems == tab.D and plan.num_shards == tab.n_shards and plan.num_buckets == tab.n_buckets
     return plan, tab
@@ -117,13 +129,13 @@ def median_plans(B, wl, dtype):
 
 def test_resnet50_shaped_run_every_iteration(B):
     wl = workloads.config(2)
-    plan, tab = fixed_plans(B, wl, torch.float32)
+    plan, tab = fixed_plans(B, wl, "f32")
     R = run_payload_mode(B, wl, plan, tab, range(wl.iterations))
     assert wl.iterations == 50 and bool((R != 0).any())
 
 
-@pytest.mark.parametrize("cfg,dtype", [(3, torch.float32), (4, torch.float32), (4, torch.bfloat16),
-                                       (5, torch.float32)])
+@pytest.mark.parametrize("cfg,dtype", [(3, "f32"), (4, "f32"), (4, "bf16"), (5, "f32"), (5, "bf16_res32"),
+                                       (5, "f32_pay16")])
 def test_first_two_periods_plus_one_at_full_size(B, cfg, dtype):
     wl = workloads.config(cfg)
     if cfg == 4:
@@ -135,8 +147,7 @@ def test_first_two_periods_plus_one_at_full_size(B, cfg, dtype):
     run_payload_mode(B, wl, plan, tab, steps, dtype)
 
 
-@pytest.mark.parametrize("cfg,dtype", [(3, torch.float32), (3, torch.bfloat16), (5, torch.float32),
-                                       (5, torch.bfloat16)])
+@pytest.mark.parametrize("cfg,dtype", [(3, "f32"), (3, "bf16"), (5, "f32"), (5, "bf16")])
 def test_paper_sharding_at_full_size(B, cfg, dtype):
     """Median sharding of the VGG-19- and GPT-2-medium-shaped sets: shards of millions of elements (thousands
     of tiles each, many dealing blocks).  First period whole-arena, second bucket by bucket, then one more

@@ -147,35 +147,6 @@ def test_half_payload_on_median_shards_and_buckets(B):
         same_bits(out.cpu().numpy(), out_c, f"dense t={t}")
 
 
-def test_half_payload_full_size_gpt2_medium(B):
-    """The benchmark's workload at full size (payload mode, default knobs), every
-    element against the oracle, on the step that sends the short last shard."""
-    wl = workloads.config(5)
-    K, N, D = wl.K, wl.n_workers, wl.D
-    plan = B.covap_plan(wl.numel, wl.shard_elems, K, dtype=B.COVAP_F32_PAY16)
-    tab = oracle.plan_fixed(wl.numel, wl.shard_elems, (25 << 20) // 4)
-    stride = (plan.packed_elems_max + 7) // 8 * 8
-    recv = torch.empty(N, stride, dtype=torch.float16, device=DEV)
-    recv[1:] = workloads.payload_rows(wl, N - 1, stride, 0, DEV, torch.float16)
-    R = workloads.gradient(wl, 1, 0, DEV)
-    Rc = R.cpu().numpy()
-    out = torch.empty(D, device=DEV)
-    t = 14
-    G = workloads.gradient(wl, 0, t, DEV)
-    B.covap_compress(plan, t, G, R, recv[0])
-    B.covap_decompress(plan, t, recv, out, n_workers=N, stride_elems=stride)
-    torch.cuda.synchronize()
-    P = plan.packed_elems(t)
-    recv_c = half_bits(recv)
-    sent_gpu = recv_c[0, :P].copy()
-    oracle.compress(tab, K, t, G.cpu().numpy(), Rc, recv_c[0])
-    same_bits(sent_gpu, recv_c[0, :P], "send")
-    same_bits(R.cpu().numpy(), Rc, "residual")
-    out_c = np.empty(D, np.float32)
-    oracle.decompress(tab, K, t, recv_c, out_c)
-    same_bits(out.cpu().numpy(), out_c, "dense")
-
-
 def test_half_payload_argument_errors(B):
     plan = B.covap_plan([4096], 512, 2, dtype=B.COVAP_F32_PAY16)
     G = torch.zeros(4096, device=DEV)
