@@ -5,7 +5,6 @@ construction (small integers, c = 1, N = 2), with the layout taken from the orac
 planner and filter.  The oracle's element loops are not run at this size (17 GB per
 buffer); their arithmetic is covered by the other parity tests, the addressing is what
 is at stake here."""
-import numpy as np
 import pytest
 import torch
 
