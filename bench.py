@@ -45,6 +45,8 @@ def parse_args():
     ap.add_argument("--shard-mode", choices=["fixed", "median"], default="fixed",
                     help="fixed-size shards (default) or the median sharding of Sec. III-C")
     ap.add_argument("--tune", action="append", default=[], help="key=value launch knob")
+    ap.add_argument("--shard-elems", type=int, default=0,
+                    help="fixed-size shards of this many elements instead of the configuration's own")
     ap.add_argument("--row-align", type=int, default=1024,
                     help="receive rows start on multiples of this many elements (default 1024)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -93,9 +95,12 @@ DTYPES = {  # name -> (gradient/dense, residual, payload) torch dtype names and 
 class Run:
     """One workload resident in HBM: plan, gradient ring, residual, receive rows, dense result."""
 
-    def __init__(self, torch, B, workloads, cfg, dtype, shard_mode, dev="cuda:0", ring=3, row_align=1024):
+    def __init__(self, torch, B, workloads, cfg, dtype, shard_mode, dev="cuda:0", ring=3, row_align=1024,
+                 shard_elems=0):
         self.torch, self.B = torch, B
         self.wl = wl = workloads.config(cfg)
+        if shard_elems:
+            wl.shard_elems = shard_elems
         t, r, p, code = DTYPES[dtype]
         self.tdtype, self.rdtype, self.pdtype = getattr(torch, t), getattr(torch, r), getattr(torch, p)
         self.esz, self.rsz, self.psz = (torch.empty(0, dtype=d).element_size() for d in (self.tdtype, self.rdtype, self.pdtype))
@@ -209,7 +214,8 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    run = Run(torch, B, workloads, args.config, args.dtype, args.shard_mode, dev, row_align=args.row_align)
+    run = Run(torch, B, workloads, args.config, args.dtype, args.shard_mode, dev, row_align=args.row_align,
+              shard_elems=args.shard_elems)
     wl, plan, D, N, K = run.wl, run.plan, run.D, run.N, run.K
     esz, stride, ring, residual, recv, dense = run.esz, run.stride, run.ring, run.residual, run.recv, run.dense
     stream = torch.cuda.current_stream()

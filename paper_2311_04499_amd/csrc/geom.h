@@ -78,9 +78,10 @@ COVAP_HD bool resolve_tile(const fixed_geom &g, uint32_t tile, uint32_t tile_ele
 // The grid does not walk the tiles in list order.  A long run of sent tiles makes
 // decompress run in lock-step "generations" of long-lived waves whose last, partly
 // filled generation is pure loss, so sent and unsent tiles are dealt out in blocks
-// of 2^g_shift tiles that alternate in proportion (measured: 18 % on the
-// VGG-19-shaped set against sent-first order).  Much finer alternation is harmful:
-// neighbouring workgroups would then write streams a power of two apart.  Block j
+// of 2^g_shift tiles (the host picks 1024, fewer for small launches) that alternate in
+// proportion (measured: 18 % on the VGG-19-shaped set against sent-first order).
+// Alternating workgroup by workgroup is harmful: neighbouring workgroups would then
+// write streams a power of two apart.  Block j
 // of the grid is a sent block iff floor((j+1) * rho / 2^32) > floor(j * rho / 2^32)
 // with rho = ceil(B_s * 2^32 / (B_s + B_u)) for B_s sent and B_u unsent blocks: the
 // floor counts the sent blocks before j, rises by 0 or 1 per block and reaches
