@@ -95,6 +95,10 @@ def lib():
         L.orc_decompress_pay16.restype = None
         L.orc_decompress_pay16.argtypes = [_u16p, C.c_int32, C.c_int64, _f32p, _i64p, _i64p, C.c_int64,
                                            C.c_int64, C.c_int32, C.c_uint64, C.c_int64]
+        for name, pin, pout in (("f32", _f32p, _f32p), ("bf16", _u16p, _u16p), ("pay16", _u16p, _f32p)):
+            f = getattr(L, "orc_unpack_mean_" + name)
+            f.restype = None
+            f.argtypes = [pin, C.c_int32, pout, _i64p, _i64p, C.c_int64, C.c_int64, C.c_int32, C.c_uint64, C.c_int64]
         L.orc_fp16_compress.restype = None
         L.orc_fp16_compress.argtypes = [_f32p, _f32p, C.c_int64, C.c_float, _u16p]
         L.orc_fp16_mean.restype = None
@@ -307,6 +311,25 @@ def decompress(tab: ShardTable, interval: int, t: int, recv, out, bucket: int = 
         _chk(out, recv.dtype)
         f = getattr(lib(), "orc_decompress_" + name)
         args = (_p(recv, ptr), recv.shape[0], recv.shape[1], _p(out, ptr))
+    off, ln = _p(tab.off, _i64p), _p(tab.len, _i64p)
+    calls = [lambda a=a, b=b: f(*args, off, ln, a, b, interval, t, tab.align)
+             for a, b in _ranges(tab, lo, hi, threads)]
+    _run(calls, threads)
+
+
+def unpack_mean(tab: ShardTable, interval: int, t: int, summed, n_workers: int, out, bucket: int = -1,
+                threads: int = 1) -> None:
+    """The step after a sum-AllReduce: `summed` is one payload row (the element-wise sum of the
+    workers' payloads), out = summed / n_workers where a shard was sent, +0 elsewhere.
+    summed uint16 with out float32 selects the half-payload form."""
+    lo, hi = tab.bucket_range(bucket)
+    if summed.dtype == np.uint16 and out.dtype == np.float32:
+        _chk(summed, np.uint16), _chk(out, np.float32)
+        f, args = lib().orc_unpack_mean_pay16, (_p(summed, _u16p), n_workers, _p(out, _f32p))
+    else:
+        name, ptr = _kind(summed)
+        _chk(summed, summed.dtype), _chk(out, summed.dtype)
+        f, args = getattr(lib(), "orc_unpack_mean_" + name), (_p(summed, ptr), n_workers, _p(out, ptr))
     off, ln = _p(tab.off, _i64p), _p(tab.len, _i64p)
     calls = [lambda a=a, b=b: f(*args, off, ln, a, b, interval, t, tab.align)
              for a, b in _ranges(tab, lo, hi, threads)]

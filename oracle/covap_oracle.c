@@ -450,6 +450,45 @@ void orc_decompress_bf16(const uint16_t *recv, int32_t N, int64_t stride,
     }
 }
 
+/*
+ * The same step when the exchange is a sum-AllReduce, which is how the paper
+ * runs it (Sec. II-A: the gradients are aggregated by AllReduce and averaged;
+ * Sec. III-B: COVAP keeps AllReduce because every worker sends the same
+ * shards).  `summed` is ONE payload row, the element-wise sum of the N workers'
+ * payloads as the collective delivered it, in the layout orc_compress_* writes.
+ * For shards [sh_lo, sh_hi):
+ *     selected:   out[i] = summed[q] / N
+ *     unselected: out[i] = +0
+ * The order in which the collective added the N payloads is its own; this
+ * routine only divides.
+ */
+void orc_unpack_mean_f32(const float *summed, int32_t N, float *out,
+                         const int64_t *off, const int64_t *len,
+                         int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t, int64_t align)
+{
+    int64_t q = orc_packed_end(len, sh_lo, I, t, align);
+    for (int64_t s = sh_lo; s < sh_hi; ++s) {
+        int sel = orc_selected(s, t, I);
+        if (sel) q = round_up(q, align);
+        for (int64_t i = off[s]; i < off[s] + len[s]; ++i)
+            out[i] = sel ? summed[q++] / (float)N : 0.0f;
+    }
+}
+
+/* bf16 payload and result: widen, divide in fp32, one RNE back. */
+void orc_unpack_mean_bf16(const uint16_t *summed, int32_t N, uint16_t *out,
+                          const int64_t *off, const int64_t *len,
+                          int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t, int64_t align)
+{
+    int64_t q = orc_packed_end(len, sh_lo, I, t, align);
+    for (int64_t s = sh_lo; s < sh_hi; ++s) {
+        int sel = orc_selected(s, t, I);
+        if (sel) q = round_up(q, align);
+        for (int64_t i = off[s]; i < off[s] + len[s]; ++i)
+            out[i] = sel ? f32_to_bf16(bf16_to_f32(summed[q++]) / (float)N) : (uint16_t)0;
+    }
+}
+
 /* ------------------------------------------------------------------ */
 /* Top-k sparsifier with error feedback (contrast; Sec. I, Table II)   */
 /* ------------------------------------------------------------------ */
@@ -649,6 +688,21 @@ void orc_decompress_pay16(const uint16_t *recv, int32_t N, int64_t stride,
                 out[i] = 0.0f;
             }
         }
+    }
+}
+
+/* Half-precision payload summed by the collective (in half precision: that is
+ * the collective's arithmetic, not this routine's); fp32 result = widened sum / N. */
+void orc_unpack_mean_pay16(const uint16_t *summed, int32_t N, float *out,
+                           const int64_t *off, const int64_t *len,
+                           int64_t sh_lo, int64_t sh_hi, int32_t I, uint64_t t, int64_t align)
+{
+    int64_t q = orc_packed_end(len, sh_lo, I, t, align);
+    for (int64_t s = sh_lo; s < sh_hi; ++s) {
+        int sel = orc_selected(s, t, I);
+        if (sel) q = round_up(q, align);
+        for (int64_t i = off[s]; i < off[s] + len[s]; ++i)
+            out[i] = sel ? f16_to_f32(summed[q++]) / (float)N : 0.0f;
     }
 }
 
