@@ -353,6 +353,19 @@ def main():
             out["aliased_compress"]["topk_over_aliased"] = round(out["topk"]["us_per_iter"] / us, 1)
         del acc_buf
 
+    # ---- the step after a sum-AllReduce (Sec. II-A, III-B): the collective has added the rows; one summed row
+    # comes in, summed / N goes out.  What one GPU of a real job runs per iteration is compress + this, not the
+    # N-row mean that `value` prices.
+    P_period = sum(plan.packed_elems(t) for t in range(K)) / K
+    pay_esz = recv.element_size()
+    us = timed_us(lambda t: B.covap_decompress_reduced(plan, t, recv[min(1, N - 1)], dense, N, stream=stream), reps=2 * K, warm=K)
+    red_bytes = pay_esz * P_period + esz * D
+    out["allreduce_form"] = {"decompress_reduced_us": round(us, 2), "algorithmic_bytes": round(red_bytes),
+                             "GB/s": round(red_bytes / (us * 1e-6) / 1e9, 1),
+                             "frac": round(red_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                             "compress_plus_decompress_reduced_us": round(tc_avg * 1e3 + us, 1),
+                             "gradient_GB/s": round(esz * D / ((tc_avg * 1e3 + us) * 1e-6) / 1e9, 1)}
+
     # ---- per-bucket streamed mode: one launch per communication bucket, as a DDP hook
     # would issue them while backward is still running (Sec. II-B); eager launches,
     # HIP graphs (one per residue of the step), and overlap with a synthetic backward
@@ -425,6 +438,9 @@ def compact(out, details):
     if "aliased_compress" in out:
         a = out["aliased_compress"]
         line["aliased_compress"] = {k: a[k] for k in ("us_per_iter", "topk_over_aliased") if k in a}
+    if "allreduce_form" in out:
+        a = out["allreduce_form"]
+        line["allreduce_form"] = {k: a[k] for k in ("decompress_reduced_us", "frac", "compress_plus_decompress_reduced_us")}
     if "streamed" in out:
         st = out["streamed"]
         line["streamed"] = {"buckets": st["buckets"], "eager_us_per_step": st["eager_us_per_step"],

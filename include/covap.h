@@ -16,7 +16,8 @@
  *                                                          Sec. II-A, Sec. III-B
  * Steps 1-4 are covap_compress (one kernel), step 5 is covap_decompress (one
  * kernel).  The exchange itself (AllReduce) is not part of this library: the
- * caller hands covap_decompress the N payload rows.
+ * caller hands covap_decompress the N payload rows, or, after a sum-AllReduce,
+ * hands covap_decompress_reduced the one summed row.
  *
  * Conventions
  *  - Pointers marked [device] are HIP device pointers owned by the caller; the
@@ -241,6 +242,26 @@ covap_status_t covap_decompress(const covap_plan_t *plan, uint64_t step, int32_t
                                 const void *recv, int32_t n_workers, int64_t stride_elems,
                                 void *dense_out, void *stream);
 
+/* Step 5 when the exchange is a sum-AllReduce, as the paper runs it (Sec. II-A:
+ * AllReduce, then the average; Sec. III-B: COVAP keeps AllReduce because every
+ * worker sends the same shards): the collective has already added the workers'
+ * payloads, and what is left is the division and the unpack.
+ *   summed     [device] const, ONE payload row in covap_compress's layout for
+ *              this step: the element-wise sum of the n_workers payloads, in the
+ *              payload's element type (the order and precision of that sum are
+ *              the collective's); at least packed_base + packed_elems elements
+ *              for the bucket
+ *   n_workers  the divisor
+ *   dense_out  [device] as in covap_decompress: summed / n_workers where the
+ *              shard was sent (widened to fp32, IEEE division, one rounding
+ *              back for bf16), +0.0 elsewhere
+ * Reads packed_elems and writes the bucket's elements, whatever n_workers is.
+ * Same bits as covap_decompress on one row holding that sum with the divisor
+ * n_workers.  EINVAL: n_workers < 1, null/misaligned/overlapping pointers. */
+covap_status_t covap_decompress_reduced(const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                                        const void *summed, int32_t n_workers, void *dense_out,
+                                        void *stream);
+
 /* ---- fine-grained top-k sparsifier (contrast point; Sec. I, Table II) --- */
 
 /* Bytes of device workspace topk_compress needs for n elements of `dtype`
@@ -356,6 +377,13 @@ covap_status_t covap_probe_mfma(float *out, int32_t workgroups, int32_t iters, i
  *   "topk_pass1_waves"   waves that share a 1024-element tile in the first pass of
  *                        topk_compress: 1, 2, 4
  *   "topk_pass1_lds_pad" as decompress_lds_pad, for that pass: 0, 6144, 8192, 24576
+ * Value -1 returns a knob to "never set".  While "decompress_threads",
+ * "decompress_tile" and "decompress_lds_pad" are all in that state, a decompress
+ * call that reads fewer payload elements than it writes dense ones (few rows:
+ * covap_decompress_reduced always, covap_decompress with n_workers below about the
+ * interval) runs as 256-thread workgroups without the LDS reservation: it is bound
+ * by its stores, and that shape fills memory faster; covap_tune_get reports the
+ * many-row values.
  * No knob changes any result bit.  EINVAL for an unknown key or value.  For
  * tuning sweeps and tests only: the knobs are global to the process (every plan and
  * every later call sees a change).  Stores and loads are atomic and a hot-path call

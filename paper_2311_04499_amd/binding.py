@@ -114,6 +114,8 @@ def lib():
     L.covap_compress_aliased.argtypes = [_vp, C.c_uint64, C.c_int32, _vp, _vp, C.c_int64, _vp]
     L.covap_decompress.restype = C.c_int
     L.covap_decompress.argtypes = [_vp, C.c_uint64, C.c_int32, _vp, C.c_int32, C.c_int64, _vp, _vp]
+    L.covap_decompress_reduced.restype = C.c_int
+    L.covap_decompress_reduced.argtypes = [_vp, C.c_uint64, C.c_int32, _vp, C.c_int32, _vp, _vp]
     L.topk_workspace_bytes.restype = C.c_size_t
     L.topk_workspace_bytes.argtypes = [C.c_int64, C.c_int32]
     L.topk_compress.restype = C.c_int
@@ -316,6 +318,16 @@ def covap_decompress(plan: Plan, step: int, recv, dense_out, n_workers: Optional
     _need(dense_out, "dense_out", plan.total_elems, _GRAD_ESZ[plan.dtype])
     _check(lib().covap_decompress(plan.handle, step, bucket, _ptr(recv), n_workers, stride_elems,
                                   _ptr(dense_out), _stream(stream)))
+
+
+def covap_decompress_reduced(plan: Plan, step: int, summed, dense_out, n_workers: int, bucket: int = -1,
+                             stream=None) -> None:
+    used = plan.packed_elems(step, bucket)
+    if used > 0:
+        _need(summed, "summed", plan.packed_base(step, bucket) + used, _PAYLOAD_ESZ[plan.dtype])
+    _need(dense_out, "dense_out", plan.total_elems, _GRAD_ESZ[plan.dtype])
+    _check(lib().covap_decompress_reduced(plan.handle, step, bucket, _ptr(summed), n_workers, _ptr(dense_out),
+                                          _stream(stream)))
 
 
 def topk_workspace_bytes(n: int, dtype: int = COVAP_F32) -> int:

@@ -761,10 +761,10 @@ bool launch_compress(const covap::tuning &tn, const covap_plan_s *plan, const co
 template <typename OPS>
 bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
                        const covap::call_range &cr, hipStream_t st, const void *recv, void *out,
-                       int32_t N, int64_t stride, covap::launch_status &ls)
+                       int32_t N, int32_t divisor, int64_t stride, covap::launch_status &ls)
 {
-    const int pow2 = (N & (N - 1)) == 0;
-    const float n_f = (float)N, inv_n = 1.0f / n_f;
+    const int pow2 = (divisor & (divisor - 1)) == 0;
+    const float n_f = (float)divisor, inv_n = 1.0f / n_f;
     return pick<64, 256>(tn.decompress_threads, [&](auto T) {
         pick<1, 2, 4>(tn.decompress_tile, [&](auto U) {
             pick<1, 2, 4>(tn.decompress_unroll, [&](auto WU) {
@@ -786,10 +786,10 @@ bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
 // 16-byte payload vector per thread).
 bool launch_decompress_pay16(const covap::tuning &tn, const covap_plan_s *plan,
                              const covap::call_range &cr, hipStream_t st, const void *recv, void *out,
-                             int32_t N, int64_t stride, covap::launch_status &ls)
+                             int32_t N, int32_t divisor, int64_t stride, covap::launch_status &ls)
 {
-    const int pow2 = (N & (N - 1)) == 0;
-    const float n_f = (float)N, inv_n = 1.0f / n_f;
+    const int pow2 = (divisor & (divisor - 1)) == 0;
+    const float n_f = (float)divisor, inv_n = 1.0f / n_f;
     return pick<64, 256>(tn.decompress_threads, [&](auto T) {
         pick<1, 2, 4>(tn.decompress_unroll, [&](auto WU) {
             pick<0, 1>(tn.nontemporal, [&](auto NT) {
@@ -912,40 +912,70 @@ covap_status_t covap_compress_aliased(const covap_plan_t *plan, uint64_t step, i
     return ls.report("covap_compress_aliased");
 }
 
-covap_status_t covap_decompress(const covap_plan_t *plan, uint64_t step, int32_t bucket,
-                                const void *recv, int32_t n_workers, int64_t stride_elems,
-                                void *dense_out, void *stream)
+// Shared body of covap_decompress and covap_decompress_reduced: `rows` payload
+// rows are added in row order and the sum is divided by `divisor`.
+static covap_status_t decompress_call(const char *who, const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                                      const void *recv, int32_t rows, int32_t divisor, int64_t stride_elems,
+                                      void *dense_out, void *stream)
 {
     covap::clear_error();
     covap::call_range cr;
     const covap_status_t rs = covap::resolve(plan, step, bucket, &cr);
     if (rs != COVAP_OK) return rs;
-    if (!recv || !dense_out) return fail(COVAP_EINVAL, "covap_decompress: null device pointer");
+    if (!recv || !dense_out) return fail(COVAP_EINVAL, who, "null device pointer");
     if (!aligned16(recv) || !aligned16(dense_out))
-        return fail(COVAP_EINVAL, "covap_decompress: device pointers must be 16-byte aligned");
-    if (n_workers < 1) return fail(COVAP_EINVAL, "covap_decompress: n_workers < 1");
+        return fail(COVAP_EINVAL, who, "device pointers must be 16-byte aligned");
+    if (rows < 1 || divisor < 1) return fail(COVAP_EINVAL, who, "n_workers < 1");
+    if (rows == 1 && stride_elems < 0) stride_elems = cr.packed_base + cr.packed_elems;   // one row: its own length
     if (cr.packed_elems > 0 && stride_elems < cr.packed_base + cr.packed_elems)
-        return fail(COVAP_EINVAL, "covap_decompress: row stride smaller than the packed payload");
-    if (n_workers > 1 && stride_elems % plan->elems_per_vec != 0)
-        return fail(COVAP_EINVAL, "covap_decompress: row stride must be a multiple of 16 bytes");
+        return fail(COVAP_EINVAL, who, "row stride smaller than the packed payload");
+    if (rows > 1 && stride_elems % plan->elems_per_vec != 0)
+        return fail(COVAP_EINVAL, who, "row stride must be a multiple of 16 bytes");
     const int32_t dt = plan->opts.dtype;
-    if (overlap(recv, (int64_t)n_workers * stride_elems * payload_esz(dt), dense_out,
-                plan->total_elems * grad_esz(dt)))
-        return fail(COVAP_EINVAL, "covap_decompress: recv and dense_out must not overlap");
+    if (overlap(recv, (int64_t)rows * stride_elems * payload_esz(dt), dense_out, plan->total_elems * grad_esz(dt)))
+        return fail(COVAP_EINVAL, who, "the payload and dense_out must not overlap");
     if (cr.sh_hi == cr.sh_lo) return COVAP_OK;
 
-    const covap::tuning tn = covap::tune();
+    covap::tuning tn = covap::tune();
+    // Few rows: the call writes more than it reads and is bound by its stores.  256-thread
+    // workgroups without the LDS reservation fill memory faster than the one-wave shape that
+    // suits many rows (measured crossover: rows x packed elements = dense elements).
+    const covap_shard_rec &first = plan->shards[cr.sh_lo], &last = plan->shards[cr.sh_hi - 1];
+    if (tn.decompress_shape_unset && (int64_t)rows * cr.packed_elems < last.off + last.len - first.off) {
+        tn.decompress_threads = 256;
+        tn.decompress_tile = 1;
+        tn.decompress_lds_pad = 0;
+    }
     hipStream_t st = (hipStream_t)stream;
     covap::launch_status ls;
     bool ok;
     if (dt == COVAP_F32)
-        ok = launch_decompress<ops_f32>(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems, ls);
+        ok = launch_decompress<ops_f32>(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, ls);
     else if (dt == COVAP_F32_PAY16)
-        ok = launch_decompress_pay16(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems, ls);
+        ok = launch_decompress_pay16(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, ls);
     else
-        ok = launch_decompress<ops_bf16>(tn, plan, cr, st, recv, dense_out, n_workers, stride_elems, ls);
-    if (!ok) return fail(COVAP_EINVAL, "covap_decompress: launch knobs select no kernel");
-    return ls.report("covap_decompress");
+        ok = launch_decompress<ops_bf16>(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, ls);
+    if (!ok) return fail(COVAP_EINVAL, who, "launch knobs select no kernel");
+    return ls.report(who);
+}
+
+covap_status_t covap_decompress(const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                                const void *recv, int32_t n_workers, int64_t stride_elems,
+                                void *dense_out, void *stream)
+{
+    if (stride_elems < 0) {
+        covap::clear_error();
+        return fail(COVAP_EINVAL, "covap_decompress", "row stride smaller than the packed payload");
+    }
+    return decompress_call("covap_decompress", plan, step, bucket, recv, n_workers, n_workers, stride_elems,
+                           dense_out, stream);
+}
+
+covap_status_t covap_decompress_reduced(const covap_plan_t *plan, uint64_t step, int32_t bucket,
+                                        const void *summed, int32_t n_workers, void *dense_out, void *stream)
+{
+    return decompress_call("covap_decompress_reduced", plan, step, bucket, summed, 1, n_workers, -1, dense_out,
+                           stream);
 }
 
 covap_status_t covap_probe_copy(void *dst, const void *src, size_t bytes, void *stream)

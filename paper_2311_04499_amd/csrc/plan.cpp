@@ -362,7 +362,14 @@ namespace covap {
 tuning tune()
 {
     tuning t;
-    for (int i = 0; i < kNumKnobs; ++i) t.*(kKnobs[i].field) = knob_value(i);
+    t.decompress_shape_unset = true;
+    for (int i = 0; i < kNumKnobs; ++i) {
+        const int raw = g_knob[i].load(std::memory_order_relaxed);
+        t.*(kKnobs[i].field) = raw < 0 ? kKnobs[i].initial : raw;
+        if (raw >= 0 && (kKnobs[i].field == &tuning::decompress_threads || kKnobs[i].field == &tuning::decompress_tile ||
+                         kKnobs[i].field == &tuning::decompress_lds_pad))
+            t.decompress_shape_unset = false;
+    }
     return t;
 }
 }  // namespace covap
@@ -555,6 +562,10 @@ covap_status_t covap_tune_set(const char *key, int32_t value)
     if (!key) return fail(COVAP_EINVAL, "covap_tune_set: null key");
     for (int i = 0; i < kNumKnobs; ++i) {
         if (std::strcmp(key, kKnobs[i].key)) continue;
+        if (value == -1) {  // back to "never set"
+            g_knob[i].store(-1, std::memory_order_relaxed);
+            return COVAP_OK;
+        }
         for (int a : kKnobs[i].allowed)
             if (a >= 0 && a == value) {
                 g_knob[i].store(value, std::memory_order_relaxed);

@@ -97,6 +97,9 @@ struct tuning {
     // workgroups 6144 caps a SIMD at 7 waves instead of 8 (8192: 6); a little less data in
     // flight keeps the DRAM access pattern tighter (+1.5..3 % measured).
     int decompress_lds_pad;
+    // True while decompress_threads, decompress_tile and decompress_lds_pad have never been
+    // set: decompress may then pick the workgroup shape from the call (few rows: store-bound).
+    bool decompress_shape_unset;
     int topk_pass1_waves;     // waves that share a 1024-element tile in top-k pass 1: 1, 2, 4
     int topk_pass1_lds_pad;   // unused LDS per pass-1 workgroup, bytes: 0, 6144, 8192, 24576
 };

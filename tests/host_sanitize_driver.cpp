@@ -138,6 +138,7 @@ int main()
     CHECK(covap_ef_coeff(0.1f, 5, 0, 0.1f, &c) == COVAP_EINVAL);
     CHECK(covap_tune_set("compress_unroll", 2) == COVAP_OK && covap_tune_get("compress_unroll") == 2);
     CHECK(covap_tune_set("compress_unroll", 3) == COVAP_EINVAL);
+    CHECK(covap_tune_set("compress_unroll", -1) == COVAP_OK && covap_tune_get("compress_unroll") == 1);
     CHECK(covap_tune_set(nullptr, 1) == COVAP_EINVAL && covap_tune_get("nope") == -1);
     CHECK(covap_last_error()[0] != 0);
     std::puts("host sanitize driver: ok");

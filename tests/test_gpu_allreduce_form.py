@@ -1,0 +1,202 @@
+"""GPU parity of covap_decompress_reduced, the mean after a sum-AllReduce (Sec. II-A,
+Sec. III-B): one summed payload row divided by N and put back in place.
+
+Against the oracle bit for bit (NaN positions must coincide) for every element type,
+fixed-size and median shards, whole-arena and bucket by bucket, every launch shape (the
+model-shaped sets at full size are covered with the other full-size runs);
+against covap_decompress on the GPU where both must give the same bits (fp32 rows added
+in worker order are what covap_decompress adds itself); and the error paths.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_04499_amd import workloads
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+EINVAL = 1
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2311_04499_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available()
+    return binding
+
+
+# element type of (dense result, payload) and the plan's code
+KINDS = {
+    "f32": (torch.float32, torch.float32, "COVAP_F32"),
+    "bf16": (torch.bfloat16, torch.bfloat16, "COVAP_BF16"),
+    "bf16_res32": (torch.bfloat16, torch.bfloat16, "COVAP_BF16_RES32"),
+    "f32_pay16": (torch.float32, torch.float16, "COVAP_F32_PAY16"),
+}
+
+
+def to_np(t):
+    t = t.detach().cpu().contiguous()
+    if t.dtype in (torch.bfloat16, torch.float16):
+        return t.view(torch.int16).numpy().view(np.uint16).copy()
+    return t.numpy().copy()
+
+
+def same(got, want, what, is_nan):
+    g = got.view(np.uint32 if got.itemsize == 4 else np.uint16)
+    w = want.view(g.dtype)
+    if np.array_equal(g, w):
+        return
+    ng, nw = is_nan(got), is_nan(want)
+    if np.array_equal(ng, nw) and np.array_equal(g[~ng], w[~nw]):
+        return
+    bad = np.nonzero(g != w)[0]
+    raise AssertionError(f"{what}: {bad.size} of {g.size} differ, first at {bad[0]}: got {g[bad[0]]:#x} want {w[bad[0]]:#x}")
+
+
+def nan_of(kind):
+    if KINDS[kind][0] == torch.float32:
+        return np.isnan
+    return lambda a: (a & 0x7fff) > 0x7f80                        # bf16 bit patterns
+
+
+def plans(B, kind, numel, K, S=0, cap=25 << 20, ref=0):
+    gdt, pdt, code = KINDS[kind]
+    esz = 4 if gdt == torch.float32 else 2
+    pay_esz = 4 if pdt == torch.float32 else 2
+    if S:
+        plan = B.covap_plan(numel, S, K, dtype=getattr(B, code), bucket_cap_bytes=cap)
+        tab = oracle.plan_fixed(numel, S, max(1, cap // esz))
+    else:
+        plan = B.covap_plan(numel, 0, K, dtype=getattr(B, code), bucket_cap_bytes=cap, mode=B.COVAP_SHARD_MEDIAN,
+                            ref_elems=ref)
+        tab = oracle.plan_median(numel, max(1, cap // esz), K, ref, 1024 // pay_esz)   # 1 KiB of payload
+    assert plan.total_elems == tab.D and plan.num_shards == tab.n_shards and plan.num_buckets == tab.n_buckets
+    return plan, tab
+
+
+SPECIALS = [0.0, -0.0, float("inf"), float("-inf"), float("nan"), 1e-45, -3e-45, 1.1754942e-38, 1e-40, 3.4e38,
+            -3.4e38, 1.0, -1.0, 3.0, 65504.0, 6e-8, 5.9e-8, 6.1e-5, 1e-7, -65520.0]
+
+
+def summed_row(P, kind, seed):
+    """A row as a collective might leave it: wide range of magnitudes, specials in front."""
+    g = torch.Generator().manual_seed(seed)
+    x = torch.randn(P + 16, generator=g) * torch.pow(10.0, torch.randint(-6, 6, (P + 16,), generator=g).float())
+    n = min(P, len(SPECIALS))
+    x[:n] = torch.tensor(SPECIALS[:n])
+    return x.to(KINDS[kind][1]).to(DEV)
+
+
+def check(B, plan, tab, K, kind, t, N, per_bucket, seed=0):
+    P = plan.packed_elems(t)
+    assert P == oracle.packed_elems(tab, K, t)
+    summed = summed_row(P, kind, 1000 * seed + 17 * t + N)
+    out = torch.full((tab.D,), float("nan"), dtype=KINDS[kind][0], device=DEV)
+    out_c, summed_c = to_np(out), to_np(summed)
+    for b in (range(tab.n_buckets) if per_bucket else [-1]):
+        B.covap_decompress_reduced(plan, t, summed, out, N, bucket=b)
+    oracle.unpack_mean(tab, K, t, summed_c, N, out_c)
+    torch.cuda.synchronize()
+    same(to_np(out), out_c, f"{kind} t={t} N={N} per_bucket={per_bucket}", nan_of(kind))
+
+
+SHAPES = [
+    dict(numel=[100_003], S=4096, K=3),
+    dict(numel=[7], S=8, K=2),
+    dict(numel=[8 * 4096 + 9, 1, 77], S=8192, K=4),
+    dict(numel=[300_000, 12_345], S=8192, K=3, cap=100_000),
+    dict(numel=[1_003, 2_001, 30_007, 5, 4_099, 17, 90_001, 3], K=3, cap=20_000),
+    dict(numel=[41_011, 167_813, 1_074_805, 70_794, 76_697, 5_551], K=4, cap=4, ref=55_903),
+    dict(numel=[2_500_000, 7], K=2, cap=4),                       # a shard of many dealing blocks beside a tiny one
+]
+
+
+@pytest.mark.parametrize("kind", list(KINDS))
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: f"{'fixed' if s.get('S') else 'median'}-{sum(s['numel'])}")
+def test_against_the_oracle(B, kind, shape):
+    plan, tab = plans(B, kind, shape["numel"], shape["K"], shape.get("S", 0), shape.get("cap", 25 << 20),
+                      shape.get("ref", 0))
+    K = shape["K"]
+    for t in range(K + 1):
+        for N in (1, 2, 3, 7, 64, 100):
+            check(B, plan, tab, K, kind, t, N, per_bucket=(t + N) % 2 == 1)
+    check(B, plan, tab, K, kind, 10 ** 15 + 7, 24, False)
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16", "f32_pay16"])
+def test_every_launch_shape(B, kind):
+    plan, tab = plans(B, kind, [1_003, 200_001, 30_007, 5, 4_099, 17, 900_001, 3], 3, cap=200_000)
+    keys = ("decompress_threads", "decompress_tile", "decompress_unroll", "nontemporal", "decompress_lds_pad")
+    old = {k: B.covap_tune_get(k) for k in keys}
+    try:
+        for threads in (64, 256):
+            for tile in (1, 2, 4):
+                for unroll in (1, 2, 4):
+                    for nt in (0, 1):
+                        for k, v in zip(keys, (threads, tile, unroll, nt, 8192 * nt)):
+                            B.covap_tune_set(k, v)
+                        check(B, plan, tab, 3, kind, tile + unroll, 7, per_bucket=bool(nt), seed=threads)
+    finally:
+        for k in old:
+            B.covap_tune_set(k, -1)                    # back to never set
+
+
+def test_equals_the_row_form_when_the_rows_are_added_in_worker_order(B):
+    """fp32: adding the N rows one after the other in fp32 is the sum covap_decompress forms
+    itself, so both entry points must return the same bits, full fidelity from compress on."""
+    wl = workloads.config(1)
+    K, N = 3, 5
+    for S, cap in ((4096, 25 << 20), (0, 40_000)):
+        plan, tab = plans(B, "f32", wl.numel, K, S=S, cap=cap)
+        D, stride = tab.D, (plan.packed_elems_max + 3) // 4 * 4
+        R = [torch.zeros(D, device=DEV) for _ in range(N)]
+        for t in range(2 * K + 1):
+            recv = torch.zeros(N, stride, device=DEV)
+            for w in range(N):
+                G = workloads.gradient(wl, w, t, DEV, torch.float32)
+                G = torch.cat([G, torch.ones(max(0, D - G.numel()), device=DEV)])[:D].contiguous()
+                B.covap_compress(plan, t, G, R[w], recv[w])
+            acc = recv[0].clone()
+            for w in range(1, N):
+                acc += recv[w]
+            a = torch.full((D,), float("nan"), device=DEV)
+            b = torch.full((D,), float("nan"), device=DEV)
+            B.covap_decompress(plan, t, recv, a)
+            B.covap_decompress_reduced(plan, t, acc, b, N)
+            torch.cuda.synchronize()
+            assert torch.equal(a.view(torch.int32), b.view(torch.int32)), (S, t)
+            out_c = np.full(D, np.nan, np.float32)
+            oracle.decompress(tab, K, t, to_np(recv), out_c)
+            same(to_np(b), out_c, f"S={S} t={t}", np.isnan)
+
+
+def test_argument_errors(B):
+    plan, tab = plans(B, "f32", [10_000], 4, S=1024)
+    P = plan.packed_elems_max
+    summed = torch.zeros(P, device=DEV)
+    out = torch.zeros(tab.D, device=DEV)
+    L = B.lib()
+    h, sp, op = plan.handle, summed.data_ptr(), out.data_ptr()
+    assert L.covap_decompress_reduced(h, 0, -1, sp, 0, op, None) == EINVAL
+    assert b"n_workers" in L.covap_last_error()
+    assert L.covap_decompress_reduced(h, 0, -1, None, 4, op, None) == EINVAL
+    assert L.covap_decompress_reduced(h, 0, -1, sp, 4, None, None) == EINVAL
+    assert L.covap_decompress_reduced(h, 0, -1, sp + 4, 4, op, None) == EINVAL
+    assert b"aligned" in L.covap_last_error()
+    assert L.covap_decompress_reduced(h, 0, 99, sp, 4, op, None) == 4                 # COVAP_ERANGE: no such bucket
+    assert L.covap_decompress_reduced(None, 0, -1, sp, 4, op, None) == EINVAL
+    assert L.covap_decompress_reduced(h, 0, -1, op, 4, op, None) == EINVAL          # overlap
+    assert b"overlap" in L.covap_last_error()
+    with pytest.raises(ValueError):
+        B.covap_decompress_reduced(plan, 0, summed[:P - 1], out, 4)                        # short payload
+    with pytest.raises(ValueError):
+        B.covap_decompress_reduced(plan, 0, summed, out[:tab.D - 1], 4)
+    with pytest.raises(ValueError):
+        B.covap_decompress_reduced(plan, 0, summed.to(torch.bfloat16), out, 4)             # wrong element type
+    # nothing above wrote to out; a good call does
+    assert not bool(out.any())
+    B.covap_decompress_reduced(plan, 0, torch.ones(P, device=DEV), out, 4)
+    torch.cuda.synchronize()
+    assert float(out.sum()) == 0.25 * plan.packed_elems(0)

@@ -4,7 +4,8 @@ the measurement plan fixes: every iteration of the ResNet-50-shaped run, the fir
 twice, so accumulate -> send -> clear -> accumulate happens at full size), in the
 benchmark's launch configuration (payload mode, default knobs, its row stride).
 Every element of the payload, the residual and the dense result is compared with the
-oracle after every step.  The same sets under the paper's own sharding (Sec. III-C:
+oracle after every step, and so is the dense result of the form that takes one summed
+payload row (the step after a sum-AllReduce).  The same sets under the paper's own sharding (Sec. III-C:
 25 MiB communication tensors cut by the median rule into pieces of several million
 elements), whole-arena and bucket by bucket.
 
@@ -106,6 +107,18 @@ def run_payload_mode(B, wl, plan, tab, steps, kind="f32", per_bucket=lambda t: F
         same_bits(recv[0], recv_c[0], f"send t={t}")              # untouched positions keep the NaN prefill on both sides
         same_bits(R, Rc, f"residual t={t}")
         same_bits(out, out_c, f"dense t={t}")
+        # the same step after a sum-AllReduce: the rows added up (here one after the other, in the
+        # payload's own type) and handed over as one row
+        acc = recv[0].clone()
+        for w in range(1, N):
+            acc += recv[w]
+        out.fill_(float("nan"))
+        out_c[:] = to_np(out)
+        for b in buckets:
+            B.covap_decompress_reduced(plan, t, acc, out, N, bucket=b)
+        oracle.unpack_mean(tab, K, t, to_np(acc), N, out_c, threads=THREADS)
+        torch.cuda.synchronize()
+        same_bits(out, out_c, f"dense after a summed exchange t={t}")
     return R
 
 

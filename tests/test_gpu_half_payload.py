@@ -80,8 +80,8 @@ def test_half_payload_iterations(B, numel, S, K, N, c):
             torch.cuda.synchronize()
             same_bits(out.cpu().numpy(), out_c, f"dense t={t}")
     finally:
-        for k, v in old.items():
-            B.covap_tune_set(k, v)
+        for k in old:
+            B.covap_tune_set(k, -1)                    # back to never set
 
 
 def test_half_payload_special_values(B):

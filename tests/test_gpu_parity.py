@@ -202,8 +202,8 @@ def test_launch_shape_knobs(B, key):
             run_iterations(B, wl, [9_001, 12_345], 1000, 5, 3, 6, per_bucket=True, cap_bytes=9000)
             run_iterations(B, wl, [8 * 4096 + 9], 8192, 4, 3, 5, dtype=torch.bfloat16)
     finally:
-        for k, v in old.items():
-            B.covap_tune_set(k, v)
+        for k in old:
+            B.covap_tune_set(k, -1)                    # back to never set
 
 
 def test_largest_launch_shapes_together(B):
@@ -214,8 +214,8 @@ def test_largest_launch_shapes_together(B):
         wl = workloads.scaled_down(workloads.config(1), [300_007], 16384)
         run_iterations(B, wl, [300_007], 16384, 4, 9, 5)
     finally:
-        for k, v in old.items():
-            B.covap_tune_set(k, v)
+        for k in old:
+            B.covap_tune_set(k, -1)                    # back to never set
 
 
 @pytest.mark.parametrize("numel,S,K,N", [([100_003], 4096, 3, 4), ([7], 8, 2, 3), ([8 * 4096 + 9], 8192, 4, 5),
@@ -339,8 +339,8 @@ def test_median_sharded_bf16_and_knobs(B):
             plans = make_median_plans(B, layers, 4, dtype=dtype, cap_bytes=40_000)
             run_iterations(B, wl, layers, 0, 4, 5, 6, dtype=dtype, plans=plans)
     finally:
-        for k, v in old.items():
-            B.covap_tune_set(k, v)
+        for k in old:
+            B.covap_tune_set(k, -1)                    # back to never set
     plans = make_median_plans(B, layers, 4, dtype=torch.bfloat16, cap_bytes=40_000)
     run_iterations(B, wl, layers, 0, 4, 3, 9, dtype=torch.bfloat16, plans=plans, c=0.25)
 
@@ -360,8 +360,8 @@ def test_median_sharded_long_shards_bf16_and_largest_launch_shapes(B):
             plans = make_median_plans(B, layers, 2, dtype=dtype, cap_bytes=4)
             run_iterations(B, wl, layers, 0, 2, 2, 3, dtype=dtype, plans=plans, per_bucket=True, c=0.5)
     finally:
-        for k, v in old.items():
-            B.covap_tune_set(k, v)
+        for k in old:
+            B.covap_tune_set(k, -1)                    # back to never set
     for dtype in (torch.float32, torch.bfloat16):
         plans = make_median_plans(B, layers, 3, dtype=dtype, cap_bytes=25 << 20, ref=400_000)
         run_iterations(B, wl, layers, 0, 3, 2, 7, dtype=dtype, plans=plans)
@@ -448,8 +448,8 @@ def test_mixed_precision_bf16_with_fp32_residual(B, numel, S, K, c):
             torch.cuda.synchronize()
             assert_same(to_np(out), out_c, f"dense t={t}")
     finally:
-        for k, v in old.items():
-            B.covap_tune_set(k, v)
+        for k in old:
+            B.covap_tune_set(k, -1)                    # back to never set
 
 
 def test_mixed_precision_on_median_shards(B):

@@ -192,6 +192,16 @@ def test_hot_path_rejects_bad_arguments_before_touching_the_gpu(B):
         B.covap_tune_set("compress_unroll", 3)
     assert B.covap_tune_get("compress_unroll") in (1, 2, 4)
     assert B.covap_tune_get("compress_threads") in (64, 256)
+    # -1 returns a knob to "never set": its initial value applies again
+    first = B.covap_tune_get("decompress_lds_pad")
+    B.covap_tune_set("decompress_lds_pad", 8192)
+    assert B.covap_tune_get("decompress_lds_pad") == 8192
+    B.covap_tune_set("decompress_lds_pad", -1)
+    assert B.covap_tune_get("decompress_lds_pad") == first
+    with pytest.raises(B.CovapError):
+        B.covap_tune_set("decompress_lds_pad", -2)
+    assert L.covap_decompress_reduced(p.handle, 0, -1, 1 << 20, 0, 1 << 30, None) == 1      # n_workers < 1
+    assert L.covap_decompress_reduced(p.handle, 0, 7, 1 << 20, 2, 1 << 30, None) == 4       # no such bucket
 
 
 @pytest.mark.parametrize("numel", [[0], [0, 0, 0], [5, 0, 7], [0, 16, 0]])
