@@ -373,7 +373,7 @@ covap_status_t covap_probe_mfma(float *out, int32_t workgroups, int32_t iters, i
  *   "decompress_unroll"  payload rows loaded before they are summed: 1, 2, 4
  *   "nontemporal"        streaming cache hints on loads and stores: 0, 1
  *   "decompress_lds_pad" bytes of unused LDS reserved per decompress workgroup, which
- *                        caps its occupancy: 0, 6144, 8192
+ *                        caps its occupancy: 0, 6144, 8192, 24576, 32768, 49152
  *   "topk_pass1_waves"   waves that share a 1024-element tile in the first pass of
  *                        topk_compress: 1, 2, 4
  *   "topk_pass1_lds_pad" as decompress_lds_pad, for that pass: 0, 6144, 8192, 24576
@@ -381,9 +381,10 @@ covap_status_t covap_probe_mfma(float *out, int32_t workgroups, int32_t iters, i
  * "decompress_tile" and "decompress_lds_pad" are all in that state, a decompress
  * call that reads fewer payload elements than it writes dense ones (few rows:
  * covap_decompress_reduced always, covap_decompress with n_workers below about the
- * interval) runs as 256-thread workgroups without the LDS reservation: it is bound
- * by its stores, and that shape fills memory faster; covap_tune_get reports the
- * many-row values.
+ * interval) is bound by its stores and runs in the shape that fills memory fastest:
+ * 256-thread workgroups, one 16-byte store per thread (fixed-size shards) or two and
+ * a 32 KiB reservation (variable-length shards).  covap_tune_get reports the many-row
+ * values.
  * No knob changes any result bit.  EINVAL for an unknown key or value.  For
  * tuning sweeps and tests only: the knobs are global to the process (every plan and
  * every later call sees a change).  Stores and loads are atomic and a hot-path call

@@ -39,6 +39,7 @@ using covap::tile_ref;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kProbeThreads = 64;
 
@@ -569,17 +570,13 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const u32x4 *__restrict
 // Half payload into an fp32 dense result.  A tile is kThreads * 8 elements: a
 // thread sums one 16-byte vector of eight halves over the N rows (fp32
 // accumulators, row order) and writes two 16-byte vectors of means.
-template <typename GEOM, int kThreads, int WU, bool NT>
-__global__ __launch_bounds__(kThreads) void k_decompress_pay16(const u32x4 *__restrict__ recv,
-                                                               float *__restrict__ out, GEOM g,
-                                                               int32_t N, int64_t stride_elems,
-                                                               float n_f, float inv_n, int pow2)
+template <int kThreads, int WU, bool NT>
+__device__ __forceinline__ void decompress_tile_pay16(const u32x4 *__restrict__ recv, float *__restrict__ out,
+                                                      const tile_ref &t, int32_t N, int64_t stride_elems,
+                                                      float n_f, float inv_n, int pow2)
 {
     using covap_dev::half_hi;
     using covap_dev::half_lo;
-    constexpr int TILE = kThreads * 8;
-    tile_ref t;
-    if (!covap::resolve_tile(g, blockIdx.x, (uint32_t)TILE, t)) return;
     const int tid = threadIdx.x;
     float *o = out + t.off;
     if (!t.sel) {  // nothing was sent for this shard: the dense result is +0
@@ -639,6 +636,73 @@ __global__ __launch_bounds__(kThreads) void k_decompress_pay16(const u32x4 *__re
     const int rem = t.n - nv * 8;
     if (tid < rem) {
         const int64_t e = (int64_t)nv * 8 + tid;
+        const uint16_t *row = rp + e;
+        float acc = __half2float(__ushort_as_half(row[0]));
+        for (int32_t w = 1; w < N; ++w) acc += __half2float(__ushort_as_half(row[(int64_t)w * stride_elems]));
+        o[e] = ops_f32::mean1(acc, n_f, inv_n, pow2 != 0);
+    }
+}
+
+template <typename GEOM, int kThreads, int WU, bool NT>
+__global__ __launch_bounds__(kThreads) void k_decompress_pay16(const u32x4 *__restrict__ recv,
+                                                               float *__restrict__ out, GEOM g,
+                                                               int32_t N, int64_t stride_elems,
+                                                               float n_f, float inv_n, int pow2)
+{
+    tile_ref t;
+    if (!covap::resolve_tile(g, blockIdx.x, (uint32_t)(kThreads * 8), t)) return;
+    decompress_tile_pay16<kThreads, WU, NT>(recv, out, t, N, stride_elems, n_f, inv_n, pow2);
+}
+
+// The same with four elements per thread: an 8-byte load per row, one 16-byte store.
+// For calls with few rows, which are bound by their stores: one store per thread from
+// 256-thread workgroups is the shape that fills memory fastest (the loads are half as
+// wide as they could be, which costs nothing when there are few of them).
+template <typename GEOM, int kThreads, bool NT>
+__global__ __launch_bounds__(kThreads) void k_decompress_pay16_narrow(const u32x2 *__restrict__ recv,
+                                                                      float *__restrict__ out, GEOM g,
+                                                                      int32_t N, int64_t stride_elems,
+                                                                      float n_f, float inv_n, int pow2)
+{
+    using covap_dev::half_hi;
+    using covap_dev::half_lo;
+    tile_ref t;
+    if (!covap::resolve_tile(g, blockIdx.x, (uint32_t)(kThreads * 4), t)) return;
+    const int tid = threadIdx.x;
+    float *o = out + t.off;
+    const int nv = t.n / 4, rem = t.n - nv * 4;
+    if (!t.sel) {  // nothing was sent for this shard: the dense result is +0
+        const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (tid < nv) {
+            if constexpr (NT)
+                __builtin_nontemporal_store(zero, (f32x4 *)o + tid);
+            else
+                ((f32x4 *)o)[tid] = zero;
+        }
+        if (tid < rem) o[nv * 4 + tid] = 0.0f;
+        return;
+    }
+    const uint16_t *rp = (const uint16_t *)recv + t.poff;  // 16-byte aligned: 8-byte loads are aligned too
+    if (tid < nv) {
+        const u32x2 *p = (const u32x2 *)rp + tid;
+        const int64_t stride_vec = stride_elems / 4;
+        u32x2 x = NT ? __builtin_nontemporal_load(p) : *p;
+        float acc[4] = {half_lo(x.x), half_hi(x.x), half_lo(x.y), half_hi(x.y)};
+        for (int32_t w = 1; w < N; ++w) {
+            const u32x2 *q = p + (int64_t)w * stride_vec;
+            x = NT ? __builtin_nontemporal_load(q) : *q;
+            acc[0] += half_lo(x.x); acc[1] += half_hi(x.x); acc[2] += half_lo(x.y); acc[3] += half_hi(x.y);
+        }
+        f32x4 m;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) m[j] = ops_f32::mean1(acc[j], n_f, inv_n, pow2 != 0);
+        if constexpr (NT)
+            __builtin_nontemporal_store(m, (f32x4 *)o + tid);
+        else
+            ((f32x4 *)o)[tid] = m;
+    }
+    if (tid < rem) {
+        const int64_t e = (int64_t)nv * 4 + tid;
         const uint16_t *row = rp + e;
         float acc = __half2float(__ushort_as_half(row[0]));
         for (int32_t w = 1; w < N; ++w) acc += __half2float(__ushort_as_half(row[(int64_t)w * stride_elems]));
@@ -761,8 +825,9 @@ bool launch_compress(const covap::tuning &tn, const covap_plan_s *plan, const co
 template <typename OPS>
 bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
                        const covap::call_range &cr, hipStream_t st, const void *recv, void *out,
-                       int32_t N, int32_t divisor, int64_t stride, covap::launch_status &ls)
+                       int32_t N, int32_t divisor, int64_t stride, bool store_bound, covap::launch_status &ls)
 {
+    (void)store_bound;  // the shape for it is in tn already
     const int pow2 = (divisor & (divisor - 1)) == 0;
     const float n_f = (float)divisor, inv_n = 1.0f / n_f;
     return pick<64, 256>(tn.decompress_threads, [&](auto T) {
@@ -783,13 +848,23 @@ bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
 }
 
 // Half-payload decompress: the tile knob does not apply (a tile is always one
-// 16-byte payload vector per thread).
+// 16-byte payload vector per thread, or half of one in the store-bound form).
 bool launch_decompress_pay16(const covap::tuning &tn, const covap_plan_s *plan,
                              const covap::call_range &cr, hipStream_t st, const void *recv, void *out,
-                             int32_t N, int32_t divisor, int64_t stride, covap::launch_status &ls)
+                             int32_t N, int32_t divisor, int64_t stride, bool store_bound,
+                             covap::launch_status &ls)
 {
     const int pow2 = (divisor & (divisor - 1)) == 0;
     const float n_f = (float)divisor, inv_n = 1.0f / n_f;
+    if (store_bound && plan->uniform && (N == 1 || stride % 4 == 0)) {
+        return pick<0, 1>(tn.nontemporal, [&](auto NT) {
+            for_each_launch(plan, cr, 256 * 4, false, [&](const auto &g, dim3 grid) {
+                typedef std::decay_t<decltype(g)> GEOM;
+                ls += covap::launch(k_decompress_pay16_narrow<GEOM, 256, NT() != 0>, grid, dim3(256), (size_t)0, st,
+                                    (const u32x2 *)recv, (float *)out, g, N, stride, n_f, inv_n, pow2);
+            });
+        });
+    }
     return pick<64, 256>(tn.decompress_threads, [&](auto T) {
         pick<1, 2, 4>(tn.decompress_unroll, [&](auto WU) {
             pick<0, 1>(tn.nontemporal, [&](auto NT) {
@@ -937,24 +1012,31 @@ static covap_status_t decompress_call(const char *who, const covap_plan_t *plan,
     if (cr.sh_hi == cr.sh_lo) return COVAP_OK;
 
     covap::tuning tn = covap::tune();
-    // Few rows: the call writes more than it reads and is bound by its stores.  256-thread
-    // workgroups without the LDS reservation fill memory faster than the one-wave shape that
-    // suits many rows (measured crossover: rows x packed elements = dense elements).
+    // Few rows: the call writes more than it reads and is bound by its stores (measured
+    // crossover: rows x packed elements = dense elements).  How fast memory fills depends on
+    // how many stores the chip keeps in flight, with an optimum near 32 KB per compute unit:
+    // fixed-size shards reach it with one 16-byte store per thread from 256-thread workgroups
+    // at full occupancy; variable-length shards, where a wave spends part of its life
+    // resolving its tile, with two stores per thread and an LDS reservation that holds a
+    // compute unit to five such workgroups.  The one-wave shape that suits many rows is 40 %
+    // slower here.
     const covap_shard_rec &first = plan->shards[cr.sh_lo], &last = plan->shards[cr.sh_hi - 1];
-    if (tn.decompress_shape_unset && (int64_t)rows * cr.packed_elems < last.off + last.len - first.off) {
+    const bool store_bound =
+        tn.decompress_shape_unset && (int64_t)rows * cr.packed_elems < last.off + last.len - first.off;
+    if (store_bound) {
         tn.decompress_threads = 256;
-        tn.decompress_tile = 1;
-        tn.decompress_lds_pad = 0;
+        tn.decompress_tile = plan->uniform ? 1 : 2;
+        tn.decompress_lds_pad = plan->uniform ? 0 : 32768;
     }
     hipStream_t st = (hipStream_t)stream;
     covap::launch_status ls;
     bool ok;
     if (dt == COVAP_F32)
-        ok = launch_decompress<ops_f32>(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, ls);
+        ok = launch_decompress<ops_f32>(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, store_bound, ls);
     else if (dt == COVAP_F32_PAY16)
-        ok = launch_decompress_pay16(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, ls);
+        ok = launch_decompress_pay16(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, store_bound, ls);
     else
-        ok = launch_decompress<ops_bf16>(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, ls);
+        ok = launch_decompress<ops_bf16>(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, store_bound, ls);
     if (!ok) return fail(COVAP_EINVAL, who, "launch knobs select no kernel");
     return ls.report(who);
 }

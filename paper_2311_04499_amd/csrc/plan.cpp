@@ -333,7 +333,7 @@ struct knob {
     const char *key;
     int covap::tuning::*field;
     int initial;
-    int allowed[4];  // -1 ends the list
+    int allowed[6];  // -1 ends the list
 };
 const knob kKnobs[] = {
     {"compress_threads", &covap::tuning::compress_threads, 64, {64, 256, -1, -1}},
@@ -342,9 +342,9 @@ const knob kKnobs[] = {
     {"decompress_tile", &covap::tuning::decompress_tile, 1, {1, 2, 4, -1}},
     {"decompress_unroll", &covap::tuning::decompress_unroll, 1, {1, 2, 4, -1}},
     {"nontemporal", &covap::tuning::nontemporal, 1, {0, 1, -1, -1}},
-    {"decompress_lds_pad", &covap::tuning::decompress_lds_pad, 6144, {0, 6144, 8192, -1}},
+    {"decompress_lds_pad", &covap::tuning::decompress_lds_pad, 6144, {0, 6144, 8192, 24576, 32768, 49152}},
     {"topk_pass1_waves", &covap::tuning::topk_pass1_waves, 4, {1, 2, 4, -1}},
-    {"topk_pass1_lds_pad", &covap::tuning::topk_pass1_lds_pad, 0, {0, 6144, 8192, 24576}},
+    {"topk_pass1_lds_pad", &covap::tuning::topk_pass1_lds_pad, 0, {0, 6144, 8192, 24576, -1}},
 };
 constexpr int kNumKnobs = (int)(sizeof kKnobs / sizeof kKnobs[0]);
 
@@ -566,11 +566,13 @@ covap_status_t covap_tune_set(const char *key, int32_t value)
             g_knob[i].store(-1, std::memory_order_relaxed);
             return COVAP_OK;
         }
-        for (int a : kKnobs[i].allowed)
-            if (a >= 0 && a == value) {
+        for (int a : kKnobs[i].allowed) {
+            if (a < 0) break;
+            if (a == value) {
                 g_knob[i].store(value, std::memory_order_relaxed);
                 return COVAP_OK;
             }
+        }
         char msg[160];
         std::snprintf(msg, sizeof msg, "covap_tune_set: value %d not allowed for %s", (int)value, kKnobs[i].key);
         return fail(COVAP_EINVAL, msg);

@@ -93,9 +93,10 @@ struct tuning {
     int decompress_tile;      // 16-byte vectors per thread per tile: 1, 2, 4
     int decompress_unroll;    // payload rows loaded before they are summed: 1, 2, 4
     int nontemporal;          // 0 = plain loads/stores, 1 = streaming hints
-    // Unused LDS reserved per decompress workgroup, in bytes: 0, 6144 or 8192.  With one-wave
-    // workgroups 6144 caps a SIMD at 7 waves instead of 8 (8192: 6); a little less data in
-    // flight keeps the DRAM access pattern tighter (+1.5..3 % measured).
+    // Unused LDS reserved per decompress workgroup, in bytes: 0, 6144, 8192, 24576, 32768 or
+    // 49152.  With one-wave workgroups 6144 caps a SIMD at 7 waves instead of 8 (8192: 6); a
+    // little less data in flight keeps the DRAM access pattern tighter (+1.5..3 % measured).
+    // The large values are for 256-thread workgroups (32768: five per compute unit).
     int decompress_lds_pad;
     // True while decompress_threads, decompress_tile and decompress_lds_pad have never been
     // set: decompress may then pick the workgroup shape from the call (few rows: store-bound).

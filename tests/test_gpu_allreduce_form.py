@@ -135,12 +135,36 @@ def test_every_launch_shape(B, kind):
             for tile in (1, 2, 4):
                 for unroll in (1, 2, 4):
                     for nt in (0, 1):
-                        for k, v in zip(keys, (threads, tile, unroll, nt, 8192 * nt)):
+                        for k, v in zip(keys, (threads, tile, unroll, nt, (0, 32768, 49152)[(nt + tile) % 3])):
                             B.covap_tune_set(k, v)
                         check(B, plan, tab, 3, kind, tile + unroll, 7, per_bucket=bool(nt), seed=threads)
     finally:
         for k in old:
             B.covap_tune_set(k, -1)                    # back to never set
+
+
+@pytest.mark.parametrize("kind", list(KINDS))
+@pytest.mark.parametrize("S", [4096, 0], ids=["fixed", "median"])
+def test_few_rows_take_the_store_bound_launch_shape(B, kind, S):
+    """covap_decompress with fewer rows than the interval (and the launch knobs never set) runs in the shape
+    chosen for store-bound calls, the half payload in a kernel of its own: same bits as the oracle's N-row mean,
+    ragged shards and odd row strides included."""
+    numel = [100_003, 77, 1_300_001, 9] if S else [1_003, 200_001, 30_007, 5, 4_099, 17, 900_001, 3]
+    K = 8
+    plan, tab = plans(B, kind, numel, K, S=S, cap=400_000)
+    gdt, pdt, _ = KINDS[kind]
+    epv = 4 if pdt == torch.float32 else 8
+    for rows, extra in ((2, 0), (3, 5 * epv), (1, 3)):                # one row: any stride will do
+        stride = (plan.packed_elems_max + epv - 1) // epv * epv + extra
+        for t in (0, 3, K - 1):
+            recv = torch.stack([summed_row(stride - 16, kind, 100 * rows + 10 * t + w) for w in range(rows)])
+            out = torch.full((tab.D,), float("nan"), dtype=gdt, device=DEV)
+            out_c = to_np(out)
+            for b in (range(tab.n_buckets) if t == 3 else [-1]):
+                B.covap_decompress(plan, t, recv, out, n_workers=rows, stride_elems=stride, bucket=b)
+            oracle.decompress(tab, K, t, to_np(recv), out_c)
+            torch.cuda.synchronize()
+            same(to_np(out), out_c, f"{kind} rows={rows} t={t}", nan_of(kind))
 
 
 def test_equals_the_row_form_when_the_rows_are_added_in_worker_order(B):

@@ -187,7 +187,7 @@ def test_bounded_grid_compress(B, groups):
 KNOBS = {"compress_threads": [64, 256], "compress_unroll": [1, 2, 4],
          "decompress_threads": [64, 256], "decompress_tile": [1, 2, 4],
          "decompress_unroll": [1, 2, 4], "nontemporal": [0, 1],
-         "decompress_lds_pad": [0, 8192, 6144]}
+         "decompress_lds_pad": [0, 8192, 24576, 32768, 49152, 6144]}
 
 
 @pytest.mark.parametrize("key", list(KNOBS))
