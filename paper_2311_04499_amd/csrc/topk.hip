@@ -73,10 +73,16 @@ struct topk_state {
 // Slot entries per 1024-element tile.  The bins >= b_lo hold 2..10 times the keys needed (a bin is an eighth
 // of an octave), i.e. a handful per tile: with 16 slots so many tiles went on the crowded list that the call
 // took 0.95 ms instead of 0.81.
+//
+// Layout: "plane" q holds entries 8q .. 8q+7 of every tile, 32 bytes per tile: entry p of tile t is word
+// ((p / 8) * ntiles + t) * 8 + p % 8 of the array.  Most tiles have at most eight entries, so the kernels
+// of the slot tail (one thread per tile) read plane 0 densely and the others hardly at all -- a fraction of the
+// bytes a tile-major layout makes them fetch, where the 32 entries of a tile are one 128-byte line and reading
+// the first of them brings in the whole line -- while pass 1 still writes one short piece per tile and array
+// (planes of four entries made it write two, which cost pass 1 more than the tail gained).
 constexpr int kSlots = 32;
-constexpr int kSlotVecs = kSlots / 4;  // 16-byte vectors of slot entries per tile: one lane each in the slot tail
-constexpr int kSlotVecShift = kSlotVecs == 8 ? 3 : 2;
-static_assert(kSlotVecs == 1 << kSlotVecShift, "4 or 8 slot vectors per tile");
+constexpr int kSlotVecs = kSlots / 4;
+static_assert(kSlotVecs * 4 == kSlots && kSlots % 8 == 0, "whole planes of eight slot entries");
 constexpr uint32_t kCrowded = 0xffffffffu;  // slot count of a tile that did not fit and is listed instead
 // A histogram is either one row that workgroups add their non-empty LDS bins to,
 // or several partial copies ("slices"), one per workgroup, that the pick kernel
@@ -104,8 +110,8 @@ struct topk_ws {
     uint32_t *hist;       // [kHistRows][2048]: general tail levels 1, 2, 3 | slot tail levels 1, 2, 3
                           // (the sample's slices share the rows of slot level 2, which comes later)
     uint32_t *slot_cnt;   // [ntiles]
-    uint32_t *slot_idx;   // [ntiles][kSlots]
-    uint32_t *slot_bits;  // [ntiles][kSlots]  bit patterns of A
+    uint32_t *slot_idx;   // [kSlots / 8][ntiles][8]  (planes, see kSlots)
+    uint32_t *slot_bits;  // [kSlots / 8][ntiles][8]  bit patterns of A
     uint32_t *cnt_gt;     // [ntiles]  -> exclusive prefix after the scan
     uint32_t *cnt_eq;     // [ntiles]
     uint32_t *chunk_gt;   // [nchunks] -> exclusive prefix
@@ -262,7 +268,7 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 // scale, a few hot embedding rows) is put on a list instead.
 template <int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void k_topk_pass1(const float *__restrict__ G, float *R,
-                                                           int64_t n, float c, topk_state *st,
+                                                           int64_t n, int64_t ntiles, float c, topk_state *st,
                                                            uint32_t *__restrict__ slot_cnt,
                                                            uint32_t *__restrict__ slot_idx,
                                                            uint32_t *__restrict__ slot_bits,
@@ -272,7 +278,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_topk_pass1(const float *__restri
     __shared__ uint32_t wave_total[WAVES];
     const uint32_t b_lo = st->b_lo;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int64_t tile = blockIdx.x;
+    const int64_t tile = blockIdx.x;  // one workgroup per tile
     const int64_t base = tile * kTile + (int64_t)wv * ROUNDS * 256;
     f32x4 g[ROUNDS], r[ROUNDS];
     uint32_t valids[ROUNDS];
@@ -331,8 +337,9 @@ __global__ __launch_bounds__(64 * WAVES) void k_topk_pass1(const float *__restri
         for (int j = 0; j < 4; ++j) {
             if ((cand[u] >> j) & 1u) {
                 if (pos < (uint32_t)kSlots) {
-                    slot_idx[tile * kSlots + pos] = (uint32_t)(e + j);
-                    slot_bits[tile * kSlots + pos] = raw[u][j];
+                    const int64_t at = ((int64_t)(pos >> 3) * ntiles + tile) * 8 + (pos & 7u);
+                    slot_idx[at] = (uint32_t)(e + j);
+                    slot_bits[at] = raw[u][j];
                 }
                 ++pos;
             }
@@ -683,16 +690,21 @@ __device__ __forceinline__ void write_tile(float *R, int64_t n, int64_t tile, ui
 
 // ---- slot tail -------------------------------------------------------------------------
 
-// A tile's kSlots slot entries are kSlotVecs 16-byte vectors.  The slot-tail kernels give one
-// thread to each such vector, so that a wave reads 1 KB of slots at a time, and look
-// only at the entries below the tile's count.  The tiles on the crowded list have no
-// slots: every slot-tail kernel then walks the list, one wave per tile, and reads those
-// tiles from R.  When the list grows beyond a small share of the tiles (data full of
-// ties, a very large k) the general tail takes over instead.
+// The slot-tail kernels give one thread to each tile: neighbouring threads read
+// neighbouring counts and neighbouring vectors of a plane.  The tiles on the crowded
+// list have no slots: every slot-tail kernel then walks the list, one wave per tile, and
+// reads those tiles from R.  When the list grows beyond a small share of the tiles (data
+// full of ties, a very large k) the general tail takes over instead.
 __host__ __device__ inline uint32_t crowded_limit(int64_t ntiles)
 {
     const int64_t share = ntiles / 32;
     return (uint32_t)(share > 1024 ? share : 1024);
+}
+
+// Entries 4q .. 4q+3 of tile `tile` in a slot array (half of the tile's 32 bytes in plane q / 2).
+__device__ __forceinline__ u32x4 slot_vec(const uint32_t *__restrict__ slots, int64_t ntiles, int q, int64_t tile)
+{
+    return ((const u32x4 *)slots)[((int64_t)(q >> 1) * ntiles + tile) * 2 + (q & 1)];
 }
 
 // Histogram of one digit over the slot entries (level 1: all of them; levels 2, 3:
@@ -719,33 +731,35 @@ __device__ __forceinline__ void slots_hist(const topk_state *__restrict__ st,
     __syncthreads();
     uint32_t *mine = lds + (tid & (COPIES - 1)) * BINS;
     const uint32_t want = LEVEL == 1 ? 0u : st->prefix >> HI_SHIFT;  // keys have bit 31 clear
-    const int64_t nvs = ntiles * kSlotVecs;
+    auto add = [&](const u32x4 v, uint32_t first, uint32_t c) {  // entries first .. first+3 of a tile with c entries
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t key = v[j] & kAbs;
+            if (first + j < c && (key >> HI_SHIFT) == want) atomicAdd(&mine[(key >> SHIFT) & (BINS - 1)], 1u);
+        }
+    };
     const int64_t stride = (int64_t)kSlotGrid * kSlotThreads;
-    constexpr int U = 8;  // vectors in flight per thread; the counts are loaded alongside, not before
-    for (int64_t w0 = (int64_t)blockIdx.x * kSlotThreads + tid; w0 < nvs; w0 += U * stride) {
-        uint32_t cnt[U];
+    constexpr int U = 4;  // tiles in flight per thread
+    for (int64_t t0 = (int64_t)blockIdx.x * kSlotThreads + tid; t0 < ntiles; t0 += U * stride) {
+        uint32_t c[U];
         u32x4 v[U];
 #pragma unroll
         for (int i = 0; i < U; ++i) {
-            const int64_t w = w0 + i * stride;
-            cnt[i] = 0u;
-            v[i] = u32x4{0u, 0u, 0u, 0u};
-            if (w < nvs) {
-                cnt[i] = slot_cnt[w >> kSlotVecShift];
-                v[i] = ((const u32x4 *)slot_bits)[w];  // entries at or above the count are stale, and skipped below
-            }
+            const int64_t tile = t0 + i * stride;
+            c[i] = tile < ntiles ? slot_cnt[tile] : 0u;
+            if (c[i] == kCrowded) c[i] = 0u;
         }
 #pragma unroll
         for (int i = 0; i < U; ++i) {
-            const uint32_t q4 = (uint32_t)((w0 + i * stride) & (kSlotVecs - 1)) * 4u;
-            const uint32_t c = cnt[i] == kCrowded ? 0u : cnt[i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t key = v[i][j] & kAbs;
-                if (q4 + j < c && (key >> HI_SHIFT) == want)
-                    atomicAdd(&mine[(key >> SHIFT) & (BINS - 1)], 1u);
-            }
+            v[i] = u32x4{0u, 0u, 0u, 0u};
+            if (c[i] != 0u) v[i] = slot_vec(slot_bits, ntiles, 0, t0 + i * stride);
         }
+#pragma unroll
+        for (int i = 0; i < U; ++i) add(v[i], 0u, c[i]);
+#pragma unroll
+        for (int i = 0; i < U; ++i)
+            for (int q = 1; (uint32_t)q * 4u < c[i]; ++q)  // c <= kSlots: at most kSlotVecs - 1 more
+                add(slot_vec(slot_bits, ntiles, q, t0 + i * stride), (uint32_t)q * 4u, c[i]);
     }
     // the crowded tiles, from R: one wave per tile.  Level 1 counts, like the slots do,
     // only the keys at or above b_lo.
@@ -779,7 +793,7 @@ __device__ __forceinline__ void slots_hist(const topk_state *__restrict__ st,
 }
 
 // Per-tile numbers of slot entries above and at the threshold.
-// The first `groups` workgroups of the grid take part (256 threads each).
+// The first `groups` workgroups of the grid take part (256 threads each, one per tile).
 __device__ __forceinline__ void slots_count(const topk_state *__restrict__ st,
                                             const uint32_t *__restrict__ slot_cnt,
                                             const uint32_t *__restrict__ slot_bits, int64_t ntiles,
@@ -788,56 +802,37 @@ __device__ __forceinline__ void slots_count(const topk_state *__restrict__ st,
                                             uint32_t *__restrict__ cnt_gt, uint32_t *__restrict__ cnt_eq,
                                             uint32_t groups)
 {
-    const int64_t nvs = ntiles * kSlotVecs;
-    const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t tile = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const uint32_t T = st->threshold;
-    uint32_t gt = 0u, eq = 0u;
-    bool listed = false;
-    if (w < nvs) {
-        const uint32_t cnt = slot_cnt[w >> kSlotVecShift], q4 = (uint32_t)(w & (kSlotVecs - 1)) * 4u;
-        listed = cnt == kCrowded;
-        if (!listed && q4 < cnt) {
-            const u32x4 v = ((const u32x4 *)slot_bits)[w];
+    if (tile < ntiles) {
+        const uint32_t cnt = slot_cnt[tile];
+        if (cnt != kCrowded) {
+            uint32_t gt = 0u, eq = 0u;
+            for (int q = 0; (uint32_t)q * 4u < cnt; ++q) {
+                const u32x4 v = slot_vec(slot_bits, ntiles, q, tile);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t key = v[j] & kAbs;
-                gt += (q4 + j < cnt && key > T) ? 1u : 0u;
-                eq += (q4 + j < cnt && key == T) ? 1u : 0u;
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t key = v[j] & kAbs;
+                    const bool in = (uint32_t)q * 4u + j < cnt;
+                    gt += (in && key > T) ? 1u : 0u;
+                    eq += (in && key == T) ? 1u : 0u;
+                }
             }
+            cnt_gt[tile] = gt;
+            cnt_eq[tile] = eq;
         }
     }
-#pragma unroll
-    for (int d = 1; d < kSlotVecs; d <<= 1) {  // the lanes of a tile; every lane of the wave takes part
-        gt += __shfl_xor(gt, d, 64);
-        eq += __shfl_xor(eq, d, 64);
-    }
-    if (w < nvs && (w & (kSlotVecs - 1)) == 0 && !listed) {
-        cnt_gt[w >> kSlotVecShift] = gt;
-        cnt_eq[w >> kSlotVecShift] = eq;
-    }
-    // the crowded tiles, from R: one wave per tile (this kernel's waves walk the list)
+    // the crowded tiles, from R: one wave per tile (this kernel's waves walk the list;
+    // the waves arrive here whole, the branches above have closed)
     const uint32_t n_crowded = st->n_crowded;
     const uint32_t wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = groups * 4;
     for (uint32_t i = wave; i < n_crowded; i += n_waves)
         count_tile(R, n, crowded[i], T, threadIdx.x & 63, cnt_gt, cnt_eq);
 }
 
-// Exclusive prefix sum over each group of kSlotVecs neighbouring lanes (the lanes of one tile).
-__device__ __forceinline__ uint32_t tile_lanes_excl_scan(uint32_t x)
-{
-    const int l = threadIdx.x & (kSlotVecs - 1);
-    uint32_t incl = x;
-#pragma unroll
-    for (int d = 1; d < kSlotVecs; d <<= 1) {
-        const uint32_t y = __shfl_up(incl, d, 64);
-        if (l >= d) incl += y;
-    }
-    return incl - x;
-}
-
-// Ordered write of the kept slot entries; entries of a tile are in ascending index
-// order across its kSlotVecs lanes.
-// The first `groups` workgroups of the grid take part (256 threads each).
+// Ordered write of the kept slot entries: a thread walks the entries of its tile, which
+// are in ascending index order, from the position the scan gave the tile.
+// The first `groups` workgroups of the grid take part (256 threads each, one per tile).
 __device__ __forceinline__ void slots_write(float *R, int64_t n, const topk_state *__restrict__ st,
                                             const uint32_t *__restrict__ slot_cnt,
                                             const uint32_t *__restrict__ slot_idx,
@@ -850,52 +845,44 @@ __device__ __forceinline__ void slots_write(float *R, int64_t n, const topk_stat
                                             float *__restrict__ vals, uint32_t *__restrict__ idx,
                                             uint32_t kmax, uint32_t groups)
 {
-    const int64_t nvs = ntiles * kSlotVecs;
-    const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t tile = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const uint32_t T = st->threshold, ties = st->ties;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    uint32_t gtm = 0u, eqm = 0u, eq_before = 0u, tile_pos = 0u;
-    if (w < nvs) {
-        const int64_t tile = w >> kSlotVecShift;
-        const uint32_t cnt = slot_cnt[tile], q4 = (uint32_t)(w & (kSlotVecs - 1)) * 4u;
-        if (cnt != kCrowded && q4 < cnt) {
-            v = ((const u32x4 *)slot_bits)[w];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t key = v[j] & kAbs;
-                gtm |= (q4 + j < cnt && key > T) ? (1u << j) : 0u;
-                eqm |= (q4 + j < cnt && key == T) ? (1u << j) : 0u;
-            }
+    if (tile < ntiles) {
+        const uint32_t cnt = slot_cnt[tile];
+        if (cnt != kCrowded && cnt != 0u) {
             const int64_t chunk = tile / kScanChunk;
-            eq_before = chunk_eq[chunk] + cnt_eq[tile];
-            tile_pos = chunk_gt[chunk] + cnt_gt[tile] + (eq_before < ties ? eq_before : ties);
-        }
-    }
-    // every lane of the wave takes part in the two scans
-    uint32_t eq_rank = eq_before + tile_lanes_excl_scan(__popc(eqm));
-    uint32_t selm = gtm;
+            uint32_t eq_rank = chunk_eq[chunk] + cnt_eq[tile];  // ties before this tile's first
+            uint32_t pos = chunk_gt[chunk] + cnt_gt[tile] + (eq_rank < ties ? eq_rank : ties);
+            for (int q = 0; (uint32_t)q * 4u < cnt; ++q) {
+                const u32x4 v = slot_vec(slot_bits, ntiles, q, tile);
+                uint32_t selm = 0u;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        if ((eqm >> j) & 1u) {
-            if (eq_rank < ties) selm |= 1u << j;
-            ++eq_rank;
-        }
-    }
-    uint32_t pos = tile_pos + tile_lanes_excl_scan(__popc(selm));
-    if (selm != 0u) {
-        const u32x4 at = ((const u32x4 *)slot_idx)[w];
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t key = v[j] & kAbs;
+                    if ((uint32_t)q * 4u + j < cnt) {
+                        if (key > T) selm |= 1u << j;
+                        if (key == T) {
+                            if (eq_rank < ties) selm |= 1u << j;
+                            ++eq_rank;
+                        }
+                    }
+                }
+                if (selm == 0u) continue;
+                const u32x4 at = slot_vec(slot_idx, ntiles, q, tile);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (((selm >> j) & 1u) && pos < kmax) {  // pos < kmax always holds; the test keeps a corrupted workspace harmless
-                vals[pos] = __uint_as_float(v[j]);
-                idx[pos] = at[j];
-                R[at[j]] = 0.0f;
-                ++pos;
+                for (int j = 0; j < 4; ++j) {
+                    if (((selm >> j) & 1u) && pos < kmax) {  // pos < kmax always holds; the test keeps a corrupted workspace harmless
+                        vals[pos] = __uint_as_float(v[j]);
+                        idx[pos] = at[j];
+                        R[at[j]] = 0.0f;
+                        ++pos;
+                    }
+                }
             }
         }
     }
     // the crowded tiles, from R: one wave per tile (this kernel's waves walk the list;
-    // whole waves arrive here together, the branch above has closed)
+    // the waves arrive here whole, the branches above have closed)
     const uint32_t n_crowded = st->n_crowded;
     const uint32_t wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = groups * 4;
     for (uint32_t i = wave; i < n_crowded; i += n_waves)
@@ -1094,7 +1081,7 @@ covap::launch_status run_topk(const void *grad, void *residual, int64_t n, int64
     const int64_t m = (int64_t)n_s * 256;
     const int64_t want = 2 * div_up(k * m, n) + 32;
     const uint32_t target = (uint32_t)(want < ((int64_t)1 << 31) ? want : ((int64_t)1 << 31));
-    const uint32_t slot_vec_grid = (uint32_t)div_up(ntiles * kSlotVecs, 256);
+    const uint32_t slot_vec_grid = (uint32_t)div_up(ntiles, 256);  // slot-tail kernels with one thread per tile
     // the general tail's tile kernels walk the tiles with a bounded grid, so that
     // they cost next to nothing when they are not taken
     const uint32_t tail_grid = (uint32_t)(ntiles < 16384 ? ntiles : 16384);
@@ -1103,8 +1090,8 @@ covap::launch_status run_topk(const void *grad, void *residual, int64_t n, int64
     ls += covap::launch(k_topk_pick_sample, dim3(1), dim3(kPickThreads), 0, st, ws.state, hs, target);
     const covap::tuning tn = covap::tune();
     const auto pass1 = tn.topk_pass1_waves == 4 ? k_topk_pass1<4> : (tn.topk_pass1_waves == 2 ? k_topk_pass1<2> : k_topk_pass1<1>);
-    ls += covap::launch(pass1, dim3((uint32_t)ntiles), dim3(64 * tn.topk_pass1_waves), (size_t)tn.topk_pass1_lds_pad,
-                        st, G, R, n, ef_coeff, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.crowded);
+    ls += covap::launch(pass1, dim3((uint32_t)ntiles), dim3(64 * tn.topk_pass1_waves),
+                        (size_t)tn.topk_pass1_lds_pad, st, G, R, n, ntiles, ef_coeff, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.crowded);
     if (k > 0) {
         // every kernel from here on serves whichever tail the first one switches on
         const uint32_t gen1024 = (uint32_t)std::min<int64_t>(kGenGrid, div_up(nvec > 0 ? nvec : 1, kSlotThreads));
