@@ -52,9 +52,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBins12 = 2048;  // digits of levels 1 and 2: key bits 30..20 and 19..9
 constexpr int kBins3 = 512;    // digit of level 3: key bits 8..0
-constexpr int kHistThreads = 256;
 constexpr int kTile = 1024;        // elements per compaction tile: 64 lanes x 4 vectors x 4 elements
-constexpr int kScanChunk = 1024;   // tile counts scanned per workgroup in phase A
+constexpr int kScanChunk = 256;    // tiles per chunk: one workgroup of kScanChunk threads counts, scans and writes a chunk
 constexpr uint32_t kAbs = 0x7fffffffu;
 
 // Selection state, first words of the workspace.
@@ -68,6 +67,7 @@ struct topk_state {
     uint32_t b_lo;       // pass 1 looks only at keys whose level-1 bin is >= b_lo
     uint32_t k;          // the k of this call
     uint32_t n_crowded;  // tiles that did not fit their slots; the slot tail reads those from R
+    uint32_t tickets[3]; // general tail: workgroups that have added their share of the histogram of level 1, 2, 3
 };
 
 // Slot entries per 1024-element tile.  The bins >= b_lo hold 2..10 times the keys needed (a bin is an eighth
@@ -98,13 +98,6 @@ constexpr int kSampleChunks = 1024;  // the sample: this many chunks of 64 vecto
 constexpr int kSampleThreads = 256;
 enum { kAlways = 0, kSlotTail = 1, kGeneralTail = 2 };
 
-// True if a kernel of tail `gate` has nothing to do.
-__device__ __forceinline__ bool skip_tail(const topk_state *st, int gate)
-{
-    const uint32_t ov = st->overflow;
-    return (gate == kSlotTail && ov != 0u) || (gate == kGeneralTail && ov == 0u);
-}
-
 struct topk_ws {
     topk_state *state;
     uint32_t *hist;       // [kHistRows][2048]: general tail levels 1, 2, 3 | slot tail levels 1, 2, 3
@@ -117,13 +110,15 @@ struct topk_ws {
     uint32_t *chunk_gt;   // [nchunks] -> exclusive prefix
     uint32_t *chunk_eq;   // [nchunks]
     uint32_t *crowded;    // [ntiles]  list of the tiles that did not fit their slots (any order)
+    uint32_t *pre_gt;     // [ntiles]  slot tail, crowded tiles only: kept entries of the regular tiles
+    uint32_t *pre_eq;     //           before the tile in its chunk (above / at the threshold)
 };
 
 __host__ __device__ constexpr int64_t div_up(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Byte offsets of the workspace's parts for n elements, each on a 256-byte boundary.
 struct ws_offsets {
-    size_t state, hist, slot_cnt, slot_idx, slot_bits, cnt_gt, cnt_eq, chunk_gt, chunk_eq, crowded, total;
+    size_t state, hist, slot_cnt, slot_idx, slot_bits, cnt_gt, cnt_eq, chunk_gt, chunk_eq, crowded, pre_gt, pre_eq, total;
 };
 
 constexpr size_t round256(size_t bytes) { return (bytes + 255) / 256 * 256; }
@@ -144,6 +139,8 @@ constexpr ws_offsets ws_offsets_for(int64_t n)
     o.chunk_gt = off;  off += round256(nchunks * 4);
     o.chunk_eq = off;  off += round256(nchunks * 4);
     o.crowded = off;   off += round256(ntiles * 4);
+    o.pre_gt = off;    off += round256(ntiles * 4);
+    o.pre_eq = off;    off += round256(ntiles * 4);
     o.total = off;
     return o;
 }
@@ -163,6 +160,8 @@ size_t ws_layout(int64_t n, void *base, topk_ws *out)
         out->chunk_gt = (uint32_t *)(b + o.chunk_gt);
         out->chunk_eq = (uint32_t *)(b + o.chunk_eq);
         out->crowded = (uint32_t *)(b + o.crowded);
+        out->pre_gt = (uint32_t *)(b + o.pre_gt);
+        out->pre_eq = (uint32_t *)(b + o.pre_eq);
     }
     return o.total;
 }
@@ -189,7 +188,8 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x)
 
 // ---- sample (and workspace reset) ---------------------------------------------------
 
-// Resets the selection state and the atomically accumulated histogram rows, and
+// Resets the selection state, the atomically accumulated histogram rows and the chunk
+// totals, and
 // takes the level-1 histogram of A on `n_s` chunks of 64 vectors spread evenly
 // over the `nchunks` full chunks of the data.  Each workgroup stores its LDS
 // histogram as its own slice.  Grid: kSlotGrid workgroups of kSampleThreads.
@@ -197,13 +197,22 @@ __global__ __launch_bounds__(kSampleThreads) void k_topk_sample(const float *__r
                                                                 const float *__restrict__ R, float c,
                                                                 int64_t nchunks, int32_t n_s,
                                                                 topk_state *st, uint32_t *hist_rows,
-                                                                uint32_t *__restrict__ slices, uint32_t k)
+                                                                uint32_t *__restrict__ slices, uint32_t k,
+                                                                uint32_t *chunk_gt, uint32_t *chunk_eq,
+                                                                int32_t nchunks_scan)
 {
     __shared__ uint32_t lds[kBins12];
     const int tid = threadIdx.x;
     const int gid = blockIdx.x * kSampleThreads + tid;
     for (int i = gid; i < kAtomicRows * 2048; i += kSlotGrid * kSampleThreads) hist_rows[i] = 0u;
+    for (int i = gid; i < nchunks_scan; i += kSlotGrid * kSampleThreads) {  // the slot tail adds to these
+        chunk_gt[i] = 0u;
+        chunk_eq[i] = 0u;
+    }
     if (gid == 0) {
+        st->tickets[0] = 0u;
+        st->tickets[1] = 0u;
+        st->tickets[2] = 0u;
         st->prefix = 0u;
         st->k_rem = k;
         st->threshold = 0u;
@@ -359,7 +368,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_topk_pass1(const float *__restri
 
 // Histogram of one digit of the keys in R: level 1 counts every key, levels 2 and 3
 // the keys that match the prefix found so far.  Persistent workgroups: each walks
-// tiles of kHistThreads vectors with a grid stride and keeps one LDS histogram per
+// tiles of NT vectors with a grid stride and keeps one LDS histogram per
 // wave.
 // NT threads per workgroup; `lds` holds 4 * BINS counters (one histogram per wave
 // modulo four); the first `groups` workgroups of the grid take part.
@@ -508,10 +517,10 @@ __device__ __forceinline__ u32x4 load_keys(const float *R, int64_t n, int64_t e,
     return k;
 }
 
-// Numbers of keys above and at the threshold in one 1024-element tile of R (one wave).
-__device__ __forceinline__ void count_tile(const float *__restrict__ R, int64_t n, int64_t tile, uint32_t T,
-                                           int lane, uint32_t *__restrict__ cnt_gt,
-                                           uint32_t *__restrict__ cnt_eq)
+// Numbers of keys above and at the threshold in one 1024-element tile of R.  One wave;
+// every lane gets both sums.
+__device__ __forceinline__ void tile_counts(const float *__restrict__ R, int64_t n, int64_t tile, uint32_t T,
+                                            int lane, uint32_t *gt_out, uint32_t *eq_out)
 {
     const int64_t base = tile * kTile;
     uint32_t gt = 0u, eq = 0u;
@@ -527,121 +536,101 @@ __device__ __forceinline__ void count_tile(const float *__restrict__ R, int64_t 
             eq += (ok && k[j] == T) ? 1u : 0u;
         }
     }
-    gt = wave_sum(gt);
-    eq = wave_sum(eq);
-    if (lane == 0) {
-        cnt_gt[tile] = gt;
-        cnt_eq[tile] = eq;
-    }
+    *gt_out = wave_sum(gt);
+    *eq_out = wave_sum(eq);
 }
 
-__global__ __launch_bounds__(64) void k_topk_count(const float *__restrict__ R, int64_t n, int64_t ntiles,
-                                                   const topk_state *__restrict__ st,
-                                                   uint32_t *__restrict__ cnt_gt,
-                                                   uint32_t *__restrict__ cnt_eq)
+// Exclusive prefix sum of x over the NT threads of a workgroup; *total gets the sum.
+// `ldsw` holds one word per wave.  Barriers inside: every thread must call it.
+template <int NT = kScanChunk>
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t x, uint32_t *ldsw, uint32_t *total)
 {
-    if (skip_tail(st, kGeneralTail)) return;
-    const uint32_t T = st->threshold;
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x)
-        count_tile(R, n, tile, T, threadIdx.x, cnt_gt, cnt_eq);
-}
-
-// Phase A: each workgroup turns kScanChunk tile counts into chunk-local
-// exclusive prefixes and writes the chunk totals.
-__global__ __launch_bounds__(256) void k_topk_scan_a(uint32_t *cnt_gt, uint32_t *cnt_eq,
-                                                     int64_t ntiles, uint32_t *chunk_gt,
-                                                     uint32_t *chunk_eq)
-{
-    __shared__ uint32_t sg[256], se[256];
-    const int tid = threadIdx.x;
-    const int64_t base = (int64_t)blockIdx.x * kScanChunk + tid * 4;
-    uint32_t g[4], e[4], tg = 0u, te = 0u;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const bool ok = base + j < ntiles;
-        g[j] = ok ? cnt_gt[base + j] : 0u;
-        e[j] = ok ? cnt_eq[base + j] : 0u;
-        tg += g[j];
-        te += e[j];
-    }
-    sg[tid] = tg;
-    se[tid] = te;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const uint32_t incl = wave_incl_scan(x);
+    if (lane == 63) ldsw[wv] = incl;
     __syncthreads();
-    for (int d = 1; d < 256; d <<= 1) {
-        const uint32_t yg = tid >= d ? sg[tid - d] : 0u, ye = tid >= d ? se[tid - d] : 0u;
-        __syncthreads();
-        sg[tid] += yg;
-        se[tid] += ye;
-        __syncthreads();
-    }
-    uint32_t pg = sg[tid] - tg, pe = se[tid] - te;
+    uint32_t before = 0u, all = 0u;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        if (base + j < ntiles) {
-            cnt_gt[base + j] = pg;
-            cnt_eq[base + j] = pe;
-        }
-        pg += g[j];
-        pe += e[j];
+    for (int w = 0; w < NT / 64; ++w) {
+        const uint32_t t = ldsw[w];
+        before += w < wv ? t : 0u;
+        all += t;
     }
-    if (tid == 255) {
-        chunk_gt[blockIdx.x] = sg[255];
-        chunk_eq[blockIdx.x] = se[255];
+    __syncthreads();  // ldsw is free again
+    *total = all;
+    return before + incl - x;
+}
+
+// General tail: per-tile counts over the residual, one wave per tile; the first `groups`
+// workgroups (kSlotThreads threads each) walk the tiles.
+__device__ __forceinline__ void general_count(const float *__restrict__ R, int64_t n, int64_t ntiles,
+                                              const topk_state *__restrict__ st, uint32_t *__restrict__ cnt_gt,
+                                              uint32_t *__restrict__ cnt_eq, uint32_t groups)
+{
+    constexpr int kWaves = kSlotThreads / 64;
+    const uint32_t T = st->threshold;
+    const int lane = threadIdx.x & 63;
+    for (int64_t tile = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6); tile < ntiles;
+         tile += (int64_t)groups * kWaves) {
+        uint32_t gt, eq;
+        tile_counts(R, n, tile, T, lane, &gt, &eq);
+        if (lane == 0) {
+            cnt_gt[tile] = gt;
+            cnt_eq[tile] = eq;
+        }
+    }
+}
+
+// General tail, scan phase A: workgroup c turns the counts of the kScanChunk tiles of
+// chunk c into chunk-local exclusive prefixes and writes the chunk's totals.
+__device__ __forceinline__ void general_scan_a(uint32_t *cnt_gt, uint32_t *cnt_eq, int64_t ntiles,
+                                               uint32_t *chunk_gt, uint32_t *chunk_eq, uint32_t *lds16)
+{
+    const int64_t tile = (int64_t)blockIdx.x * kScanChunk + threadIdx.x;  // kScanChunk threads
+    const bool in = tile < ntiles;
+    const uint32_t g = in ? cnt_gt[tile] : 0u, e = in ? cnt_eq[tile] : 0u;
+    uint32_t tg, te;
+    const uint32_t pg = block_excl_scan(g, lds16, &tg), pe = block_excl_scan(e, lds16, &te);
+    if (in) {
+        cnt_gt[tile] = pg;
+        cnt_eq[tile] = pe;
+    }
+    if (threadIdx.x == 0) {
+        chunk_gt[blockIdx.x] = tg;
+        chunk_eq[blockIdx.x] = te;
     }
 }
 
 // Phase B: one workgroup scans the chunk totals in place (exclusive).
-__global__ __launch_bounds__(256) void k_topk_scan_b(uint32_t *chunk_gt, uint32_t *chunk_eq,
-                                                     int64_t nchunks)
+__global__ __launch_bounds__(kSlotThreads) void k_topk_scan_b(uint32_t *chunk_gt, uint32_t *chunk_eq,
+                                                              int64_t nchunks)
 {
-    __shared__ uint32_t sg[256], se[256];
-    __shared__ uint32_t carry_g, carry_e;
-    const int tid = threadIdx.x;
-    if (tid == 0) {
-        carry_g = 0u;
-        carry_e = 0u;
-    }
-    __syncthreads();
-    for (int64_t base = 0; base < nchunks; base += 256) {
-        const int64_t i = base + tid;
+    __shared__ uint32_t ldsw[kSlotThreads / 64];
+    uint32_t carry_g = 0u, carry_e = 0u;  // the same in every thread
+    for (int64_t base = 0; base < nchunks; base += kSlotThreads) {
+        const int64_t i = base + threadIdx.x;
         const uint32_t g = i < nchunks ? chunk_gt[i] : 0u, e = i < nchunks ? chunk_eq[i] : 0u;
-        sg[tid] = g;
-        se[tid] = e;
-        __syncthreads();
-        for (int d = 1; d < 256; d <<= 1) {
-            const uint32_t yg = tid >= d ? sg[tid - d] : 0u, ye = tid >= d ? se[tid - d] : 0u;
-            __syncthreads();
-            sg[tid] += yg;
-            se[tid] += ye;
-            __syncthreads();
-        }
+        uint32_t tg, te;
+        const uint32_t pg = block_excl_scan<kSlotThreads>(g, ldsw, &tg);
+        const uint32_t pe = block_excl_scan<kSlotThreads>(e, ldsw, &te);
         if (i < nchunks) {
-            chunk_gt[i] = carry_g + sg[tid] - g;
-            chunk_eq[i] = carry_e + se[tid] - e;
+            chunk_gt[i] = carry_g + pg;
+            chunk_eq[i] = carry_e + pe;
         }
-        __syncthreads();
-        if (tid == 255) {
-            carry_g += sg[255];
-            carry_e += se[255];
-        }
-        __syncthreads();
+        carry_g += tg;
+        carry_e += te;
     }
 }
 
-// Ordered write of one tile's kept elements, read from R (one wave).  Element order
-// inside a tile is (round u, lane, component), which is ascending index; ranks come
-// from wavefront prefix sums.
+// Ordered write of one tile's kept elements, read from R (one wave): gt_before keys above
+// the threshold and eq_before keys at it lie before the tile.  Element order inside a
+// tile is (round u, lane, component), which is ascending index; ranks come from wavefront
+// prefix sums.
 __device__ __forceinline__ void write_tile(float *R, int64_t n, int64_t tile, uint32_t T, uint32_t ties,
-                                           int lane, const uint32_t *__restrict__ cnt_gt,
-                                           const uint32_t *__restrict__ cnt_eq,
-                                           const uint32_t *__restrict__ chunk_gt,
-                                           const uint32_t *__restrict__ chunk_eq,
+                                           int lane, uint32_t gt_before, uint32_t eq_before,
                                            float *__restrict__ vals, uint32_t *__restrict__ idx,
                                            uint32_t kmax)
 {
-    const int64_t chunk = tile / kScanChunk;
-    const uint32_t gt_before = chunk_gt[chunk] + cnt_gt[tile];
-    uint32_t eq_before = chunk_eq[chunk] + cnt_eq[tile];
     uint32_t out_pos = gt_before + (eq_before < ties ? eq_before : ties);
     const int64_t base = tile * kTile;
 #pragma unroll 1
@@ -685,6 +674,27 @@ __device__ __forceinline__ void write_tile(float *R, int64_t n, int64_t tile, ui
         }
         eq_before += eq_total;
         out_pos += sel_total;
+    }
+}
+
+// General tail: the ordered write, one wave per tile; the first `groups` workgroups
+// (NT threads each) walk the tiles.
+template <int NT>
+__device__ __forceinline__ void general_write(float *R, int64_t n, int64_t ntiles,
+                                              const topk_state *__restrict__ st,
+                                              const uint32_t *__restrict__ cnt_gt,
+                                              const uint32_t *__restrict__ cnt_eq,
+                                              const uint32_t *__restrict__ chunk_gt,
+                                              const uint32_t *__restrict__ chunk_eq, float *__restrict__ vals,
+                                              uint32_t *__restrict__ idx, uint32_t kmax, uint32_t groups)
+{
+    constexpr int kWaves = NT / 64;
+    const uint32_t T = st->threshold, ties = st->ties;
+    for (int64_t tile = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6); tile < ntiles;
+         tile += (int64_t)groups * kWaves) {
+        const int64_t chunk = tile / kScanChunk;
+        write_tile(R, n, tile, T, ties, threadIdx.x & 63, chunk_gt[chunk] + cnt_gt[tile],
+                   chunk_eq[chunk] + cnt_eq[tile], vals, idx, kmax);
     }
 }
 
@@ -792,47 +802,86 @@ __device__ __forceinline__ void slots_hist(const topk_state *__restrict__ st,
     }
 }
 
-// Per-tile numbers of slot entries above and at the threshold.
-// The first `groups` workgroups of the grid take part (256 threads each, one per tile).
+// Numbers of a tile's slot entries above and at the threshold (one thread).
+__device__ __forceinline__ void slot_counts(const uint32_t *__restrict__ slot_bits, int64_t ntiles, int64_t tile,
+                                            uint32_t cnt, uint32_t T, uint32_t *gt_out, uint32_t *eq_out)
+{
+    uint32_t gt = 0u, eq = 0u;
+    for (int q = 0; (uint32_t)q * 4u < cnt; ++q) {
+        const u32x4 v = slot_vec(slot_bits, ntiles, q, tile);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t key = v[j] & kAbs;
+            const bool in = (uint32_t)q * 4u + j < cnt;
+            gt += (in && key > T) ? 1u : 0u;
+            eq += (in && key == T) ? 1u : 0u;
+        }
+    }
+    *gt_out = gt;
+    *eq_out = eq;
+}
+
+// Slot tail, counting step.  Workgroup c (kScanChunk threads, one per tile) owns the
+// tiles of chunk c: it counts their slot entries above and at the threshold and adds the
+// chunk's totals to chunk_gt / chunk_eq (zeroed by the first kernel of the call).  A
+// crowded tile has no slots: its thread records how many kept entries of the chunk's
+// REGULAR tiles lie before it (pre_gt / pre_eq); its own counts come from the residual,
+// taken by the waves of the whole grid walking the crowded list (so that a cluster of such
+// tiles is shared out evenly), stored per tile and added to the chunk totals as well.
 __device__ __forceinline__ void slots_count(const topk_state *__restrict__ st,
                                             const uint32_t *__restrict__ slot_cnt,
                                             const uint32_t *__restrict__ slot_bits, int64_t ntiles,
                                             const uint32_t *__restrict__ crowded,
                                             const float *__restrict__ R, int64_t n,
                                             uint32_t *__restrict__ cnt_gt, uint32_t *__restrict__ cnt_eq,
-                                            uint32_t groups)
+                                            uint32_t *__restrict__ pre_gt, uint32_t *__restrict__ pre_eq,
+                                            uint32_t *chunk_gt, uint32_t *chunk_eq, uint32_t groups,
+                                            uint32_t *lds16)
 {
-    const int64_t tile = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t tile = (int64_t)blockIdx.x * kScanChunk + threadIdx.x;
     const uint32_t T = st->threshold;
+    uint32_t gt = 0u, eq = 0u;
+    bool listed = false;
     if (tile < ntiles) {
         const uint32_t cnt = slot_cnt[tile];
-        if (cnt != kCrowded) {
-            uint32_t gt = 0u, eq = 0u;
-            for (int q = 0; (uint32_t)q * 4u < cnt; ++q) {
-                const u32x4 v = slot_vec(slot_bits, ntiles, q, tile);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t key = v[j] & kAbs;
-                    const bool in = (uint32_t)q * 4u + j < cnt;
-                    gt += (in && key > T) ? 1u : 0u;
-                    eq += (in && key == T) ? 1u : 0u;
-                }
-            }
-            cnt_gt[tile] = gt;
-            cnt_eq[tile] = eq;
+        listed = cnt == kCrowded;
+        if (!listed) slot_counts(slot_bits, ntiles, tile, cnt, T, &gt, &eq);
+    }
+    uint32_t tg, te;
+    const uint32_t pg = block_excl_scan(gt, lds16, &tg), pe = block_excl_scan(eq, lds16, &te);
+    if (listed) {
+        pre_gt[tile] = pg;
+        pre_eq[tile] = pe;
+    }
+    if (threadIdx.x == 0) {
+        if (tg) atomicAdd(&chunk_gt[blockIdx.x], tg);
+        if (te) atomicAdd(&chunk_eq[blockIdx.x], te);
+    }
+    // the crowded tiles, from R: one wave per tile
+    constexpr int kWaves = kScanChunk / 64;
+    const uint32_t n_crowded = st->n_crowded;
+    const int lane = threadIdx.x & 63;
+    for (uint32_t i = blockIdx.x * kWaves + (threadIdx.x >> 6); i < n_crowded; i += groups * kWaves) {
+        const int64_t t = crowded[i];
+        uint32_t g, e;
+        tile_counts(R, n, t, T, lane, &g, &e);
+        if (lane == 0) {
+            cnt_gt[t] = g;
+            cnt_eq[t] = e;
+            if (g) atomicAdd(&chunk_gt[t / kScanChunk], g);
+            if (e) atomicAdd(&chunk_eq[t / kScanChunk], e);
         }
     }
-    // the crowded tiles, from R: one wave per tile (this kernel's waves walk the list;
-    // the waves arrive here whole, the branches above have closed)
-    const uint32_t n_crowded = st->n_crowded;
-    const uint32_t wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = groups * 4;
-    for (uint32_t i = wave; i < n_crowded; i += n_waves)
-        count_tile(R, n, crowded[i], T, threadIdx.x & 63, cnt_gt, cnt_eq);
 }
 
-// Ordered write of the kept slot entries: a thread walks the entries of its tile, which
-// are in ascending index order, from the position the scan gave the tile.
-// The first `groups` workgroups of the grid take part (256 threads each, one per tile).
+// Slot tail, ordered write.  Workgroup c owns the tiles of chunk c again: every thread
+// recounts its tile (a crowded tile's counts are read back), a scan over the workgroup
+// gives each tile its position, and a thread then walks the entries of its tile, which
+// are in ascending index order.  The crowded tiles are written from the residual by the
+// waves of the whole grid walking the list; such a wave puts the tile's position together
+// from the chunk's offset, the regular tiles before it (pre_gt / pre_eq) and the crowded
+// tiles before it in the chunk, which it finds by reading the chunk's slot counts.
+// chunk_gt / chunk_eq hold exclusive prefixes by now.
 __device__ __forceinline__ void slots_write(float *R, int64_t n, const topk_state *__restrict__ st,
                                             const uint32_t *__restrict__ slot_cnt,
                                             const uint32_t *__restrict__ slot_idx,
@@ -840,70 +889,121 @@ __device__ __forceinline__ void slots_write(float *R, int64_t n, const topk_stat
                                             const uint32_t *__restrict__ crowded,
                                             const uint32_t *__restrict__ cnt_gt,
                                             const uint32_t *__restrict__ cnt_eq,
+                                            const uint32_t *__restrict__ pre_gt,
+                                            const uint32_t *__restrict__ pre_eq,
                                             const uint32_t *__restrict__ chunk_gt,
                                             const uint32_t *__restrict__ chunk_eq, int64_t ntiles,
                                             float *__restrict__ vals, uint32_t *__restrict__ idx,
-                                            uint32_t kmax, uint32_t groups)
+                                            uint32_t kmax, uint32_t groups, uint32_t *lds16)
 {
-    const int64_t tile = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t tile = (int64_t)blockIdx.x * kScanChunk + threadIdx.x;
     const uint32_t T = st->threshold, ties = st->ties;
+    uint32_t cnt = 0u, gt = 0u, eq = 0u;
     if (tile < ntiles) {
-        const uint32_t cnt = slot_cnt[tile];
-        if (cnt != kCrowded && cnt != 0u) {
-            const int64_t chunk = tile / kScanChunk;
-            uint32_t eq_rank = chunk_eq[chunk] + cnt_eq[tile];  // ties before this tile's first
-            uint32_t pos = chunk_gt[chunk] + cnt_gt[tile] + (eq_rank < ties ? eq_rank : ties);
-            for (int q = 0; (uint32_t)q * 4u < cnt; ++q) {
-                const u32x4 v = slot_vec(slot_bits, ntiles, q, tile);
-                uint32_t selm = 0u;
+        cnt = slot_cnt[tile];
+        if (cnt == kCrowded) {
+            gt = cnt_gt[tile];
+            eq = cnt_eq[tile];
+        } else {
+            slot_counts(slot_bits, ntiles, tile, cnt, T, &gt, &eq);
+        }
+    }
+    uint32_t tg, te;
+    const uint32_t pg = block_excl_scan(gt, lds16, &tg), pe = block_excl_scan(eq, lds16, &te);
+    if (cnt != kCrowded && (gt | eq) != 0u) {
+        uint32_t eq_rank = chunk_eq[blockIdx.x] + pe;  // ties before this tile's first
+        uint32_t pos = chunk_gt[blockIdx.x] + pg + (eq_rank < ties ? eq_rank : ties);
+        for (int q = 0; (uint32_t)q * 4u < cnt; ++q) {
+            const u32x4 v = slot_vec(slot_bits, ntiles, q, tile);
+            uint32_t selm = 0u;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t key = v[j] & kAbs;
-                    if ((uint32_t)q * 4u + j < cnt) {
-                        if (key > T) selm |= 1u << j;
-                        if (key == T) {
-                            if (eq_rank < ties) selm |= 1u << j;
-                            ++eq_rank;
-                        }
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t key = v[j] & kAbs;
+                if ((uint32_t)q * 4u + j < cnt) {
+                    if (key > T) selm |= 1u << j;
+                    if (key == T) {
+                        if (eq_rank < ties) selm |= 1u << j;
+                        ++eq_rank;
                     }
                 }
-                if (selm == 0u) continue;
-                const u32x4 at = slot_vec(slot_idx, ntiles, q, tile);
+            }
+            if (selm == 0u) continue;
+            const u32x4 at = slot_vec(slot_idx, ntiles, q, tile);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (((selm >> j) & 1u) && pos < kmax) {  // pos < kmax always holds; the test keeps a corrupted workspace harmless
-                        vals[pos] = __uint_as_float(v[j]);
-                        idx[pos] = at[j];
-                        R[at[j]] = 0.0f;
-                        ++pos;
-                    }
+            for (int j = 0; j < 4; ++j) {
+                if (((selm >> j) & 1u) && pos < kmax) {  // pos < kmax always holds; the test keeps a corrupted workspace harmless
+                    vals[pos] = __uint_as_float(v[j]);
+                    idx[pos] = at[j];
+                    R[at[j]] = 0.0f;
+                    ++pos;
                 }
             }
         }
     }
-    // the crowded tiles, from R: one wave per tile (this kernel's waves walk the list;
-    // the waves arrive here whole, the branches above have closed)
+    // the crowded tiles, from R: one wave per tile (the waves arrive here whole: the
+    // branches above have closed)
+    constexpr int kWaves = kScanChunk / 64;
     const uint32_t n_crowded = st->n_crowded;
-    const uint32_t wave = blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = groups * 4;
-    for (uint32_t i = wave; i < n_crowded; i += n_waves)
-        write_tile(R, n, crowded[i], T, ties, threadIdx.x & 63, cnt_gt, cnt_eq, chunk_gt, chunk_eq, vals, idx,
-                   kmax);
+    const int lane = threadIdx.x & 63;
+    for (uint32_t i = blockIdx.x * kWaves + (threadIdx.x >> 6); i < n_crowded; i += groups * kWaves) {
+        const int64_t t = crowded[i];
+        const int64_t chunk = t / kScanChunk, first = chunk * kScanChunk;
+        uint32_t g = 0u, e = 0u;
+        for (int64_t u = first + lane; u < t; u += 64) {  // crowded tiles before t in its chunk
+            if (slot_cnt[u] == kCrowded) {
+                g += cnt_gt[u];
+                e += cnt_eq[u];
+            }
+        }
+        g = wave_sum(g);
+        e = wave_sum(e);
+        write_tile(R, n, t, T, ties, lane, chunk_gt[chunk] + pre_gt[t] + g, chunk_eq[chunk] + pre_eq[t] + e, vals,
+                   idx, kmax);
+    }
 }
 
 // ---- the kernels of the tail --------------------------------------------------------------
 //
 // The slot tail and the general tail exclude each other (a device flag, set by the pick
-// that follows the first histogram below, says which runs), so each step of the two is
-// one kernel that branches on the flag: a grid large enough for either, the surplus
-// workgroups returning at once.  The digit picks stay kernels of their own.  Letting the
-// workgroup that finishes its part of a histogram last do the pick (a ticket counter) was
-// tried and is slower on this chip: the device-scope release that must precede the ticket
-// writes back the L2 of the workgroup's XCD, which costs 10-12 us per kernel even when
-// issued by one thread per workgroup (40 us when every thread fences) -- more than the
-// 4-5 us of the launch it saves; the same holds for folding the second scan phase into
-// the first.
+// that follows the first histogram below, says which runs), and the host cannot know which:
+// every step is one kernel that branches on the flag, with a grid large enough for either
+// and the surplus workgroups returning at once.  So that neither tail adds launches to the
+// other, the general tail is shaped to the slot tail's seven steps:
+//
+//     step          slot tail                       general tail
+//     hist_step<2>  histogram of digit 2, slots     histogram of digit 1 over R + its pick
+//     pick_step<2>  pick of digit 2                 histogram of digit 2 over R + its pick
+//     hist_step<3>  histogram of digit 3, slots     histogram of digit 3 over R + its pick
+//     pick_step<3>  pick of digit 3                 per-tile counts over R
+//     count         counts + totals per chunk       scan of the tile counts, chunk by chunk
+//     scan_b        scan of the chunk totals        the same
+//     emit          ordered write from the slots    ordered write from R
+//
+// In the general tail the workgroup that adds its share of a histogram last does the pick
+// (a ticket counter).  On the slot tail, the usual one, the picks stay kernels of their
+// own: the device-scope release that must precede a ticket writes back the L2 of the
+// workgroup's XCD, which costs 10-12 us per kernel on this chip -- more than the 4-5 us of
+// the launch it saves -- and that price is only worth paying where it keeps the rare tail
+// from adding three launches to every call.
 
-constexpr int kGenGrid = 512;  // general-tail histogram passes: workgroups of kSlotThreads threads
+constexpr int kGenGrid = 256;  // general-tail passes over R: workgroups of kSlotThreads threads
+
+// General tail: histogram of digit LEVEL over R by the first `groups` workgroups, then
+// the pick by whichever of them finishes last.  `lds` holds 4 * 2048 words.
+template <int LEVEL>
+__device__ __forceinline__ void general_hist_pick(const float *__restrict__ R, int64_t n, topk_state *st,
+                                                  uint32_t *row, uint32_t *lds, uint32_t groups)
+{
+    __shared__ uint32_t last;
+    general_hist<LEVEL, kSlotThreads>(R, n, st, row, lds, groups);
+    __threadfence();  // this thread's additions to the row are visible device-wide ...
+    __syncthreads();  // ... for every thread of the workgroup, before the workgroup's ticket
+    if (threadIdx.x == 0) last = atomicAdd(&st->tickets[LEVEL - 1], 1u) == groups - 1u ? 1u : 0u;
+    __syncthreads();
+    if (last == 0u) return;  // the whole workgroup leaves
+    __threadfence();  // the other workgroups' additions are visible to this one
+    pick<LEVEL, kGeneralTail, kSlotThreads>(st, row, 1, 0u, lds);
+}
 
 __global__ __launch_bounds__(kPickThreads) void k_topk_pick_sample(topk_state *st, const uint32_t *hist,
                                                                    uint32_t target)
@@ -932,17 +1032,17 @@ __global__ __launch_bounds__(kPickThreads) void k_topk_pick1(topk_state *st, con
     pick<1, kSlotTail, kPickThreads>(st, slices, kSlotGrid, crowded_max, lds);
 }
 
-// Slot tail: histogram of digit LEVEL (2 or 3) over the slots.  General tail: of digit
-// LEVEL - 1 over the whole residual.
+// Slot tail: histogram of digit LEVEL (2 or 3) over the slots.  General tail: histogram
+// and pick of digit 1 (LEVEL 2) or 3 (LEVEL 3) over the whole residual.
 template <int LEVEL>
-__global__ __launch_bounds__(kSlotThreads) void k_topk_digit(const topk_state *__restrict__ st,
-                                                             const uint32_t *__restrict__ slot_cnt,
-                                                             const uint32_t *__restrict__ slot_bits,
-                                                             int64_t ntiles,
-                                                             const uint32_t *__restrict__ crowded,
-                                                             const float *__restrict__ R, int64_t n,
-                                                             uint32_t *__restrict__ slices,
-                                                             uint32_t *__restrict__ row, uint32_t gen_groups)
+__global__ __launch_bounds__(kSlotThreads) void k_topk_hist_step(topk_state *st,
+                                                                 const uint32_t *__restrict__ slot_cnt,
+                                                                 const uint32_t *__restrict__ slot_bits,
+                                                                 int64_t ntiles,
+                                                                 const uint32_t *__restrict__ crowded,
+                                                                 const float *__restrict__ R, int64_t n,
+                                                                 uint32_t *__restrict__ slices, uint32_t *row,
+                                                                 uint32_t gen_groups)
 {
     __shared__ uint32_t lds[4 * kBins12];
     if (st->overflow == 0u) {  // the same answer in every workgroup: it was fixed by an earlier kernel
@@ -950,75 +1050,78 @@ __global__ __launch_bounds__(kSlotThreads) void k_topk_digit(const topk_state *_
         slots_hist<LEVEL>(st, slot_cnt, slot_bits, ntiles, crowded, R, n, slices, lds);
     } else {
         if (blockIdx.x >= gen_groups) return;
-        general_hist<LEVEL - 1, kSlotThreads>(R, n, st, row, lds, gen_groups);
+        general_hist_pick<LEVEL == 2 ? 1 : 3>(R, n, st, row, lds, gen_groups);
     }
 }
 
-// The pick after k_topk_digit<LEVEL>.
+// Slot tail: the pick after k_topk_hist_step<LEVEL> (one workgroup).  General tail:
+// histogram and pick of digit 2 (LEVEL 2), or the per-tile counts over the residual (LEVEL 3).
 template <int LEVEL>
-__global__ __launch_bounds__(kPickThreads) void k_topk_pick_digit(topk_state *st, const uint32_t *slices,
-                                                                  const uint32_t *row)
+__global__ __launch_bounds__(kSlotThreads) void k_topk_pick_step(topk_state *st, const uint32_t *slices,
+                                                                 const float *__restrict__ R, int64_t n,
+                                                                 int64_t ntiles, uint32_t *row,
+                                                                 uint32_t *__restrict__ cnt_gt,
+                                                                 uint32_t *__restrict__ cnt_eq,
+                                                                 uint32_t gen_groups)
 {
-    __shared__ uint32_t lds[kPickLds];
-    if (st->overflow == 0u)
-        pick<LEVEL, kSlotTail, kPickThreads>(st, slices, kSlotGrid, 0u, lds);
-    else
-        pick<LEVEL - 1, kGeneralTail, kPickThreads>(st, row, 1, 0u, lds);
-}
-
-// Slot tail: per-tile counts against the threshold.  General tail: histogram of the third digit.
-__global__ __launch_bounds__(256) void k_topk_count_or_digit3(const topk_state *__restrict__ st,
-                                                              const uint32_t *__restrict__ slot_cnt,
-                                                              const uint32_t *__restrict__ slot_bits,
-                                                              int64_t ntiles,
-                                                              const uint32_t *__restrict__ crowded,
-                                                              const float *__restrict__ R, int64_t n,
-                                                              uint32_t *__restrict__ cnt_gt,
-                                                              uint32_t *__restrict__ cnt_eq,
-                                                              uint32_t *__restrict__ row, uint32_t slot_groups,
-                                                              uint32_t gen_groups)
-{
-    __shared__ uint32_t lds[4 * kBins3];
+    __shared__ uint32_t lds[4 * kBins12];
     if (st->overflow == 0u) {
-        if (blockIdx.x >= slot_groups) return;
-        slots_count(st, slot_cnt, slot_bits, ntiles, crowded, R, n, cnt_gt, cnt_eq, slot_groups);
+        if (blockIdx.x != 0u) return;
+        pick<LEVEL, kSlotTail, kSlotThreads>(st, slices, kSlotGrid, 0u, lds);
     } else {
         if (blockIdx.x >= gen_groups) return;
-        general_hist<3, 256>(R, n, st, row, lds, gen_groups);
+        if constexpr (LEVEL == 2)
+            general_hist_pick<2>(R, n, st, row, lds, gen_groups);
+        else
+            general_count(R, n, ntiles, st, cnt_gt, cnt_eq, gen_groups);
     }
 }
 
-// General tail only: the third digit's pick (returns at once otherwise).
-__global__ __launch_bounds__(kPickThreads) void k_topk_pick3_general(topk_state *st, const uint32_t *row)
+// One workgroup per chunk of kScanChunk tiles.  Slot tail: counts and chunk totals.
+// General tail: first phase of the scan of the per-tile counts.
+__global__ __launch_bounds__(kScanChunk) void k_topk_count(const topk_state *__restrict__ st,
+                                                             const uint32_t *__restrict__ slot_cnt,
+                                                             const uint32_t *__restrict__ slot_bits,
+                                                             int64_t ntiles,
+                                                             const uint32_t *__restrict__ crowded,
+                                                             const float *__restrict__ R, int64_t n,
+                                                             uint32_t *cnt_gt, uint32_t *cnt_eq,
+                                                             uint32_t *__restrict__ pre_gt,
+                                                             uint32_t *__restrict__ pre_eq, uint32_t *chunk_gt,
+                                                             uint32_t *chunk_eq)
 {
-    __shared__ uint32_t lds[kPickLds];
-    if (st->overflow == 0u) return;
-    pick<3, kGeneralTail, kPickThreads>(st, row, 1, 0u, lds);
+    __shared__ uint32_t lds16[kScanChunk / 64];
+    if (st->overflow == 0u)
+        slots_count(st, slot_cnt, slot_bits, ntiles, crowded, R, n, cnt_gt, cnt_eq, pre_gt, pre_eq, chunk_gt,
+                    chunk_eq, gridDim.x, lds16);
+    else
+        general_scan_a(cnt_gt, cnt_eq, ntiles, chunk_gt, chunk_eq, lds16);
 }
 
-// The ordered write of (value, index), and +0 into the residual there: from the slots, or
-// (general tail) from the residual, one wave per tile.
-__global__ __launch_bounds__(256) void k_topk_emit(float *R, int64_t n, const topk_state *__restrict__ st,
-                                                   const uint32_t *__restrict__ slot_cnt,
-                                                   const uint32_t *__restrict__ slot_idx,
-                                                   const uint32_t *__restrict__ slot_bits,
-                                                   const uint32_t *__restrict__ crowded,
-                                                   const uint32_t *__restrict__ cnt_gt,
-                                                   const uint32_t *__restrict__ cnt_eq,
-                                                   const uint32_t *__restrict__ chunk_gt,
-                                                   const uint32_t *__restrict__ chunk_eq, int64_t ntiles,
-                                                   float *__restrict__ vals, uint32_t *__restrict__ idx,
-                                                   uint32_t kmax, uint32_t slot_groups)
+// The ordered write of (value, index), and +0 into the residual there: from the slots
+// (one workgroup per chunk), or (general tail) from the residual, one wave per tile.
+__global__ __launch_bounds__(kScanChunk) void k_topk_emit(float *R, int64_t n, const topk_state *__restrict__ st,
+                                                            const uint32_t *__restrict__ slot_cnt,
+                                                            const uint32_t *__restrict__ slot_idx,
+                                                            const uint32_t *__restrict__ slot_bits,
+                                                            const uint32_t *__restrict__ crowded,
+                                                            const uint32_t *__restrict__ cnt_gt,
+                                                            const uint32_t *__restrict__ cnt_eq,
+                                                            const uint32_t *__restrict__ pre_gt,
+                                                            const uint32_t *__restrict__ pre_eq,
+                                                            const uint32_t *__restrict__ chunk_gt,
+                                                            const uint32_t *__restrict__ chunk_eq, int64_t ntiles,
+                                                            float *__restrict__ vals, uint32_t *__restrict__ idx,
+                                                            uint32_t kmax, uint32_t slot_groups, uint32_t gen_groups)
 {
+    __shared__ uint32_t lds16[kScanChunk / 64];
     if (st->overflow == 0u) {
         if (blockIdx.x >= slot_groups) return;
-        slots_write(R, n, st, slot_cnt, slot_idx, slot_bits, crowded, cnt_gt, cnt_eq, chunk_gt, chunk_eq, ntiles,
-                    vals, idx, kmax, slot_groups);
+        slots_write(R, n, st, slot_cnt, slot_idx, slot_bits, crowded, cnt_gt, cnt_eq, pre_gt, pre_eq, chunk_gt,
+                    chunk_eq, ntiles, vals, idx, kmax, slot_groups, lds16);
     } else {
-        const uint32_t T = st->threshold, ties = st->ties;
-        const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = (int64_t)gridDim.x * 4;
-        for (int64_t tile = wave; tile < ntiles; tile += n_waves)
-            write_tile(R, n, tile, T, ties, threadIdx.x & 63, cnt_gt, cnt_eq, chunk_gt, chunk_eq, vals, idx, kmax);
+        if (blockIdx.x >= gen_groups) return;
+        general_write<kScanChunk>(R, n, ntiles, st, cnt_gt, cnt_eq, chunk_gt, chunk_eq, vals, idx, kmax, gen_groups);
     }
 }
 
@@ -1066,10 +1169,7 @@ covap::launch_status run_topk(const void *grad, void *residual, int64_t n, int64
     float *R = (float *)residual;
     const int64_t nvec = n / 4;
     const int64_t ntiles = div_up(n, kTile);
-    const int64_t nchunks = div_up(ntiles, kScanChunk);
-    // persistent grids: enough workgroups to fill 256 CUs several times over
-    int64_t hist_grid = div_up(nvec > 0 ? nvec : 1, kHistThreads);
-    if (hist_grid > 2048) hist_grid = 2048;
+    const uint32_t nchunks = (uint32_t)div_up(ntiles, kScanChunk);
 
     uint32_t *h1g = ws.hist, *h2g = h1g + 2048, *h3g = h2g + 2048, *h1s = ws.hist + kAtomicRows * 2048,
              *h2s = h1s + kSlotGrid * 2048, *h3s = h2s + kSlotGrid * 2048, *hs = h2s;
@@ -1081,46 +1181,40 @@ covap::launch_status run_topk(const void *grad, void *residual, int64_t n, int64
     const int64_t m = (int64_t)n_s * 256;
     const int64_t want = 2 * div_up(k * m, n) + 32;
     const uint32_t target = (uint32_t)(want < ((int64_t)1 << 31) ? want : ((int64_t)1 << 31));
-    const uint32_t slot_vec_grid = (uint32_t)div_up(ntiles, 256);  // slot-tail kernels with one thread per tile
-    // the general tail's tile kernels walk the tiles with a bounded grid, so that
-    // they cost next to nothing when they are not taken
-    const uint32_t tail_grid = (uint32_t)(ntiles < 16384 ? ntiles : 16384);
     ls += covap::launch(k_topk_sample, dim3(kSlotGrid), dim3(kSampleThreads), 0, st, G, R, ef_coeff, nchunks_s, n_s,
-                        ws.state, ws.hist, hs, (uint32_t)k);
+                        ws.state, ws.hist, hs, (uint32_t)k, ws.chunk_gt, ws.chunk_eq, (int32_t)nchunks);
     ls += covap::launch(k_topk_pick_sample, dim3(1), dim3(kPickThreads), 0, st, ws.state, hs, target);
     const covap::tuning tn = covap::tune();
     const auto pass1 = tn.topk_pass1_waves == 4 ? k_topk_pass1<4> : (tn.topk_pass1_waves == 2 ? k_topk_pass1<2> : k_topk_pass1<1>);
     ls += covap::launch(pass1, dim3((uint32_t)ntiles), dim3(64 * tn.topk_pass1_waves),
-                        (size_t)tn.topk_pass1_lds_pad, st, G, R, n, ntiles, ef_coeff, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.crowded);
+                        (size_t)tn.topk_pass1_lds_pad, st, G, R, n, ntiles, ef_coeff, ws.state, ws.slot_cnt,
+                        ws.slot_idx, ws.slot_bits, ws.crowded);
     if (k > 0) {
-        // every kernel from here on serves whichever tail the first one switches on
-        const uint32_t gen1024 = (uint32_t)std::min<int64_t>(kGenGrid, div_up(nvec > 0 ? nvec : 1, kSlotThreads));
-        const uint32_t gen256 = (uint32_t)hist_grid;
-        const uint32_t digit_grid = gen1024 > (uint32_t)kSlotGrid ? gen1024 : (uint32_t)kSlotGrid;
+        // every kernel from here on serves whichever tail the first pick switches on; the general
+        // tail's passes walk the data with bounded grids
+        const uint32_t gen_hist = (uint32_t)std::min<int64_t>(kGenGrid, div_up(nvec > 0 ? nvec : 1, kSlotThreads));
+        const uint32_t gen_tiles = (uint32_t)std::min<int64_t>(4 * kGenGrid, div_up(ntiles, kSlotThreads / 64));
+        const uint32_t hist_grid = gen_hist > (uint32_t)kSlotGrid ? gen_hist : (uint32_t)kSlotGrid;
         ls += covap::launch(k_topk_digit1, dim3(kSlotGrid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt,
                             ws.slot_bits, ntiles, ws.crowded, R, n, h1s);
         ls += covap::launch(k_topk_pick1, dim3(1), dim3(kPickThreads), 0, st, ws.state, h1s, crowded_limit(ntiles));
-        ls += covap::launch(k_topk_digit<2>, dim3(digit_grid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt,
-                            ws.slot_bits, ntiles, ws.crowded, R, n, h2s, h1g, gen1024);
-        ls += covap::launch(k_topk_pick_digit<2>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h2s, h1g);
-        ls += covap::launch(k_topk_digit<3>, dim3(digit_grid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt,
-                            ws.slot_bits, ntiles, ws.crowded, R, n, h3s, h2g, gen1024);
-        ls += covap::launch(k_topk_pick_digit<3>, dim3(1), dim3(kPickThreads), 0, st, ws.state, h3s, h2g);
-        ls += covap::launch(k_topk_count_or_digit3, dim3(slot_vec_grid > gen256 ? slot_vec_grid : gen256), dim3(256), 0,
-                            st, ws.state, ws.slot_cnt, ws.slot_bits, ntiles, ws.crowded, R, n, ws.cnt_gt, ws.cnt_eq,
-                            h3g, slot_vec_grid, gen256);
-        // general tail only (both return at once otherwise): its last pick, per-tile counts over the residual
-        ls += covap::launch(k_topk_pick3_general, dim3(1), dim3(kPickThreads), 0, st, ws.state, h3g);
-        ls += covap::launch(k_topk_count, dim3(tail_grid), dim3(64), 0, st, R, n, ntiles, ws.state, ws.cnt_gt,
-                            ws.cnt_eq);
-        // exclusive scan of the per-tile counts, then the ordered write
-        ls += covap::launch(k_topk_scan_a, dim3((uint32_t)nchunks), dim3(256), 0, st, ws.cnt_gt, ws.cnt_eq, ntiles,
+        ls += covap::launch(k_topk_hist_step<2>, dim3(hist_grid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt,
+                            ws.slot_bits, ntiles, ws.crowded, R, n, h2s, h1g, gen_hist);
+        ls += covap::launch(k_topk_pick_step<2>, dim3(gen_hist), dim3(kSlotThreads), 0, st, ws.state, h2s, R, n,
+                            ntiles, h2g, ws.cnt_gt, ws.cnt_eq, gen_hist);
+        ls += covap::launch(k_topk_hist_step<3>, dim3(hist_grid), dim3(kSlotThreads), 0, st, ws.state, ws.slot_cnt,
+                            ws.slot_bits, ntiles, ws.crowded, R, n, h3s, h3g, gen_hist);
+        ls += covap::launch(k_topk_pick_step<3>, dim3(gen_tiles), dim3(kSlotThreads), 0, st, ws.state, h3s, R, n,
+                            ntiles, h3g, ws.cnt_gt, ws.cnt_eq, gen_tiles);
+        ls += covap::launch(k_topk_count, dim3(nchunks), dim3(kScanChunk), 0, st, ws.state, ws.slot_cnt,
+                            ws.slot_bits, ntiles, ws.crowded, R, n, ws.cnt_gt, ws.cnt_eq, ws.pre_gt, ws.pre_eq,
                             ws.chunk_gt, ws.chunk_eq);
-        ls += covap::launch(k_topk_scan_b, dim3(1), dim3(256), 0, st, ws.chunk_gt, ws.chunk_eq, nchunks);
-        const uint32_t emit_waves = tail_grid / 4 + 1;
-        ls += covap::launch(k_topk_emit, dim3(slot_vec_grid > emit_waves ? slot_vec_grid : emit_waves), dim3(256), 0, st,
-                            R, n, ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.crowded, ws.cnt_gt, ws.cnt_eq,
-                            ws.chunk_gt, ws.chunk_eq, ntiles, (float *)out_vals, out_idx, (uint32_t)k, slot_vec_grid);
+        ls += covap::launch(k_topk_scan_b, dim3(1), dim3(kSlotThreads), 0, st, ws.chunk_gt, ws.chunk_eq, (int64_t)nchunks);
+        const uint32_t gen_emit = (uint32_t)std::min<int64_t>(16 * kGenGrid, div_up(ntiles, kScanChunk / 64));
+        ls += covap::launch(k_topk_emit, dim3(nchunks > gen_emit ? nchunks : gen_emit), dim3(kScanChunk), 0, st, R, n,
+                            ws.state, ws.slot_cnt, ws.slot_idx, ws.slot_bits, ws.crowded, ws.cnt_gt, ws.cnt_eq,
+                            ws.pre_gt, ws.pre_eq, ws.chunk_gt, ws.chunk_eq, ntiles, (float *)out_vals, out_idx,
+                            (uint32_t)k, nchunks, gen_emit);
     }
     return ls;
 }
