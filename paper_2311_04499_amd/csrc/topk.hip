@@ -416,11 +416,13 @@ __device__ __forceinline__ void general_hist(const float *__restrict__ R, int64_
 //               longer than `target` that too many tiles missed their slots: either
 //               switches the general tail on.
 //   LEVEL 2, 3  wanted = k_rem; the digit extends the prefix; level 3 fixes T.
-// One workgroup of NT >= 256 threads runs it: all of them add up the slices, the first
-// 256 then scan.  `lds` holds 256 + BINS words.  Barriers inside: every thread of the
-// workgroup must call it, and nothing that needs a barrier may follow.
+// One workgroup of NT threads runs it.  All of them add up the slices: a thread takes four
+// neighbouring counters (one 16-byte load per slice) of every G-th slice, G = NT / (BINS / 4),
+// with up to 16 loads in flight, and the G partial sums meet in LDS.  The first 256 threads
+// then scan.  `lds` holds kPickLds words.  Barriers inside: every thread of the workgroup
+// must call it, and nothing that needs a barrier may follow.
 constexpr int kPickThreads = 1024;
-constexpr int kPickLds = 256 + kBins12;
+constexpr int kPickLds = 4 + 4 * kPickThreads;  // words; the array must be 16-byte aligned
 
 template <int LEVEL, int GATE, int NT>
 __device__ __forceinline__ void pick(topk_state *st, const uint32_t *hist, int nslices, uint32_t target,
@@ -429,45 +431,58 @@ __device__ __forceinline__ void pick(topk_state *st, const uint32_t *hist, int n
     constexpr int BINS = LEVEL == 3 ? kBins3 : kBins12;
     constexpr int PER = BINS / 256;
     constexpr int SHIFT = LEVEL <= 1 ? 20 : (LEVEL == 2 ? 9 : 0);
-    uint32_t *part = lds, *total = lds + 256;
+    constexpr int Q = BINS / 4, G = NT / Q;
+    static_assert(NT % Q == 0 && G >= 1 && G * BINS <= 4 * kPickThreads, "slice groups fill the workgroup");
+    uint32_t *wave_tot = lds, *sums = lds + 4;  // sums: [G][BINS], 16-byte aligned
     const int tid = threadIdx.x;
     const uint32_t k_rem = LEVEL == 0 ? target : (LEVEL == 1 ? st->k : st->k_rem);
     const uint32_t base_prefix = LEVEL <= 1 ? 0u : st->prefix;
-    for (int bin = tid; bin < BINS; bin += NT) {  // neighbouring threads read neighbouring counters
-        uint32_t c[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-        int sl = 0;
-        for (; sl + 8 <= nslices; sl += 8) {  // eight independent loads in flight
+    {
+        const int quad = tid % Q, grp = tid / Q;
+        const u32x4 *col = (const u32x4 *)hist + quad;  // rows are 2048 counters = 512 vectors apart
+        u32x4 acc = {0u, 0u, 0u, 0u};
+        int sl = grp;
+        for (; sl + 15 * G < nslices; sl += 16 * G) {
+            u32x4 x[16];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) c[j] += hist[(sl + j) * 2048 + bin];
+            for (int j = 0; j < 16; ++j) x[j] = col[(sl + j * G) * 512];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc += x[j];
         }
-        for (; sl < nslices; ++sl) c[0] += hist[sl * 2048 + bin];
-        total[bin] = ((c[0] + c[1]) + (c[2] + c[3])) + ((c[4] + c[5]) + (c[6] + c[7]));
+        for (; sl + 7 * G < nslices; sl += 8 * G) {
+            u32x4 x[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = col[(sl + j * G) * 512];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc += x[j];
+        }
+        for (; sl < nslices; sl += G) acc += col[sl * 512];
+        ((u32x4 *)sums)[grp * Q + quad] = acc;
     }
     __syncthreads();
-    // The scan is the work of the first 256 threads; the others only keep every
-    // barrier complete (a barrier must be reached by all threads of the workgroup).
+    // The scan is the work of the first 256 threads (four waves); the others only keep
+    // every barrier complete (a barrier must be reached by all threads of the workgroup).
     const bool scanner = tid < 256;
     // scanner t owns bins [BINS - (t+1)*PER, BINS - t*PER): thread 0 the top ones
     uint32_t h[PER];
-    uint32_t mine = 0u;
+    uint32_t mine = 0u, incl = 0u;
     if (scanner) {
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
-            h[j] = total[BINS - 1 - (tid * PER + j)];  // descending bin order
-            mine += h[j];
+            const int bin = BINS - 1 - (tid * PER + j);  // descending bin order
+            uint32_t c = 0u;
+#pragma unroll
+            for (int g = 0; g < G; ++g) c += sums[g * BINS + bin];
+            h[j] = c;
+            mine += c;
         }
-        part[tid] = mine;
+        incl = wave_incl_scan(mine);  // whole waves: 256 is a multiple of 64
+        if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
     }
     __syncthreads();
-    // inclusive scan over the scanners (Hillis-Steele in LDS)
-    for (int d = 1; d < 256; d <<= 1) {
-        const uint32_t y = (scanner && tid >= d) ? part[tid - d] : 0u;
-        __syncthreads();
-        if (scanner) part[tid] += y;
-        __syncthreads();
-    }
     if (!scanner) return;  // no barrier follows
-    const uint32_t incl = part[tid], excl = incl - mine;
+    for (int w = 0; w < (tid >> 6); ++w) incl += wave_tot[w];
+    const uint32_t excl = incl - mine;
     if (LEVEL == 1 && GATE == kSlotTail && tid == 255) {
         if (incl < k_rem) atomicOr(&st->overflow, 2u);
         if (st->n_crowded > target) atomicOr(&st->overflow, 1u);  // target: the longest list the slot tail takes
@@ -1008,7 +1023,7 @@ __device__ __forceinline__ void general_hist_pick(const float *__restrict__ R, i
 __global__ __launch_bounds__(kPickThreads) void k_topk_pick_sample(topk_state *st, const uint32_t *hist,
                                                                    uint32_t target)
 {
-    __shared__ uint32_t lds[kPickLds];
+    __shared__ __align__(16) uint32_t lds[kPickLds];
     pick<0, kAlways, kPickThreads>(st, hist, kSlotGrid, target, lds);
 }
 
@@ -1021,14 +1036,14 @@ __global__ __launch_bounds__(kSlotThreads) void k_topk_digit1(const topk_state *
                                                               const float *__restrict__ R, int64_t n,
                                                               uint32_t *__restrict__ slices)
 {
-    __shared__ uint32_t lds[4 * kBins12];
+    __shared__ __align__(16) uint32_t lds[4 * kBins12];
     slots_hist<1>(st, slot_cnt, slot_bits, ntiles, crowded, R, n, slices, lds);
 }
 
 __global__ __launch_bounds__(kPickThreads) void k_topk_pick1(topk_state *st, const uint32_t *slices,
                                                              uint32_t crowded_max)
 {
-    __shared__ uint32_t lds[kPickLds];
+    __shared__ __align__(16) uint32_t lds[kPickLds];
     pick<1, kSlotTail, kPickThreads>(st, slices, kSlotGrid, crowded_max, lds);
 }
 
@@ -1044,7 +1059,7 @@ __global__ __launch_bounds__(kSlotThreads) void k_topk_hist_step(topk_state *st,
                                                                  uint32_t *__restrict__ slices, uint32_t *row,
                                                                  uint32_t gen_groups)
 {
-    __shared__ uint32_t lds[4 * kBins12];
+    __shared__ __align__(16) uint32_t lds[4 * kBins12];
     if (st->overflow == 0u) {  // the same answer in every workgroup: it was fixed by an earlier kernel
         if (blockIdx.x >= (uint32_t)kSlotGrid) return;
         slots_hist<LEVEL>(st, slot_cnt, slot_bits, ntiles, crowded, R, n, slices, lds);
@@ -1064,7 +1079,7 @@ __global__ __launch_bounds__(kSlotThreads) void k_topk_pick_step(topk_state *st,
                                                                  uint32_t *__restrict__ cnt_eq,
                                                                  uint32_t gen_groups)
 {
-    __shared__ uint32_t lds[4 * kBins12];
+    __shared__ __align__(16) uint32_t lds[4 * kBins12];
     if (st->overflow == 0u) {
         if (blockIdx.x != 0u) return;
         pick<LEVEL, kSlotTail, kSlotThreads>(st, slices, kSlotGrid, 0u, lds);
