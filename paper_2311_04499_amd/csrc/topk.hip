@@ -748,24 +748,52 @@ __device__ __forceinline__ void slots_hist(const topk_state *__restrict__ st,
     constexpr int BINS = LEVEL == 3 ? kBins3 : kBins12;
     constexpr int SHIFT = LEVEL == 1 ? 20 : (LEVEL == 2 ? 9 : 0);
     constexpr int HI_SHIFT = LEVEL == 1 ? 31 : (LEVEL == 2 ? 20 : 9);
-    // Level 1 sees every entry and nearly all of them fall into a handful of bins just
-    // above b_lo: four copies of the histogram, picked by lane, spread those LDS atomics.
+    // Level 1 sees every entry, and nearly all of them fall into the eight bins from b_lo up
+    // (one octave): a thread counts those in the eight 8-bit fields of a register, and a wave
+    // adds its fields up and makes eight LDS additions every six tiles per lane (at most 192
+    // entries, so no field overflows).  The other bins, and the other levels, add to LDS
+    // entry by entry; four copies of the level-1 histogram, picked by lane, spread those.
     constexpr int COPIES = LEVEL == 1 ? 4 : 1;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
     for (int i = tid; i < COPIES * BINS; i += kSlotThreads) lds[i] = 0u;
     __syncthreads();
     uint32_t *mine = lds + (tid & (COPIES - 1)) * BINS;
     const uint32_t want = LEVEL == 1 ? 0u : st->prefix >> HI_SHIFT;  // keys have bit 31 clear
+    const uint32_t b_lo = st->b_lo;
+    uint64_t packed = 0ull;
+    auto count = [&](uint32_t key) {  // key: bit 31 clear, matches the prefix
+        if constexpr (LEVEL == 1) {
+            const uint32_t rel = (key >> 20) - b_lo;  // >= 0: only keys at or above b_lo are looked at
+            if (rel < 8u)
+                packed += 1ull << (rel * 8u);
+            else
+                atomicAdd(&mine[key >> 20], 1u);
+        } else {
+            atomicAdd(&mine[(key >> SHIFT) & (BINS - 1)], 1u);
+        }
+    };
+    auto flush = [&]() {  // whole waves only
+        if constexpr (LEVEL == 1) {
+#pragma unroll
+            for (int f = 0; f < 8; ++f) {
+                const uint32_t c = wave_sum((uint32_t)(packed >> (8 * f)) & 255u);
+                if (lane == f && c != 0u) atomicAdd(&mine[b_lo + f], c);  // c != 0: the bin exists
+            }
+            packed = 0ull;
+        }
+    };
     auto add = [&](const u32x4 v, uint32_t first, uint32_t c) {  // entries first .. first+3 of a tile with c entries
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t key = v[j] & kAbs;
-            if (first + j < c && (key >> HI_SHIFT) == want) atomicAdd(&mine[(key >> SHIFT) & (BINS - 1)], 1u);
+            if (first + j < c && (key >> HI_SHIFT) == want) count(key);
         }
     };
     const int64_t stride = (int64_t)kSlotGrid * kSlotThreads;
-    constexpr int U = 4;  // tiles in flight per thread
-    for (int64_t t0 = (int64_t)blockIdx.x * kSlotThreads + tid; t0 < ntiles; t0 += U * stride) {
+    constexpr int U = 6;  // tiles in flight per thread (6 x kSlots = 192 entries: below the 255 a field holds)
+    // the loop runs on the wave's first tile, so that a wave stays whole (flush needs all lanes)
+    for (int64_t w0 = (int64_t)blockIdx.x * kSlotThreads + (tid - lane); w0 < ntiles; w0 += U * stride) {
+        const int64_t t0 = w0 + lane;
         uint32_t c[U];
         u32x4 v[U];
 #pragma unroll
@@ -785,13 +813,12 @@ __device__ __forceinline__ void slots_hist(const topk_state *__restrict__ st,
         for (int i = 0; i < U; ++i)
             for (int q = 1; (uint32_t)q * 4u < c[i]; ++q)  // c <= kSlots: at most kSlotVecs - 1 more
                 add(slot_vec(slot_bits, ntiles, q, t0 + i * stride), (uint32_t)q * 4u, c[i]);
+        flush();
     }
     // the crowded tiles, from R: one wave per tile.  Level 1 counts, like the slots do,
     // only the keys at or above b_lo.
     const uint32_t n_crowded = st->n_crowded;
     if (n_crowded <= crowded_limit(ntiles)) {
-        const uint32_t b_lo = st->b_lo;
-        const int lane = tid & 63;
         constexpr int kWaves = kSlotThreads / 64;
         for (uint32_t i = blockIdx.x * kWaves + (tid >> 6); i < n_crowded; i += kSlotGrid * kWaves) {
             const int64_t base = (int64_t)crowded[i] * kTile;
@@ -803,9 +830,10 @@ __device__ __forceinline__ void slots_hist(const topk_state *__restrict__ st,
                 for (int j = 0; j < 4; ++j) {
                     const bool ok = ((valid >> j) & 1u) && (key[j] >> HI_SHIFT) == want &&
                                     (LEVEL != 1 || (key[j] >> 20) >= b_lo);
-                    if (ok) atomicAdd(&mine[(key[j] >> SHIFT) & (BINS - 1)], 1u);
+                    if (ok) count(key[j]);
                 }
             }
+            flush();  // 16 keys per lane and tile
         }
     }
     __syncthreads();
