@@ -285,7 +285,7 @@ covap_status_t topk_compress(const void *grad, void *residual, int64_t n, int64_
  * workspace around: code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc.  Same arguments (without the workspace), same kernels and
  * the same result bits as topk_compress; the workspace is a fixed array inside the
- * library's code object (about 6.1 MB on every GPU the library runs on, held until
+ * library's code object (about 6.2 MB on every GPU the library runs on, held until
  * the process ends), whose device address is looked up once per device on the first
  * call made with that device current.  The call allocates nothing and frees nothing.
  *   n at most topk_static_max_elems() = 2^24 elements; EINVAL beyond that (use

@@ -12,8 +12,9 @@
 //                                                                (reads 2D, writes D)
 //   then everything works on the slots only (a fraction of a percent of the data):
 //   histograms of bits 30..20, 19..9 and 8..0 -> threshold key T and the number of
-//   ties to keep; per-tile counts; 3-phase exclusive scan; ordered write of
-//   (value, index), R <- +0 there.
+//   ties to keep; kept entries per chunk of 256 tiles and a scan of those totals;
+//   ordered write of (value, index), R <- +0 there (positions inside a chunk from a
+//   scan in the writing workgroup).
 //
 // A tile with more than 32 such elements (clustered data: a layer with a larger
 // gradient scale, a few hot embedding rows) gets no slots: it is put on a list, and
@@ -26,7 +27,8 @@
 // histogram passes, a counting pass and a compaction pass over R (5 more reads of
 // D).  The two tails exclude each other, so the host launches one sequence of kernels
 // whose steps branch on the flag (surplus workgroups of the larger grid return at
-// once); no host round trip is needed.  Both tails give the same bits.
+// once), twelve launches in all; no host round trip is needed.  Both tails give the
+// same bits.
 //
 // key = bit pattern of |A| as an unsigned integer: a total order on magnitudes
 // (NaN above Inf).  Among keys equal to T the lowest indices are kept, which
@@ -1268,7 +1270,7 @@ covap::launch_status run_topk(const void *grad, void *residual, int64_t n, int64
 // from a fixed array in the code object.  Every GPU the library runs on holds its own
 // copy at its own address until the process ends; host code must not use the array's
 // name as an address, only what hipGetSymbolAddress returns for the current device.
-constexpr int64_t kStaticMaxN = (int64_t)1 << 24;  // 16 Mi elements: about 6.1 MB of workspace
+constexpr int64_t kStaticMaxN = (int64_t)1 << 24;  // 16 Mi elements: about 6.2 MB of workspace
 constexpr size_t kStaticBytes = ws_offsets_for(kStaticMaxN).total;
 constexpr int kMaxDevices = 64;
 
