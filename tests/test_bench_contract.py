@@ -44,3 +44,7 @@ def test_json_line_on_the_small_configuration():
     for key in ("value", "unit", "cores", "kind", "sample"):
         assert key in cb, key
     assert cb["kind"] == "oracle" and cb["cores"] == 1 and cb["value"] > 0
+    ar = d["allreduce_form"]                              # the step after a sum-AllReduce, measured beside the N-row form
+    assert ar["decompress_reduced_us"] > 0 and 0 < ar["frac"] < 1
+    assert ar["compress_plus_decompress_reduced_us"] > ar["decompress_reduced_us"]
+    assert len(lines[0]) < 4000                           # the line stays a digest; the details go to a file
