@@ -196,6 +196,48 @@ def test_equals_the_row_form_when_the_rows_are_added_in_worker_order(B):
             same(to_np(b), out_c, f"S={S} t={t}", np.isnan)
 
 
+def test_under_hip_graph_replay(B):
+    """compress + the reduced form captured once per residue of the step, bucket by bucket, and replayed
+    with eager work in between: every replay gives the oracle's bits (no memset nodes, no allocation)."""
+    numel, K, N = [300_000, 12_345, 77], 3, 8
+    for S, cap in ((8192, 100_000), (0, 100_000)):
+        plan, tab = plans(B, "f32", numel, K, S=S, cap=cap)
+        wl = workloads.scaled_down(workloads.config(2), numel, S or 8192)
+        D = tab.D
+        G = torch.ones(D, device=DEV)
+        R = torch.zeros(D, device=DEV)
+        send = torch.zeros(plan.packed_elems_max + 8, device=DEV)
+        out = torch.zeros(D, device=DEV)
+        side = torch.cuda.Stream()
+        graphs = []
+        for r in range(K):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for b in range(tab.n_buckets):
+                    B.covap_compress(plan, r, G, R, send, ef_coeff=0.5, bucket=b)
+                for b in range(tab.n_buckets):
+                    B.covap_decompress_reduced(plan, r, send, out, N, bucket=b)   # as if N workers had sent the same
+            graphs.append(g)
+        R.zero_()
+        Rc = np.zeros(D, np.float32)
+        for t in range(2 * K + 1):
+            g_new = workloads.gradient(wl, 0, t, DEV)
+            G[:g_new.numel()].copy_(g_new[:D])
+            send.fill_(float("nan"))
+            out.fill_(float("nan"))
+            send_c, out_c = to_np(send), to_np(out)
+            torch.cuda.synchronize()
+            graphs[t % K].replay()
+            scratch = torch.randn(1000, device=DEV).sum().item()       # eager work between replays
+            torch.cuda.synchronize()
+            oracle.compress(tab, K, t, to_np(G), Rc, send_c, 0.5)
+            oracle.unpack_mean(tab, K, t, send_c, N, out_c)
+            same(to_np(send), send_c, f"send S={S} t={t}", np.isnan)
+            same(to_np(R), Rc, f"residual S={S} t={t}", np.isnan)
+            same(to_np(out), out_c, f"dense S={S} t={t}", np.isnan)
+            assert scratch == scratch
+
+
 def test_argument_errors(B):
     plan, tab = plans(B, "f32", [10_000], 4, S=1024)
     P = plan.packed_elems_max
