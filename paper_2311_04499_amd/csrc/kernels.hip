@@ -1,6 +1,7 @@
 // COVAP hot-path kernels for gfx950 (MI355X): covap_compress (also on a bounded,
-// persistent grid), its aliased form and covap_decompress, plus the measurement
-// probes (two plain streaming kernels and one that only keeps the matrix cores busy).
+// persistent grid), its aliased form, covap_decompress and covap_decompress_reduced
+// (the same kernels on one summed row), plus the measurement probes (two plain
+// streaming kernels and one that only keeps the matrix cores busy).
 //
 // Both kernels are pure HBM streaming (at most one FMA per 12 bytes moved), so
 // the design is about memory access only:
@@ -8,7 +9,8 @@
 //     "tile" of THREADS * UNROLL consecutive vectors of ONE shard, so the filter's
 //     decision (sent / kept) is uniform over the workgroup and costs a few
 //     scalar integer operations per tile -- never per element.  The measured best
-//     on MI355X is the smallest shape: one wave, one vector per thread;
+//     on MI355X is the smallest shape: one wave, one vector per thread (decompress
+//     calls with few rows, which are bound by their stores, take 256 threads);
 //   * all loads of a tile are issued before the first use; decompress walks the N
 //     payload rows with one row in flight per wave (more was slower);
 //   * data that is not read again in the same iteration (everything here) is
