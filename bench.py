@@ -497,6 +497,32 @@ def streamed(torch, B, run, ms_step, args):
             "eager_us_per_step": round(eager_wall_us, 1),
             "whole_arena_us_per_step": round(ms_step * 1e3, 1)}
 
+    # the same launches dealt out to two streams (bucket b on stream b mod 2; a bucket's decompress follows its
+    # compress on the same stream): the next bucket's kernel starts while the last one's final waves drain
+    try:
+        pair = [torch.cuda.Stream(), torch.cuda.Stream()]
+        fork, joins = torch.cuda.Event(), [torch.cuda.Event(), torch.cuda.Event()]
+
+        def per_bucket_two_streams(t):
+            main = torch.cuda.current_stream()
+            fork.record(main)
+            for st in pair:
+                st.wait_event(fork)
+            for b in range(nb):
+                B.covap_compress(plan, t, ring[0], residual, recv[0], bucket=b, stream=pair[b % 2])
+            for b in range(nb):
+                B.covap_decompress(plan, t, recv, dense, n_workers=N, stride_elems=stride, bucket=b,
+                                   stream=pair[b % 2])
+            for st, ev in zip(pair, joins):
+                ev.record(st)
+                main.wait_event(ev)
+
+        per_bucket_two_streams(0)
+        _, two_wall_us = timed(per_bucket_two_streams, reps)
+        sres["eager_two_streams_us_per_step"] = round(two_wall_us, 1)
+    except Exception as e:                              # reported, never hidden
+        sres["two_streams_error"] = repr(e)[:200]
+
     # what a bucket hook would do: compress bucket by bucket as the gradients become
     # ready, average everything in one call once the exchange is over
     def hook_like(t):
