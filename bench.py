@@ -444,6 +444,7 @@ def compact(out, details):
     if "streamed" in out:
         st = out["streamed"]
         line["streamed"] = {"buckets": st["buckets"], "eager_us_per_step": st["eager_us_per_step"],
+                            "two_streams_us_per_step": st.get("eager_two_streams_us_per_step"),
                             "graph_us_per_step": st.get("graph_us_per_step")}
         brief_ov = lambda v: {k: v[k] for k in ("hidden_frac", "exposed_us", "sync_only_us", "compress_us", "backward_us")}
         if "overlap" in st:
