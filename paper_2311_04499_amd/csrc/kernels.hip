@@ -827,9 +827,8 @@ bool launch_compress(const covap::tuning &tn, const covap_plan_s *plan, const co
 template <typename OPS>
 bool launch_decompress(const covap::tuning &tn, const covap_plan_s *plan,
                        const covap::call_range &cr, hipStream_t st, const void *recv, void *out,
-                       int32_t N, int32_t divisor, int64_t stride, bool store_bound, covap::launch_status &ls)
+                       int32_t N, int32_t divisor, int64_t stride, covap::launch_status &ls)
 {
-    (void)store_bound;  // the shape for it is in tn already
     const int pow2 = (divisor & (divisor - 1)) == 0;
     const float n_f = (float)divisor, inv_n = 1.0f / n_f;
     return pick<64, 256>(tn.decompress_threads, [&](auto T) {
@@ -1034,11 +1033,11 @@ static covap_status_t decompress_call(const char *who, const covap_plan_t *plan,
     covap::launch_status ls;
     bool ok;
     if (dt == COVAP_F32)
-        ok = launch_decompress<ops_f32>(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, store_bound, ls);
+        ok = launch_decompress<ops_f32>(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, ls);
     else if (dt == COVAP_F32_PAY16)
         ok = launch_decompress_pay16(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, store_bound, ls);
     else
-        ok = launch_decompress<ops_bf16>(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, store_bound, ls);
+        ok = launch_decompress<ops_bf16>(tn, plan, cr, st, recv, dense_out, rows, divisor, stride_elems, ls);
     if (!ok) return fail(COVAP_EINVAL, who, "launch knobs select no kernel");
     return ls.report(who);
 }

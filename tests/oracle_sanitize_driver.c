@@ -38,6 +38,12 @@ void orc_decompress_bf16(const uint16_t *, int32_t, int64_t, uint16_t *, const i
                          int64_t, int32_t, uint64_t, int64_t);
 void orc_decompress_pay16(const uint16_t *, int32_t, int64_t, float *, const int64_t *, const int64_t *, int64_t,
                           int64_t, int32_t, uint64_t, int64_t);
+void orc_unpack_mean_f32(const float *, int32_t, float *, const int64_t *, const int64_t *, int64_t, int64_t, int32_t,
+                         uint64_t, int64_t);
+void orc_unpack_mean_bf16(const uint16_t *, int32_t, uint16_t *, const int64_t *, const int64_t *, int64_t, int64_t,
+                          int32_t, uint64_t, int64_t);
+void orc_unpack_mean_pay16(const uint16_t *, int32_t, float *, const int64_t *, const int64_t *, int64_t, int64_t,
+                           int32_t, uint64_t, int64_t);
 int32_t orc_topk_f32(const float *, float *, int64_t, int64_t, float, float *, uint32_t *);
 int32_t orc_randk_f32(const float *, float *, int64_t, const uint32_t *, int64_t, float, float *);
 void orc_fp16_compress(const float *, float *, int64_t, float, uint16_t *);
@@ -105,6 +111,10 @@ static int hot_path(const int64_t *off, const int64_t *len, const int32_t *bucke
             orc_decompress_f32(recv, N, stride, out, off, len, 0, n_sh, I, t, align);
             orc_decompress_bf16(recvb, N, stride, outb, off, len, 0, n_sh, I, t, align);
             orc_decompress_pay16(recvb, N, stride, out, off, len, 0, n_sh, I, t, align);
+            /* one summed row: the first row of the receive buffers stands in for it */
+            orc_unpack_mean_f32(recv, N, out, off, len, 0, n_sh, I, t, align);
+            orc_unpack_mean_bf16(recvb, N, outb, off, len, 0, n_sh, I, t, align);
+            orc_unpack_mean_pay16(recvb, N, out, off, len, 0, n_sh, I, t, align);
         } else { /* bucket by bucket */
             int64_t total = 0, lo = 0;
             for (int32_t b = 0; b < n_buckets; ++b) {
@@ -115,6 +125,9 @@ static int hot_path(const int64_t *off, const int64_t *len, const int32_t *bucke
                 orc_compress_aliased(acc, accs, 4, off, len, lo, hi, I, t, align);
                 orc_decompress_f32(recv, N, stride, out, off, len, lo, hi, I, t, align);
                 orc_decompress_bf16(recvb, N, stride, outb, off, len, lo, hi, I, t, align);
+                orc_unpack_mean_f32(recv, N, out, off, len, lo, hi, I, t, align);
+                orc_unpack_mean_bf16(recvb, N, outb, off, len, lo, hi, I, t, align);
+                orc_unpack_mean_pay16(recvb, N, out, off, len, lo, hi, I, t, align);
                 lo = hi;
             }
             CHECK(lo == n_sh && total == sent);
