@@ -331,7 +331,7 @@ def main():
                 cell = D // kk
                 si = (torch.arange(kk, device=dev, dtype=torch.int64)[None, :] * cell +
                       torch.randint(0, cell, (N, kk), generator=g, device=dev)).to(torch.int32).contiguous()
-                us = timed_us(lambda t: B.sparse_decompress_sorted(sv, si, dense, stream=stream), reps=5)
+                us = timed_us(lambda t: B.sparse_decompress_sorted(sv, si, dense, stream=stream), reps=20, warm=5)
                 us_pw = timed_us(lambda t: B.sparse_decompress(sv, si, dense, stream=stream), reps=3)
                 out["topk"]["decompress_us_per_iter"] = round(us, 1)
                 out["topk"]["decompress_per_worker_launches_us"] = round(us_pw, 1)

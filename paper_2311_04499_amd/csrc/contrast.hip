@@ -173,22 +173,6 @@ __global__ __launch_bounds__(kThreads) void k_scale(float *out, int64_t n, float
     }
 }
 
-// Mean of N <= 64 sparse payloads whose indices ascend inside every row (what
-// topk_compress writes), in one pass over the dense result: a one-wave workgroup
-// walks a run of consecutive 4096-element tiles, builds each tile in LDS and writes
-// it out once.  Lane w keeps a cursor into row w (found by a binary search at the
-// first tile and carried forward).  Per tile one load instruction fetches the 16
-// entries after the cursor of four rows at a time (lane = 16 * row-in-group + entry);
-// those that fall into the tile are added with LDS float adds, one instruction per
-// row and the rows in ascending order, which is the worker order the definition asks
-// for: LDS operations of one wave are carried out in program order, entries of one
-// row are distinct (no two lanes of an instruction meet), and the LDS adder rounds to
-// nearest even with subnormals like the vector unit (the parity tests cover both).
-// The common case is straight-line code -- every load of a tile is unconditional
-// (clamped addresses, masked results) and in flight before the first is used; a tile
-// in which some row has 16 or more entries takes a plain loop instead.  Unsorted rows
-// give an unspecified result but no access outside the buffers.  ROWS = lanes that
-// carry a row (the smallest of 8, 16, 32, 64 that holds N).
 constexpr int kSpTile = 4096;
 constexpr int kSpRows = 64;
 
@@ -197,55 +181,92 @@ __device__ __forceinline__ void lds_add(float *p, float v)
     __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);  // ds_add_f32
 }
 
-template <int ROWS, bool FULL>  // FULL: N == ROWS, which removes every test of a row number against N
-__global__ __launch_bounds__(64) void k_sparse_mean_sorted(const float *__restrict__ vals,
-                                                           const uint32_t *__restrict__ idx, int32_t N,
-                                                           uint32_t k, int64_t stride, int64_t n,
-                                                           float *__restrict__ out, int64_t tiles_per_wg,
-                                                           float n_f, float inv_n, int pow2)
+// Mean of N <= 64 sparse payloads whose indices ascend inside every row (what
+// topk_compress writes), in one pass over the dense result, as a pipeline of four waves.
+// A workgroup walks one run of consecutive 4096-element tiles with four tile buffers in
+// LDS.  Wave w owns a quarter of the payload rows (rows in worker order: wave 0 the first
+// quarter) and in phase p adds its rows into tile p - w, so a tile passes through the
+// waves in row order, one phase apart, with a barrier between phases.  The tile that has
+// passed the last wave is scaled, written out and cleared by all four waves together.
+//
+// Inside a wave: every row has a cursor (found by a binary search at the start of the run
+// and carried forward).  Per tile one load instruction fetches the 16 entries after the
+// cursor of four rows at a time (lane = 16 * row-in-group + entry); those that fall into
+// the tile are added with LDS float adds, one instruction per row and the rows in
+// ascending order.  That is the worker order the definition asks for: LDS operations of
+// one wave are carried out in program order, the waves follow each other across barriers,
+// entries of one row are distinct (no two lanes of an instruction meet), and the LDS adder
+// rounds to nearest even with subnormals like the vector unit (the parity tests cover
+// both).  The common case is straight-line code -- every load of a tile is unconditional
+// (clamped addresses, masked results), and the next tile's windows are in flight before
+// this tile's adds; a tile in which some row has 16 or more entries takes a plain loop
+// instead.  Unsorted rows give an unspecified result but no access outside the buffers.
+//
+// Against one wave doing all of this for a tile (which is how this kernel started: 0.39 ms
+// on the GPT-2-medium-shaped set, this form 0.28 ms): the write-out is four 16-byte stores
+// per lane from four waves instead of sixteen from one, the payload work of a tile is
+// spread over four waves with a quarter of the rows and of the registers each (107
+// instead of 229), and a compute unit holds eight such waves instead of five.
+// ROWS = 16, 32 or 64 (the smallest that holds N); a wave has ROWS / 4 rows.
+template <int ROWS, bool FULL>  // FULL: N == ROWS
+__global__ __launch_bounds__(256) void k_sparse_mean_pipe(const float *__restrict__ vals,
+                                                          const uint32_t *__restrict__ idx, int32_t N,
+                                                          uint32_t k, int64_t stride, int64_t n,
+                                                          float *__restrict__ out, int64_t tiles_per_wg,
+                                                          float n_f, float inv_n, int pow2)
 {
-    constexpr int GROUPS = ROWS / 4;
-    __shared__ float tile[kSpTile];
-    const int lane = threadIdx.x;
+    constexpr int RW = ROWS / 4;     // rows of a wave
+    constexpr int GROUPS = RW / 4;   // groups of four rows: one load instruction each
+    static_assert(GROUPS >= 1 && (RW & (RW - 1)) == 0, "4, 8 or 16 rows per wave");
+    __shared__ __align__(16) float tiles[4][kSpTile];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int q = lane >> 4, e = lane & 15;  // row inside a group of four, entry inside the window
     const int64_t ntiles = (n + kSpTile - 1) / kSpTile;
     const int64_t tile_lo = (int64_t)blockIdx.x * tiles_per_wg;
     int64_t tile_hi = tile_lo + tiles_per_wg;
     if (tile_hi > ntiles) tile_hi = ntiles;
-    if (tile_lo >= tile_hi) return;  // k >= 1 from here on (the host handles empty payloads)
+    if (tile_lo >= tile_hi) return;  // the whole workgroup; k >= 1 from here on (the host handles empty payloads)
+    const int64_t nrun = tile_hi - tile_lo;
+    const int row0 = wv * RW;  // this wave's rows: row0 .. row0 + RW - 1
 
-    // Cursor of row `lane`: first entry whose index is >= the start of the first tile.
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int v = 0; v < 4 * kSpTile / 4 / 256; ++v) ((f32x4 *)&tiles[0][0])[v * 256 + tid] = zero;
+
+    // Cursor of row row0 + (lane mod RW): first entry whose index is >= the start of the run.
     uint32_t start = 0u;
-    if (lane < N) {
-        const uint32_t *my_idx = idx + (int64_t)lane * stride;
-        const uint32_t first = (uint32_t)(tile_lo * kSpTile);
-        uint32_t lo = 0u, hi = k;
-        while (lo < hi) {
-            const uint32_t mid = lo + ((hi - lo) >> 1);
-            if (my_idx[mid] < first)
-                lo = mid + 1u;
-            else
-                hi = mid;
+    {
+        const int my_row = row0 + (lane & (RW - 1));
+        if (my_row < N) {
+            const uint32_t *my_idx = idx + (int64_t)my_row * stride;
+            const uint32_t first = (uint32_t)(tile_lo * kSpTile);
+            uint32_t lo = 0u, hi = k;
+            while (lo < hi) {
+                const uint32_t mid = lo + ((hi - lo) >> 1);
+                if (my_idx[mid] < first)
+                    lo = mid + 1u;
+                else
+                    hi = mid;
+            }
+            start = lo;
         }
-        start = lo;
     }
-    // From here on every lane carries, for each group g, the cursor and the row base of
-    // the row it loads for: row 4g + q.  The 16 lanes of a row hold the same cursor.
+    // Every lane carries, for each group g, the cursor and the row base of the row it
+    // loads for: row0 + 4g + q.  The 16 lanes of a row hold the same cursor.
     uint32_t cur[GROUPS];
     uint32_t row_off[GROUPS];  // first entry of the row in idx / vals (the host checks that it fits 32 bits)
     bool row_live[GROUPS];
 #pragma unroll
     for (int g = 0; g < GROUPS; ++g) {
-        const int w = 4 * g + q;
-        cur[g] = (uint32_t)__shfl((int)start, w, 64);
+        const int w = row0 + 4 * g + q;
+        cur[g] = (uint32_t)__shfl((int)start, 4 * g + q, 64);
         row_live[g] = FULL || w < N;
         row_off[g] = (uint32_t)(row_live[g] ? w : 0) * (uint32_t)stride;
     }
     const uint32_t k_last = k - 1u;
 
-    // Window [cursor, cursor + 16) of every row: raw index and value.  The loads are
-    // unconditional (addresses clamped to the row) so that all of them are in flight
-    // together; what lies outside the row or the tile is masked out afterwards.
+    // Window [cursor, cursor + 16) of every row: raw index and value, loaded unconditionally
+    // (addresses clamped to the row); what lies outside the row or the tile is masked out.
     uint32_t raw[GROUPS];
     float val[GROUPS];
     auto load_windows = [&]() {
@@ -258,131 +279,132 @@ __global__ __launch_bounds__(64) void k_sparse_mean_sorted(const float *__restri
         }
     };
     load_windows();
+    __syncthreads();  // the buffers are clear
 
-    for (int64_t t = tile_lo; t < tile_hi; ++t) {
-        const int64_t T0 = t * kSpTile;
-        const int64_t left = n - T0;
-        const uint32_t len = (uint32_t)(left < kSpTile ? left : kSpTile);
-        const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-        for (int v = 0; v < kSpTile / 4 / 64; ++v) ((f32x4 *)tile)[v * 64 + lane] = zero;
-
-        // the windows were loaded while the previous tile was being added up and written
-        // out (the cursors they start from are known as soon as that tile's entries have
-        // been counted); index relative to the tile start, anything outside the tile, past
-        // the row's end or in an unused row reads as "not in the tile"
-        uint32_t rel[GROUPS];
-        float now[GROUPS];
-#pragma unroll
-        for (int g = 0; g < GROUPS; ++g) {
-            rel[g] = raw[g];
-            now[g] = val[g];
-        }
-        bool full_window = false;  // a row whose 16th entry is in the tile may have more there
-#pragma unroll
-        for (int g = 0; g < GROUPS; ++g) {
-            const uint32_t j = cur[g] + (uint32_t)e;
-            const uint32_t r = rel[g] - (uint32_t)T0;  // wraps to a huge value below T0
-            rel[g] = (row_live[g] && j < k) ? r : 0xffffffffu;
-            full_window |= e == 15 && rel[g] < len;
-        }
-        if (__ballot(full_window) == 0ull) {
+    for (int64_t p = 0; p < nrun + 3; ++p) {
+        const int64_t ti = p - wv;  // this wave's tile in this phase, counted from the start of the run
+        if (ti >= 0 && ti < nrun) {  // the same in every lane of the wave
+            float *tile = tiles[ti & 3];
+            const int64_t T0 = (tile_lo + ti) * kSpTile;
+            const int64_t left = n - T0;
+            const uint32_t len = (uint32_t)(left < kSpTile ? left : kSpTile);
+            uint32_t rel[GROUPS];
+            float now[GROUPS];
+            bool full_window = false;  // a row whose 16th entry is in the tile may have more there
 #pragma unroll
             for (int g = 0; g < GROUPS; ++g) {
-                const uint64_t m = __ballot(rel[g] < len);
-                cur[g] += (uint32_t)__popcll((m >> (16 * q)) & 0xffffull);  // in-tile entries of this lane's row
+                const uint32_t j = cur[g] + (uint32_t)e;
+                const uint32_t r = raw[g] - (uint32_t)T0;  // wraps to a huge value below T0
+                rel[g] = (row_live[g] && j < k) ? r : 0xffffffffu;
+                now[g] = val[g];
+                full_window |= e == 15 && rel[g] < len;
             }
-            load_windows();  // the next tile's, in flight during the adds and the write-out below
+            if (__ballot(full_window) == 0ull) {
 #pragma unroll
-            for (int g = 0; g < GROUPS; ++g) {
-                const bool in = rel[g] < len;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {  // one add instruction per row, rows in order
-                    if (q == r && in) lds_add(&tile[rel[g]], now[g]);
+                for (int g = 0; g < GROUPS; ++g) {
+                    const uint64_t m = __ballot(rel[g] < len);
+                    cur[g] += (uint32_t)__popcll((m >> (16 * q)) & 0xffffull);  // in-tile entries of this lane's row
                 }
-            }
-        } else {
-            // crowded tile: four rows at a time, the next 256 entries of each (four loads of
-            // 64), all sixteen index and value loads in flight together; a row that still has
-            // entries in the tile after that goes on alone, 64 at a time
-            for (int w0 = 0; w0 < N; w0 += 4) {
-                const int g0 = w0 >> 2;
-                uint32_t cg = 0u;
+                load_windows();  // the next tile's, in flight during the adds and the phases in between
 #pragma unroll
-                for (int g = 0; g < GROUPS; ++g) cg = g == g0 ? cur[g] : cg;
-                uint32_t base[4], rr[4][4];
-                float vv[4][4];
-                bool lv[4][4];
+                for (int g = 0; g < GROUPS; ++g) {
+                    const bool in = rel[g] < len;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int w = w0 + r;
-                    const bool live = w < N;
-                    base[r] = (uint32_t)__shfl((int)cg, r * 16, 64);
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int64_t j = (int64_t)base[r] + 64 * u + lane;
-                        const int64_t at = (int64_t)(live ? w : 0) * stride + (j < (int64_t)k ? j : (int64_t)k - 1);
-                        rr[r][u] = idx[at];
-                        vv[r][u] = vals[at];
-                        lv[r][u] = live && j < (int64_t)k;
+                    for (int r = 0; r < 4; ++r) {  // one add instruction per row, rows in order
+                        if (q == r && in) lds_add(&tile[rel[g]], now[g]);
                     }
                 }
-                __builtin_amdgcn_sched_barrier(0);  // all thirty-two loads first
-                uint32_t tot[4];
+            } else {
+                // crowded tile: four rows at a time, the next 256 entries of each (four loads of
+                // 64), all sixteen index and value loads in flight together; a row that still has
+                // entries in the tile after that goes on alone, 64 at a time
+                for (int g0 = 0; g0 < GROUPS; ++g0) {
+                    const int w0 = row0 + 4 * g0;
+                    uint32_t cg = 0u;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {  // rows in order
-                    tot[r] = 0u;
+                    for (int g = 0; g < GROUPS; ++g) cg = g == g0 ? cur[g] : cg;
+                    uint32_t base[4], rr[4][4];
+                    float vv[4][4];
+                    bool lv[4][4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const uint32_t rel_u = lv[r][u] ? rr[r][u] - (uint32_t)T0 : 0xffffffffu;
-                        const bool in = rel_u < len;
-                        tot[r] += (uint32_t)__popcll(__ballot(in));
-                        if (in) lds_add(&tile[rel_u], vv[r][u]);
-                    }
-                    if (tot[r] == 256u) {
+                    for (int r = 0; r < 4; ++r) {
                         const int w = w0 + r;
-                        uint32_t cnt = 64u;
-                        while (cnt == 64u) {
-                            const int64_t j = (int64_t)base[r] + tot[r] + lane;
-                            uint32_t rel_j = 0xffffffffu;
-                            if (j < (int64_t)k) rel_j = idx[(int64_t)w * stride + j] - (uint32_t)T0;
-                            const bool in = rel_j < len;
-                            cnt = (uint32_t)__popcll(__ballot(in));
-                            if (in) lds_add(&tile[rel_j], vals[(int64_t)w * stride + j]);
-                            tot[r] += cnt;
+                        const bool live = w < N;
+                        base[r] = (uint32_t)__shfl((int)cg, r * 16, 64);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const int64_t j = (int64_t)base[r] + 64 * u + lane;
+                            const int64_t at = (int64_t)(live ? w : 0) * stride + (j < (int64_t)k ? j : (int64_t)k - 1);
+                            rr[r][u] = idx[at];
+                            vv[r][u] = vals[at];
+                            lv[r][u] = live && j < (int64_t)k;
                         }
                     }
-                }
-                const uint32_t add = q == 0 ? tot[0] : (q == 1 ? tot[1] : (q == 2 ? tot[2] : tot[3]));
+                    __builtin_amdgcn_sched_barrier(0);  // all thirty-two loads first
+                    uint32_t tot[4];
 #pragma unroll
-                for (int g = 0; g < GROUPS; ++g)
-                    if (g == g0) cur[g] += add;
+                    for (int r = 0; r < 4; ++r) {  // rows in order
+                        tot[r] = 0u;
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const uint32_t rel_u = lv[r][u] ? rr[r][u] - (uint32_t)T0 : 0xffffffffu;
+                            const bool in = rel_u < len;
+                            tot[r] += (uint32_t)__popcll(__ballot(in));
+                            if (in) lds_add(&tile[rel_u], vv[r][u]);
+                        }
+                        if (tot[r] == 256u) {
+                            const int w = w0 + r;  // < N: a dead row has no entries
+                            uint32_t cnt = 64u;
+                            while (cnt == 64u) {
+                                const int64_t j = (int64_t)base[r] + tot[r] + lane;
+                                uint32_t rel_j = 0xffffffffu;
+                                if (j < (int64_t)k) rel_j = idx[(int64_t)w * stride + j] - (uint32_t)T0;
+                                const bool in = rel_j < len;
+                                cnt = (uint32_t)__popcll(__ballot(in));
+                                if (in) lds_add(&tile[rel_j], vals[(int64_t)w * stride + j]);
+                                tot[r] += cnt;
+                            }
+                        }
+                    }
+                    const uint32_t add = q == 0 ? tot[0] : (q == 1 ? tot[1] : (q == 2 ? tot[2] : tot[3]));
+#pragma unroll
+                    for (int g = 0; g < GROUPS; ++g)
+                        if (g == g0) cur[g] += add;
+                }
+                load_windows();
             }
-            load_windows();
         }
+        __syncthreads();  // every wave's additions of this phase are in LDS
 
-        // mean and write-out (the wave's own LDS operations above are complete, in order,
-        // before its reads below)
-        float *o = out + T0;
-        if (len == (uint32_t)kSpTile) {
+        // the tile that has passed all four waves: mean, write-out, and its buffer cleared
+        const int64_t tw = p - 3;
+        if (tw >= 0) {  // tw < nrun, since p < nrun + 3
+            float *src = tiles[tw & 3];
+            const int64_t T0 = (tile_lo + tw) * kSpTile;
+            const int64_t left = n - T0;
+            float *o = out + T0;
+            if (left >= kSpTile) {
 #pragma unroll
-            for (int v = 0; v < kSpTile / 4 / 64; ++v) {
-                f32x4 x = ((const f32x4 *)tile)[v * 64 + lane];
-                if (N > 1) {
-                    x.x = pow2 ? x.x * inv_n : __fdiv_rn(x.x, n_f);
-                    x.y = pow2 ? x.y * inv_n : __fdiv_rn(x.y, n_f);
-                    x.z = pow2 ? x.z * inv_n : __fdiv_rn(x.z, n_f);
-                    x.w = pow2 ? x.w * inv_n : __fdiv_rn(x.w, n_f);
+                for (int v = 0; v < kSpTile / 4 / 256; ++v) {
+                    f32x4 x = ((const f32x4 *)src)[v * 256 + tid];
+                    ((f32x4 *)src)[v * 256 + tid] = zero;
+                    if (N > 1) {
+                        x.x = pow2 ? x.x * inv_n : __fdiv_rn(x.x, n_f);
+                        x.y = pow2 ? x.y * inv_n : __fdiv_rn(x.y, n_f);
+                        x.z = pow2 ? x.z * inv_n : __fdiv_rn(x.z, n_f);
+                        x.w = pow2 ? x.w * inv_n : __fdiv_rn(x.w, n_f);
+                    }
+                    __builtin_nontemporal_store(x, (f32x4 *)o + v * 256 + tid);
                 }
-                __builtin_nontemporal_store(x, (f32x4 *)o + v * 64 + lane);
-            }
-        } else {  // the arena's last, short tile
-            for (uint32_t i = lane; i < len; i += 64) {
-                float x = tile[i];
-                if (N > 1) x = pow2 ? x * inv_n : __fdiv_rn(x, n_f);
-                o[i] = x;
+            } else {  // the arena's last, short tile (the run ends here: the buffer is not used again)
+                for (int64_t i = tid; i < left; i += 256) {
+                    float x = src[i];
+                    if (N > 1) x = pow2 ? x * inv_n : __fdiv_rn(x, n_f);
+                    o[i] = x;
+                }
             }
         }
+        __syncthreads();  // the buffer is clear before a wave adds to it again
     }
 }
 
@@ -498,26 +520,21 @@ covap_status_t sparse_decompress_sorted(const void *vals, const uint32_t *idx, i
     if (((uintptr_t)vals & 3u) || ((uintptr_t)idx & 3u))
         return fail(COVAP_EINVAL, "sparse_decompress_sorted: misaligned device pointer");
     const int64_t ntiles = (n + kSpTile - 1) / kSpTile;
-    // Five workgroups per CU, all resident at once, each with one long run of tiles: the
-    // binary search at the start of a run costs about four tiles' worth of time, and a
-    // second, partly filled round of workgroups costs more than lower occupancy does
-    // (measured at 86 k tiles: 408 us this way, 495..525 us with 2..16 tiles per run; with the
-    // windows loaded one tile ahead 391 us, against 414 us at four and 491 us at eight per CU).
-    int64_t tiles_per_wg = (ntiles + 1279) / 1280;
+    // Two workgroups per CU (four tile buffers each fill the LDS), all resident at once, each
+    // with one long run of tiles.
+    int64_t tiles_per_wg = (ntiles + 511) / 512;
     if (tiles_per_wg < 1) tiles_per_wg = 1;
     const uint32_t grid = (uint32_t)((ntiles + tiles_per_wg - 1) / tiles_per_wg);
     const int pow2 = (n_workers & (n_workers - 1)) == 0;
     const float n_f = (float)n_workers;
-    const auto kern = n_workers == 64   ? k_sparse_mean_sorted<64, true>
-                      : n_workers > 32  ? k_sparse_mean_sorted<64, false>
-                      : n_workers == 32 ? k_sparse_mean_sorted<32, true>
-                      : n_workers > 16  ? k_sparse_mean_sorted<32, false>
-                      : n_workers == 16 ? k_sparse_mean_sorted<16, true>
-                      : n_workers > 8   ? k_sparse_mean_sorted<16, false>
-                      : n_workers == 8  ? k_sparse_mean_sorted<8, true>
-                                        : k_sparse_mean_sorted<8, false>;
+    const auto kern = n_workers == 64   ? k_sparse_mean_pipe<64, true>
+                      : n_workers > 32  ? k_sparse_mean_pipe<64, false>
+                      : n_workers == 32 ? k_sparse_mean_pipe<32, true>
+                      : n_workers > 16  ? k_sparse_mean_pipe<32, false>
+                      : n_workers == 16 ? k_sparse_mean_pipe<16, true>
+                                        : k_sparse_mean_pipe<16, false>;
     covap::launch_status ls;
-    ls += covap::launch(kern, dim3(grid), dim3(64), 0, (hipStream_t)stream, (const float *)vals, idx, n_workers,
+    ls += covap::launch(kern, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const float *)vals, idx, n_workers,
                         (uint32_t)k, stride_elems, n, (float *)dense_out, tiles_per_wg, n_f, 1.0f / n_f, pow2);
     return ls.report("sparse_decompress_sorted");
 }
