@@ -171,6 +171,38 @@ def test_sorted_sparse_mean_shapes(B, n, k, N, kind):
     same(out.cpu().numpy(), oracle.sparse_mean(vc, ic, k, n), "dense mean")
 
 
+@pytest.mark.parametrize("n,N", [(30_000_017, 64), (12_345_678, 20), (9_000_001, 9), (20_000_000, 32)])
+def test_sorted_sparse_mean_long_runs(B, n, N):
+    """Arenas of thousands of tiles: a workgroup then walks a run of many tiles, the four tile buffers are
+    reused phase after phase and the cursors and prefetched windows are carried along.  Rows mix a spread part
+    (one entry per cell), a stretch where every row hits the same elements (the order of the adds matters) and a
+    dense cluster (hundreds of entries of a row in one tile)."""
+    rng = np.random.default_rng(n + N)
+    cell = 1_000
+    k_spread = n // cell
+    shared = np.sort(rng.choice(np.arange(n // 3, n // 3 + 200_000), 3_000, replace=False)).astype(np.uint32)
+    rows_i, rows_v = [], []
+    for w in range(N):
+        spread = (np.arange(k_spread, dtype=np.int64) * cell + rng.integers(0, cell, k_spread)).astype(np.uint32)
+        lo = n // 2 + 50_000 * (w % 3)
+        cluster = (lo + np.sort(rng.choice(20_000, 2_500, replace=False))).astype(np.uint32)
+        i = np.unique(np.concatenate([spread, shared, cluster]))
+        rows_i.append(i)
+    k = min(len(i) for i in rows_i)
+    ic = np.stack([np.sort(rng.choice(i, k, replace=False)) if len(i) > k else i for i in rows_i]).astype(np.uint32)
+    vc = (rng.standard_normal((N, k)) * 10.0 ** rng.integers(-3, 4, (N, k))).astype(np.float32)
+    vals = torch.from_numpy(vc).to(DEV)
+    idx = torch.from_numpy(ic.view(np.int32)).to(DEV)
+    out = torch.full((n,), float("nan"), device=DEV)
+    B.sparse_decompress_sorted(vals, idx, out, k=k, n_workers=N)
+    torch.cuda.synchronize()
+    same(out.cpu().numpy(), oracle.sparse_mean(vc, ic, k, n), f"dense mean n={n} N={N}")
+    out2 = torch.full((n,), float("nan"), device=DEV)
+    B.sparse_decompress(vals, idx, out2, k=k, n_workers=N)             # the per-worker form: the same bits
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int32), out2.view(torch.int32))
+
+
 def test_argument_errors(B):
     G = torch.zeros(100, device=DEV)
     R = torch.zeros(100, device=DEV)
