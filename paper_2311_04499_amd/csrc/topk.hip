@@ -4,10 +4,9 @@
 // decides how much work the exact selection has to do, never what it returns.
 //
 //   sample   A = fma(c, R, G) on 1024 evenly spread 256-element chunks; histogram of
-//            key bits 30..20 -> a bin b_lo that very probably lies at or below the bin
-//            of the k-th largest key, with only a fraction of a percent of the keys
-//            at or above it                                          (reads 2 MB)
-//   pass 1   A = fma(c, R, G); R <- A; every element whose bin is >= b_lo is copied,
+//            key bits 30..20 -> a key t_lo that very probably lies at or below
+//            the k-th largest key, with only a few times k keys at or above it                                          (reads 2 MB)
+//   pass 1   A = fma(c, R, G); R <- A; every element whose key is >= t_lo is copied,
 //            in index order, into a 32-entry slot array of its 1024-element tile
 //                                                                (reads 2D, writes D)
 //   then everything works on the slots only (a fraction of a percent of the data):
@@ -21,7 +20,7 @@
 // every kernel of the slot tail then also walks that list and reads those tiles
 // from R, one wave per tile.
 //
-// If the bins >= b_lo turn out to hold fewer than k keys (the sample misled), or if
+// If fewer than k keys turn out to be >= t_lo (the sample misled), or if
 // the list grows beyond 1/32 of the tiles (data full of ties, a very large k), a
 // flag is raised on the device and the general path runs instead: three full
 // histogram passes, a counting pass and a compaction pass over R (5 more reads of
@@ -65,15 +64,15 @@ struct topk_state {
     uint32_t threshold;  // T, valid after level 3
     uint32_t ties;       // number of keys == T to keep, valid after level 3
     uint32_t overflow;   // != 0: the general tail runs (bit 0: too many tiles did not fit their
-                         // slots, bit 1: the bins >= b_lo hold fewer than k keys)
-    uint32_t b_lo;       // pass 1 looks only at keys whose level-1 bin is >= b_lo
+                         // slots, bit 1: fewer than k keys are >= t_lo)
+    uint32_t t_lo;       // pass 1 looks only at keys >= t_lo
     uint32_t k;          // the k of this call
     uint32_t n_crowded;  // tiles that did not fit their slots; the slot tail reads those from R
     uint32_t tickets[3]; // general tail: workgroups that have added their share of the histogram of level 1, 2, 3
 };
 
-// Slot entries per 1024-element tile.  The bins >= b_lo hold 2..10 times the keys needed (a bin is an eighth
-// of an octave), i.e. a handful per tile: with 16 slots so many tiles went on the crowded list that the call
+// Slot entries per 1024-element tile.  1.25 to 3 times the keys needed are >= t_lo, i.e. a handful per tile
+// up to k = 1 % of the data: with 16 slots so many tiles went on the crowded list that the call
 // took 0.95 ms instead of 0.81.
 //
 // Layout: "plane" q holds entries 8q .. 8q+7 of every tile, 32 bytes per tile: entry p of tile t is word
@@ -220,7 +219,7 @@ __global__ __launch_bounds__(kSampleThreads) void k_topk_sample(const float *__r
         st->threshold = 0u;
         st->ties = 0u;
         st->overflow = 0u;
-        st->b_lo = 0u;
+        st->t_lo = 0u;
         st->k = k;
         st->n_crowded = 0u;
     }
@@ -271,7 +270,7 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 }
 
 // Error feedback, residual write, and the ordered copy of every key whose level-1
-// bin is >= b_lo into the slots of its tile.  One workgroup of WAVES waves per
+// key is >= t_lo into the slots of its tile.  One workgroup of WAVES waves per
 // 1024-element tile, in four rounds of 64 lanes x 4 elements (ascending index
 // order); a wave takes 4 / WAVES consecutive rounds.  Ranks inside a round come from
 // the lane masks of the four components, ranks across waves through LDS.  A tile
@@ -287,7 +286,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_topk_pass1(const float *__restri
 {
     constexpr int ROUNDS = 4 / WAVES;
     __shared__ uint32_t wave_total[WAVES];
-    const uint32_t b_lo = st->b_lo;
+    const uint32_t t_lo = st->t_lo;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int64_t tile = blockIdx.x;  // one workgroup per tile
     const int64_t base = tile * kTile + (int64_t)wv * ROUNDS * 256;
@@ -318,7 +317,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_topk_pass1(const float *__restri
         raw[u] = __builtin_bit_cast(u32x4, a);
         bool cj[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) cj[j] = ((valid >> j) & 1u) && ((raw[u][j] & kAbs) >> 20) >= b_lo;
+        for (int j = 0; j < 4; ++j) cj[j] = ((valid >> j) & 1u) && (raw[u][j] & kAbs) >= t_lo;
         const uint64_t m0 = __ballot(cj[0]), m1 = __ballot(cj[1]), m2 = __ballot(cj[2]), m3 = __ballot(cj[3]);
         cand[u] = (cj[0] ? 1u : 0u) | (cj[1] ? 2u : 0u) | (cj[2] ? 4u : 0u) | (cj[3] ? 8u : 0u);
         rank[u] = running;
@@ -411,10 +410,10 @@ __device__ __forceinline__ void general_hist(const float *__restrict__ R, int64_
 
 // Finds the digit at which the count from the top reaches the wanted count: the
 // largest b with sum_{j >= b} hist[j] >= wanted.  One workgroup.
-//   LEVEL 0     on the sample: wanted = `target`; the digit becomes b_lo (0 if the
-//               sample is too small to tell)
+//   LEVEL 0     on the sample: wanted = `target`; the digit, refined by interpolation inside
+//               its bin, becomes t_lo (0 if the sample is too small to tell)
 //   LEVEL 1     wanted = k; the digit opens the prefix.  On the slots (GATE kSlotTail)
-//               a total below k means that b_lo was too high, and a crowded list
+//               a total below k means that t_lo was too high, and a crowded list
 //               longer than `target` that too many tiles missed their slots: either
 //               switches the general tail on.
 //   LEVEL 2, 3  wanted = k_rem; the digit extends the prefix; level 3 fixes T.
@@ -496,7 +495,10 @@ __device__ __forceinline__ void pick(topk_state *st, const uint32_t *hist, int n
             if (above + h[j] >= k_rem) {
                 const uint32_t bin = (uint32_t)(BINS - 1 - (tid * PER + j));
                 if (LEVEL == 0) {
-                    st->b_lo = bin;
+                    // the key inside the bin above which the wanted count lies, taking the bin's
+                    // keys as evenly spread (a heuristic bound: nothing exact depends on it)
+                    const uint32_t need = k_rem - above;  // 1 .. h[j] of this bin's keys, from its top
+                    st->t_lo = (bin << 20) + (uint32_t)(((uint64_t)(h[j] - need) << 20) / h[j]);
                     break;
                 }
                 const uint32_t prefix = base_prefix | (bin << SHIFT);
@@ -750,7 +752,7 @@ __device__ __forceinline__ void slots_hist(const topk_state *__restrict__ st,
     constexpr int BINS = LEVEL == 3 ? kBins3 : kBins12;
     constexpr int SHIFT = LEVEL == 1 ? 20 : (LEVEL == 2 ? 9 : 0);
     constexpr int HI_SHIFT = LEVEL == 1 ? 31 : (LEVEL == 2 ? 20 : 9);
-    // Level 1 sees every entry, and nearly all of them fall into the eight bins from b_lo up
+    // Level 1 sees every entry, and nearly all of them fall into the eight bins from t_lo's up
     // (one octave): a thread counts those in the eight 8-bit fields of a register, and a wave
     // adds its fields up and makes eight LDS additions every six tiles per lane (at most 192
     // entries, so no field overflows).  The other bins, and the other levels, add to LDS
@@ -761,11 +763,11 @@ __device__ __forceinline__ void slots_hist(const topk_state *__restrict__ st,
     __syncthreads();
     uint32_t *mine = lds + (tid & (COPIES - 1)) * BINS;
     const uint32_t want = LEVEL == 1 ? 0u : st->prefix >> HI_SHIFT;  // keys have bit 31 clear
-    const uint32_t b_lo = st->b_lo;
+    const uint32_t t_lo = st->t_lo, b_lo = t_lo >> 20;
     uint64_t packed = 0ull;
     auto count = [&](uint32_t key) {  // key: bit 31 clear, matches the prefix
         if constexpr (LEVEL == 1) {
-            const uint32_t rel = (key >> 20) - b_lo;  // >= 0: only keys at or above b_lo are looked at
+            const uint32_t rel = (key >> 20) - b_lo;  // >= 0: only keys at or above t_lo are looked at
             if (rel < 8u)
                 packed += 1ull << (rel * 8u);
             else
@@ -818,7 +820,7 @@ __device__ __forceinline__ void slots_hist(const topk_state *__restrict__ st,
         flush();
     }
     // the crowded tiles, from R: one wave per tile.  Level 1 counts, like the slots do,
-    // only the keys at or above b_lo.
+    // only the keys at or above t_lo.
     const uint32_t n_crowded = st->n_crowded;
     if (n_crowded <= crowded_limit(ntiles)) {
         constexpr int kWaves = kSlotThreads / 64;
@@ -831,7 +833,7 @@ __device__ __forceinline__ void slots_hist(const topk_state *__restrict__ st,
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const bool ok = ((valid >> j) & 1u) && (key[j] >> HI_SHIFT) == want &&
-                                    (LEVEL != 1 || (key[j] >> 20) >= b_lo);
+                                    (LEVEL != 1 || key[j] >= t_lo);
                     if (ok) count(key[j]);
                 }
             }
@@ -1218,13 +1220,16 @@ covap::launch_status run_topk(const void *grad, void *residual, int64_t n, int64
 
     uint32_t *h1g = ws.hist, *h2g = h1g + 2048, *h3g = h2g + 2048, *h1s = ws.hist + kAtomicRows * 2048,
              *h2s = h1s + kSlotGrid * 2048, *h3s = h2s + kSlotGrid * 2048, *hs = h2s;
-    // the sample: n_s of the full 256-element chunks; the bin it proposes holds about
-    // twice the keys that are needed (plus a floor for small k), so that the bins
-    // >= b_lo hold at least k keys unless the sample is far off
+    // the sample: n_s of the full 256-element chunks.  The key it proposes has `want` of the sample's
+    // keys at or above it: three times the sample's share of k while that share is small (the sample
+    // takes whole chunks, so on clustered data its share of the large keys varies a lot), falling to
+    // 1.25 times for k around 1 % of the data, where more would no longer fit the slots; plus a floor.
     const int64_t nchunks_s = nvec / 64;
     const int32_t n_s = (int32_t)(nchunks_s < kSampleChunks ? nchunks_s : kSampleChunks);
     const int64_t m = (int64_t)n_s * 256;
-    const int64_t want = 2 * div_up(k * m, n) + 32;
+    const int64_t ks = div_up(k * m, n);  // the sample's share of k
+    const int64_t quarters = ks <= 512 ? 12 : (ks >= 2048 ? 5 : 12 - (ks - 512) * 7 / 1536);  // margin in quarters
+    const int64_t want = div_up(ks * quarters, 4) + 32;
     const uint32_t target = (uint32_t)(want < ((int64_t)1 << 31) ? want : ((int64_t)1 << 31));
     ls += covap::launch(k_topk_sample, dim3(kSlotGrid), dim3(kSampleThreads), 0, st, G, R, ef_coeff, nchunks_s, n_s,
                         ws.state, ws.hist, hs, (uint32_t)k, ws.chunk_gt, ws.chunk_eq, (int32_t)nchunks);
