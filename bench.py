@@ -300,7 +300,15 @@ def main():
                            "vs_covap_compress_plus_decompress": round(topk_us / (ms_step * 1e3), 2),
                            # the other half of the stated goal: compression overhead at least 10x below top-k's
                            "target_10x_below_topk_met": bool(ratio >= 10.0)}
-            del ws, vals, idx, res2
+            # the ratio of the paper's Table II (k = 1 %), for context beside the 0.1 % this benchmark is quoted on
+            k1 = -(-D // 100)
+            vals1 = torch.empty(k1, dtype=torch.float32, device=dev)
+            idx1 = torch.empty(k1, dtype=torch.int32, device=dev)
+            us1 = timed_us(lambda t: B.topk_compress(ring[t % 3], res2, k1, vals1, idx1, ws, stream=stream),
+                           reps=max(5, min(args.steps, 20)), warm=3)
+            out["topk"]["at_1_percent"] = {"k": k1, "us_per_iter": round(us1, 1),
+                                           "vs_covap_compress": round(us1 / (tc_avg * 1e3), 2)}
+            del ws, vals, idx, res2, vals1, idx1
         except B.CovapError as e:
             out["topk"] = {"error": str(e)}
 
@@ -435,6 +443,8 @@ def compact(out, details):
         t = out["topk"]
         line["topk"] = {k: t[k] for k in ("us_per_iter", "vs_covap_compress", "target_10x_below_topk_met",
                                           "decompress_us_per_iter") if k in t}
+        if "at_1_percent" in t:
+            line["topk"]["us_per_iter_at_1_percent"] = t["at_1_percent"]["us_per_iter"]
     if "aliased_compress" in out:
         a = out["aliased_compress"]
         line["aliased_compress"] = {k: a[k] for k in ("us_per_iter", "topk_over_aliased") if k in a}
