@@ -71,8 +71,8 @@ struct topk_state {
     uint32_t tickets[3]; // general tail: workgroups that have added their share of the histogram of level 1, 2, 3
 };
 
-// Slot entries per 1024-element tile.  1.25 to 3 times the keys needed are >= t_lo, i.e. a handful per tile
-// up to k = 1 % of the data: with 16 slots so many tiles went on the crowded list that the call
+// Slot entries per 1024-element tile.  2 to 10 times the keys needed are >= t_lo for small k (1.25 to 2 times
+// around k = 1 % of the data), i.e. a handful per tile: with 16 slots so many tiles went on the crowded list that the call
 // took 0.95 ms instead of 0.81.
 //
 // Layout: "plane" q holds entries 8q .. 8q+7 of every tile, 32 bytes per tile: entry p of tile t is word
@@ -410,8 +410,9 @@ __device__ __forceinline__ void general_hist(const float *__restrict__ R, int64_
 
 // Finds the digit at which the count from the top reaches the wanted count: the
 // largest b with sum_{j >= b} hist[j] >= wanted.  One workgroup.
-//   LEVEL 0     on the sample: wanted = `target`; the digit, refined by interpolation inside
-//               its bin, becomes t_lo (0 if the sample is too small to tell)
+//   LEVEL 0     on the sample: wanted = `target`; the digit's lowest key (GATE 0) or a key inside
+//               its bin found by interpolation (GATE 1) becomes t_lo (0 if the sample is too
+//               small to tell)
 //   LEVEL 1     wanted = k; the digit opens the prefix.  On the slots (GATE kSlotTail)
 //               a total below k means that t_lo was too high, and a crowded list
 //               longer than `target` that too many tiles missed their slots: either
@@ -495,10 +496,11 @@ __device__ __forceinline__ void pick(topk_state *st, const uint32_t *hist, int n
             if (above + h[j] >= k_rem) {
                 const uint32_t bin = (uint32_t)(BINS - 1 - (tid * PER + j));
                 if (LEVEL == 0) {
-                    // the key inside the bin above which the wanted count lies, taking the bin's
-                    // keys as evenly spread (a heuristic bound: nothing exact depends on it)
+                    // GATE != 0: the key inside the bin above which the wanted count lies, taking the
+                    // bin's keys as evenly spread; otherwise the bin's lowest key, which can only admit
+                    // more.  (A heuristic bound either way: nothing exact depends on it.)
                     const uint32_t need = k_rem - above;  // 1 .. h[j] of this bin's keys, from its top
-                    st->t_lo = (bin << 20) + (uint32_t)(((uint64_t)(h[j] - need) << 20) / h[j]);
+                    st->t_lo = (bin << 20) + (GATE != 0 ? (uint32_t)(((uint64_t)(h[j] - need) << 20) / h[j]) : 0u);
                     break;
                 }
                 const uint32_t prefix = base_prefix | (bin << SHIFT);
@@ -1052,11 +1054,13 @@ __device__ __forceinline__ void general_hist_pick(const float *__restrict__ R, i
     pick<LEVEL, kGeneralTail, kSlotThreads>(st, row, 1, 0u, lds);
 }
 
+// INTERPOLATE: the bound is placed inside the level-1 bin (for larger k, see run_topk).
+template <bool INTERPOLATE>
 __global__ __launch_bounds__(kPickThreads) void k_topk_pick_sample(topk_state *st, const uint32_t *hist,
                                                                    uint32_t target)
 {
     __shared__ __align__(16) uint32_t lds[kPickLds];
-    pick<0, kAlways, kPickThreads>(st, hist, kSlotGrid, target, lds);
+    pick<0, INTERPOLATE ? 1 : 0, kPickThreads>(st, hist, kSlotGrid, target, lds);
 }
 
 // Level-1 histogram of the slots (the pick that follows decides which tail runs).
@@ -1220,20 +1224,26 @@ covap::launch_status run_topk(const void *grad, void *residual, int64_t n, int64
 
     uint32_t *h1g = ws.hist, *h2g = h1g + 2048, *h3g = h2g + 2048, *h1s = ws.hist + kAtomicRows * 2048,
              *h2s = h1s + kSlotGrid * 2048, *h3s = h2s + kSlotGrid * 2048, *hs = h2s;
-    // the sample: n_s of the full 256-element chunks.  The key it proposes has `want` of the sample's
-    // keys at or above it: three times the sample's share of k while that share is small (the sample
-    // takes whole chunks, so on clustered data its share of the large keys varies a lot), falling to
-    // 1.25 times for k around 1 % of the data, where more would no longer fit the slots; plus a floor.
+    // The sample: n_s of the full 256-element chunks; it proposes a key with `want` of the sample's keys
+    // at or above it.  While the sample's share of k is small, `want` is twice that share plus a floor
+    // and the key is the lower edge of a level-1 bin (an eighth of an octave): 2 to 10 times k keys are
+    // then at or above it, and only more when the keys crowd just below the k-th largest (as they do
+    // under error feedback), which errs on the safe side and which the 32 slots of a tile absorb.  For
+    // k around 1 % of the data that many keys no longer fit the slots, so the margin falls to 1.25 times
+    // the share and the key is placed inside the bin by interpolation; where that misjudges, the general
+    // tail takes over, as it would have anyway.
     const int64_t nchunks_s = nvec / 64;
     const int32_t n_s = (int32_t)(nchunks_s < kSampleChunks ? nchunks_s : kSampleChunks);
     const int64_t m = (int64_t)n_s * 256;
     const int64_t ks = div_up(k * m, n);  // the sample's share of k
-    const int64_t quarters = ks <= 512 ? 12 : (ks >= 2048 ? 5 : 12 - (ks - 512) * 7 / 1536);  // margin in quarters
+    const bool interpolate = ks > 512;
+    const int64_t quarters = ks <= 512 ? 8 : (ks >= 2048 ? 5 : 8 - (ks - 512) * 3 / 1536);  // margin in quarters
     const int64_t want = div_up(ks * quarters, 4) + 32;
     const uint32_t target = (uint32_t)(want < ((int64_t)1 << 31) ? want : ((int64_t)1 << 31));
     ls += covap::launch(k_topk_sample, dim3(kSlotGrid), dim3(kSampleThreads), 0, st, G, R, ef_coeff, nchunks_s, n_s,
                         ws.state, ws.hist, hs, (uint32_t)k, ws.chunk_gt, ws.chunk_eq, (int32_t)nchunks);
-    ls += covap::launch(k_topk_pick_sample, dim3(1), dim3(kPickThreads), 0, st, ws.state, hs, target);
+    ls += covap::launch(interpolate ? k_topk_pick_sample<true> : k_topk_pick_sample<false>, dim3(1), dim3(kPickThreads), 0,
+                        st, ws.state, hs, target);
     const covap::tuning tn = covap::tune();
     const auto pass1 = tn.topk_pass1_waves == 4 ? k_topk_pass1<4> : (tn.topk_pass1_waves == 2 ? k_topk_pass1<2> : k_topk_pass1<1>);
     ls += covap::launch(pass1, dim3((uint32_t)ntiles), dim3(64 * tn.topk_pass1_waves),

@@ -235,7 +235,7 @@ def test_a_misleading_sample_falls_back_to_the_general_tail(B):
 
 def test_the_sampled_bound_is_used_on_smooth_data(B):
     """White box: on Gaussian data the bound (word 5 of the workspace, a key) lies a little
-    below the k-th largest key -- between k and about four times k keys are at or above it --
+    below the k-th largest key -- between k and about ten times k keys are at or above it --
     and the slot tail produces the result."""
     n = 3_000_017
     k = n // 1000
@@ -254,7 +254,7 @@ def test_the_sampled_bound_is_used_on_smooth_data(B):
     key = np.abs(Gn).view(np.uint32)
     kth = int(np.sort(key)[n - k])
     t_lo = int(st[5])
-    assert 0 < t_lo <= kth and k <= int((key >= t_lo).sum()) <= 5 * k
+    assert 0 < t_lo <= kth and k <= int((key >= t_lo).sum()) <= 12 * k
     ov, oi = oracle.topk(Gn, Rn, k)
     assert np.array_equal(idx.cpu().numpy().view(np.uint32), oi)
     assert np.array_equal(vals.cpu().numpy().view(np.uint32), ov.view(np.uint32))
