@@ -304,6 +304,7 @@ def main():
             k1 = -(-D // 100)
             vals1 = torch.empty(k1, dtype=torch.float32, device=dev)
             idx1 = torch.empty(k1, dtype=torch.int32, device=dev)
+            res2.zero_()                                 # its own error-feedback history, from the start
             us1 = timed_us(lambda t: B.topk_compress(ring[t % 3], res2, k1, vals1, idx1, ws, stream=stream),
                            reps=max(5, min(args.steps, 20)), warm=3)
             out["topk"]["at_1_percent"] = {"k": k1, "us_per_iter": round(us1, 1),

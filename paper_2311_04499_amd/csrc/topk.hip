@@ -21,7 +21,7 @@
 // from R, one wave per tile.
 //
 // If fewer than k keys turn out to be >= t_lo (the sample misled), or if
-// the list grows beyond 1/32 of the tiles (data full of ties, a very large k), a
+// the list grows beyond a quarter of the tiles (data full of ties, a very large k), a
 // flag is raised on the device and the general path runs instead: three full
 // histogram passes, a counting pass and a compaction pass over R (5 more reads of
 // D).  The two tails exclude each other, so the host launches one sequence of kernels
@@ -71,7 +71,7 @@ struct topk_state {
     uint32_t tickets[3]; // general tail: workgroups that have added their share of the histogram of level 1, 2, 3
 };
 
-// Slot entries per 1024-element tile.  2 to 10 times the keys needed are >= t_lo for small k (1.25 to 2 times
+// Slot entries per 1024-element tile.  2 to 10 times the keys needed are >= t_lo for small k (1.5 to 2 times
 // around k = 1 % of the data), i.e. a handful per tile: with 16 slots so many tiles went on the crowded list that the call
 // took 0.95 ms instead of 0.81.
 //
@@ -499,8 +499,20 @@ __device__ __forceinline__ void pick(topk_state *st, const uint32_t *hist, int n
                     // GATE != 0: the key inside the bin above which the wanted count lies, taking the
                     // bin's keys as evenly spread; otherwise the bin's lowest key, which can only admit
                     // more.  (A heuristic bound either way: nothing exact depends on it.)
-                    const uint32_t need = k_rem - above;  // 1 .. h[j] of this bin's keys, from its top
-                    st->t_lo = (bin << 20) + (GATE != 0 ? (uint32_t)(((uint64_t)(h[j] - need) << 20) / h[j]) : 0u);
+                    uint32_t inside = 0u;  // offset of the key above the bin's lower edge
+                    if (GATE != 0) {
+                        // The count from the top grows geometrically through a bin of a smooth tail, and
+                        // faster than that towards the lower edge when keys crowd below the k-th largest:
+                        // a geometric fit between the counts at the two edges errs low, the safe side.
+                        // (Linear in the count when nothing lies above the bin.)
+                        const float total = (float)(above + h[j]), want_f = (float)k_rem;
+                        const float s = above > 0u ? __log2f(want_f / (float)above) / __log2f(total / (float)above)
+                                                   : (want_f / total);  // share of the bin's width, from its top
+                        const float down = fminf(fmaxf(s, 0.0f), 1.0f) * 1048576.0f;
+                        inside = 1048576u - (uint32_t)down;
+                        if (inside > 1048575u) inside = 1048575u;
+                    }
+                    st->t_lo = (bin << 20) + inside;
                     break;
                 }
                 const uint32_t prefix = base_prefix | (bin << SHIFT);
@@ -728,7 +740,7 @@ __device__ __forceinline__ void general_write(float *R, int64_t n, int64_t ntile
 // full of ties, a very large k) the general tail takes over instead.
 __host__ __device__ inline uint32_t crowded_limit(int64_t ntiles)
 {
-    const int64_t share = ntiles / 32;
+    const int64_t share = ntiles / 4;
     return (uint32_t)(share > 1024 ? share : 1024);
 }
 
@@ -1229,7 +1241,7 @@ covap::launch_status run_topk(const void *grad, void *residual, int64_t n, int64
     // and the key is the lower edge of a level-1 bin (an eighth of an octave): 2 to 10 times k keys are
     // then at or above it, and only more when the keys crowd just below the k-th largest (as they do
     // under error feedback), which errs on the safe side and which the 32 slots of a tile absorb.  For
-    // k around 1 % of the data that many keys no longer fit the slots, so the margin falls to 1.25 times
+    // k around 1 % of the data that many keys no longer fit the slots, so the margin falls to 1.5 times
     // the share and the key is placed inside the bin by interpolation; where that misjudges, the general
     // tail takes over, as it would have anyway.
     const int64_t nchunks_s = nvec / 64;
@@ -1237,7 +1249,7 @@ covap::launch_status run_topk(const void *grad, void *residual, int64_t n, int64
     const int64_t m = (int64_t)n_s * 256;
     const int64_t ks = div_up(k * m, n);  // the sample's share of k
     const bool interpolate = ks > 512;
-    const int64_t quarters = ks <= 512 ? 8 : (ks >= 2048 ? 5 : 8 - (ks - 512) * 3 / 1536);  // margin in quarters
+    const int64_t quarters = ks <= 512 ? 8 : (ks >= 2048 ? 6 : 8 - (ks - 512) * 2 / 1536);  // margin in quarters
     const int64_t want = div_up(ks * quarters, 4) + 32;
     const uint32_t target = (uint32_t)(want < ((int64_t)1 << 31) ? want : ((int64_t)1 << 31));
     ls += covap::launch(k_topk_sample, dim3(kSlotGrid), dim3(kSampleThreads), 0, st, G, R, ef_coeff, nchunks_s, n_s,
