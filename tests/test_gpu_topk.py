@@ -106,6 +106,33 @@ def test_medium_sizes_with_error_feedback_over_steps(B, cfg, n):
         assert np.array_equal(R.cpu().numpy().view(np.uint32), Rc.view(np.uint32))
 
 
+@pytest.mark.parametrize("per_mille", [3, 10, 13])
+def test_larger_ratios_with_error_feedback_over_steps(B, per_mille):
+    """k = 0.3 %, 1 % (the ratio of the paper's Table II) and 1.3 % of the data: the bound from the sample is
+    then placed inside its level-1 bin by interpolation and the margin is small.  Eight iterations with the
+    residual carried over (keys crowd just below the k-th largest, long crowded lists appear), bit for bit
+    against the oracle; the slot tail has to produce these, not the fall-back."""
+    n = 2_100_003
+    wl = workloads.scaled_down(workloads.config(5), [n], 4096)
+    k = -(-n * per_mille // 1000)
+    R = torch.zeros(n, device=DEV)
+    Rc = np.zeros(n, np.float32)
+    ws = torch.empty(B.topk_workspace_bytes(n), dtype=torch.uint8, device=DEV)
+    vals = torch.empty(k, device=DEV)
+    idx = torch.empty(k, dtype=torch.int32, device=DEV)
+    on_slots = 0
+    for t in range(8):
+        G = workloads.gradient(wl, 0, t, DEV)
+        B.topk_compress(G, R, k, vals, idx, ws)
+        ov, oi = oracle.topk(G.cpu().numpy(), Rc, k)
+        torch.cuda.synchronize()
+        on_slots += tail_taken(ws) == "slots"
+        assert np.array_equal(idx.cpu().numpy().view(np.uint32), oi), t
+        assert np.array_equal(vals.cpu().numpy().view(np.uint32), ov.view(np.uint32)), t
+        assert np.array_equal(R.cpu().numpy().view(np.uint32), Rc.view(np.uint32)), t
+    assert on_slots >= 6                                   # a fall-back now and then is allowed, not the rule
+
+
 def test_full_benchmark_size_by_properties(B):
     """GPT-2-medium-shaped set, k = 0.1 %: count, order, values, residual, the
     magnitude cut and the tie rule together determine the result uniquely."""
