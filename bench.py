@@ -458,7 +458,8 @@ def compact(out, details):
         st = out["streamed"]
         line["streamed"] = {"buckets": st["buckets"], "eager_us_per_step": st["eager_us_per_step"],
                             "side_streams_us_per_step": st.get("eager_side_streams_us_per_step"),
-                            "graph_us_per_step": st.get("graph_us_per_step")}
+                            "graph_us_per_step": st.get("graph_us_per_step"),
+                            "graph_side_streams_us_per_step": st.get("graph_side_streams_us_per_step")}
         brief_ov = lambda v: {k: v[k] for k in ("hidden_frac", "exposed_us", "sync_only_us", "compress_us", "backward_us")}
         if "overlap" in st:
             line["streamed"]["overlap"] = dict(brief_ov(st["overlap"]), variant=st["overlap"]["variant"])
@@ -564,6 +565,24 @@ def streamed(torch, B, run, ms_step, args):
         sres["graph_us_per_step"] = round(graph_wall_us, 1)
     except Exception as e:                              # reported, never hidden
         sres["graph_error"] = repr(e)[:200]
+    # the same graphs with the launches dealt out to the side streams inside the capture (fork and join events
+    # become graph edges, so buckets on different streams may run side by side on replay)
+    if "eager_side_streams_us_per_step" in sres:
+        try:
+            graphs2 = []
+            side2 = torch.cuda.Stream()
+            for r in range(K):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side2):
+                    per_bucket_two_streams(r)
+                graphs2.append(g)
+            for g in graphs2:
+                g.replay()
+            _, graph2_wall_us = timed(lambda t: graphs2[t % K].replay(), reps)
+            sres["graph_side_streams_us_per_step"] = round(graph2_wall_us, 1)
+            del graphs2
+        except Exception as e:                          # reported, never hidden
+            sres["graph_side_streams_error"] = repr(e)[:200]
 
     # Overlap (Sec. II-B: compression is meant to hide behind backward propagation).  The stand-in for
     # backward is one bf16 GEMM (4096^3, the library's own kernel) per bucket on the main stream; compress of

@@ -411,6 +411,56 @@ def test_per_bucket_calls_under_hip_graph_replay(B):
         assert scratch == scratch
 
 
+def test_per_bucket_calls_on_three_streams_inside_a_hip_graph(B):
+    """The per-bucket launches dealt out to three streams inside the capture (bucket b on stream b mod 3, a
+    bucket's decompress after its compress on the same stream; fork and join events become graph edges).  Buckets
+    touch disjoint ranges, so any interleaving must give the oracle's bits, replay after replay."""
+    numel, S, K, N = [300_000, 12_345, 200_001], 8192, 3, 4
+    wl = workloads.scaled_down(workloads.config(2), numel, S)
+    plan, tab = make_plans(B, numel, S, K, cap_bytes=100_000)
+    D = tab.D
+    stride = (plan.packed_elems_max + 3) // 4 * 4
+    G = torch.empty(D, device=DEV)
+    R = torch.zeros(D, device=DEV)
+    recv = torch.zeros(N, stride, device=DEV)
+    out = torch.zeros(D, device=DEV)
+    main, sides = torch.cuda.Stream(), [torch.cuda.Stream() for _ in range(3)]
+    graphs = []
+    for r in range(K):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=main):
+            fork = torch.cuda.Event()
+            fork.record(main)
+            for st in sides:
+                st.wait_event(fork)
+            for b in range(tab.n_buckets):
+                B.covap_compress(plan, r, G, R, recv[0], ef_coeff=0.5, bucket=b, stream=sides[b % 3])
+            for b in range(tab.n_buckets):
+                B.covap_decompress(plan, r, recv, out, bucket=b, stream=sides[b % 3])
+            for st in sides:
+                join = torch.cuda.Event()
+                join.record(st)
+                main.wait_event(join)
+        graphs.append(g)
+    R.zero_()
+    Rc = np.zeros(D, np.float32)
+    for t in range(2 * K + 1):
+        G.copy_(workloads.gradient(wl, 0, t, DEV))
+        recv.copy_(workloads.payload_rows(wl, N, stride, t, DEV, first_worker=0))
+        recv_c = to_np(recv)
+        torch.cuda.synchronize()
+        graphs[t % K].replay()
+        scratch = torch.randn(1000, device=DEV).sum().item()       # eager work between replays
+        torch.cuda.synchronize()
+        oracle.compress(tab, K, t, to_np(G), Rc, recv_c[0], 0.5)
+        out_c = np.zeros(D, np.float32)
+        oracle.decompress(tab, K, t, recv_c, out_c)
+        assert_same(to_np(recv[0]), recv_c[0], f"send t={t}")
+        assert_same(to_np(R), Rc, f"residual t={t}")
+        assert_same(to_np(out), out_c, f"dense t={t}")
+        assert scratch == scratch
+
+
 # ------------------------------------------------------------------ bf16 gradients, fp32 residual
 
 @pytest.mark.parametrize("numel,S,K,c", [([100_003], 4096, 3, 1.0), ([7], 8, 2, 0.5), ([8 * 4096 + 9], 8192, 4, 0.3),
